@@ -1,0 +1,133 @@
+/*
+ * lsm.h -- C ABI of the MI355X (gfx950) chunkwise linear-sequence-modeling library.
+ *
+ * The library evaluates, for every (batch, head) pair independently, the
+ * unified LSM recurrence of the paper (Eq. 5) with the rank-1 update of
+ * Table 1 (BLA, Lightning Attn / RetNet, Mamba2, GLA / RWKV6 / HGRN2 rows)
+ *
+ *     M_t = diag(a_t) M_{t-1} + k_t^T v_t ,      o_t = q_t M_t ,
+ *
+ * in the chunkwise-parallel form of Algorithm 2 (intra-chunk masked scores +
+ * inter-chunk product with the prefix of chunk states), generalised to a
+ * decay, and its backward.  q_t, k_t are 1 x d_k rows, v_t, o_t are 1 x d_v
+ * rows, M is d_k x d_v.  The decay is passed as log-decay g = log a <= 0.
+ *
+ * Readings of the paper fixed by this ABI: o_t sees token t itself; the mask
+ * of Algorithm 2 is the multiplicative 0/1 lower triangle; there is no
+ * normaliser, feature map or 1/sqrt(d) scale inside the library; a vector
+ * decay acts on the key dimension (rows of M); the decay of token t hits
+ * M_{t-1}, the token's own k_t^T v_t enters undecayed.
+ *
+ * All data pointers are DEVICE pointers (HIP), 16-byte aligned, to dense
+ * row-major arrays.  The caller owns every buffer; the library allocates
+ * nothing, keeps nothing between calls and never synchronises: all work is
+ * enqueued on `stream` and outputs are valid once the stream reaches that
+ * point.  Outputs are overwritten, never accumulated; inputs are not
+ * modified; outputs must not alias inputs or each other.  Results are
+ * bitwise reproducible from run to run (no atomics).
+ *
+ * Every argument check happens before the first HIP call, so the error
+ * returns below can be exercised on a host without a GPU.
+ */
+#ifndef LSM_H
+#define LSM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Decay coefficient kinds (Table 1, "Parameter" column). */
+typedef enum {
+    LSM_DECAY_NONE   = 0, /* a = 1 (BLA);                      log_decay must be NULL          */
+    LSM_DECAY_HEAD   = 1, /* fixed a per head (Lightning/RetNet);   log_decay [H]              */
+    LSM_DECAY_SCALAR = 2, /* a_t scalar per token (Mamba2 style);   log_decay [B,H,T]          */
+    LSM_DECAY_VECTOR = 3  /* a_t in R^{d_k} per token (GLA style);  log_decay [B,H,T,d_k]      */
+} lsm_decay_kind;
+
+/* Element type of q, k, v, o, d_o, dq, dk, dv.  States, decays and their gradients are fp32. */
+typedef enum { LSM_DTYPE_F32 = 0, LSM_DTYPE_BF16 = 1 } lsm_dtype;
+
+typedef enum {
+    LSM_OK              =  0,
+    LSM_ERR_NULL        = -1, /* a required pointer is NULL, or a forbidden one is not           */
+    LSM_ERR_SHAPE       = -2, /* non-positive dimension, struct_size mismatch, size overflow     */
+    LSM_ERR_UNSUPPORTED = -3, /* d_k, d_v not in {64,128,256}; chunk_size not in {16,32,64,128};
+                                 unknown decay_kind / dtype                                      */
+    LSM_ERR_ALIGN       = -4, /* a pointer is not 16-byte aligned                                */
+    LSM_ERR_WORKSPACE   = -5, /* workspace NULL or smaller than the *_workspace_bytes() figure   */
+    LSM_ERR_LAUNCH      = -6  /* HIP reported an error when the kernels were enqueued            */
+} lsm_status;
+
+typedef struct {
+    uint32_t struct_size; /* = sizeof(lsm_params) */
+    int32_t  B, H, T;     /* batch, heads, tokens per sequence (any T >= 1; the last chunk may be ragged) */
+    int32_t  d_k, d_v;    /* key / value head dimensions                                         */
+    int32_t  chunk_size;  /* C: tokens per chunk of Algorithm 2 (size of the quadratic block)    */
+    int32_t  decay_kind;  /* lsm_decay_kind                                                      */
+    int32_t  dtype;       /* lsm_dtype                                                           */
+} lsm_params;
+
+/*
+ * Forward (Algorithm 2 with decay; Eq. 5; Table 1).
+ *   q, k        [B,H,T,d_k]  dtype          in
+ *   v           [B,H,T,d_v]  dtype          in
+ *   log_decay   per decay_kind, fp32, finite and <= 0 (not checked)      in
+ *   init_state  NULL (= zeros) or [B,H,d_k,d_v] fp32: M_0                in
+ *   o           [B,H,T,d_v]  dtype          out
+ *   final_state NULL (not wanted) or [B,H,d_k,d_v] fp32: M_T             out
+ *   workspace   device scratch of at least lsm_chunk_fwd_workspace_bytes(p); contents undefined after the call
+ *   stream      hipStream_t, NULL = the default stream
+ * Returns an lsm_status.  On any error nothing has been enqueued, except for
+ * LSM_ERR_LAUNCH, where earlier kernels of the call may have been.
+ */
+int lsm_chunk_fwd(const lsm_params* p,
+                  const void* q, const void* k, const void* v,
+                  const float* log_decay, const float* init_state,
+                  void* o, float* final_state,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of  L = <o, d_o> + <M_T, d_final_state>  (the paper states no
+ * backward; it is the adjoint of the forward above, evaluated chunkwise with a
+ * reverse scan over chunk-state gradients).  Chunk states are recomputed from
+ * the inputs; nothing saved by the forward call is needed.
+ *   q,k,v,log_decay,init_state   as in the forward                         in
+ *   d_o            [B,H,T,d_v] dtype                                       in
+ *   d_final_state  NULL (= zeros) or [B,H,d_k,d_v] fp32                    in
+ *   dq, dk         [B,H,T,d_k] dtype;  dv [B,H,T,d_v] dtype                out
+ *   d_log_decay    shape of log_decay, fp32.  Must be NULL for LSM_DECAY_NONE;
+ *                  for the other kinds NULL skips it                       out
+ *   d_init_state   NULL (not wanted) or [B,H,d_k,d_v] fp32                 out
+ */
+int lsm_chunk_bwd(const lsm_params* p,
+                  const void* q, const void* k, const void* v,
+                  const float* log_decay, const float* init_state,
+                  const void* d_o, const float* d_final_state,
+                  void* dq, void* dk, void* dv,
+                  float* d_log_decay, float* d_init_state,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Scratch the calls above need, in bytes; 0 if *p is invalid.  Host-only, no HIP call. */
+size_t lsm_chunk_fwd_workspace_bytes(const lsm_params* p);
+size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p);
+
+/*
+ * Which kernel family a parameter set is routed to: 1 = bf16 MFMA kernels,
+ * 0 = generic fp32-arithmetic kernels, negative = lsm_status of invalid params.
+ * Host-only.  (Both families run on the GPU; there is no CPU fallback.)
+ */
+int lsm_kernel_path(const lsm_params* p);
+
+/* Static, NUL-terminated description of a status code. */
+const char* lsm_status_string(int status);
+
+/* ABI version, bumped when a signature or struct changes. */
+int lsm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSM_H */

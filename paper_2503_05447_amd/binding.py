@@ -1,0 +1,165 @@
+"""Thin Python binding of the C-ABI library declared in include/lsm.h.
+
+Argument marshalling only: tensors are torch device tensors (PyTorch is used
+for device memory and streams, nothing else), every step of the path runs in
+the HIP kernels of liblsm_hip.so.  There is no fallback: if the library cannot
+be loaded, importing works but every call raises.
+"""
+import ctypes
+import os
+
+from . import build as _build
+
+DECAY_NONE, DECAY_HEAD, DECAY_SCALAR, DECAY_VECTOR = 0, 1, 2, 3
+DTYPE_F32, DTYPE_BF16 = 0, 1
+
+
+class LsmError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: status %d (%s)" % (where, status, _status_string(status)))
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("B", ctypes.c_int32), ("H", ctypes.c_int32),
+                ("T", ctypes.c_int32), ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32),
+                ("chunk_size", ctypes.c_int32), ("decay_kind", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def library():
+    """Load liblsm_hip.so (building it only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        _build.build_library()
+    lib = ctypes.CDLL(path)
+    vp, sz, pp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(_Params)
+    lib.lsm_chunk_fwd.restype = ctypes.c_int
+    lib.lsm_chunk_fwd.argtypes = [pp] + [vp] * 8 + [sz, vp]
+    lib.lsm_chunk_bwd.restype = ctypes.c_int
+    lib.lsm_chunk_bwd.argtypes = [pp] + [vp] * 13 + [sz, vp]
+    lib.lsm_chunk_fwd_workspace_bytes.restype = sz
+    lib.lsm_chunk_fwd_workspace_bytes.argtypes = [pp]
+    lib.lsm_chunk_bwd_workspace_bytes.restype = sz
+    lib.lsm_chunk_bwd_workspace_bytes.argtypes = [pp]
+    lib.lsm_kernel_path.restype = ctypes.c_int
+    lib.lsm_kernel_path.argtypes = [pp]
+    lib.lsm_status_string.restype = ctypes.c_char_p
+    lib.lsm_status_string.argtypes = [ctypes.c_int]
+    lib.lsm_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _status_string(status):
+    return library().lsm_status_string(int(status)).decode()
+
+
+def make_params(B, H, T, d_k, d_v, chunk_size, decay_kind, dtype):
+    return _Params(ctypes.sizeof(_Params), B, H, T, d_k, d_v, chunk_size, decay_kind, dtype)
+
+
+def lsm_chunk_fwd_workspace_bytes(params):
+    return int(library().lsm_chunk_fwd_workspace_bytes(ctypes.byref(params)))
+
+
+def lsm_chunk_bwd_workspace_bytes(params):
+    return int(library().lsm_chunk_bwd_workspace_bytes(ctypes.byref(params)))
+
+
+def kernel_path(params):
+    """1 = MFMA kernels, 0 = generic fp32-arithmetic kernels, < 0 = invalid parameters."""
+    return int(library().lsm_kernel_path(ctypes.byref(params)))
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(None)
+
+
+def _check(t, shape, dtype, name):
+    import torch  # noqa: F401
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError("%s: need a contiguous device tensor %s of %s, got %s %s on %s"
+                         % (name, tuple(shape), dtype, tuple(t.shape), t.dtype, t.device))
+
+
+def _setup(q, k, v, log_decay, decay_kind, chunk_size):
+    import torch
+    if q.dtype == torch.float32:
+        dt = DTYPE_F32
+    elif q.dtype == torch.bfloat16:
+        dt = DTYPE_BF16
+    else:
+        raise ValueError("q must be float32 or bfloat16")
+    B, H, T, dk = q.shape
+    dv = v.shape[-1]
+    _check(q, (B, H, T, dk), q.dtype, "q")
+    _check(k, (B, H, T, dk), q.dtype, "k")
+    _check(v, (B, H, T, dv), q.dtype, "v")
+    gshape = {DECAY_NONE: None, DECAY_HEAD: (H,), DECAY_SCALAR: (B, H, T), DECAY_VECTOR: (B, H, T, dk)}[decay_kind]
+    if gshape is not None:
+        if log_decay is None:
+            raise ValueError("log_decay required for this decay kind")
+        _check(log_decay, gshape, torch.float32, "log_decay")
+    elif log_decay is not None:
+        raise ValueError("log_decay must be None for DECAY_NONE")
+    p = make_params(B, H, T, dk, dv, chunk_size, decay_kind, dt)
+    return p, (B, H, T, dk, dv), gshape
+
+
+def _stream_handle(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None,
+                  want_final_state=True, workspace=None, stream=None):
+    """o, final_state = chunkwise forward of M_t = diag(a_t) M_{t-1} + k_t^T v_t, o_t = q_t M_t.
+
+    Enqueues on ``stream`` (default: torch's current stream) and returns without synchronising.
+    """
+    import torch
+    p, (B, H, T, dk, dv), _ = _setup(q, k, v, log_decay, decay_kind, chunk_size)
+    _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
+    need = lsm_chunk_fwd_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    o = torch.empty((B, H, T, dv), dtype=q.dtype, device=q.device)
+    final = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
+    rc = library().lsm_chunk_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(init_state),
+                                 _ptr(o), _ptr(final), _ptr(workspace), workspace.numel(), _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_chunk_fwd")
+    return o, final
+
+
+def lsm_chunk_bwd(q, k, v, log_decay, decay_kind, d_o, chunk_size=64, init_state=None, d_final_state=None,
+                  want_d_log_decay=True, want_d_init_state=True, workspace=None, stream=None):
+    """dict(dq, dk, dv, dg, d_init_state): chunkwise backward of <o, d_o> + <M_T, d_final_state>."""
+    import torch
+    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_decay, decay_kind, chunk_size)
+    _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
+    _check(d_final_state, (B, H, dk, dv), torch.float32, "d_final_state")
+    _check(d_o, (B, H, T, dv), q.dtype, "d_o")
+    need = lsm_chunk_bwd_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    dq = torch.empty_like(q)
+    dk_ = torch.empty_like(k)
+    dv_ = torch.empty_like(v)
+    dg = torch.empty(gshape, dtype=torch.float32, device=q.device) if (gshape and want_d_log_decay) else None
+    d_init = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_d_init_state else None
+    rc = library().lsm_chunk_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(init_state),
+                                 _ptr(d_o), _ptr(d_final_state), _ptr(dq), _ptr(dk_), _ptr(dv_), _ptr(dg),
+                                 _ptr(d_init), _ptr(workspace), workspace.numel(), _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_chunk_bwd")
+    return dict(dq=dq, dk=dk_, dv=dv_, dg=dg, d_init_state=d_init)

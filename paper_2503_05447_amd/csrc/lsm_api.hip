@@ -1,0 +1,106 @@
+// C-ABI front end: argument validation, routing to a kernel family, status strings.
+// All checks run before the first HIP call so they can be exercised without a GPU.
+#include "../../include/lsm.h"
+#include "lsm_internal.h"
+
+namespace {
+
+bool dim_ok(int d) { return d == 64 || d == 128 || d == 256; }
+bool chunk_ok(int c) { return c == 16 || c == 32 || c == 64 || c == 128; }
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_params(const lsm_params* p, lsm::Dims* d) {
+    if (!p) return LSM_ERR_NULL;
+    if (p->struct_size != sizeof(lsm_params)) return LSM_ERR_SHAPE;
+    if (p->B < 1 || p->H < 1 || p->T < 1 || p->d_k < 1 || p->d_v < 1 || p->chunk_size < 1) return LSM_ERR_SHAPE;
+    if (p->decay_kind < 0 || p->decay_kind > 3) return LSM_ERR_UNSUPPORTED;
+    if (p->dtype != LSM_DTYPE_F32 && p->dtype != LSM_DTYPE_BF16) return LSM_ERR_UNSUPPORTED;
+    if (!dim_ok(p->d_k) || !dim_ok(p->d_v) || !chunk_ok(p->chunk_size)) return LSM_ERR_UNSUPPORTED;
+    // index arithmetic inside the kernels is 64-bit, grid dimensions are not
+    const long long bh = (long long)p->B * p->H;
+    const long long n = ((long long)p->T + p->chunk_size - 1) / p->chunk_size;
+    if (bh > 65535 || n > 0x7fffffffLL || bh * p->T > (1LL << 40)) return LSM_ERR_SHAPE;
+    d->B = p->B; d->H = p->H; d->T = p->T; d->dk = p->d_k; d->dv = p->d_v; d->C = p->chunk_size;
+    d->N = int(n); d->kind = p->decay_kind; d->bf16 = p->dtype == LSM_DTYPE_BF16;
+    return LSM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lsm_version(void) { return 1; }
+
+const char* lsm_status_string(int status) {
+    switch (status) {
+        case LSM_OK: return "ok";
+        case LSM_ERR_NULL: return "a required pointer is NULL or a forbidden pointer is not NULL";
+        case LSM_ERR_SHAPE: return "bad dimension or struct_size";
+        case LSM_ERR_UNSUPPORTED: return "unsupported d_k/d_v/chunk_size/decay_kind/dtype";
+        case LSM_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case LSM_ERR_WORKSPACE: return "workspace missing or too small";
+        case LSM_ERR_LAUNCH: return "HIP error while enqueuing kernels";
+        default: return "unknown status";
+    }
+}
+
+int lsm_kernel_path(const lsm_params* p) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    return lsm::mfma_supported(d) ? 1 : 0;
+}
+
+size_t lsm_chunk_fwd_workspace_bytes(const lsm_params* p) {
+    lsm::Dims d{};
+    if (check_params(p, &d) != LSM_OK) return 0;
+    return lsm::mfma_supported(d) ? lsm::mfma_fwd_workspace(d) : lsm::generic_fwd_workspace(d);
+}
+
+size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p) {
+    lsm::Dims d{};
+    if (check_params(p, &d) != LSM_OK) return 0;
+    return lsm::mfma_supported(d) ? lsm::mfma_bwd_workspace(d) : lsm::generic_bwd_workspace(d);
+}
+
+int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
+                  const float* init_state, void* o, float* final_state, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !o) return LSM_ERR_NULL;
+    if ((d.kind == LSM_DECAY_NONE) != (log_decay == nullptr)) return LSM_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_decay) ||
+        misaligned(init_state) || misaligned(final_state) || misaligned(workspace))
+        return LSM_ERR_ALIGN;
+    const size_t need = lsm_chunk_fwd_workspace_bytes(p);
+    if (!workspace || workspace_bytes < need) return LSM_ERR_WORKSPACE;
+    lsm::FwdArgs a{q, k, v, log_decay, init_state, o, final_state, workspace, static_cast<hipStream_t>(stream)};
+    const hipError_t e = lsm::mfma_supported(d) ? lsm::mfma_fwd(d, a) : lsm::generic_fwd(d, a);
+    return e == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
+}
+
+int lsm_chunk_bwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
+                  const float* init_state, const void* d_o, const float* d_final_state, void* dq, void* dk,
+                  void* dv, float* d_log_decay, float* d_init_state, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !d_o || !dq || !dk || !dv) return LSM_ERR_NULL;
+    if ((d.kind == LSM_DECAY_NONE) != (log_decay == nullptr)) return LSM_ERR_NULL;
+    if (d.kind == LSM_DECAY_NONE && d_log_decay) return LSM_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(d_o) || misaligned(dq) || misaligned(dk) ||
+        misaligned(dv) || misaligned(log_decay) || misaligned(init_state) || misaligned(d_final_state) ||
+        misaligned(d_log_decay) || misaligned(d_init_state) || misaligned(workspace))
+        return LSM_ERR_ALIGN;
+    const size_t need = lsm_chunk_bwd_workspace_bytes(p);
+    if (!workspace || workspace_bytes < need) return LSM_ERR_WORKSPACE;
+    lsm::BwdArgs a{q, k, v, log_decay, init_state, d_o, d_final_state, dq, dk, dv, d_log_decay, d_init_state,
+                   workspace, static_cast<hipStream_t>(stream)};
+    const hipError_t e = lsm::mfma_supported(d) ? lsm::mfma_bwd(d, a) : lsm::generic_bwd(d, a);
+    return e == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,96 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+include/lsm.h declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2503_05447_amd as pkg
+from paper_2503_05447_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lsm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lsm_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = pkg.library()
+    names = declared_symbols()
+    assert {"lsm_chunk_fwd", "lsm_chunk_bwd", "lsm_chunk_fwd_workspace_bytes", "lsm_chunk_bwd_workspace_bytes",
+            "lsm_status_string", "lsm_version", "lsm_kernel_path"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.lsm_version() >= 1
+
+
+def P(**kw):
+    base = dict(B=2, H=2, T=100, d_k=64, d_v=64, chunk_size=64, decay_kind=2, dtype=1)
+    base.update(kw)
+    return pkg.make_params(**base)
+
+
+def fwd(p, q=0x1000, k=0x2000, v=0x3000, g=0x4000, m0=None, o=0x5000, mT=None, ws=0x10000, wsb=1 << 40):
+    vp = ctypes.c_void_p
+    return pkg.library().lsm_chunk_fwd(ctypes.byref(p), vp(q), vp(k), vp(v), vp(g), vp(m0), vp(o), vp(mT), vp(ws), wsb, vp(None))
+
+
+def bwd(p, q=0x1000, k=0x2000, v=0x3000, g=0x4000, m0=None, d_o=0x6000, dmT=None, dq=0x7000, dk=0x8000, dv=0x9000,
+        dg=0xa000, dm0=None, ws=0x10000, wsb=1 << 40):
+    vp = ctypes.c_void_p
+    return pkg.library().lsm_chunk_bwd(ctypes.byref(p), vp(q), vp(k), vp(v), vp(g), vp(m0), vp(d_o), vp(dmT), vp(dq),
+                                       vp(dk), vp(dv), vp(dg), vp(dm0), vp(ws), wsb, vp(None))
+
+
+def test_error_codes_are_reached_before_any_launch():
+    ERR_NULL, ERR_SHAPE, ERR_UNSUP, ERR_ALIGN, ERR_WS = -1, -2, -3, -4, -5
+    assert fwd(P(), q=None) == ERR_NULL
+    assert fwd(P(), o=None) == ERR_NULL
+    assert fwd(P(), g=None) == ERR_NULL                       # decay required
+    assert fwd(P(decay_kind=0)) == ERR_NULL                   # decay forbidden for kind none
+    assert bwd(P(decay_kind=0), g=None) == ERR_NULL           # d_log_decay forbidden for kind none
+    assert bwd(P(), dq=None) == ERR_NULL
+    assert fwd(P(T=0)) == ERR_SHAPE
+    assert fwd(P(B=-1)) == ERR_SHAPE
+    bad = P(); bad.struct_size = 12
+    assert fwd(bad) == ERR_SHAPE
+    assert fwd(P(d_k=96)) == ERR_UNSUP
+    assert fwd(P(d_v=512)) == ERR_UNSUP
+    assert fwd(P(chunk_size=48)) == ERR_UNSUP
+    assert fwd(P(decay_kind=4)) == ERR_UNSUP
+    assert fwd(P(dtype=2)) == ERR_UNSUP
+    assert fwd(P(), k=0x2004) == ERR_ALIGN
+    assert bwd(P(), dm0=0xb008) == ERR_ALIGN
+    assert fwd(P(), ws=None) == ERR_WS
+    assert fwd(P(), wsb=16) == ERR_WS
+    assert bwd(P(), wsb=16) == ERR_WS
+    assert pkg.library().lsm_chunk_fwd(None, *([ctypes.c_void_p(None)] * 8), 0, ctypes.c_void_p(None)) == ERR_NULL
+
+
+def test_workspace_queries_and_status_strings():
+    p = P()
+    f, b = pkg.lsm_chunk_fwd_workspace_bytes(p), pkg.lsm_chunk_bwd_workspace_bytes(p)
+    assert f > 0 and b >= f
+    assert pkg.lsm_chunk_fwd_workspace_bytes(P(d_k=3)) == 0
+    assert pkg.lsm_chunk_bwd_workspace_bytes(P(T=0)) == 0
+    assert pkg.kernel_path(P()) in (0, 1)
+    assert pkg.kernel_path(P(dtype=0)) == 0                   # fp32 inputs never take bf16 MFMA operands
+    assert pkg.kernel_path(P(d_k=3)) < 0
+    # workspace grows with the number of chunks
+    assert pkg.lsm_chunk_fwd_workspace_bytes(P(T=6400)) > f
+    for s in range(0, -7, -1):
+        assert len(binding._status_string(s)) > 1
+    assert binding._status_string(-99) == "unknown status"
+    with pytest.raises(pkg.LsmError):
+        raise pkg.LsmError(-3, "x")
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    q = torch.zeros(1, 1, 8, 64)
+    with pytest.raises(ValueError):
+        pkg.lsm_chunk_fwd(q, q, q, None, pkg.DECAY_NONE, 64)
