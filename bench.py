@@ -1,0 +1,158 @@
+"""Benchmark of the LSM chunkwise forward+backward on one MI355X.
+
+A step = one lsm_chunk_fwd + one lsm_chunk_bwd over one batch of synthetic inputs of the chosen
+benchmark configuration (default: configuration 3, the shape the headline metric is quoted on:
+B=4, H=16, T=8192, d_k=d_v=128, per-token scalar decay, bf16, chunk 64).  Inputs, outputs and the
+workspace are resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def algorithmic_bytes_per_token_head(cfg, which):
+    """Compulsory HBM bytes per token-head: every input read once, every output written once."""
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    dk, dv = cfg["dk"], cfg["dv"]
+    gam = {0: 0, 1: 0, 2: 4, 3: 4 * dk}[cfg["kind"]]
+    fwd = (2 * dk + dv) * e + gam + dv * e
+    bwd = (2 * dk + 2 * dv) * e + gam + (2 * dk + dv) * e + gam
+    return {"fwd": fwd, "bwd": bwd, "both": fwd + bwd}[which]
+
+
+def algorithmic_flops_per_token_head(cfg):
+    """Chunk-dense convention: the full C x C block is computed and masked (Algorithm 2)."""
+    dk, dv, C = cfg["dk"], cfg["dv"], cfg["chunk"]
+    fwd = 2 * C * (dk + dv) + 4 * dk * dv
+    bwd = 2 * C * (3 * dk + 2 * dv) + 8 * dk * dv
+    return fwd, bwd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import lsm_workloads as wl
+    import paper_2503_05447_amd as pkg
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    x, cfg = wl.make_config(args.config - 1)
+    backward = cfg["backward"]
+    tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+
+    def mv(a, dt):
+        return None if a is None else torch.from_numpy(a).to(dev).to(dt).contiguous()
+
+    q, k, v, d_o = (mv(x[n], tdt) for n in ("q", "k", "v", "d_o"))
+    g, m0 = mv(x["g"], torch.float32), mv(x["m0"], torch.float32)
+    kind, C = cfg["kind"], cfg["chunk"]
+    B, H, T, dk, dv = cfg["B"], cfg["H"], cfg["T"], cfg["dk"], cfg["dv"]
+    p = pkg.make_params(B, H, T, dk, dv, C, kind, 1 if cfg["dtype"] == "bf16" else 0)
+    ws = torch.empty(max(pkg.lsm_chunk_fwd_workspace_bytes(p), pkg.lsm_chunk_bwd_workspace_bytes(p), 256),
+                     dtype=torch.uint8, device=dev)
+
+    def step():
+        out = pkg.lsm_chunk_fwd(q, k, v, g, kind, C, m0, workspace=ws)
+        grads = pkg.lsm_chunk_bwd(q, k, v, g, kind, d_o, C, m0, workspace=ws) if backward else None
+        return out, grads
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    pkg.lsm_profile_start()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        last = step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = pkg.lsm_profile_stop()
+    sec = (t1 - t0) / args.steps
+    tokens = B * T
+    th = B * H * T
+
+    per_kernel = {}
+    for name, ms in prof:
+        per_kernel.setdefault(name, []).append(ms)
+    kavg = {n: float(np.mean(v_)) for n, v_ in per_kernel.items()}
+    dominant = max(kavg, key=kavg.get)
+    # algorithmic bytes of the dominant kernel's launch: the compulsory traffic of the pass it belongs to
+    which = "bwd" if ("grad" in dominant or "bwd" in dominant or "dstate" in dominant) else "fwd"
+    abytes = algorithmic_bytes_per_token_head(cfg, which) * th
+    achieved = abytes / (kavg[dominant] * 1e-3) / 1e9
+    ffl, bfl = algorithmic_flops_per_token_head(cfg)
+    flops = (ffl + (bfl if backward else 0)) * th
+    tflops = flops / sec / 1e12
+
+    result = {
+        "metric": "LSM chunkwise fwd+bwd tokens/s and TFLOP/s (%MFMA peak) at H=16,d=128,T=8192",
+        "value": tokens / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": cfg["name"], "B": B, "H": H, "T": T, "d_k": dk, "d_v": dv, "chunk": C,
+                   "decay_kind": wl.KIND_NAMES[kind], "passes": "fwd+bwd" if backward else "fwd",
+                   "kernel_path": "mfma" if pkg.kernel_path(p) == 1 else "generic"},
+        "tflops": tflops, "mfma_peak_frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+        "hbm_frac_whole_step": algorithmic_bytes_per_token_head(cfg, "both" if backward else "fwd") * th / sec / 1e9 / HBM_PEAK_GBS,
+        "kernel_ms": kavg,
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": abytes},
+    }
+
+    if not args.no_cpu_baseline or not args.no_check:
+        from oracle import lsm_oracle_bwd, lsm_oracle_fwd, oracle_threads
+        # bounded sample: the first `nb` batch elements of the same workload (all heads, full T)
+        nb = max(1, min(B, (1 << 18) // (H * T) or 1))
+        sl = slice(0, nb)
+        gs = x["g"] if (x["g"] is None or kind == wl.KIND_HEAD) else x["g"][sl]
+        m0s = None if x["m0"] is None else x["m0"][sl]
+        c0 = time.perf_counter()
+        o_ref, mT_ref = lsm_oracle_fwd(x["q"][sl], x["k"][sl], x["v"][sl], gs, kind, m0s)
+        r_ref = lsm_oracle_bwd(x["q"][sl], x["k"][sl], x["v"][sl], gs, kind, x["d_o"][sl], m0s) if backward else None
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {"value": nb * T / (c1 - c0), "unit": "tokens/s", "cores": oracle_threads(),
+                                  "kind": "oracle",
+                                  "sample": "batch elements 0..%d of the same workload, all %d heads, full T=%d, %s"
+                                            % (nb - 1, H, T, "fwd+bwd" if backward else "fwd"),
+                                  "seconds": c1 - c0}
+        if not args.no_check:
+            (o, mT), grads = last
+            def err(got, ref, ulp):
+                got = got.float().cpu().numpy().astype(np.float64)
+                e = np.maximum(np.abs(got - ref) - ulp * np.abs(ref), 0).max()
+                return float(e / max(np.sqrt(np.mean(ref ** 2)), 1e-300))
+            ulp = 2.0 ** -8 if cfg["dtype"] == "bf16" else 0.0   # half-ulp of the bf16 output container
+            par = {"o": err(o[sl], o_ref, ulp), "final_state": err(mT[sl], mT_ref, 0.0)}
+            if backward:
+                par.update(dq=err(grads["dq"][sl], r_ref["dq"], ulp), dk=err(grads["dk"][sl], r_ref["dk"], ulp),
+                           dv=err(grads["dv"][sl], r_ref["dv"], ulp))
+                if kind in (wl.KIND_SCALAR, wl.KIND_VECTOR):
+                    par["dg"] = err(grads["dg"][sl], r_ref["dg"], 0.0)
+            result["parity_err_over_rms"] = par
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

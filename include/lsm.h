@@ -121,6 +121,17 @@ size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p);
  */
 int lsm_kernel_path(const lsm_params* p);
 
+/*
+ * Optional per-kernel timing for benchmarks (not part of the method).  After lsm_profile_start()
+ * every kernel the library enqueues is bracketed by a pair of HIP events on the call's stream;
+ * lsm_profile_stop() waits for them, writes up to `capacity` (kernel id, elapsed ms) pairs in launch
+ * order, returns how many it wrote, and switches timing off again.  Process-wide state: do not use
+ * from concurrent threads while other calls are in flight.  lsm_kernel_name() names an id.
+ */
+int lsm_profile_start(void);
+int lsm_profile_stop(int* kernel_ids, float* milliseconds, int capacity);
+const char* lsm_kernel_name(int kernel_id);
+
 /* Static, NUL-terminated description of a status code. */
 const char* lsm_status_string(int status);
 

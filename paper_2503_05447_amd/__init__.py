@@ -3,4 +3,5 @@ from .binding import (  # noqa: F401
     DECAY_NONE, DECAY_HEAD, DECAY_SCALAR, DECAY_VECTOR,
     LsmError, library, kernel_path, lsm_chunk_fwd, lsm_chunk_bwd,
     lsm_chunk_fwd_workspace_bytes, lsm_chunk_bwd_workspace_bytes, make_params,
+    lsm_profile_start, lsm_profile_stop,
 )

@@ -52,6 +52,11 @@ def library():
     lib.lsm_status_string.restype = ctypes.c_char_p
     lib.lsm_status_string.argtypes = [ctypes.c_int]
     lib.lsm_version.restype = ctypes.c_int
+    lib.lsm_profile_start.restype = ctypes.c_int
+    lib.lsm_profile_stop.restype = ctypes.c_int
+    lib.lsm_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+    lib.lsm_kernel_name.restype = ctypes.c_char_p
+    lib.lsm_kernel_name.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
 
@@ -75,6 +80,19 @@ def lsm_chunk_bwd_workspace_bytes(params):
 def kernel_path(params):
     """1 = MFMA kernels, 0 = generic fp32-arithmetic kernels, < 0 = invalid parameters."""
     return int(library().lsm_kernel_path(ctypes.byref(params)))
+
+
+def lsm_profile_start():
+    """Bracket every kernel the library enqueues with HIP events until lsm_profile_stop()."""
+    library().lsm_profile_start()
+
+
+def lsm_profile_stop(capacity=65536):
+    """Return [(kernel name, elapsed ms), ...] in launch order and switch timing off."""
+    ids = (ctypes.c_int * capacity)()
+    ms = (ctypes.c_float * capacity)()
+    n = library().lsm_profile_stop(ids, ms, capacity)
+    return [(library().lsm_kernel_name(ids[i]).decode(), float(ms[i])) for i in range(n)]
 
 
 def _ptr(t):

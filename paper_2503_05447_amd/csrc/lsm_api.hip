@@ -3,6 +3,32 @@
 #include "../../include/lsm.h"
 #include "lsm_internal.h"
 
+#include <mutex>
+#include <vector>
+
+namespace lsm {
+namespace {
+struct ProfRec { int id; hipEvent_t t0, t1; };
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+}  // namespace
+
+void prof_begin(int kernel_id, hipStream_t stream) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    ProfRec r{kernel_id, nullptr, nullptr};
+    if (hipEventCreate(&r.t0) != hipSuccess || hipEventCreate(&r.t1) != hipSuccess) return;
+    (void)hipEventRecord(r.t0, stream);
+    g_prof.push_back(r);
+}
+void prof_end(hipStream_t stream) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof.empty()) (void)hipEventRecord(g_prof.back().t1, stream);
+}
+}  // namespace lsm
+
 namespace {
 
 bool dim_ok(int d) { return d == 64 || d == 128 || d == 256; }
@@ -42,6 +68,41 @@ const char* lsm_status_string(int status) {
         case LSM_ERR_LAUNCH: return "HIP error while enqueuing kernels";
         default: return "unknown status";
     }
+}
+
+int lsm_profile_start(void) {
+    std::lock_guard<std::mutex> lk(lsm::g_prof_mu);
+    for (auto& r : lsm::g_prof) { (void)hipEventDestroy(r.t0); (void)hipEventDestroy(r.t1); }
+    lsm::g_prof.clear();
+    lsm::g_prof_on = true;
+    return LSM_OK;
+}
+
+int lsm_profile_stop(int* kernel_ids, float* milliseconds, int capacity) {
+    std::lock_guard<std::mutex> lk(lsm::g_prof_mu);
+    lsm::g_prof_on = false;
+    int n = 0;
+    for (auto& r : lsm::g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.t1) == hipSuccess && hipEventElapsedTime(&ms, r.t0, r.t1) == hipSuccess &&
+            n < capacity && kernel_ids && milliseconds) {
+            kernel_ids[n] = r.id;
+            milliseconds[n] = ms;
+            ++n;
+        }
+        (void)hipEventDestroy(r.t0);
+        (void)hipEventDestroy(r.t1);
+    }
+    lsm::g_prof.clear();
+    return n;
+}
+
+const char* lsm_kernel_name(int kernel_id) {
+    static const char* names[lsm::KID_COUNT] = {
+        "generic_cumsum", "generic_chunk_state", "generic_scan", "generic_output", "generic_chunk_dstate",
+        "generic_reverse_scan", "generic_grad", "head_reduce", "mfma_state_scan_fwd", "mfma_output",
+        "mfma_state_scan_bwd", "mfma_dstate_scan", "mfma_grad"};
+    return kernel_id >= 0 && kernel_id < lsm::KID_COUNT ? names[kernel_id] : "unknown";
 }
 
 int lsm_kernel_path(const lsm_params* p) {

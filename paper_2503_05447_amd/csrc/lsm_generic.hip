@@ -297,18 +297,18 @@ hipError_t fwd_t(const Dims& d, const FwdArgs& a) {
     const dim3 grid(d.N, d.BH()), block(kThreads);
     const int sz = d.dk * d.dv;
     auto q = static_cast<const TIO*>(a.q), k = static_cast<const TIO*>(a.k), v = static_cast<const TIO*>(a.v);
-    if (d.kind != 0) hipLaunchKernelGGL(k_cumsum, grid, block, 0, a.stream, d, a.g, w.bcum);
-    hipLaunchKernelGGL((k_local_state<TIO, 0>), grid, block, 0, a.stream, d, k, v, w.bcum, w.states);
-    hipLaunchKernelGGL((k_scan<false>), dim3((sz + kThreads - 1) / kThreads, d.BH()), block, 0, a.stream, d, w.bcum,
-                       w.states, a.m0, a.mT);
+    if (d.kind != 0) { ProfScope ps(KID_GEN_CUMSUM, a.stream); hipLaunchKernelGGL(k_cumsum, grid, block, 0, a.stream, d, a.g, w.bcum); }
+    { ProfScope ps(KID_GEN_STATE, a.stream); hipLaunchKernelGGL((k_local_state<TIO, 0>), grid, block, 0, a.stream, d, k, v, w.bcum, w.states); }
+    { ProfScope ps(KID_GEN_SCAN, a.stream); hipLaunchKernelGGL((k_scan<false>), dim3((sz + kThreads - 1) / kThreads, d.BH()), block, 0, a.stream, d, w.bcum,
+                       w.states, a.m0, a.mT); }
     const size_t lds = size_t(d.C) * d.C * 4;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_output<TIO>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((k_output<TIO>), grid, block, lds, a.stream, d, q, k, v, w.bcum, w.states,
-                       static_cast<TIO*>(a.o));
+    { ProfScope ps(KID_GEN_OUTPUT, a.stream); hipLaunchKernelGGL((k_output<TIO>), grid, block, lds, a.stream, d, q, k, v, w.bcum, w.states,
+                       static_cast<TIO*>(a.o)); }
     return hipGetLastError();
 }
 
@@ -326,19 +326,21 @@ hipError_t bwd_t(const Dims& d, const BwdArgs& a) {
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
         if (e != hipSuccess) return e;
     }
-    if (d.kind != 0) hipLaunchKernelGGL(k_cumsum, grid, block, 0, a.stream, d, a.g, w.bcum);
-    hipLaunchKernelGGL((k_local_state<TIO, 0>), grid, block, 0, a.stream, d, k, v, w.bcum, w.states);
-    hipLaunchKernelGGL((k_scan<false>), sgrid, block, 0, a.stream, d, w.bcum, w.states, a.m0,
-                       static_cast<float*>(nullptr));
-    hipLaunchKernelGGL((k_local_state<TIO, 1>), grid, block, 0, a.stream, d, q, d_o, w.bcum, w.dstates);
-    hipLaunchKernelGGL((k_scan<true>), sgrid, block, 0, a.stream, d, w.bcum, w.dstates, a.d_mT, a.d_m0);
+    if (d.kind != 0) { ProfScope ps(KID_GEN_CUMSUM, a.stream); hipLaunchKernelGGL(k_cumsum, grid, block, 0, a.stream, d, a.g, w.bcum); }
+    { ProfScope ps(KID_GEN_STATE, a.stream); hipLaunchKernelGGL((k_local_state<TIO, 0>), grid, block, 0, a.stream, d, k, v, w.bcum, w.states); }
+    { ProfScope ps(KID_GEN_SCAN, a.stream); hipLaunchKernelGGL((k_scan<false>), sgrid, block, 0, a.stream, d, w.bcum, w.states, a.m0,
+                       static_cast<float*>(nullptr)); }
+    { ProfScope ps(KID_GEN_DSTATE, a.stream); hipLaunchKernelGGL((k_local_state<TIO, 1>), grid, block, 0, a.stream, d, q, d_o, w.bcum, w.dstates); }
+    { ProfScope ps(KID_GEN_RSCAN, a.stream); hipLaunchKernelGGL((k_scan<true>), sgrid, block, 0, a.stream, d, w.bcum, w.dstates, a.d_mT, a.d_m0); }
     const bool want_dg = a.dg != nullptr;
-    hipLaunchKernelGGL((k_grad<TIO>), grid, block, lds, a.stream, d, q, k, v, d_o, w.bcum, w.states, w.dstates,
+    { ProfScope ps(KID_GEN_GRAD, a.stream); hipLaunchKernelGGL((k_grad<TIO>), grid, block, lds, a.stream, d, q, k, v, d_o, w.bcum, w.states, w.dstates,
                        static_cast<TIO*>(a.dq), static_cast<TIO*>(a.dk), static_cast<TIO*>(a.dv),
                        (want_dg && d.kind != 1) ? a.dg : static_cast<float*>(nullptr), w.wq, w.wk,
-                       (want_dg && d.kind == 1) ? w.dg_tok : static_cast<float*>(nullptr));
-    if (want_dg && d.kind == 1)
+                       (want_dg && d.kind == 1) ? w.dg_tok : static_cast<float*>(nullptr)); }
+    if (want_dg && d.kind == 1) {
+        ProfScope ps(KID_HEAD_REDUCE, a.stream);
         hipLaunchKernelGGL(k_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dg_tok, a.dg);
+    }
     return hipGetLastError();
 }
 

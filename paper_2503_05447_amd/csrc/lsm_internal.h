@@ -39,6 +39,20 @@ struct BwdArgs {
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Kernel identifiers reported by the optional per-kernel timing (lsm_profile_start / _stop).
+enum KernelId {
+    KID_GEN_CUMSUM = 0, KID_GEN_STATE, KID_GEN_SCAN, KID_GEN_OUTPUT, KID_GEN_DSTATE, KID_GEN_RSCAN, KID_GEN_GRAD,
+    KID_HEAD_REDUCE, KID_MFMA_STATE, KID_MFMA_OUTPUT, KID_MFMA_STATE_BWD, KID_MFMA_DSTATE, KID_MFMA_GRAD, KID_COUNT
+};
+// Bracket a kernel launch with events when timing is switched on (no-ops otherwise).
+void prof_begin(int kernel_id, hipStream_t stream);
+void prof_end(hipStream_t stream);
+struct ProfScope {
+    hipStream_t s;
+    ProfScope(int id, hipStream_t stream) : s(stream) { prof_begin(id, stream); }
+    ~ProfScope() { prof_end(s); }
+};
+
 // Generic family: fp32 arithmetic on plain ALU, every supported shape, both element types.
 size_t generic_fwd_workspace(const Dims& d);
 size_t generic_bwd_workspace(const Dims& d);

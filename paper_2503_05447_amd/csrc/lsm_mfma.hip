@@ -168,6 +168,9 @@ __device__ __forceinline__ void cumulative_decay(const Dims& d, const float* g, 
 // decayed operand is split into a bf16 head and a bf16 remainder (two MFMAs) so that the rounding of
 // k * w does not show in a state that one token dominates.
 // edge_in = M_0 (or d M_T), edge_out = M_T (or d M_0), fp32 [i][v], either may be NULL.
+// states_rem (may be NULL) receives the bf16 remainder S - bf16(S) in the same layout: the decay
+// gradient contracts q_u S d_o_u^T into one scalar per token, where the 2^-9 rounding of a state that
+// a single token dominates is visible.
 struct StateFrags {
     u32x4 a[4], b[4];  // [2*tb + s]: 8 features of token 32*tb + lane%32, A side and B side
     float g;
@@ -201,6 +204,7 @@ template <int MODE>
 __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t* __restrict__ xa,
                                                          const uint16_t* __restrict__ xb,
                                                          const float* __restrict__ g, uint16_t* __restrict__ states,
+                                                         uint16_t* __restrict__ states_rem,
                                                          const float* __restrict__ edge_in,
                                                          float* __restrict__ edge_out) {
     __shared__ __align__(16) float wts[4][C];
@@ -232,6 +236,11 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
         _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
             u32x2 v = {pack2(acc[4 * gg], acc[4 * gg + 1]), pack2(acc[4 * gg + 2], acc[4 * gg + 3])};
             *reinterpret_cast<u32x2*>(dst + 8 * gg) = v;
+            if (states_rem) {  // bf16 remainder of the same elements, for the consumer that needs ~16 bits
+                u32x2 r = {pack2(acc[4 * gg] - bf16_lo(v.x), acc[4 * gg + 1] - bf16_hi(v.x)),
+                           pack2(acc[4 * gg + 2] - bf16_lo(v.y), acc[4 * gg + 3] - bf16_hi(v.y))};
+                *reinterpret_cast<u32x2*>(states_rem + (dst - states) + 8 * gg) = r;
+            }
         }
 
         // chunk-local cumulative log-decay across the wave, per-token weight of the decayed operand
@@ -366,7 +375,11 @@ __global__ __launch_bounds__(kThreads) void mk_output(Dims d, const uint16_t* __
         const float w = __expf(bs[32 * jb + n]);
         _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[r] *= w;
         const int kmax = jb == 0 ? 2 : 4;  // keys r >= 32 never reach queries j < 32
-        _Pragma("unroll") for (int ks = 0; ks < kmax; ++ks) acc = mfma(vt[ks], frag_perm(P, LDP, 32 * jb + n, 16 * ks, half), acc);
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)
+            if (ks < kmax) {
+                acc = mfma(vt[ks], frag_perm(P, LDP, 32 * jb + n, 16 * ks, half), acc);
+                acc = mfma(vt[ks], frag_perm(Pr, LDP, 32 * jb + n, 16 * ks, half), acc);
+            }
         store_block_t(stage, LD, 32 * jb + n, 32 * wave, half, acc);
     }
     __syncthreads();
@@ -391,6 +404,7 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
                                                     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                     const uint16_t* __restrict__ d_o, const float* __restrict__ g,
                                                     const uint16_t* __restrict__ states,
+                                                    const uint16_t* __restrict__ states_rem,
                                                     const uint16_t* __restrict__ dstates,
                                                     uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
                                                     uint16_t* __restrict__ dv, float* __restrict__ dg_tok) {
@@ -415,10 +429,14 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
     const uint16_t* dS = dstates + (size_t(bh) * d.N + c) * D * D;
 
     // rows i in [32w, 32w+32) of S and dS: A operands [m = i][k = v]
-    bf16x8 sfrag[8], dsfrag[8];
+    bf16x8 sfrag[8], dsfrag[8], srfrag[8];
+    const bool want_dg = dg_tok != nullptr;  // then states_rem is present
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
         sfrag[ks] = *reinterpret_cast<const bf16x8*>(S + (32 * wave + n) * D + 16 * ks + 8 * half);
         dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + (32 * wave + n) * D + 16 * ks + 8 * half);
+        if (want_dg)
+            srfrag[ks] = *reinterpret_cast<const bf16x8*>(states_rem + (S - states) + (32 * wave + n) * D + 16 * ks +
+                                                          8 * half);
     }
     load_tile(Q, q, tok0, L, tid);
     load_tile(K, k, tok0, L, tid);
@@ -433,7 +451,9 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
         float z = 0.f;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
             u32x4 a = __builtin_bit_cast(u32x4, sfrag[ks]), b = __builtin_bit_cast(u32x4, dsfrag[ks]);
-            _Pragma("unroll") for (int p = 0; p < 4; ++p) z += bf16_lo(a[p]) * bf16_lo(b[p]) + bf16_hi(a[p]) * bf16_hi(b[p]);
+            u32x4 ar = __builtin_bit_cast(u32x4, srfrag[ks]);
+            _Pragma("unroll") for (int p = 0; p < 4; ++p)
+                z += (bf16_lo(a[p]) + bf16_lo(ar[p])) * bf16_lo(b[p]) + (bf16_hi(a[p]) + bf16_hi(ar[p])) * bf16_hi(b[p]);
         }
         for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
         if (lane == 0) zred[wave] = z;
@@ -464,7 +484,6 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
     make_identity(lane, i0, i1);
     __syncthreads();
 
-    const bool want_dg = dg_tok != nullptr;
     f32x16 accq[2], acck[2];
     // ---- dq^T[i][j] and dk^T[i][r] for i in this wave's slice
     {
@@ -479,9 +498,11 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
         }
         _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
             const int tok = 32 * nb + n;  // j for dq, r for dk
-            f32x16 aq = {0}, ak = {0};
+            f32x16 aq = {0}, ak = {0}, aqr = {0};  // aqr: remainder of S, enters the decay gradient only
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                aq = mfma(sfrag[ks], frag(dO, LD, tok, 16 * ks + 8 * half), aq);
+                const bf16x8 dof = frag(dO, LD, tok, 16 * ks + 8 * half);
+                aq = mfma(sfrag[ks], dof, aq);
+                if (want_dg) aqr = mfma(srfrag[ks], dof, aqr);
                 ak = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak);
             }
             const float wq = __expf(bs[tok]), wk = __expf(bC - bs[tok]);
@@ -513,8 +534,8 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
                 _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
                     u32x2 qq = *reinterpret_cast<const u32x2*>(Q + tok * LD + 32 * wave + 8 * gg + 4 * half);
                     u32x2 kk = *reinterpret_cast<const u32x2*>(K + tok * LD + 32 * wave + 8 * gg + 4 * half);
-                    pq += bf16_lo(qq.x) * aq[4 * gg] + bf16_hi(qq.x) * aq[4 * gg + 1] + bf16_lo(qq.y) * aq[4 * gg + 2] +
-                          bf16_hi(qq.y) * aq[4 * gg + 3];
+                    pq += bf16_lo(qq.x) * (aq[4 * gg] + wq * aqr[4 * gg]) + bf16_hi(qq.x) * (aq[4 * gg + 1] + wq * aqr[4 * gg + 1]) +
+                          bf16_lo(qq.y) * (aq[4 * gg + 2] + wq * aqr[4 * gg + 2]) + bf16_hi(qq.y) * (aq[4 * gg + 3] + wq * aqr[4 * gg + 3]);
                     pk += bf16_lo(kk.x) * ak[4 * gg] + bf16_hi(kk.x) * ak[4 * gg + 1] + bf16_lo(kk.y) * ak[4 * gg + 2] +
                           bf16_hi(kk.y) * ak[4 * gg + 3];
                 }
@@ -606,7 +627,7 @@ __global__ void mk_head_reduce(Dims d, const float* __restrict__ dg_tok, float* 
 }
 
 struct Ws {
-    uint16_t *states, *dstates;
+    uint16_t *states, *dstates, *states_rem;
     float* dg_tok;
     size_t bytes;
 };
@@ -618,6 +639,7 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
     const size_t st = align256(size_t(d.BH()) * d.N * D * D * 2);
     w.states = reinterpret_cast<uint16_t*>(p + off); off += st;
     if (bwd) { w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st; }
+    if (bwd && d.kind != 0) { w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += st; }
     if (bwd && d.kind == 1) { w.dg_tok = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.T * 4); }
     w.bytes = off;
     return w;
@@ -643,9 +665,10 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     hipError_t e;
     if ((e = allow_lds(mk_output, kOutLds)) != hipSuccess) return e;
-    hipLaunchKernelGGL((mk_state_seq<0>), sgrid, block, 0, a.stream, d, k, v, a.g, w.states, a.m0, a.mT);
-    hipLaunchKernelGGL(mk_output, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
-                       static_cast<uint16_t*>(a.o));
+    { ProfScope ps(KID_MFMA_STATE, a.stream); hipLaunchKernelGGL((mk_state_seq<0>), sgrid, block, 0, a.stream, d, k, v, a.g, w.states,
+                       static_cast<uint16_t*>(nullptr), a.m0, a.mT); }
+    { ProfScope ps(KID_MFMA_OUTPUT, a.stream); hipLaunchKernelGGL(mk_output, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
+                       static_cast<uint16_t*>(a.o)); }
     return hipGetLastError();
 }
 
@@ -656,14 +679,18 @@ hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     auto d_o = static_cast<const uint16_t*>(a.d_o);
     hipError_t e;
     if ((e = allow_lds(mk_grad, kGradLds)) != hipSuccess) return e;
-    hipLaunchKernelGGL((mk_state_seq<1>), sgrid, block, 0, a.stream, d, v, k, a.g, w.states, a.m0,
-                       static_cast<float*>(nullptr));
-    hipLaunchKernelGGL((mk_state_seq<2>), sgrid, block, 0, a.stream, d, d_o, q, a.g, w.dstates, a.d_mT, a.d_m0);
+    { ProfScope ps(KID_MFMA_STATE_BWD, a.stream); hipLaunchKernelGGL((mk_state_seq<1>), sgrid, block, 0, a.stream, d, v, k, a.g, w.states,
+                       a.dg ? w.states_rem : static_cast<uint16_t*>(nullptr), a.m0, static_cast<float*>(nullptr)); }
+    { ProfScope ps(KID_MFMA_DSTATE, a.stream); hipLaunchKernelGGL((mk_state_seq<2>), sgrid, block, 0, a.stream, d, d_o, q, a.g, w.dstates,
+                       static_cast<uint16_t*>(nullptr), a.d_mT, a.d_m0); }
     float* dg_tok = nullptr;
     if (a.dg) dg_tok = d.kind == 1 ? w.dg_tok : a.dg;  // per-token scalar decay: written in place
-    hipLaunchKernelGGL(mk_grad, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.dstates,
-                       static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv), dg_tok);
-    if (a.dg && d.kind == 1) hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dg_tok, a.dg);
+    { ProfScope ps(KID_MFMA_GRAD, a.stream); hipLaunchKernelGGL(mk_grad, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem, w.dstates,
+                       static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv), dg_tok); }
+    if (a.dg && d.kind == 1) {
+        ProfScope ps(KID_HEAD_REDUCE, a.stream);
+        hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dg_tok, a.dg);
+    }
     return hipGetLastError();
 }
 
