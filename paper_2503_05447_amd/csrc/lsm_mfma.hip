@@ -171,6 +171,7 @@ __device__ __forceinline__ void cumulative_decay(const Dims& d, const float* g, 
 // states_rem (may be NULL) receives the bf16 remainder S - bf16(S) in the same layout: the decay
 // gradient contracts q_u S d_o_u^T into one scalar per token, where the 2^-9 rounding of a state that
 // a single token dominates is visible.
+constexpr int kStatePrefetch = 2;
 struct StateFrags {
     u32x4 a[4], b[4];  // [2*tb + s]: 8 features of token 32*tb + lane%32, A side and B side
     float g;
@@ -224,12 +225,18 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
             acc[r] = MODE == 0 ? e[mm * D + nn] : e[nn * D + mm];
         }
     }
-    StateFrags cur, nxt;
+    // loads run kStatePrefetch chunks ahead of the arithmetic: one chunk of arithmetic is shorter than
+    // a trip to HBM, and each wave has nothing else to hide that latency with
+    StateFrags fr[kStatePrefetch];
     const int first = MODE == 2 ? d.N - 1 : 0, step = MODE == 2 ? -1 : 1;
-    state_load<MODE>(d, xa, xb, g, bh, first, 32 * mb, 32 * nb, lane, cur);
-    for (int it = 0; it < d.N; ++it) {
+    _Pragma("unroll") for (int j = 0; j < kStatePrefetch; ++j)
+        if (j < d.N) state_load<MODE>(d, xa, xb, g, bh, first + step * j, 32 * mb, 32 * nb, lane, fr[j]);
+    for (int it0 = 0; it0 < d.N; it0 += kStatePrefetch) {
+      _Pragma("unroll") for (int j = 0; j < kStatePrefetch; ++j) {
+        const int it = it0 + j;
+        if (it >= d.N) break;
         const int c = first + step * it;
-        if (it + 1 < d.N) state_load<MODE>(d, xa, xb, g, bh, c + step, 32 * mb, 32 * nb, lane, nxt);
+        StateFrags& cur = fr[j];
 
         // emit the state this chunk starts from (MODE 2: the gradient this chunk ends with)
         uint16_t* dst = states + (size_t(bh) * d.N + c) * sz + (32 * nb + n) * D + 32 * mb + 4 * half;
@@ -291,7 +298,9 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
             acc = mfma(A[ks], B[ks], acc);
             if (decays) acc = kDecayA ? mfma(R[ks], B[ks], acc) : mfma(A[ks], R[ks], acc);
         }
-        cur = nxt;
+        if (it + kStatePrefetch < d.N)
+            state_load<MODE>(d, xa, xb, g, bh, c + step * kStatePrefetch, 32 * mb, 32 * nb, lane, cur);
+      }
     }
     if (edge_out) {
         float* e = edge_out + size_t(bh) * sz;
