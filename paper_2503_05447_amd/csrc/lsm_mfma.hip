@@ -61,6 +61,22 @@ __device__ __forceinline__ bf16x8 frag_perm(const uint16_t* tile, int ld, int ro
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// Token-major operand straight out of a row-major [token][feature] LDS tile with the LDS transpose
+// read: lane l receives feature col0 + l%32 of tokens row0 + 8*(l/32) + 0..7 (natural k order).
+// Each group of 16 lanes reads a 4-token x 16-feature patch as 8-byte pieces (lane r of the group:
+// token r/4, features 4*(r%4)..+3) and the hardware hands lane i of the group feature i, 4 tokens.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 frag_tr(const uint16_t* tile, int ld, int row0, int col0, int lane) {
+    const int r = lane & 15, nblk = (lane >> 4) & 1, half = lane >> 5;
+    const uint16_t* p = tile + (row0 + 8 * half + (r >> 2)) * ld + col0 + 16 * nblk + 4 * (r & 3);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ld));
+    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    u32x4 v = {l2.x, l2.y, h2.x, h2.y};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
 // B operand of the identity for the two k-steps of a 32-wide feature block
 __device__ __forceinline__ void make_identity(int lane, bf16x8& i0, bf16x8& i1) {
     const int n = lane & 31, half = lane >> 5;
@@ -154,6 +170,27 @@ __device__ __forceinline__ void cumulative_decay(const Dims& d, const float* g, 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Decay preparation for the state passes: per chunk c of (b,h), padded to 64 tokens,
+//   wdec[t] = e^{b_C - b_t} ,  winc[t] = e^{b_t} ,  lam[c] = e^{b_C}
+// (grid: N x BH, one wave).  Keeps the wave scan and the exponentials out of the sequential loop.
+__global__ __launch_bounds__(64) void mk_decay_prep(Dims d, const float* __restrict__ g, float* __restrict__ wdec,
+                                                    float* __restrict__ winc, float* __restrict__ lam) {
+    const int c = blockIdx.x, bh = blockIdx.y, lane = threadIdx.x;
+    const int t0 = c * C, L = min(C, d.T - t0);
+    float x = 0.f;
+    if (lane < L) x = d.kind == 1 ? g[bh % d.H] : g[size_t(bh) * d.T + t0 + lane];
+    for (int off = 1; off < 64; off <<= 1) {
+        const float y = __shfl_up(x, off, 64);
+        if (lane >= off) x += y;
+    }
+    const float bC = __shfl(x, 63, 64);
+    const size_t base = (size_t(bh) * d.N + c) * C;
+    wdec[base + lane] = __expf(bC - x);
+    winc[base + lane] = __expf(x);
+    if (lane == 0) lam[size_t(bh) * d.N + c] = __expf(bC);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Chunk states and the scan over chunks, fused: one wave owns a 32 x 32 block of the d_k x d_v
 // state in MFMA accumulators (fp32) and walks the chunks of its sequence in order,
 //     S_{c+1} = e^{b_C} S_c + sum_r (k_r e^{b_C - b_r})^T v_r ,
@@ -166,55 +203,110 @@ __device__ __forceinline__ void cumulative_decay(const Dims& d, const float* g, 
 //           (A side = d_o, B side = q decayed)
 // Both operands of the token contraction come from identity turns, so their k order agrees.  The
 // decayed operand is split into a bf16 head and a bf16 remainder (two MFMAs) so that the rounding of
-// k * w does not show in a state that one token dominates.
+// k * w does not show in a state that one token dominates.  DEC = false (no decay) skips all of it.
+// The loop is software-pipelined: the operands of chunk c+1 are turned, weighted and packed while
+// the accumulation of chunk c is in the matrix pipe; loads run kStatePrefetch chunks ahead.
 // edge_in = M_0 (or d M_T), edge_out = M_T (or d M_0), fp32 [i][v], either may be NULL.
 // states_rem (may be NULL) receives the bf16 remainder S - bf16(S) in the same layout: the decay
 // gradient contracts q_u S d_o_u^T into one scalar per token, where the 2^-9 rounding of a state that
 // a single token dominates is visible.
-constexpr int kStatePrefetch = 2;
-struct StateFrags {
-    u32x4 a[4], b[4];  // [2*tb + s]: 8 features of token 32*tb + lane%32, A side and B side
-    float g;
+constexpr int LDB = 40;  // row stride (elements) of a 64 x 32 B-side slice in LDS
+// LDS: 2 x (A tile 64 x LD | B slice head 64 x LDB | B slice remainder 64 x LDB) for chunks k+1, k+2
+//      | 2 x (stage head | stage remainder), 32 x LD each
+constexpr int kStateTile = C * LD + 2 * C * LDB;
+constexpr int kStateLds = (2 * kStateTile + 4 * 32 * LD) * 2;
+
+struct StateRegs {  // one thread's share of a chunk on its way from global memory to LDS
+    u32x4 a[4], b;
+    float w;        // weight of the B-slice row this thread carries
+    float lam;
 };
 
-template <int MODE>
-__device__ __forceinline__ void state_load(const Dims& d, const uint16_t* xa, const uint16_t* xb, const float* g,
-                                           int bh, int c, int fa0, int fb0, int lane, StateFrags& f) {
-    const int t0 = c * C, L = min(C, d.T - t0), m = lane & 31, half = lane >> 5;
+// coalesced: the A side as whole 256-byte rows (16 lanes per row), the B side as 64-byte row slices.
+// Branch-free (rows beyond the ragged end are read from the last valid row and zeroed afterwards) so
+// that the compiler can count outstanding loads exactly and need not drain the queue.
+template <bool DEC>
+__device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, const uint16_t* xb, const float* wts,
+                                            const float* lam, int bh, int c, int fb0, int tid, StateRegs& r) {
+    const int t0 = c * C, L = min(C, d.T - t0);
     const size_t tok0 = size_t(bh) * d.T + t0;
-    _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
-        const int tok = 32 * tb + m;
-        _Pragma("unroll") for (int s = 0; s < 2; ++s) {
-            u32x4 va = {0, 0, 0, 0}, vb = {0, 0, 0, 0};
-            if (tok < L) {
-                va = *reinterpret_cast<const u32x4*>(xa + (tok0 + tok) * D + fa0 + 16 * s + 8 * half);
-                vb = *reinterpret_cast<const u32x4*>(xb + (tok0 + tok) * D + fb0 + 16 * s + 8 * half);
-            }
-            f.a[2 * tb + s] = va;
-            f.b[2 * tb + s] = vb;
-        }
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        u32x4 v = *reinterpret_cast<const u32x4*>(xa + (tok0 + min(row, L - 1)) * D + cp * 8);
+        const uint32_t keep = row < L ? 0xffffffffu : 0u;
+        r.a[it] = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
     }
-    f.g = 0.f;
-    if (lane < L) {
-        if (d.kind == 1) f.g = g[bh % d.H];
-        else if (d.kind == 2) f.g = g[tok0 + lane];
+    const int row = tid >> 2, cp = tid & 3;
+    u32x4 v = *reinterpret_cast<const u32x4*>(xb + (tok0 + min(row, L - 1)) * D + fb0 + cp * 8);
+    const uint32_t keep = row < L ? 0xffffffffu : 0u;
+    r.b = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
+    if (DEC) {
+        r.w = wts[(size_t(bh) * d.N + c) * C + row];
+        r.lam = lam[size_t(bh) * d.N + c];
+    }
+}
+// The B slice carries the decay: each row is multiplied by its token's weight in fp32 and stored as a
+// bf16 head plus a bf16 remainder, once per workgroup.
+template <bool DEC>
+__device__ __forceinline__ void state_to_lds(const StateRegs& r, uint16_t* bufA, uint16_t* bufB, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        *reinterpret_cast<u32x4*>(bufA + row * LD + cp * 8) = r.a[it];
+    }
+    uint16_t* dst = bufB + (tid >> 2) * LDB + (tid & 3) * 8;
+    if (DEC) {
+        u32x4 hi, lo;
+        _Pragma("unroll") for (int p = 0; p < 4; ++p) {
+            const float x0 = bf16_lo(r.b[p]) * r.w, x1 = bf16_hi(r.b[p]) * r.w;
+            const uint32_t h = pack2(x0, x1);
+            hi[p] = h;
+            lo[p] = pack2(x0 - bf16_lo(h), x1 - bf16_hi(h));
+        }
+        *reinterpret_cast<u32x4*>(dst) = hi;
+        *reinterpret_cast<u32x4*>(dst + C * LDB) = lo;
+    } else {
+        *reinterpret_cast<u32x4*>(dst) = r.b;
     }
 }
 
-template <int MODE>
+// 32 x 128 staged state rows -> their contiguous 8 KiB in global memory
+__device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        *reinterpret_cast<u32x4*>(dst + row * D + cp * 8) = *reinterpret_cast<const u32x4*>(stage + row * LD + cp * 8);
+    }
+}
+
+template <int MODE, bool DEC>
 __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t* __restrict__ xa,
                                                          const uint16_t* __restrict__ xb,
-                                                         const float* __restrict__ g, uint16_t* __restrict__ states,
+                                                         const float* __restrict__ wts,
+                                                         const float* __restrict__ lam,
+                                                         uint16_t* __restrict__ states,
                                                          uint16_t* __restrict__ states_rem,
                                                          const float* __restrict__ edge_in,
                                                          float* __restrict__ edge_out) {
-    __shared__ __align__(16) float wts[4][C];
-    const int nb = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, mb = tid >> 6;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);         // [2][kStateTile]
+    uint16_t* stage = tiles + 2 * kStateTile;                    // [2][2][32 * LD]: parity, head / remainder
+    // The four workgroups of a (b,h) pair read the same A-side rows.  Workgroups are dealt to the 8
+    // XCDs round-robin by linear id, so the id is decoded such that those four share an XCD (and
+    // its L2): id = xcd + 8 * (4 * (bh / 8) + nb), bh = xcd + 8 * (bh / 8).
+    int nb, bh;
+    {
+        const int id = blockIdx.x, nwg = gridDim.x, full = (nwg / 32) * 32;  // 32 = 8 XCDs x 4 blocks
+        if (id < full) {
+            const int xcd = id & 7, slot = id >> 3;
+            nb = slot & 3;
+            bh = xcd + 8 * (slot >> 2);
+        } else {  // tail when B*H is not a multiple of 8
+            nb = (id - full) & 3;
+            bh = (full >> 2) + ((id - full) >> 2);
+        }
+    }
+    const int tid = threadIdx.x, lane = tid & 63, mb = tid >> 6;
     const int n = lane & 31, half = lane >> 5;
-    constexpr bool kDecayA = MODE == 0;
     constexpr int sz = D * D;
-    bf16x8 i0, i1;
-    make_identity(lane, i0, i1);
 
     // acc[4g+j] = state element (m = 32mb + 8g + 4half + j, n = 32nb + lane%32); MODE 0: m = i, else m = v
     f32x16 acc = {0};
@@ -225,89 +317,59 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
             acc[r] = MODE == 0 ? e[mm * D + nn] : e[nn * D + mm];
         }
     }
-    // loads run kStatePrefetch chunks ahead of the arithmetic: one chunk of arithmetic is shorter than
-    // a trip to HBM, and each wave has nothing else to hide that latency with
-    StateFrags fr[kStatePrefetch];
     const int first = MODE == 2 ? d.N - 1 : 0, step = MODE == 2 ? -1 : 1;
-    _Pragma("unroll") for (int j = 0; j < kStatePrefetch; ++j)
-        if (j < d.N) state_load<MODE>(d, xa, xb, g, bh, first + step * j, 32 * mb, 32 * nb, lane, fr[j]);
-    for (int it0 = 0; it0 < d.N; it0 += kStatePrefetch) {
-      _Pragma("unroll") for (int j = 0; j < kStatePrefetch; ++j) {
-        const int it = it0 + j;
-        if (it >= d.N) break;
-        const int c = first + step * it;
-        StateFrags& cur = fr[j];
+    auto bufA = [&](int k) { return tiles + (k & 1) * kStateTile; };
+    auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
+    auto slot = [&](int k) { return (size_t(bh) * d.N + (first + step * k)) * sz + size_t(32 * nb) * D; };
 
-        // emit the state this chunk starts from (MODE 2: the gradient this chunk ends with)
-        uint16_t* dst = states + (size_t(bh) * d.N + c) * sz + (32 * nb + n) * D + 32 * mb + 4 * half;
-        _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
-            u32x2 v = {pack2(acc[4 * gg], acc[4 * gg + 1]), pack2(acc[4 * gg + 2], acc[4 * gg + 3])};
-            *reinterpret_cast<u32x2*>(dst + 8 * gg) = v;
-            if (states_rem) {  // bf16 remainder of the same elements, for the consumer that needs ~16 bits
-                u32x2 r = {pack2(acc[4 * gg] - bf16_lo(v.x), acc[4 * gg + 1] - bf16_hi(v.x)),
-                           pack2(acc[4 * gg + 2] - bf16_lo(v.y), acc[4 * gg + 3] - bf16_hi(v.y))};
-                *reinterpret_cast<u32x2*>(states_rem + (dst - states) + 8 * gg) = r;
-            }
-        }
-
-        // chunk-local cumulative log-decay across the wave, per-token weight of the decayed operand
-        float b = cur.g;
-        for (int off = 1; off < 64; off <<= 1) {
-            const float y = __shfl_up(b, off, 64);
-            if (lane >= off) b += y;
-        }
-        const float bC = __shfl(b, 63, 64);
-        const bool decays = d.kind != 0;
-        if (decays) {
-            __builtin_amdgcn_wave_barrier();
-            wts[mb][lane] = MODE == 2 ? __expf(b) : __expf(bC - b);
-            __builtin_amdgcn_wave_barrier();
-        }
-        bf16x8 A[4], B[4], R[4];  // R: remainder of the decayed side
-        _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
-            f32x16 ta = {0}, tbk = {0};
-            ta = mfma(__builtin_bit_cast(bf16x8, cur.a[2 * tb]), i0, ta);
-            ta = mfma(__builtin_bit_cast(bf16x8, cur.a[2 * tb + 1]), i1, ta);
-            tbk = mfma(__builtin_bit_cast(bf16x8, cur.b[2 * tb]), i0, tbk);
-            tbk = mfma(__builtin_bit_cast(bf16x8, cur.b[2 * tb + 1]), i1, tbk);
-            if (decays) {
-                f32x16& t = kDecayA ? ta : tbk;
-                f32x16 rem;
-                _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
-                    const float4 w = *reinterpret_cast<const float4*>(&wts[mb][32 * tb + 8 * gg + 4 * half]);
-                    t[4 * gg + 0] *= w.x; t[4 * gg + 1] *= w.y; t[4 * gg + 2] *= w.z; t[4 * gg + 3] *= w.w;
-                }
-                _Pragma("unroll") for (int r = 0; r < 16; r += 2) {
-                    const uint32_t h = pack2(t[r], t[r + 1]);
-                    rem[r] = t[r] - bf16_lo(h);
-                    rem[r + 1] = t[r + 1] - bf16_hi(h);
-                }
-                R[2 * tb] = pack_step(rem, 0);
-                R[2 * tb + 1] = pack_step(rem, 1);
-            }
-            A[2 * tb] = pack_step(ta, 0);
-            A[2 * tb + 1] = pack_step(ta, 1);
-            B[2 * tb] = pack_step(tbk, 0);
-            B[2 * tb + 1] = pack_step(tbk, 1);
-        }
-        if (decays) {
-            const float lamc = __expf(bC);
-            _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[r] *= lamc;
-        }
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
-            acc = mfma(A[ks], B[ks], acc);
-            if (decays) acc = kDecayA ? mfma(R[ks], B[ks], acc) : mfma(A[ks], R[ks], acc);
-        }
-        if (it + kStatePrefetch < d.N)
-            state_load<MODE>(d, xa, xb, g, bh, c + step * kStatePrefetch, 32 * mb, 32 * nb, lane, cur);
-      }
+    // prologue: chunks 0 and 1 -> LDS, chunk 2 in flight.  Global loads are issued two iterations
+    // before their data is written to LDS: one iteration is shorter than a trip to HBM.
+    StateRegs r0, r1;
+    float lam_cur = 1.f, lam_nxt = 1.f;
+    state_gload<DEC>(d, xa, xb, wts, lam, bh, first, 32 * nb, tid, r0);
+    if (d.N > 1) state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step, 32 * nb, tid, r1);
+    state_to_lds<DEC>(r0, bufA(0), bufB(0), tid);
+    lam_cur = r0.lam;
+    if (d.N > 1) {
+        state_to_lds<DEC>(r1, bufA(1), bufB(1), tid);
+        lam_nxt = r1.lam;
     }
+    state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(2, d.N - 1), 32 * nb, tid, r0);
+    __syncthreads();
+
+    // One chunk, straight-line code: r0 holds chunk k+2 (loaded earlier, written to LDS at the end), r1
+    // receives chunk k+3; chunk indices past the end are clamped (the data lands in a buffer nobody reads).
+    for (int k = 0; k < d.N; ++k) {
+        state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(k + 3, d.N - 1), 32 * nb, tid, r1);
+        // stage the state this chunk starts from (MODE 2: the gradient this chunk ends with)
+        uint16_t* sh = stage + (k & 1) * 2 * 32 * LD;
+        if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
+        else store_block_t(sh, LD, n, 32 * mb, half, acc);
+        if (DEC) {
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[x] *= lam_cur;
+        }
+        // acc[m][n] += sum_t A[t][32mb + m] * Bw[t][n]: both operands read token-major out of LDS
+        const uint16_t *ta = bufA(k), *tb = bufB(k);
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 fa = frag_tr(ta, LD, 16 * ks, 32 * mb, lane);
+            acc = mfma(fa, frag_tr(tb, LDB, 16 * ks, 0, lane), acc);
+            if (DEC) acc = mfma(fa, frag_tr(tb + C * LDB, LDB, 16 * ks, 0, lane), acc);
+        }
+        __syncthreads();  // every wave is done with the tiles of chunk k; the staged state is complete
+        state_to_lds<DEC>(r0, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
+        state_store(states + slot(k), sh, tid);        // contiguous rows
+        if (states_rem) state_store(states_rem + slot(k), sh + 32 * LD, tid);
+        lam_cur = lam_nxt;
+        lam_nxt = r0.lam;
+        r0 = r1;
+    }
+    __syncthreads();
     if (edge_out) {
         float* e = edge_out + size_t(bh) * sz;
-        _Pragma("unroll") for (int r = 0; r < 16; ++r) {
-            const int mm = 32 * mb + 8 * (r >> 2) + 4 * half + (r & 3), nn = 32 * nb + n;
-            if (MODE == 0) e[mm * D + nn] = acc[r];
-            else e[nn * D + mm] = acc[r];
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+            const int mm = 32 * mb + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * nb + n;
+            if (MODE == 0) e[mm * D + nn] = acc[x];
+            else e[nn * D + mm] = acc[x];
         }
     }
 }
@@ -637,7 +699,7 @@ __global__ void mk_head_reduce(Dims d, const float* __restrict__ dg_tok, float* 
 
 struct Ws {
     uint16_t *states, *dstates, *states_rem;
-    float* dg_tok;
+    float *dg_tok, *wdec, *winc, *lam;
     size_t bytes;
 };
 
@@ -649,6 +711,11 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
     w.states = reinterpret_cast<uint16_t*>(p + off); off += st;
     if (bwd) { w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st; }
     if (bwd && d.kind != 0) { w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += st; }
+    if (d.kind != 0) {
+        w.wdec = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * C * 4);
+        w.winc = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * C * 4);
+        w.lam = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * 4);
+    }
     if (bwd && d.kind == 1) { w.dg_tok = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.T * 4); }
     w.bytes = off;
     return w;
@@ -668,34 +735,69 @@ bool mfma_supported(const Dims& d) {
 size_t mfma_fwd_workspace(const Dims& d) { return carve(d, nullptr, false).bytes; }
 size_t mfma_bwd_workspace(const Dims& d) { return carve(d, nullptr, true).bytes; }
 
+namespace {
+template <int MODE>
+void launch_state(const Dims& d, hipStream_t st, const uint16_t* xa, const uint16_t* xb, const float* wts,
+                  const float* lam, uint16_t* states, uint16_t* rem, const float* ein, float* eout) {
+    const dim3 sgrid(D / 32 * d.BH()), block(kThreads);
+    if (d.kind == 0) {
+        if (allow_lds(mk_state_seq<MODE, false>, kStateLds) != hipSuccess) return;
+        hipLaunchKernelGGL((mk_state_seq<MODE, false>), sgrid, block, kStateLds, st, d, xa, xb, wts, lam, states, rem, ein, eout);
+    } else {
+        if (allow_lds(mk_state_seq<MODE, true>, kStateLds) != hipSuccess) return;
+        hipLaunchKernelGGL((mk_state_seq<MODE, true>), sgrid, block, kStateLds, st, d, xa, xb, wts, lam, states, rem, ein, eout);
+    }
+}
+void launch_prep(const Dims& d, hipStream_t st, const float* g, const Ws& w) {
+    if (d.kind == 0) return;
+    ProfScope ps(KID_MFMA_PREP, st);
+    hipLaunchKernelGGL(mk_decay_prep, dim3(d.N, d.BH()), dim3(64), 0, st, d, g, w.wdec, w.winc, w.lam);
+}
+}  // namespace
+
 hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     Ws w = carve(d, a.ws, false);
-    const dim3 grid(d.N, d.BH()), block(kThreads), sgrid(D / 32, d.BH());
+    const dim3 grid(d.N, d.BH()), block(kThreads);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     hipError_t e;
     if ((e = allow_lds(mk_output, kOutLds)) != hipSuccess) return e;
-    { ProfScope ps(KID_MFMA_STATE, a.stream); hipLaunchKernelGGL((mk_state_seq<0>), sgrid, block, 0, a.stream, d, k, v, a.g, w.states,
-                       static_cast<uint16_t*>(nullptr), a.m0, a.mT); }
-    { ProfScope ps(KID_MFMA_OUTPUT, a.stream); hipLaunchKernelGGL(mk_output, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
-                       static_cast<uint16_t*>(a.o)); }
+    launch_prep(d, a.stream, a.g, w);
+    {
+        ProfScope ps(KID_MFMA_STATE, a.stream);
+        launch_state<0>(d, a.stream, k, v, w.wdec, w.lam, w.states, nullptr, a.m0, a.mT);
+    }
+    {
+        ProfScope ps(KID_MFMA_OUTPUT, a.stream);
+        hipLaunchKernelGGL(mk_output, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
+                           static_cast<uint16_t*>(a.o));
+    }
     return hipGetLastError();
 }
 
 hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     Ws w = carve(d, a.ws, true);
-    const dim3 grid(d.N, d.BH()), block(kThreads), sgrid(D / 32, d.BH());
+    const dim3 grid(d.N, d.BH()), block(kThreads);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     auto d_o = static_cast<const uint16_t*>(a.d_o);
     hipError_t e;
     if ((e = allow_lds(mk_grad, kGradLds)) != hipSuccess) return e;
-    { ProfScope ps(KID_MFMA_STATE_BWD, a.stream); hipLaunchKernelGGL((mk_state_seq<1>), sgrid, block, 0, a.stream, d, v, k, a.g, w.states,
-                       a.dg ? w.states_rem : static_cast<uint16_t*>(nullptr), a.m0, static_cast<float*>(nullptr)); }
-    { ProfScope ps(KID_MFMA_DSTATE, a.stream); hipLaunchKernelGGL((mk_state_seq<2>), sgrid, block, 0, a.stream, d, d_o, q, a.g, w.dstates,
-                       static_cast<uint16_t*>(nullptr), a.d_mT, a.d_m0); }
+    launch_prep(d, a.stream, a.g, w);
+    {
+        ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
+        launch_state<1>(d, a.stream, v, k, w.wdec, w.lam, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr);
+    }
+    {
+        ProfScope ps(KID_MFMA_DSTATE, a.stream);
+        launch_state<2>(d, a.stream, d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0);
+    }
     float* dg_tok = nullptr;
     if (a.dg) dg_tok = d.kind == 1 ? w.dg_tok : a.dg;  // per-token scalar decay: written in place
-    { ProfScope ps(KID_MFMA_GRAD, a.stream); hipLaunchKernelGGL(mk_grad, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem, w.dstates,
-                       static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv), dg_tok); }
+    {
+        ProfScope ps(KID_MFMA_GRAD, a.stream);
+        hipLaunchKernelGGL(mk_grad, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem,
+                           w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
+                           static_cast<uint16_t*>(a.dv), dg_tok);
+    }
     if (a.dg && d.kind == 1) {
         ProfScope ps(KID_HEAD_REDUCE, a.stream);
         hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dg_tok, a.dg);
