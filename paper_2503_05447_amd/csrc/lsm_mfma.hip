@@ -465,31 +465,100 @@ __global__ __launch_bounds__(kThreads) void mk_output(Dims d, const uint16_t* __
 //   dk^T[i][r] = e^{b_C-b_r} sum_v dS[i][v] v_r[v]   + sum_j Q^T[i][j] G[j][r]
 //   dv^T[v][r] = e^{b_C-b_r} sum_i dS^T[v][i] k_r[i] + sum_j dO^T[v][j] As[j][r]
 //   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + sum_r k_r.dk_r^{inter} + e^{b_C} <S, dS>
-// Wave w owns i (and v) in [32w, 32w+32).
-// G, its transpose and As are each kept as a bf16 head plus a bf16 remainder (see mk_output).
-// LDS: Q | K | V | dO (64 x LD; later stages of dq, dk, dv) | G [j][r] | Gt [r][j] | Ast [r][j]
-//      (head and remainder, 64 x LDP each) | bs (64) | red (4 x 64 x 3 floats: per-wave partial row dots) | zred
-constexpr int kGradLds = (4 * C * LD + 6 * C * LDP) * 2 + C * 4 + 4 * 64 * 3 * 4 + 64;
+// Wave w owns i (and v) in [32w, 32w+32) and never exchanges data with the other waves before the
+// final staging: every 32 x 32 block of G, G^T and As it needs is computed by the wave itself and
+// consumed straight from its accumulator registers (as the B operand of the next MFMA, head and
+// remainder), the partner operand K^T / Q^T / dO^T coming from the LDS transpose read in the
+// matching k order.  That costs three times the score MFMAs but no LDS space, no LDS round trip and
+// no barrier, and lets two workgroups share a CU.
+// LDS: Q | K | V | dO (64 x LD; later stages of dq, dk, dv) | bs (64) | red (4 x 3 x 64 floats:
+//      per-wave partial row dots) | zred
+constexpr int kGradLds = 4 * C * LD * 2 + C * 4 + 4 * 64 * 3 * 4 + 64;
 
-__global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __restrict__ q,
-                                                    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                    const uint16_t* __restrict__ d_o, const float* __restrict__ g,
-                                                    const uint16_t* __restrict__ states,
-                                                    const uint16_t* __restrict__ states_rem,
-                                                    const uint16_t* __restrict__ dstates,
-                                                    uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
-                                                    uint16_t* __restrict__ dv, float* __restrict__ dg_tok) {
+// same as frag_tr, k in the permuted order of a D-layout operand: tokens row0 + 4*half + {0..3}
+// and row0 + 8 + 4*half + {0..3}
+__device__ __forceinline__ bf16x8 frag_tr_perm(const uint16_t* tile, int ld, int row0, int col0, int lane) {
+    const int r = lane & 15, nblk = (lane >> 4) & 1, half = lane >> 5;
+    const uint16_t* p = tile + (row0 + 4 * half + (r >> 2)) * ld + col0 + 16 * nblk + 4 * (r & 3);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * ld));
+    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    u32x4 v = {l2.x, l2.y, h2.x, h2.y};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// D[m][n] = sum_f Am[m0 + m][f] * Bm[n0 + n][f] over the 128 features of two row-major LDS tiles
+__device__ __forceinline__ f32x16 score_block(const uint16_t* Am, int m0, const uint16_t* Bm, int n0, int n, int half) {
+    f32x16 acc = {0};
+    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+        acc = mfma(frag(Am, LD, m0 + n, 16 * ks + 8 * half), frag(Bm, LD, n0 + n, 16 * ks + 8 * half), acc);
+    return acc;
+}
+
+// mask and decay of a score block in D layout; ROWS_R: rows index keys r and the lane's column a query j
+template <bool ROWS_R>
+__device__ __forceinline__ void decay_mask(f32x16& acc, int m0, int ncol, const float* bs, int half) {
+    const float bn = bs[ncol];
+    _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+        const int mi = m0 + 8 * (x >> 2) + 4 * half + (x & 3);
+        const int j = ROWS_R ? ncol : mi, r = ROWS_R ? mi : ncol;
+        const float e = ROWS_R ? bn - bs[mi] : bs[mi] - bn;
+        acc[x] = r <= j ? acc[x] * __expf(e) : 0.f;
+    }
+}
+
+// head and remainder operands (two k-steps each) of a D-layout block
+__device__ __forceinline__ void split_ops(const f32x16& d, bf16x8* hi, bf16x8* lo) {
+    f32x16 rem;
+    _Pragma("unroll") for (int x = 0; x < 16; x += 2) {
+        const uint32_t h = pack2(d[x], d[x + 1]);
+        rem[x] = d[x] - bf16_lo(h);
+        rem[x + 1] = d[x + 1] - bf16_hi(h);
+    }
+    hi[0] = pack_step(d, 0);
+    hi[1] = pack_step(d, 1);
+    lo[0] = pack_step(rem, 0);
+    lo[1] = pack_step(rem, 1);
+}
+
+struct PackedBlock { u32x2 v[4]; };  // a D-layout block rounded to bf16: v[g] = rows 8g + 4half + 0..3
+__device__ __forceinline__ PackedBlock pack_block(const f32x16& d) {
+    PackedBlock p;
+    _Pragma("unroll") for (int g = 0; g < 4; ++g)
+        p.v[g] = u32x2{pack2(d[4 * g + 0], d[4 * g + 1]), pack2(d[4 * g + 2], d[4 * g + 3])};
+    return p;
+}
+__device__ __forceinline__ void store_packed(uint16_t* dst, int ld, int nrow, int m0, int half, const PackedBlock& p) {
+    _Pragma("unroll") for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<u32x2*>(dst + nrow * ld + m0 + 8 * g + 4 * half) = p.v[g];
+}
+// sum over this lane's 16 features of x[tok][32w + ...] * acc[...]
+__device__ __forceinline__ float row_dot(const uint16_t* X, int tok, int wave, int half, const f32x16& a) {
+    float s = 0.f;
+    _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
+        const u32x2 x = *reinterpret_cast<const u32x2*>(X + tok * LD + 32 * wave + 8 * gg + 4 * half);
+        s += bf16_lo(x.x) * a[4 * gg] + bf16_hi(x.x) * a[4 * gg + 1] + bf16_lo(x.y) * a[4 * gg + 2] +
+             bf16_hi(x.y) * a[4 * gg + 3];
+    }
+    return s;
+}
+
+__global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* __restrict__ q,
+                                                       const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                       const uint16_t* __restrict__ d_o, const float* __restrict__ g,
+                                                       const uint16_t* __restrict__ states,
+                                                       const uint16_t* __restrict__ states_rem,
+                                                       const uint16_t* __restrict__ dstates,
+                                                       uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
+                                                       uint16_t* __restrict__ dv, float* __restrict__ dg_tok) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = Q + C * LD;
     uint16_t* V = K + C * LD;
     uint16_t* dO = V + C * LD;
-    constexpr int kRem = C * LDP;  // remainder tile follows its head
-    uint16_t* G = dO + C * LD;
-    uint16_t* Gt = G + 2 * C * LDP;
-    uint16_t* Ast = Gt + 2 * C * LDP;
-    float* bs = reinterpret_cast<float*>(Ast + 2 * C * LDP);
-    float* red = bs + C;          // [wave][3][64]: q.dq, k.dk, k.dk_inter partial sums over this wave's i
+    float* bs = reinterpret_cast<float*>(dO + C * LD);
+    float* red = bs + C;             // [wave][3][64]: q.dq, k.dk, k.dk_inter partial sums over this wave's i
     float* zred = red + 4 * 3 * 64;  // [wave]: partial <S, dS>
 
     const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -498,13 +567,12 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
     const int n = lane & 31, half = lane >> 5;
     const uint16_t* S = states + (size_t(bh) * d.N + c) * D * D;
     const uint16_t* dS = dstates + (size_t(bh) * d.N + c) * D * D;
-
-    // rows i in [32w, 32w+32) of S and dS: A operands [m = i][k = v]
-    bf16x8 sfrag[8], dsfrag[8], srfrag[8];
     const bool want_dg = dg_tok != nullptr;  // then states_rem is present
+
+    // rows i in [32w, 32w+32) of S (and its remainder): A operands [m = i][k = v]
+    bf16x8 sfrag[8], srfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
         sfrag[ks] = *reinterpret_cast<const bf16x8*>(S + (32 * wave + n) * D + 16 * ks + 8 * half);
-        dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + (32 * wave + n) * D + 16 * ks + 8 * half);
         if (want_dg)
             srfrag[ks] = *reinterpret_cast<const bf16x8*>(states_rem + (S - states) + (32 * wave + n) * D + 16 * ks +
                                                           8 * half);
@@ -517,8 +585,44 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
     __syncthreads();
     const float bC = bs[C - 1];
 
-    // <S, dS> over this wave's rows
-    if (dg_tok) {
+    PackedBlock resq[2], resk[2], resv[2];
+    // ---- dq^T[i][j], i in this wave's slice
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        const int tok = 32 * nb + n;  // j
+        f32x16 aq = {0}, aqr = {0};   // aqr: remainder of S, enters the decay gradient only
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 dof = frag(dO, LD, tok, 16 * ks + 8 * half);
+            aq = mfma(sfrag[ks], dof, aq);
+            if (want_dg) aqr = mfma(srfrag[ks], dof, aqr);
+        }
+        const float wq = __expf(bs[tok]);
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) aq[x] *= wq;
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)
+            if (rb <= nb) {
+                f32x16 G = score_block(V, 32 * rb, dO, 32 * nb, n, half);  // D[m = r][n = j] = v_r . d_o_j
+                decay_mask<true>(G, 32 * rb, tok, bs, half);
+                bf16x8 hi[2], lo[2];
+                split_ops(G, hi, lo);
+                _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
+                    const bf16x8 kt = frag_tr_perm(K, LD, 32 * rb + 16 * s2, 32 * wave, lane);
+                    aq = mfma(kt, hi[s2], aq);
+                    aq = mfma(kt, lo[s2], aq);
+                }
+            }
+        if (want_dg) {
+            f32x16 full = aq;
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) full[x] += wq * aqr[x];
+            float pq = row_dot(Q, tok, wave, half, full);
+            pq += __shfl_xor(pq, 32, 64);
+            if (half == 0) red[(wave * 3 + 0) * 64 + tok] = pq;
+        }
+        resq[nb] = pack_block(aq);
+    }
+    // ---- <S, dS> over this wave's rows, then dk^T[i][r]
+    bf16x8 dsfrag[8];
+    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+        dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + (32 * wave + n) * D + 16 * ks + 8 * half);
+    if (want_dg) {
         float z = 0.f;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
             u32x4 a = __builtin_bit_cast(u32x4, sfrag[ks]), b = __builtin_bit_cast(u32x4, dsfrag[ks]);
@@ -529,115 +633,48 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
         for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
         if (lane == 0) zred[wave] = z;
     }
-
-    // score quadrants: 3 products x 3 non-zero quadrants = 9 jobs over 4 waves
-    //   job kind 0: Ast[r][j] : D[m = j][n = r] = Q rows x K rows (k = i), masked and decayed
-    //   job kind 1: G  [j][r] : D[m = r][n = j] = V rows x dO rows (k = v)
-    //   job kind 2: Gt [r][j] : D[m = j][n = r] = dO rows x V rows
-    for (int job = wave; job < 9; job += 4) {
-        const int kind = job / 3, qd = job % 3;
-        const int rb = qd == 2 ? 1 : 0, jb = qd == 0 ? 0 : 1;  // (0,0), (0,1), (1,1)
-        const uint16_t* Am = kind == 0 ? Q : (kind == 1 ? V : dO);
-        const uint16_t* Bm = kind == 0 ? K : (kind == 1 ? dO : V);
-        const int mrow = kind == 1 ? 32 * rb : 32 * jb, nrow = kind == 1 ? 32 * jb : 32 * rb;
-        f32x16 acc = {0};
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-            acc = mfma(frag(Am, LD, mrow + n, 16 * ks + 8 * half), frag(Bm, LD, nrow + n, 16 * ks + 8 * half), acc);
-        _Pragma("unroll") for (int r16 = 0; r16 < 16; ++r16) {
-            const int mi = mrow + 8 * (r16 >> 2) + 4 * half + (r16 & 3), ni = nrow + n;
-            const int j = kind == 1 ? ni : mi, r = kind == 1 ? mi : ni;
-            acc[r16] = r <= j ? acc[r16] * __expf(bs[j] - bs[r]) : 0.f;
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        const int tok = 32 * nb + n;  // r
+        f32x16 ak = {0};
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak);
+        const float wk = __expf(bC - bs[tok]);
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) ak[x] *= wk;
+        float pk_inter = 0.f;
+        if (want_dg) pk_inter = row_dot(K, tok, wave, half, ak);
+        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb)
+            if (jb >= nb) {
+                f32x16 Gt = score_block(dO, 32 * jb, V, 32 * nb, n, half);  // D[m = j][n = r] = d_o_j . v_r
+                decay_mask<false>(Gt, 32 * jb, tok, bs, half);
+                bf16x8 hi[2], lo[2];
+                split_ops(Gt, hi, lo);
+                _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
+                    const bf16x8 qt = frag_tr_perm(Q, LD, 32 * jb + 16 * s2, 32 * wave, lane);
+                    ak = mfma(qt, hi[s2], ak);
+                    ak = mfma(qt, lo[s2], ak);
+                }
+            }
+        if (want_dg) {
+            float pk = row_dot(K, tok, wave, half, ak);
+            pk += __shfl_xor(pk, 32, 64);
+            pk_inter += __shfl_xor(pk_inter, 32, 64);
+            if (half == 0) {
+                red[(wave * 3 + 1) * 64 + tok] = pk;
+                red[(wave * 3 + 2) * 64 + tok] = pk_inter;
+            }
         }
-        uint16_t* dst = kind == 0 ? Ast : (kind == 1 ? G : Gt);
-        store_block_t_split(dst, dst + kRem, LDP, nrow + n, mrow, half, acc);
+        resk[nb] = pack_block(ak);
     }
-    bf16x8 i0, i1;
-    make_identity(lane, i0, i1);
-    __syncthreads();
-
-    f32x16 accq[2], acck[2];
-    // ---- dq^T[i][j] and dk^T[i][r] for i in this wave's slice
-    {
-        bf16x8 kt[4], qt[4];
-        _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
-            f32x16 t = turn_block(K, LD, 32 * tb, 32 * wave, lane, i0, i1);
-            kt[2 * tb] = pack_step(t, 0);
-            kt[2 * tb + 1] = pack_step(t, 1);
-            t = turn_block(Q, LD, 32 * tb, 32 * wave, lane, i0, i1);
-            qt[2 * tb] = pack_step(t, 0);
-            qt[2 * tb + 1] = pack_step(t, 1);
-        }
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            const int tok = 32 * nb + n;  // j for dq, r for dk
-            f32x16 aq = {0}, ak = {0}, aqr = {0};  // aqr: remainder of S, enters the decay gradient only
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 dof = frag(dO, LD, tok, 16 * ks + 8 * half);
-                aq = mfma(sfrag[ks], dof, aq);
-                if (want_dg) aqr = mfma(srfrag[ks], dof, aqr);
-                ak = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak);
-            }
-            const float wq = __expf(bs[tok]), wk = __expf(bC - bs[tok]);
-            float pk_inter = 0.f;
-            _Pragma("unroll") for (int r = 0; r < 16; ++r) { aq[r] *= wq; ak[r] *= wk; }
-            if (want_dg) {
-                // k . dk_inter over this lane's 16 features
-                _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
-                    u32x2 kk = *reinterpret_cast<const u32x2*>(K + tok * LD + 32 * wave + 8 * gg + 4 * half);
-                    pk_inter += bf16_lo(kk.x) * ak[4 * gg] + bf16_hi(kk.x) * ak[4 * gg + 1] +
-                                bf16_lo(kk.y) * ak[4 * gg + 2] + bf16_hi(kk.y) * ak[4 * gg + 3];
-                }
-            }
-            // intra: dq over keys r <= j (k-steps of r), dk over queries j >= r (k-steps of j)
-            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
-                if (!(nb == 0 && ks >= 2)) {
-                    aq = mfma(kt[ks], frag_perm(G, LDP, tok, 16 * ks, half), aq);
-                    aq = mfma(kt[ks], frag_perm(G + kRem, LDP, tok, 16 * ks, half), aq);
-                }
-                if (!(nb == 1 && ks < 2)) {
-                    ak = mfma(qt[ks], frag_perm(Gt, LDP, tok, 16 * ks, half), ak);
-                    ak = mfma(qt[ks], frag_perm(Gt + kRem, LDP, tok, 16 * ks, half), ak);
-                }
-            }
-            accq[nb] = aq;
-            acck[nb] = ak;
-            if (want_dg) {
-                float pq = 0.f, pk = 0.f;
-                _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
-                    u32x2 qq = *reinterpret_cast<const u32x2*>(Q + tok * LD + 32 * wave + 8 * gg + 4 * half);
-                    u32x2 kk = *reinterpret_cast<const u32x2*>(K + tok * LD + 32 * wave + 8 * gg + 4 * half);
-                    pq += bf16_lo(qq.x) * (aq[4 * gg] + wq * aqr[4 * gg]) + bf16_hi(qq.x) * (aq[4 * gg + 1] + wq * aqr[4 * gg + 1]) +
-                          bf16_lo(qq.y) * (aq[4 * gg + 2] + wq * aqr[4 * gg + 2]) + bf16_hi(qq.y) * (aq[4 * gg + 3] + wq * aqr[4 * gg + 3]);
-                    pk += bf16_lo(kk.x) * ak[4 * gg] + bf16_hi(kk.x) * ak[4 * gg + 1] + bf16_lo(kk.y) * ak[4 * gg + 2] +
-                          bf16_hi(kk.y) * ak[4 * gg + 3];
-                }
-                pq += __shfl_xor(pq, 32, 64);
-                pk += __shfl_xor(pk, 32, 64);
-                pk_inter += __shfl_xor(pk_inter, 32, 64);
-                if (half == 0) {
-                    red[(wave * 3 + 0) * 64 + tok] = pq;
-                    red[(wave * 3 + 1) * 64 + tok] = pk;
-                    red[(wave * 3 + 2) * 64 + tok] = pk_inter;
-                }
-            }
-        }
-    }
-    // ---- dv^T[v][r] for v in this wave's slice
-    f32x16 accv[2];
+    // ---- dv^T[v][r], v in this wave's slice
     {
         // dS^T rows of this wave: turn dS[i-block][v-slice] straight from global memory
-        bf16x8 dst_[8], dot[4];
-        const int m = lane & 31;
+        bf16x8 i0, i1, dst_[8];
+        make_identity(lane, i0, i1);
         _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) {
             f32x16 t = {0};
-            t = mfma(*reinterpret_cast<const bf16x8*>(dS + (32 * ib + m) * D + 32 * wave + 8 * half), i0, t);
-            t = mfma(*reinterpret_cast<const bf16x8*>(dS + (32 * ib + m) * D + 32 * wave + 16 + 8 * half), i1, t);
+            t = mfma(*reinterpret_cast<const bf16x8*>(dS + (32 * ib + n) * D + 32 * wave + 8 * half), i0, t);
+            t = mfma(*reinterpret_cast<const bf16x8*>(dS + (32 * ib + n) * D + 32 * wave + 16 + 8 * half), i1, t);
             dst_[2 * ib] = pack_step(t, 0);
             dst_[2 * ib + 1] = pack_step(t, 1);
-        }
-        _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
-            f32x16 t = turn_block(dO, LD, 32 * tb, 32 * wave, lane, i0, i1);
-            dot[2 * tb] = pack_step(t, 0);
-            dot[2 * tb + 1] = pack_step(t, 1);
         }
         _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
             const int r = 32 * nb + n;
@@ -645,19 +682,26 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) av = mfma(dst_[ks], frag_perm(K, LD, r, 16 * ks, half), av);
             const float wk = __expf(bC - bs[r]);
             _Pragma("unroll") for (int x = 0; x < 16; ++x) av[x] *= wk;
-            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)
-                if (!(nb == 1 && ks < 2)) {
-                    av = mfma(dot[ks], frag_perm(Ast, LDP, r, 16 * ks, half), av);
-                    av = mfma(dot[ks], frag_perm(Ast + kRem, LDP, r, 16 * ks, half), av);
+            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb)
+                if (jb >= nb) {
+                    f32x16 As = score_block(Q, 32 * jb, K, 32 * nb, n, half);  // D[m = j][n = r] = q_j . k_r
+                    decay_mask<false>(As, 32 * jb, r, bs, half);
+                    bf16x8 hi[2], lo[2];
+                    split_ops(As, hi, lo);
+                    _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
+                        const bf16x8 dot = frag_tr_perm(dO, LD, 32 * jb + 16 * s2, 32 * wave, lane);
+                        av = mfma(dot, hi[s2], av);
+                        av = mfma(dot, lo[s2], av);
+                    }
                 }
-            accv[nb] = av;
+            resv[nb] = pack_block(av);
         }
     }
-    __syncthreads();  // every wave is done with Q, K, V, dO, G, Gt, Ast
+    __syncthreads();  // every wave is done with Q, K, V, dO
     _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        store_block_t(Q, LD, 32 * nb + n, 32 * wave, half, accq[nb]);
-        store_block_t(K, LD, 32 * nb + n, 32 * wave, half, acck[nb]);
-        store_block_t(V, LD, 32 * nb + n, 32 * wave, half, accv[nb]);
+        store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
+        store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
+        store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
     }
     __syncthreads();
     store_tile(dq, Q, tok0, L, tid);
@@ -671,8 +715,7 @@ __global__ __launch_bounds__(kThreads) void mk_grad(Dims d, const uint16_t* __re
             tail += red[(wv * 3 + 2) * 64 + tid];
         }
         for (int off = 32; off > 0; off >>= 1) tail += __shfl_xor(tail, off, 64);
-        // suffix sum of w over tokens >= tid
-        float sfx = w;
+        float sfx = w;  // suffix sum of w over tokens >= tid
         for (int off = 1; off < 64; off <<= 1) {
             const float y = __shfl_down(sfx, off, 64);
             if (tid + off < 64) sfx += y;
