@@ -500,11 +500,15 @@ __device__ __forceinline__ f32x16 score_block(const uint16_t* Am, int m0, const 
 template <bool ROWS_R>
 __device__ __forceinline__ void decay_mask(f32x16& acc, int m0, int ncol, const float* bs, int half) {
     const float bn = bs[ncol];
-    _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-        const int mi = m0 + 8 * (x >> 2) + 4 * half + (x & 3);
-        const int j = ROWS_R ? ncol : mi, r = ROWS_R ? mi : ncol;
-        const float e = ROWS_R ? bn - bs[mi] : bs[mi] - bn;
-        acc[x] = r <= j ? acc[x] * __expf(e) : 0.f;
+    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+        const float4 bm = *reinterpret_cast<const float4*>(bs + m0 + 8 * g + 4 * half);
+        const float bmv[4] = {bm.x, bm.y, bm.z, bm.w};
+        _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
+            const int mi = m0 + 8 * g + 4 * half + jj, x = 4 * g + jj;
+            const int j = ROWS_R ? ncol : mi, r = ROWS_R ? mi : ncol;
+            const float e = ROWS_R ? bn - bmv[jj] : bmv[jj] - bn;
+            acc[x] = r <= j ? acc[x] * __expf(e) : 0.f;
+        }
     }
 }
 
@@ -570,9 +574,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     const bool want_dg = dg_tok != nullptr;  // then states_rem is present
 
     // rows i in [32w, 32w+32) of S (and its remainder): A operands [m = i][k = v]
-    bf16x8 sfrag[8], srfrag[8];
+    bf16x8 sfrag[8], srfrag[8], dsfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
         sfrag[ks] = *reinterpret_cast<const bf16x8*>(S + (32 * wave + n) * D + 16 * ks + 8 * half);
+        dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + (32 * wave + n) * D + 16 * ks + 8 * half);
         if (want_dg)
             srfrag[ks] = *reinterpret_cast<const bf16x8*>(states_rem + (S - states) + (32 * wave + n) * D + 16 * ks +
                                                           8 * half);
@@ -619,9 +624,6 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
         resq[nb] = pack_block(aq);
     }
     // ---- <S, dS> over this wave's rows, then dk^T[i][r]
-    bf16x8 dsfrag[8];
-    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-        dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + (32 * wave + n) * D + 16 * ks + 8 * half);
     if (want_dg) {
         float z = 0.f;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
