@@ -324,7 +324,7 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
 
     // prologue: chunks 0 and 1 -> LDS, chunk 2 in flight.  Global loads are issued two iterations
     // before their data is written to LDS: one iteration is shorter than a trip to HBM.
-    StateRegs r0, r1;
+    StateRegs r0, r1, r2;
     float lam_cur = 1.f, lam_nxt = 1.f;
     state_gload<DEC>(d, xa, xb, wts, lam, bh, first, 32 * nb, tid, r0);
     if (d.N > 1) state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step, 32 * nb, tid, r1);
@@ -335,12 +335,15 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
         lam_nxt = r1.lam;
     }
     state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(2, d.N - 1), 32 * nb, tid, r0);
+    state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(3, d.N - 1), 32 * nb, tid, r1);
     __syncthreads();
 
-    // One chunk, straight-line code: r0 holds chunk k+2 (loaded earlier, written to LDS at the end), r1
-    // receives chunk k+3; chunk indices past the end are clamped (the data lands in a buffer nobody reads).
-    for (int k = 0; k < d.N; ++k) {
-        state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(k + 3, d.N - 1), 32 * nb, tid, r1);
+    // One chunk, straight-line code: rw holds chunk k+2 (loaded three iterations ago, written to LDS
+    // at the end), rl receives chunk k+4; chunk indices past the end are clamped (the data lands in a
+    // buffer nobody reads).  The three register sets rotate by unrolling, never by copying: a copy
+    // would wait for the load issued in the same iteration.
+    auto iteration = [&](int k, StateRegs& rw, StateRegs& rl) {
+        state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(k + 4, d.N - 1), 32 * nb, tid, rl);
         // stage the state this chunk starts from (MODE 2: the gradient this chunk ends with)
         uint16_t* sh = stage + (k & 1) * 2 * 32 * LD;
         if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
@@ -356,13 +359,20 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
             if (DEC) acc = mfma(fa, frag_tr(tb + C * LDB, LDB, 16 * ks, 0, lane), acc);
         }
         __syncthreads();  // every wave is done with the tiles of chunk k; the staged state is complete
-        state_to_lds<DEC>(r0, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
+        state_to_lds<DEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
         state_store(states + slot(k), sh, tid);        // contiguous rows
         if (states_rem) state_store(states_rem + slot(k), sh + 32 * LD, tid);
         lam_cur = lam_nxt;
-        lam_nxt = r0.lam;
-        r0 = r1;
+        lam_nxt = rw.lam;
+    };
+    int k = 0;
+    for (; k + 2 < d.N; k += 3) {
+        iteration(k, r0, r2);
+        iteration(k + 1, r1, r0);
+        iteration(k + 2, r2, r1);
     }
+    if (k < d.N) iteration(k, r0, r2);
+    if (k + 1 < d.N) iteration(k + 1, r1, r0);
     __syncthreads();
     if (edge_out) {
         float* e = edge_out + size_t(bh) * sz;
