@@ -384,107 +384,6 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Output of one chunk:  O^T[v][j] = e^{b_j} sum_i S^T[v][i] q_j[i] + sum_{r<=j} V^T[v][r] P[j][r],
-// P[j][r] = (q_j . k_r) e^{b_j - b_r}.   Wave w owns v in [32w, 32w+32).
-// The scores are kept as a bf16 head and a bf16 remainder (two MFMAs per k-step): an output that one
-// key dominates would otherwise carry the full 2^-9 rounding of its score.
-// LDS: Q | K (later the O stage) | V (64 x LD each) | P head, P remainder (64 x LDP each) | bs
-constexpr int kOutLds = (3 * C * LD + 2 * C * LDP) * 2 + C * 4;
-
-__global__ __launch_bounds__(kThreads) void mk_output(Dims d, const uint16_t* __restrict__ q,
-                                                      const uint16_t* __restrict__ k,
-                                                      const uint16_t* __restrict__ v, const float* __restrict__ g,
-                                                      const uint16_t* __restrict__ states,
-                                                      uint16_t* __restrict__ o) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* K = Q + C * LD;
-    uint16_t* V = K + C * LD;
-    uint16_t* P = V + C * LD;
-    uint16_t* Pr = P + C * LDP;
-    float* bs = reinterpret_cast<float*>(Pr + C * LDP);
-    uint16_t* stage = K;
-
-    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = c * C, L = min(C, d.T - t0);
-    const size_t tok0 = size_t(bh) * d.T + t0;
-    const int n = lane & 31, half = lane >> 5;
-
-    // state rows of this wave straight from global memory: A operand [m = v][k = i]
-    const uint16_t* St = states + (size_t(bh) * d.N + c) * D * D;
-    bf16x8 sfrag[8];
-    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-        sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + (32 * wave + n) * D + 16 * ks + 8 * half);
-
-    load_tile(Q, q, tok0, L, tid);
-    load_tile(K, k, tok0, L, tid);
-    load_tile(V, v, tok0, L, tid);
-    cumulative_decay(d, g, bh, t0, L, bs, tid);
-    __syncthreads();
-
-    // scores, quadrant (rb, jb) with rb <= jb:  D[m = r][n = j] = sum_i K[r][i] Q[j][i]
-    {
-        const int rb = wave & 1, jb = wave >> 1;
-        if (rb <= jb) {
-            f32x16 acc = {0};
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                acc = mfma(frag(K, LD, 32 * rb + n, 16 * ks + 8 * half), frag(Q, LD, 32 * jb + n, 16 * ks + 8 * half), acc);
-            const int j = 32 * jb + n;
-            const float bj = bs[j];
-            _Pragma("unroll") for (int r16 = 0; r16 < 16; ++r16) {
-                const int r = 32 * rb + 8 * (r16 >> 2) + 4 * half + (r16 & 3);
-                acc[r16] = r <= j ? acc[r16] * __expf(bj - bs[r]) : 0.f;
-            }
-            store_block_t_split(P, Pr, LDP, j, 32 * rb, half, acc);
-        }
-    }
-    // V^T of this wave's 32 value columns, as A operand [m = v][k = r (permuted)]
-    bf16x8 i0, i1;
-    make_identity(lane, i0, i1);
-    bf16x8 vt[4];
-    _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
-        f32x16 t = turn_block(V, LD, 32 * tb, 32 * wave, lane, i0, i1);
-        vt[2 * tb + 0] = pack_step(t, 0);
-        vt[2 * tb + 1] = pack_step(t, 1);
-    }
-    __syncthreads();
-
-    for (int jb = 0; jb < 2; ++jb) {
-        f32x16 acc = {0};
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) acc = mfma(sfrag[ks], frag(Q, LD, 32 * jb + n, 16 * ks + 8 * half), acc);
-        const float w = __expf(bs[32 * jb + n]);
-        _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[r] *= w;
-        const int kmax = jb == 0 ? 2 : 4;  // keys r >= 32 never reach queries j < 32
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)
-            if (ks < kmax) {
-                acc = mfma(vt[ks], frag_perm(P, LDP, 32 * jb + n, 16 * ks, half), acc);
-                acc = mfma(vt[ks], frag_perm(Pr, LDP, 32 * jb + n, 16 * ks, half), acc);
-            }
-        store_block_t(stage, LD, 32 * jb + n, 32 * wave, half, acc);
-    }
-    __syncthreads();
-    store_tile(o, stage, tok0, L, tid);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Gradients of one chunk (scalar decay kinds).  S = state at the chunk start [i][v], dS = gradient
-// of the state at the chunk end [i][v].  D_jr = e^{b_j-b_r} for r <= j, else 0.
-//   dA = d_o V^T ,  G = dA * D ,  As = (Q K^T) * D
-//   dq^T[i][j] = e^{b_j}     sum_v S[i][v]  d_o_j[v] + sum_r K^T[i][r] G[j][r]
-//   dk^T[i][r] = e^{b_C-b_r} sum_v dS[i][v] v_r[v]   + sum_j Q^T[i][j] G[j][r]
-//   dv^T[v][r] = e^{b_C-b_r} sum_i dS^T[v][i] k_r[i] + sum_j dO^T[v][j] As[j][r]
-//   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + sum_r k_r.dk_r^{inter} + e^{b_C} <S, dS>
-// Wave w owns i (and v) in [32w, 32w+32) and never exchanges data with the other waves before the
-// final staging: every 32 x 32 block of G, G^T and As it needs is computed by the wave itself and
-// consumed straight from its accumulator registers (as the B operand of the next MFMA, head and
-// remainder), the partner operand K^T / Q^T / dO^T coming from the LDS transpose read in the
-// matching k order.  That costs three times the score MFMAs but no LDS space, no LDS round trip and
-// no barrier, and lets two workgroups share a CU.
-// LDS: Q | K | V | dO (64 x LD; later stages of dq, dk, dv) | bs (64) | red (4 x 3 x 64 floats:
-//      per-wave partial row dots) | zred
-constexpr int kGradLds = 4 * C * LD * 2 + C * 4 + 4 * 64 * 3 * 4 + 64;
-
 // same as frag_tr, k in the permuted order of a D-layout operand: tokens row0 + 4*half + {0..3}
 // and row0 + 8 + 4*half + {0..3}
 __device__ __forceinline__ bf16x8 frag_tr_perm(const uint16_t* tile, int ld, int row0, int col0, int lane) {
@@ -557,6 +456,90 @@ __device__ __forceinline__ float row_dot(const uint16_t* X, int tok, int wave, i
     }
     return s;
 }
+
+// ---------------------------------------------------------------------------------------------
+// Output of one chunk:  O^T[v][j] = e^{b_j} sum_i S^T[v][i] q_j[i] + sum_{r<=j} V^T[v][r] P[j][r],
+// P[j][r] = (q_j . k_r) e^{b_j - b_r}.   Wave w owns v in [32w, 32w+32) and computes every 32 x 32
+// block of P it needs itself: the block stays in its accumulator registers and is fed to the next
+// MFMA as the B operand (bf16 head + bf16 remainder: an output that one key dominates would
+// otherwise carry the full 2^-9 rounding of its score), V^T coming from the LDS transpose read in
+// the matching k order.  No LDS copy of P, no barrier between the two products.
+// LDS: Q | K (later the O stage) | V (64 x LD each) | bs
+constexpr int kOutLds = 3 * C * LD * 2 + C * 4;
+
+__global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t* __restrict__ q,
+                                                         const uint16_t* __restrict__ k,
+                                                         const uint16_t* __restrict__ v, const float* __restrict__ g,
+                                                         const uint16_t* __restrict__ states,
+                                                         uint16_t* __restrict__ o) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* K = Q + C * LD;
+    uint16_t* V = K + C * LD;
+    float* bs = reinterpret_cast<float*>(V + C * LD);
+    uint16_t* stage = K;
+
+    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = c * C, L = min(C, d.T - t0);
+    const size_t tok0 = size_t(bh) * d.T + t0;
+    const int n = lane & 31, half = lane >> 5;
+
+    // state rows of this wave straight from global memory: A operand [m = v][k = i]
+    const uint16_t* St = states + (size_t(bh) * d.N + c) * D * D;
+    bf16x8 sfrag[8];
+    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+        sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + (32 * wave + n) * D + 16 * ks + 8 * half);
+
+    load_tile(Q, q, tok0, L, tid);
+    load_tile(K, k, tok0, L, tid);
+    load_tile(V, v, tok0, L, tid);
+    cumulative_decay(d, g, bh, t0, L, bs, tid);
+    __syncthreads();
+
+    PackedBlock res[2];
+    _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+        const int j = 32 * jb + n;
+        f32x16 acc = {0};
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) acc = mfma(sfrag[ks], frag(Q, LD, j, 16 * ks + 8 * half), acc);
+        const float w = __expf(bs[j]);
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[x] *= w;
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)
+            if (rb <= jb) {  // keys r >= 32 never reach queries j < 32
+                f32x16 P = score_block(K, 32 * rb, Q, 32 * jb, n, half);  // D[m = r][n = j] = k_r . q_j
+                decay_mask<true>(P, 32 * rb, j, bs, half);
+                bf16x8 hi[2], lo[2];
+                split_ops(P, hi, lo);
+                _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
+                    const bf16x8 vt = frag_tr_perm(V, LD, 32 * rb + 16 * s2, 32 * wave, lane);
+                    acc = mfma(vt, hi[s2], acc);
+                    acc = mfma(vt, lo[s2], acc);
+                }
+            }
+        res[jb] = pack_block(acc);
+    }
+    __syncthreads();  // every wave is done with K
+    _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) store_packed(stage, LD, 32 * jb + n, 32 * wave, half, res[jb]);
+    __syncthreads();
+    store_tile(o, stage, tok0, L, tid);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gradients of one chunk (scalar decay kinds).  S = state at the chunk start [i][v], dS = gradient
+// of the state at the chunk end [i][v].  D_jr = e^{b_j-b_r} for r <= j, else 0.
+//   dA = d_o V^T ,  G = dA * D ,  As = (Q K^T) * D
+//   dq^T[i][j] = e^{b_j}     sum_v S[i][v]  d_o_j[v] + sum_r K^T[i][r] G[j][r]
+//   dk^T[i][r] = e^{b_C-b_r} sum_v dS[i][v] v_r[v]   + sum_j Q^T[i][j] G[j][r]
+//   dv^T[v][r] = e^{b_C-b_r} sum_i dS^T[v][i] k_r[i] + sum_j dO^T[v][j] As[j][r]
+//   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + sum_r k_r.dk_r^{inter} + e^{b_C} <S, dS>
+// Wave w owns i (and v) in [32w, 32w+32) and never exchanges data with the other waves before the
+// final staging: every 32 x 32 block of G, G^T and As it needs is computed by the wave itself and
+// consumed straight from its accumulator registers (as the B operand of the next MFMA, head and
+// remainder), the partner operand K^T / Q^T / dO^T coming from the LDS transpose read in the
+// matching k order.  That costs three times the score MFMAs but no LDS space, no LDS round trip and
+// no barrier, and lets two workgroups share a CU.
+// LDS: Q | K | V | dO (64 x LD; later stages of dq, dk, dv) | bs (64) | red (4 x 3 x 64 floats:
+//      per-wave partial row dots) | zred
+constexpr int kGradLds = 4 * C * LD * 2 + C * 4 + 4 * 64 * 3 * 4 + 64;
 
 __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* __restrict__ q,
                                                        const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
