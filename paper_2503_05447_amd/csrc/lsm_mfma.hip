@@ -399,9 +399,15 @@ __device__ __forceinline__ bf16x8 frag_tr_perm(const uint16_t* tile, int ld, int
 
 // D[m][n] = sum_f Am[m0 + m][f] * Bm[n0 + n][f] over the 128 features of two row-major LDS tiles
 __device__ __forceinline__ f32x16 score_block(const uint16_t* Am, int m0, const uint16_t* Bm, int n0, int n, int half) {
+    // all sixteen fragments are requested before the first MFMA so that one LDS latency is paid, not eight
+    bf16x8 fa[8], fb[8];
+    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+        fa[ks] = frag(Am, LD, m0 + n, 16 * ks + 8 * half);
+        fb[ks] = frag(Bm, LD, n0 + n, 16 * ks + 8 * half);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the requests above, the MFMAs below
     f32x16 acc = {0};
-    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-        acc = mfma(frag(Am, LD, m0 + n, 16 * ks + 8 * half), frag(Bm, LD, n0 + n, 16 * ks + 8 * half), acc);
+    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) acc = mfma(fa[ks], fb[ks], acc);
     return acc;
 }
 
@@ -659,24 +665,28 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
         }
         resk[nb] = pack_block(ak);
     }
-    // ---- dv^T[v][r], v in this wave's slice
+    // ---- dv^T[v][r], v in this wave's slice.  The inter part contracts over the rows i of dS, which
+    // the four waves hold as their A fragments: they are handed over through the V tile (dead by now),
+    // 64 rows at a time, and read back token-major with the LDS transpose read.
     {
-        // dS^T rows of this wave: turn dS[i-block][v-slice] straight from global memory
-        bf16x8 i0, i1, dst_[8];
-        make_identity(lane, i0, i1);
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) {
-            f32x16 t = {0};
-            t = mfma(*reinterpret_cast<const bf16x8*>(dS + (32 * ib + n) * D + 32 * wave + 8 * half), i0, t);
-            t = mfma(*reinterpret_cast<const bf16x8*>(dS + (32 * ib + n) * D + 32 * wave + 16 + 8 * half), i1, t);
-            dst_[2 * ib] = pack_step(t, 0);
-            dst_[2 * ib + 1] = pack_step(t, 1);
+        f32x16 av[2] = {{0}, {0}};
+        _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {
+            __syncthreads();  // hf = 0: every wave is done with V; hf = 1: done with the first 64 rows
+            if ((wave >> 1) == hf) {
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                    *reinterpret_cast<bf16x8*>(V + (32 * (wave & 1) + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
+            }
+            __syncthreads();
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+                const bf16x8 dst = frag_tr(V, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 64 hf + 16 ks + ..
+                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                    av[nb] = mfma(dst, frag(K, LD, 32 * nb + n, 64 * hf + 16 * ks + 8 * half), av[nb]);
+            }
         }
         _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
             const int r = 32 * nb + n;
-            f32x16 av = {0};
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) av = mfma(dst_[ks], frag_perm(K, LD, r, 16 * ks, half), av);
             const float wk = __expf(bC - bs[r]);
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) av[x] *= wk;
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
             _Pragma("unroll") for (int jb = 0; jb < 2; ++jb)
                 if (jb >= nb) {
                     f32x16 As = score_block(Q, 32 * jb, K, 32 * nb, n, half);  // D[m = j][n = r] = q_j . k_r
@@ -685,11 +695,11 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
                     split_ops(As, hi, lo);
                     _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
                         const bf16x8 dot = frag_tr_perm(dO, LD, 32 * jb + 16 * s2, 32 * wave, lane);
-                        av = mfma(dot, hi[s2], av);
-                        av = mfma(dot, lo[s2], av);
+                        av[nb] = mfma(dot, hi[s2], av[nb]);
+                        av[nb] = mfma(dot, lo[s2], av[nb]);
                     }
                 }
-            resv[nb] = pack_block(av);
+            resv[nb] = pack_block(av[nb]);
         }
     }
     __syncthreads();  // every wave is done with Q, K, V, dO
