@@ -212,9 +212,10 @@ __global__ __launch_bounds__(64) void mk_decay_prep(Dims d, const float* __restr
 // a single token dominates is visible.
 constexpr int LDB = 40;  // row stride (elements) of a 64 x 32 B-side slice in LDS
 // LDS: 2 x (A tile 64 x LD | B slice head 64 x LDB | B slice remainder 64 x LDB) for chunks k+1, k+2
-//      | 2 x (stage head | stage remainder), 32 x LD each
+//      | stage head | stage remainder, 32 x LD each (every wave stages and stores its own block)
 constexpr int kStateTile = C * LD + 2 * C * LDB;
-constexpr int kStateLds = (2 * kStateTile + 4 * 32 * LD) * 2;
+constexpr int kStateLds = (2 * kStateTile + 2 * 32 * LD) * 2;      // with the remainder plane
+constexpr int kStateLdsNoRem = (2 * kStateTile + 1 * 32 * LD) * 2; // without
 
 struct StateRegs {  // one thread's share of a chunk on its way from global memory to LDS
     u32x4 a[4], b;
@@ -269,32 +270,42 @@ __device__ __forceinline__ void state_to_lds(const StateRegs& r, uint16_t* bufA,
     }
 }
 
-// 32 x 128 staged state rows -> their contiguous 8 KiB in global memory
-__device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage, int tid) {
+// One wave's staged 32 x 32 block -> global memory as 64-byte row pieces (4 lanes per row).  The wave
+// reads back only what it staged itself, and LDS serves a wave's accesses in order: no barrier.
+__device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage, int mb, int lane) {
     _Pragma("unroll") for (int it = 0; it < 2; ++it) {
-        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        *reinterpret_cast<u32x4*>(dst + row * D + cp * 8) = *reinterpret_cast<const u32x4*>(stage + row * LD + cp * 8);
+        const int row = 16 * it + (lane >> 2), col = 32 * mb + 8 * (lane & 3);
+        *reinterpret_cast<u32x4*>(dst + row * D + col) = *reinterpret_cast<const u32x4*>(stage + row * LD + col);
     }
 }
 
-template <int MODE, bool DEC>
-__global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t* __restrict__ xa,
-                                                         const uint16_t* __restrict__ xb,
-                                                         const float* __restrict__ wts,
-                                                         const float* __restrict__ lam,
-                                                         uint16_t* __restrict__ states,
-                                                         uint16_t* __restrict__ states_rem,
-                                                         const float* __restrict__ edge_in,
-                                                         float* __restrict__ edge_out) {
-    extern __shared__ __align__(16) unsigned char smem[];
+struct StateArgs {
+    const uint16_t *xa, *xb;
+    const float *wts, *lam;
+    uint16_t *states, *states_rem;
+    const float* edge_in;
+    float* edge_out;
+};
+
+template <int MODE, bool DEC, bool REM>
+__device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& sa, int wg_id, int wg_count,
+                                                unsigned char* smem) {
+    const uint16_t* __restrict__ xa = sa.xa;
+    const uint16_t* __restrict__ xb = sa.xb;
+    const float* __restrict__ wts = sa.wts;
+    const float* __restrict__ lam = sa.lam;
+    uint16_t* __restrict__ states = sa.states;
+    uint16_t* __restrict__ states_rem = sa.states_rem;
+    const float* __restrict__ edge_in = sa.edge_in;
+    float* __restrict__ edge_out = sa.edge_out;
     uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);         // [2][kStateTile]
-    uint16_t* stage = tiles + 2 * kStateTile;                    // [2][2][32 * LD]: parity, head / remainder
+    uint16_t* stage = tiles + 2 * kStateTile;                    // [2][32 * LD]: head, remainder
     // The four workgroups of a (b,h) pair read the same A-side rows.  Workgroups are dealt to the 8
     // XCDs round-robin by linear id, so the id is decoded such that those four share an XCD (and
     // its L2): id = xcd + 8 * (4 * (bh / 8) + nb), bh = xcd + 8 * (bh / 8).
     int nb, bh;
     {
-        const int id = blockIdx.x, nwg = gridDim.x, full = (nwg / 32) * 32;  // 32 = 8 XCDs x 4 blocks
+        const int id = wg_id, nwg = wg_count, full = (nwg / 32) * 32;  // 32 = 8 XCDs x 4 blocks
         if (id < full) {
             const int xcd = id & 7, slot = id >> 3;
             nb = slot & 3;
@@ -345,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
     auto iteration = [&](int k, StateRegs& rw, StateRegs& rl) {
         state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(k + 4, d.N - 1), 32 * nb, tid, rl);
         // stage the state this chunk starts from (MODE 2: the gradient this chunk ends with)
-        uint16_t* sh = stage + (k & 1) * 2 * 32 * LD;
+        uint16_t* sh = stage;
         if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
         else store_block_t(sh, LD, n, 32 * mb, half, acc);
         if (DEC) {
@@ -358,10 +369,10 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
             acc = mfma(fa, frag_tr(tb, LDB, 16 * ks, 0, lane), acc);
             if (DEC) acc = mfma(fa, frag_tr(tb + C * LDB, LDB, 16 * ks, 0, lane), acc);
         }
-        __syncthreads();  // every wave is done with the tiles of chunk k; the staged state is complete
+        __syncthreads();  // every wave is done with the tiles of chunk k
         state_to_lds<DEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
-        state_store(states + slot(k), sh, tid);        // contiguous rows
-        if (states_rem) state_store(states_rem + slot(k), sh + 32 * LD, tid);
+        state_store(states + slot(k), sh, mb, lane);
+        if (states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, lane);
         lam_cur = lam_nxt;
         lam_nxt = rw.lam;
     };
@@ -382,6 +393,22 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, const uint16_t*
             else e[nn * D + mm] = acc[x];
         }
     }
+}
+
+template <int MODE, bool DEC>
+__global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, StateArgs sa) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    state_scan_body<MODE, DEC, false>(d, sa, blockIdx.x, gridDim.x, smem);
+}
+
+// The two scans of the backward pass (states forward in time, state gradients backward in time) are
+// independent sequential chains; launched as one grid they share the CUs two workgroups at a time,
+// which hides most of each other's latency.  blockIdx.y selects the scan.
+template <bool DEC, bool REM>
+__global__ __launch_bounds__(kThreads) void mk_state_pair(Dims d, StateArgs s1, StateArgs s2) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (blockIdx.y == 0) state_scan_body<1, DEC, REM>(d, s1, blockIdx.x, gridDim.x, smem);
+    else state_scan_body<2, DEC, false>(d, s2, blockIdx.x, gridDim.x, smem);
 }
 
 // same as frag_tr, k in the permuted order of a D-layout operand: tokens row0 + 4*half + {0..3}
@@ -785,16 +812,31 @@ size_t mfma_bwd_workspace(const Dims& d) { return carve(d, nullptr, true).bytes;
 
 namespace {
 template <int MODE>
-void launch_state(const Dims& d, hipStream_t st, const uint16_t* xa, const uint16_t* xb, const float* wts,
-                  const float* lam, uint16_t* states, uint16_t* rem, const float* ein, float* eout) {
+hipError_t launch_state(const Dims& d, hipStream_t st, const StateArgs& sa) {
     const dim3 sgrid(D / 32 * d.BH()), block(kThreads);
+    const int lds = kStateLdsNoRem;
+    hipError_t e;
     if (d.kind == 0) {
-        if (allow_lds(mk_state_seq<MODE, false>, kStateLds) != hipSuccess) return;
-        hipLaunchKernelGGL((mk_state_seq<MODE, false>), sgrid, block, kStateLds, st, d, xa, xb, wts, lam, states, rem, ein, eout);
+        if ((e = allow_lds(mk_state_seq<MODE, false>, kStateLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_state_seq<MODE, false>), sgrid, block, lds, st, d, sa);
     } else {
-        if (allow_lds(mk_state_seq<MODE, true>, kStateLds) != hipSuccess) return;
-        hipLaunchKernelGGL((mk_state_seq<MODE, true>), sgrid, block, kStateLds, st, d, xa, xb, wts, lam, states, rem, ein, eout);
+        if ((e = allow_lds(mk_state_seq<MODE, true>, kStateLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_state_seq<MODE, true>), sgrid, block, lds, st, d, sa);
     }
+    return hipSuccess;
+}
+template <bool DEC, bool REM>
+hipError_t launch_state_pair_t(const Dims& d, hipStream_t st, const StateArgs& s1, const StateArgs& s2) {
+    const dim3 sgrid(D / 32 * d.BH(), 2), block(kThreads);
+    const int lds = REM ? kStateLds : kStateLdsNoRem;
+    const hipError_t e = allow_lds(mk_state_pair<DEC, REM>, kStateLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((mk_state_pair<DEC, REM>), sgrid, block, lds, st, d, s1, s2);
+    return hipSuccess;
+}
+hipError_t launch_state_pair(const Dims& d, hipStream_t st, const StateArgs& s1, const StateArgs& s2) {
+    if (d.kind == 0) return launch_state_pair_t<false, false>(d, st, s1, s2);  // no decay gradient, no remainder
+    return s1.states_rem ? launch_state_pair_t<true, true>(d, st, s1, s2) : launch_state_pair_t<true, false>(d, st, s1, s2);
 }
 void launch_prep(const Dims& d, hipStream_t st, const float* g, const Ws& w) {
     if (d.kind == 0) return;
@@ -812,7 +854,8 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     launch_prep(d, a.stream, a.g, w);
     {
         ProfScope ps(KID_MFMA_STATE, a.stream);
-        launch_state<0>(d, a.stream, k, v, w.wdec, w.lam, w.states, nullptr, a.m0, a.mT);
+        if ((e = launch_state<0>(d, a.stream, StateArgs{k, v, w.wdec, w.lam, w.states, nullptr, a.m0, a.mT})) != hipSuccess)
+            return e;
     }
     {
         ProfScope ps(KID_MFMA_OUTPUT, a.stream);
@@ -832,11 +875,9 @@ hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     launch_prep(d, a.stream, a.g, w);
     {
         ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
-        launch_state<1>(d, a.stream, v, k, w.wdec, w.lam, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr);
-    }
-    {
-        ProfScope ps(KID_MFMA_DSTATE, a.stream);
-        launch_state<2>(d, a.stream, d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0);
+        const StateArgs s1{v, k, w.wdec, w.lam, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr};
+        const StateArgs s2{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0};
+        if ((e = launch_state_pair(d, a.stream, s1, s2)) != hipSuccess) return e;
     }
     float* dg_tok = nullptr;
     if (a.dg) dg_tok = d.kind == 1 ? w.dg_tok : a.dg;  // per-token scalar decay: written in place
