@@ -12,12 +12,13 @@
 //   A operand: lane holds A[m = l%32][k = 8*half + e],  e = 0..7
 //   B operand: lane holds B[k = 8*half + e][n = l%32]
 //   D result : lane holds D[m = 8*g + 4*half + j][n = l%32] in register 4*g + j
-// A contraction over tokens needs a token-major tile with tokens along k.  Tiles arrive
-// feature-contiguous, so they are turned with an MFMA against the identity: D = X * I leaves
-// lane (n, half) with 16 tokens of feature n, which (a) is written to LDS as 8-byte pieces of a
-// transposed tile, or (b) is used directly as an operand, the partner operand then reading its k
-// index in the same permuted order ("perm" fragments below).  Decay weights are applied to the
-// fp32 values of that step, before the single rounding to bf16.
+// Tiles arrive feature-contiguous ([token][feature] rows).  A contraction over FEATURES reads its
+// operands as 16-byte row pieces (frag).  A contraction over TOKENS reads them with the LDS transpose
+// read (frag_tr: lane = feature, 8 tokens), which needs no transposed copy.  A D-layout result can
+// feed the next MFMA directly from registers as an operand whose k index runs over its rows in the
+// order 4*half + {0..3}, 8 + 4*half + {0..3}; the partner operand is then read in the same order
+// (frag_perm / frag_tr_perm).  Rounded products (scores, decayed operands, states where it matters)
+// are carried as a bf16 head plus a bf16 remainder and cost two MFMAs.
 #include "lsm_internal.h"
 
 namespace lsm {
