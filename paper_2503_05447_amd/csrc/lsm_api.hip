@@ -101,7 +101,7 @@ const char* lsm_kernel_name(int kernel_id) {
     static const char* names[lsm::KID_COUNT] = {
         "generic_cumsum", "generic_chunk_state", "generic_scan", "generic_output", "generic_chunk_dstate",
         "generic_reverse_scan", "generic_grad", "head_reduce", "mfma_state_scan_fwd", "mfma_output",
-        "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep"};
+        "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep"};
     return kernel_id >= 0 && kernel_id < lsm::KID_COUNT ? names[kernel_id] : "unknown";
 }
 
@@ -121,7 +121,7 @@ size_t lsm_chunk_fwd_workspace_bytes(const lsm_params* p) {
 size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK) return 0;
-    return lsm::mfma_supported(d) ? lsm::mfma_bwd_workspace(d) : lsm::generic_bwd_workspace(d);
+    return lsm::mfma_bwd_supported(d) ? lsm::mfma_bwd_workspace(d) : lsm::generic_bwd_workspace(d);
 }
 
 int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
@@ -160,7 +160,7 @@ int lsm_chunk_bwd(const lsm_params* p, const void* q, const void* k, const void*
     if (!workspace || workspace_bytes < need) return LSM_ERR_WORKSPACE;
     lsm::BwdArgs a{q, k, v, log_decay, init_state, d_o, d_final_state, dq, dk, dv, d_log_decay, d_init_state,
                    workspace, static_cast<hipStream_t>(stream)};
-    const hipError_t e = lsm::mfma_supported(d) ? lsm::mfma_bwd(d, a) : lsm::generic_bwd(d, a);
+    const hipError_t e = lsm::mfma_bwd_supported(d) ? lsm::mfma_bwd(d, a) : lsm::generic_bwd(d, a);
     return e == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
 }
 

@@ -19,139 +19,11 @@
 // order 4*half + {0..3}, 8 + 4*half + {0..3}; the partner operand is then read in the same order
 // (frag_perm / frag_tr_perm).  Rounded products (scores, decayed operands, states where it matters)
 // are carried as a bf16 head plus a bf16 remainder and cost two MFMAs.
-#include "lsm_internal.h"
+#include "lsm_mfma_dev.h"
 
 namespace lsm {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int C = 64;      // tokens per chunk
-constexpr int D = 128;     // d_k = d_v
-constexpr int LD = D + 8;  // row stride (elements) of a [*, 128] bf16 tile in LDS: 68 words, == 4 mod 32
-constexpr int LDP = C + 8; // row stride of a [*, 64] bf16 tile in LDS: 36 words, == 4 mod 32
-constexpr int kThreads = 256;
-
-__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    f32x2 f = {lo, hi};
-    bf16x2 h = __builtin_convertvector(f, bf16x2);
-    return __builtin_bit_cast(uint32_t, h);
-}
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// 8 consecutive bf16 of row `row` starting at column `col` (16-byte aligned)
-__device__ __forceinline__ bf16x8 frag(const uint16_t* tile, int ld, int row, int col) {
-    return *reinterpret_cast<const bf16x8*>(tile + row * ld + col);
-}
-// k index in the permuted order of a D-layout operand: columns col0 + 4*half + {0..3} and col0 + 8 + 4*half + {0..3}
-__device__ __forceinline__ bf16x8 frag_perm(const uint16_t* tile, int ld, int row, int col0, int half) {
-    u32x2 lo = *reinterpret_cast<const u32x2*>(tile + row * ld + col0 + 4 * half);
-    u32x2 hi = *reinterpret_cast<const u32x2*>(tile + row * ld + col0 + 8 + 4 * half);
-    u32x4 v = {lo.x, lo.y, hi.x, hi.y};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-// Token-major operand straight out of a row-major [token][feature] LDS tile with the LDS transpose
-// read: lane l receives feature col0 + l%32 of tokens row0 + 8*(l/32) + 0..7 (natural k order).
-// Each group of 16 lanes reads a 4-token x 16-feature patch as 8-byte pieces (lane r of the group:
-// token r/4, features 4*(r%4)..+3) and the hardware hands lane i of the group feature i, 4 tokens.
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ bf16x8 frag_tr(const uint16_t* tile, int ld, int row0, int col0, int lane) {
-    const int r = lane & 15, nblk = (lane >> 4) & 1, half = lane >> 5;
-    const uint16_t* p = tile + (row0 + 8 * half + (r >> 2)) * ld + col0 + 16 * nblk + 4 * (r & 3);
-    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ld));
-    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-    u32x4 v = {l2.x, l2.y, h2.x, h2.y};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-// B operand of the identity for the two k-steps of a 32-wide feature block
-__device__ __forceinline__ void make_identity(int lane, bf16x8& i0, bf16x8& i1) {
-    const int n = lane & 31, half = lane >> 5;
-    u32x4 a, b;
-    _Pragma("unroll") for (int w = 0; w < 4; ++w) {
-        uint32_t va = 0, vb = 0;
-        _Pragma("unroll") for (int s = 0; s < 2; ++s) {
-            const int e = 2 * w + s, k = 8 * half + e;
-            if (k == n) va |= 0x3f80u << (16 * s);
-            if (16 + k == n) vb |= 0x3f80u << (16 * s);
-        }
-        a[w] = va;
-        b[w] = vb;
-    }
-    i0 = __builtin_bit_cast(bf16x8, a);
-    i1 = __builtin_bit_cast(bf16x8, b);
-}
-
-// D[m][n] = X[row0 + m][col0 + n] for a 32x32 block of a row-major LDS tile (exact: x * 1 in fp32)
-__device__ __forceinline__ f32x16 turn_block(const uint16_t* tile, int ld, int row0, int col0, int lane,
-                                             bf16x8 i0, bf16x8 i1) {
-    const int m = lane & 31, half = lane >> 5;
-    f32x16 acc = {0};
-    acc = mfma(frag(tile, ld, row0 + m, col0 + 8 * half), i0, acc);
-    acc = mfma(frag(tile, ld, row0 + m, col0 + 16 + 8 * half), i1, acc);
-    return acc;
-}
-
-// registers 8*s .. 8*s+7 of a D-layout block as the operand of k-step s
-__device__ __forceinline__ bf16x8 pack_step(const f32x16& d, int s) {
-    u32x4 v = {pack2(d[8 * s + 0], d[8 * s + 1]), pack2(d[8 * s + 2], d[8 * s + 3]),
-               pack2(d[8 * s + 4], d[8 * s + 5]), pack2(d[8 * s + 6], d[8 * s + 7])};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-// write a D-layout block as 8-byte pieces: dst[(n)][m0 + 8g + 4half + 0..3], row stride ld
-__device__ __forceinline__ void store_block_t(uint16_t* dst, int ld, int nrow, int m0, int half, const f32x16& d) {
-    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-        u32x2 v = {pack2(d[4 * g + 0], d[4 * g + 1]), pack2(d[4 * g + 2], d[4 * g + 3])};
-        *reinterpret_cast<u32x2*>(dst + nrow * ld + m0 + 8 * g + 4 * half) = v;
-    }
-}
-
-// same, as a bf16 head in `hi` and the bf16 remainder in `lo` (x = hi + lo to ~2^-17)
-__device__ __forceinline__ void store_block_t_split(uint16_t* hi, uint16_t* lo, int ld, int nrow, int m0, int half,
-                                                    const f32x16& d) {
-    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-        const uint32_t h0 = pack2(d[4 * g + 0], d[4 * g + 1]), h1 = pack2(d[4 * g + 2], d[4 * g + 3]);
-        u32x2 vh = {h0, h1};
-        u32x2 vl = {pack2(d[4 * g + 0] - bf16_lo(h0), d[4 * g + 1] - bf16_hi(h0)),
-                    pack2(d[4 * g + 2] - bf16_lo(h1), d[4 * g + 3] - bf16_hi(h1))};
-        *reinterpret_cast<u32x2*>(hi + nrow * ld + m0 + 8 * g + 4 * half) = vh;
-        *reinterpret_cast<u32x2*>(lo + nrow * ld + m0 + 8 * g + 4 * half) = vl;
-    }
-}
-
-// 64 x 128 bf16 tile: global rows [tok0, tok0+L) -> LDS (row stride LD), rows >= L zero
-__device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
-    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        u32x4 v = {0, 0, 0, 0};
-        if (row < L) v = *reinterpret_cast<const u32x4*>(src + (tok0 + row) * D + cp * 8);
-        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = v;
-    }
-}
-// LDS tile (row stride LD) rows [0, L) -> global
-__device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
-    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        if (row < L)
-            *reinterpret_cast<u32x4*>(dst + (tok0 + row) * D + cp * 8) =
-                *reinterpret_cast<const u32x4*>(src + row * LD + cp * 8);
-    }
-}
 
 // Chunk-local inclusive cumulative log-decay b_j, j = 0..63, into LDS (tokens >= L carry g = 0).
 // Called by all threads; only wave 0 works.  Caller synchronises afterwards.
@@ -219,44 +91,66 @@ constexpr int kStateLds = (2 * kStateTile + 2 * 32 * LD) * 2;      // with the r
 constexpr int kStateLdsNoRem = (2 * kStateTile + 1 * 32 * LD) * 2; // without
 
 struct StateRegs {  // one thread's share of a chunk on its way from global memory to LDS
-    u32x4 a[4], b;
-    float w;        // weight of the B-slice row this thread carries
-    float lam;
+    u32x4 a[4], b, blo;  // blo: remainder plane of the B slice (vector decay: both planes arrive precomputed)
+    float w;             // weight of the B-slice row this thread carries
+    float lam;           // e^{b_C}: one per chunk, or (vector decay) the one of this lane's state column
+};
+
+struct StateArgs {
+    const uint16_t *xa, *xb;
+    const float *wts, *lam;
+    uint16_t *states, *states_rem;
+    const float* edge_in;
+    float* edge_out;
+    // vector decay only
+    const uint16_t* xb_lo;  // remainder plane of the decayed B-side operand
+    int a_stride;           // row stride (elements) of the A-side operand = d_v
+    int vh_count;           // 128-wide value slices per (b,h); each is scanned as a sequence of its own
 };
 
 // coalesced: the A side as whole 256-byte rows (16 lanes per row), the B side as 64-byte row slices.
 // Branch-free (rows beyond the ragged end are read from the last valid row and zeroed afterwards) so
 // that the compiler can count outstanding loads exactly and need not drain the queue.
-template <bool DEC>
-__device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, const uint16_t* xb, const float* wts,
-                                            const float* lam, int bh, int c, int fb0, int tid, StateRegs& r) {
+template <bool DEC, bool VEC>
+__device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, const uint16_t* xb,
+                                            const uint16_t* xb_lo, const float* wts, const float* lam, int a_stride,
+                                            int bh, int c, int fb0, int tid, StateRegs& r) {
     const int t0 = c * C, L = min(C, d.T - t0);
     const size_t tok0 = size_t(bh) * d.T + t0;
+    const int astride = VEC ? a_stride : D;
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        u32x4 v = *reinterpret_cast<const u32x4*>(xa + (tok0 + min(row, L - 1)) * D + cp * 8);
+        u32x4 v = *reinterpret_cast<const u32x4*>(xa + (tok0 + min(row, L - 1)) * astride + cp * 8);
         const uint32_t keep = row < L ? 0xffffffffu : 0u;
         r.a[it] = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
     }
     const int row = tid >> 2, cp = tid & 3;
-    u32x4 v = *reinterpret_cast<const u32x4*>(xb + (tok0 + min(row, L - 1)) * D + fb0 + cp * 8);
+    const size_t boff = (tok0 + min(row, L - 1)) * D + fb0 + cp * 8;
+    u32x4 v = *reinterpret_cast<const u32x4*>(xb + boff);
     const uint32_t keep = row < L ? 0xffffffffu : 0u;
     r.b = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
-    if (DEC) {
+    if (VEC) {
+        v = *reinterpret_cast<const u32x4*>(xb_lo + boff);
+        r.blo = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
+        r.lam = lam[(size_t(bh) * d.N + c) * D + fb0 + (tid & 31)];
+    } else if (DEC) {
         r.w = wts[(size_t(bh) * d.N + c) * C + row];
         r.lam = lam[size_t(bh) * d.N + c];
     }
 }
 // The B slice carries the decay: each row is multiplied by its token's weight in fp32 and stored as a
 // bf16 head plus a bf16 remainder, once per workgroup.
-template <bool DEC>
+template <bool DEC, bool VEC>
 __device__ __forceinline__ void state_to_lds(const StateRegs& r, uint16_t* bufA, uint16_t* bufB, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         *reinterpret_cast<u32x4*>(bufA + row * LD + cp * 8) = r.a[it];
     }
     uint16_t* dst = bufB + (tid >> 2) * LDB + (tid & 3) * 8;
-    if (DEC) {
+    if (VEC) {
+        *reinterpret_cast<u32x4*>(dst) = r.b;
+        *reinterpret_cast<u32x4*>(dst + C * LDB) = r.blo;
+    } else if (DEC) {
         u32x4 hi, lo;
         _Pragma("unroll") for (int p = 0; p < 4; ++p) {
             const float x0 = bf16_lo(r.b[p]) * r.w, x1 = bf16_hi(r.b[p]) * r.w;
@@ -280,19 +174,27 @@ __device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage
     }
 }
 
-struct StateArgs {
-    const uint16_t *xa, *xb;
-    const float *wts, *lam;
-    uint16_t *states, *states_rem;
-    const float* edge_in;
-    float* edge_out;
-};
+// One wave's staged block for the untransposed store of MODE 3: rows = this wave's 32 state rows m,
+// columns = the workgroup's 32 state columns n, written to dst[(32 mb + m)][n0 + n] as 64-byte pieces.
+__device__ __forceinline__ void state_store_plain(uint16_t* dst, const uint16_t* stage, int mb, int lane) {
+    _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+        const int row = 16 * it + (lane >> 2), col = 8 * (lane & 3);
+        *reinterpret_cast<u32x4*>(dst + (32 * mb + row) * D + col) =
+            *reinterpret_cast<const u32x4*>(stage + row * LD + 32 * mb + col);
+    }
+}
 
-template <int MODE, bool DEC, bool REM>
+// VEC (per-key-feature decay): the decayed operand (k e^{b_C-b} or q e^{b}) arrives precomputed as a
+// head and a remainder plane and is always the B side, so that a state column n is one key feature i
+// and e^{b_C[i]} is one factor per lane; the A side is a 128-wide slice of the value-sized operand
+// (row stride d_v), each slice being scanned like a sequence of its own.
+//   MODE 3 (VEC only): forward states with the operands of MODE 1, stored S^T [v][i] like MODE 0.
+template <int MODE, bool DEC, bool REM, bool VEC>
 __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& sa, int wg_id, int wg_count,
                                                 unsigned char* smem) {
     const uint16_t* __restrict__ xa = sa.xa;
     const uint16_t* __restrict__ xb = sa.xb;
+    const uint16_t* __restrict__ xb_lo = sa.xb_lo;
     const float* __restrict__ wts = sa.wts;
     const float* __restrict__ lam = sa.lam;
     uint16_t* __restrict__ states = sa.states;
@@ -301,53 +203,61 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     float* __restrict__ edge_out = sa.edge_out;
     uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);         // [2][kStateTile]
     uint16_t* stage = tiles + 2 * kStateTile;                    // [2][32 * LD]: head, remainder
-    // The four workgroups of a (b,h) pair read the same A-side rows.  Workgroups are dealt to the 8
+    // The four workgroups of a sequence read the same A-side rows.  Workgroups are dealt to the 8
     // XCDs round-robin by linear id, so the id is decoded such that those four share an XCD (and
-    // its L2): id = xcd + 8 * (4 * (bh / 8) + nb), bh = xcd + 8 * (bh / 8).
-    int nb, bh;
+    // its L2): id = xcd + 8 * (4 * (seq / 8) + nb), seq = xcd + 8 * (seq / 8).
+    int nb, seq;
     {
         const int id = wg_id, nwg = wg_count, full = (nwg / 32) * 32;  // 32 = 8 XCDs x 4 blocks
         if (id < full) {
             const int xcd = id & 7, slot = id >> 3;
             nb = slot & 3;
-            bh = xcd + 8 * (slot >> 2);
-        } else {  // tail when B*H is not a multiple of 8
+            seq = xcd + 8 * (slot >> 2);
+        } else {  // tail when the number of sequences is not a multiple of 8
             nb = (id - full) & 3;
-            bh = (full >> 2) + ((id - full) >> 2);
+            seq = (full >> 2) + ((id - full) >> 2);
         }
     }
+    const int bh = VEC ? seq / sa.vh_count : seq, vh = VEC ? seq % sa.vh_count : 0;
     const int tid = threadIdx.x, lane = tid & 63, mb = tid >> 6;
     const int n = lane & 31, half = lane >> 5;
     constexpr int sz = D * D;
+    const int erow = VEC ? sa.a_stride : D;  // row stride of the fp32 edge states [i][v]
 
     // acc[4g+j] = state element (m = 32mb + 8g + 4half + j, n = 32nb + lane%32); MODE 0: m = i, else m = v
     f32x16 acc = {0};
     if (edge_in) {
-        const float* e = edge_in + size_t(bh) * sz;
+        const float* e = edge_in + size_t(bh) * D * erow + D * vh;
         _Pragma("unroll") for (int r = 0; r < 16; ++r) {
             const int mm = 32 * mb + 8 * (r >> 2) + 4 * half + (r & 3), nn = 32 * nb + n;
-            acc[r] = MODE == 0 ? e[mm * D + nn] : e[nn * D + mm];
+            acc[r] = MODE == 0 ? e[mm * erow + nn] : e[nn * erow + mm];
         }
     }
     const int first = MODE == 2 ? d.N - 1 : 0, step = MODE == 2 ? -1 : 1;
     auto bufA = [&](int k) { return tiles + (k & 1) * kStateTile; };
     auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
-    auto slot = [&](int k) { return (size_t(bh) * d.N + (first + step * k)) * sz + size_t(32 * nb) * D; };
+    auto slot = [&](int k) {
+        return (size_t(seq) * d.N + (first + step * k)) * sz + (MODE == 3 ? size_t(32 * nb) : size_t(32 * nb) * D);
+    };
+    const uint16_t* xav = xa + (VEC ? D * vh : 0);
+    auto gload = [&](int c, StateRegs& r) {
+        state_gload<DEC, VEC>(d, xav, xb, xb_lo, wts, lam, sa.a_stride, bh, c, 32 * nb, tid, r);
+    };
 
     // prologue: chunks 0 and 1 -> LDS, chunk 2 in flight.  Global loads are issued two iterations
     // before their data is written to LDS: one iteration is shorter than a trip to HBM.
     StateRegs r0, r1, r2;
     float lam_cur = 1.f, lam_nxt = 1.f;
-    state_gload<DEC>(d, xa, xb, wts, lam, bh, first, 32 * nb, tid, r0);
-    if (d.N > 1) state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step, 32 * nb, tid, r1);
-    state_to_lds<DEC>(r0, bufA(0), bufB(0), tid);
+    gload(first, r0);
+    if (d.N > 1) gload(first + step, r1);
+    state_to_lds<DEC, VEC>(r0, bufA(0), bufB(0), tid);
     lam_cur = r0.lam;
     if (d.N > 1) {
-        state_to_lds<DEC>(r1, bufA(1), bufB(1), tid);
+        state_to_lds<DEC, VEC>(r1, bufA(1), bufB(1), tid);
         lam_nxt = r1.lam;
     }
-    state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(2, d.N - 1), 32 * nb, tid, r0);
-    state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(3, d.N - 1), 32 * nb, tid, r1);
+    gload(first + step * min(2, d.N - 1), r0);
+    gload(first + step * min(3, d.N - 1), r1);
     __syncthreads();
 
     // One chunk, straight-line code: rw holds chunk k+2 (loaded three iterations ago, written to LDS
@@ -355,10 +265,13 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     // buffer nobody reads).  The three register sets rotate by unrolling, never by copying: a copy
     // would wait for the load issued in the same iteration.
     auto iteration = [&](int k, StateRegs& rw, StateRegs& rl) {
-        state_gload<DEC>(d, xa, xb, wts, lam, bh, first + step * min(k + 4, d.N - 1), 32 * nb, tid, rl);
+        gload(first + step * min(k + 4, d.N - 1), rl);
         // stage the state this chunk starts from (MODE 2: the gradient this chunk ends with)
         uint16_t* sh = stage;
-        if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
+        if (MODE == 3) {
+            _Pragma("unroll") for (int x = 0; x < 16; ++x)
+                sh[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
+        } else if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
         else store_block_t(sh, LD, n, 32 * mb, half, acc);
         if (DEC) {
             _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[x] *= lam_cur;
@@ -371,9 +284,10 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
             if (DEC) acc = mfma(fa, frag_tr(tb + C * LDB, LDB, 16 * ks, 0, lane), acc);
         }
         __syncthreads();  // every wave is done with the tiles of chunk k
-        state_to_lds<DEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
-        state_store(states + slot(k), sh, mb, lane);
-        if (states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, lane);
+        state_to_lds<DEC, VEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
+        if (MODE == 3) state_store_plain(states + slot(k), sh, mb, lane);
+        else state_store(states + slot(k), sh, mb, lane);
+        if (MODE != 3 && states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, lane);
         lam_cur = lam_nxt;
         lam_nxt = rw.lam;
     };
@@ -387,11 +301,11 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     if (k + 1 < d.N) iteration(k + 1, r1, r0);
     __syncthreads();
     if (edge_out) {
-        float* e = edge_out + size_t(bh) * sz;
+        float* e = edge_out + size_t(bh) * D * erow + D * vh;
         _Pragma("unroll") for (int x = 0; x < 16; ++x) {
             const int mm = 32 * mb + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * nb + n;
-            if (MODE == 0) e[mm * D + nn] = acc[x];
-            else e[nn * D + mm] = acc[x];
+            if (MODE == 0) e[mm * erow + nn] = acc[x];
+            else e[nn * erow + mm] = acc[x];
         }
     }
 }
@@ -399,7 +313,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
 template <int MODE, bool DEC>
 __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, StateArgs sa) {
     extern __shared__ __align__(16) unsigned char smem[];
-    state_scan_body<MODE, DEC, false>(d, sa, blockIdx.x, gridDim.x, smem);
+    state_scan_body<MODE, DEC, false, false>(d, sa, blockIdx.x, gridDim.x, smem);
 }
 
 // The two scans of the backward pass (states forward in time, state gradients backward in time) are
@@ -408,22 +322,10 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, StateArgs sa) {
 template <bool DEC, bool REM>
 __global__ __launch_bounds__(kThreads) void mk_state_pair(Dims d, StateArgs s1, StateArgs s2) {
     extern __shared__ __align__(16) unsigned char smem[];
-    if (blockIdx.y == 0) state_scan_body<1, DEC, REM>(d, s1, blockIdx.x, gridDim.x, smem);
-    else state_scan_body<2, DEC, false>(d, s2, blockIdx.x, gridDim.x, smem);
+    if (blockIdx.y == 0) state_scan_body<1, DEC, REM, false>(d, s1, blockIdx.x, gridDim.x, smem);
+    else state_scan_body<2, DEC, false, false>(d, s2, blockIdx.x, gridDim.x, smem);
 }
 
-// same as frag_tr, k in the permuted order of a D-layout operand: tokens row0 + 4*half + {0..3}
-// and row0 + 8 + 4*half + {0..3}
-__device__ __forceinline__ bf16x8 frag_tr_perm(const uint16_t* tile, int ld, int row0, int col0, int lane) {
-    const int r = lane & 15, nblk = (lane >> 4) & 1, half = lane >> 5;
-    const uint16_t* p = tile + (row0 + 4 * half + (r >> 2)) * ld + col0 + 16 * nblk + 4 * (r & 3);
-    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * ld));
-    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-    u32x4 v = {l2.x, l2.y, h2.x, h2.y};
-    return __builtin_bit_cast(bf16x8, v);
-}
 
 // D[m][n] = sum_f Am[m0 + m][f] * Bm[n0 + n][f] over the 128 features of two row-major LDS tiles
 __device__ __forceinline__ f32x16 score_block(const uint16_t* Am, int m0, const uint16_t* Bm, int n0, int n, int half) {
@@ -455,31 +357,6 @@ __device__ __forceinline__ void decay_mask(f32x16& acc, int m0, int ncol, const 
     }
 }
 
-// head and remainder operands (two k-steps each) of a D-layout block
-__device__ __forceinline__ void split_ops(const f32x16& d, bf16x8* hi, bf16x8* lo) {
-    f32x16 rem;
-    _Pragma("unroll") for (int x = 0; x < 16; x += 2) {
-        const uint32_t h = pack2(d[x], d[x + 1]);
-        rem[x] = d[x] - bf16_lo(h);
-        rem[x + 1] = d[x + 1] - bf16_hi(h);
-    }
-    hi[0] = pack_step(d, 0);
-    hi[1] = pack_step(d, 1);
-    lo[0] = pack_step(rem, 0);
-    lo[1] = pack_step(rem, 1);
-}
-
-struct PackedBlock { u32x2 v[4]; };  // a D-layout block rounded to bf16: v[g] = rows 8g + 4half + 0..3
-__device__ __forceinline__ PackedBlock pack_block(const f32x16& d) {
-    PackedBlock p;
-    _Pragma("unroll") for (int g = 0; g < 4; ++g)
-        p.v[g] = u32x2{pack2(d[4 * g + 0], d[4 * g + 1]), pack2(d[4 * g + 2], d[4 * g + 3])};
-    return p;
-}
-__device__ __forceinline__ void store_packed(uint16_t* dst, int ld, int nrow, int m0, int half, const PackedBlock& p) {
-    _Pragma("unroll") for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<u32x2*>(dst + nrow * ld + m0 + 8 * g + 4 * half) = p.v[g];
-}
 // sum over this lane's 16 features of x[tok][32w + ...] * acc[...]
 __device__ __forceinline__ float row_dot(const uint16_t* X, int tok, int wave, int half, const f32x16& a) {
     float s = 0.f;
@@ -773,9 +650,21 @@ __global__ void mk_head_reduce(Dims d, const float* __restrict__ dg_tok, float* 
     if (threadIdx.x == 0) dg[h] = part[0];
 }
 
+// the forward state scan of the vector decay kind
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void mk_state_vec(Dims d, StateArgs sa) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    state_scan_body<MODE, true, false, true>(d, sa, blockIdx.x, gridDim.x, smem);
+}
+
+#include "lsm_mfma_vec.h"
+
 struct Ws {
     uint16_t *states, *dstates, *states_rem;
     float *dg_tok, *wdec, *winc, *lam;
+    // vector decay: decayed operand planes [BH*T][128], chunk decay totals [BH*N][128], scores [BH*N][64][64]
+    uint16_t *khat_hi, *khat_lo, *qhat_hi, *qhat_lo, *p_hi, *p_lo;
+    float* lamv;
     size_t bytes;
 };
 
@@ -783,8 +672,18 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
     char* p = static_cast<char*>(ws);
     size_t off = 0;
     Ws w{};
-    const size_t st = align256(size_t(d.BH()) * d.N * D * D * 2);
+    const size_t st = align256(size_t(d.BH()) * (d.dv / D) * d.N * D * D * 2);
     w.states = reinterpret_cast<uint16_t*>(p + off); off += st;
+    if (d.kind == 3) {
+        const size_t plane = align256(size_t(d.BH()) * d.T * D * 2), sc = align256(size_t(d.BH()) * d.N * C * C * 2);
+        uint16_t** planes[4] = {&w.khat_hi, &w.khat_lo, &w.qhat_hi, &w.qhat_lo};
+        for (auto pp : planes) { *pp = reinterpret_cast<uint16_t*>(p + off); off += plane; }
+        w.p_hi = reinterpret_cast<uint16_t*>(p + off); off += sc;
+        w.p_lo = reinterpret_cast<uint16_t*>(p + off); off += sc;
+        w.lamv = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * D * 4);
+        w.bytes = off;
+        return w;
+    }
     if (bwd) { w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st; }
     if (bwd && d.kind != 0) { w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += st; }
     if (d.kind != 0) {
@@ -805,8 +704,10 @@ hipError_t allow_lds(K kernel, int bytes) {
 }  // namespace
 
 bool mfma_supported(const Dims& d) {
-    return d.bf16 && d.C == C && d.dk == D && d.dv == D && d.kind != 3;
+    if (!(d.bf16 && d.C == C && d.dk == D)) return false;
+    return d.kind == 3 ? d.dv % D == 0 : d.dv == D;
 }
+bool mfma_bwd_supported(const Dims& d) { return mfma_supported(d) && d.kind != 3; }
 
 size_t mfma_fwd_workspace(const Dims& d) { return carve(d, nullptr, false).bytes; }
 size_t mfma_bwd_workspace(const Dims& d) { return carve(d, nullptr, true).bytes; }
@@ -846,7 +747,40 @@ void launch_prep(const Dims& d, hipStream_t st, const float* g, const Ws& w) {
 }
 }  // namespace
 
+namespace {
+hipError_t launch_vec_prep(const Dims& d, hipStream_t st, const uint16_t* q, const uint16_t* k, const float* g, const Ws& w) {
+    const hipError_t e = allow_lds(mk_vec_prep, kPrepLds);
+    if (e != hipSuccess) return e;
+    ProfScope ps(KID_MFMA_VEC_PREP, st);
+    hipLaunchKernelGGL(mk_vec_prep, dim3(d.N, d.BH()), dim3(kThreads), kPrepLds, st, d, q, k, g, w.khat_hi, w.khat_lo,
+                       w.qhat_hi, w.qhat_lo, w.lamv, w.p_hi, w.p_lo);
+    return hipSuccess;
+}
+
+hipError_t vec_fwd(const Dims& d, const FwdArgs& a) {
+    Ws w = carve(d, a.ws, false);
+    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    const int nvh = d.dv / D;
+    hipError_t e;
+    if ((e = launch_vec_prep(d, a.stream, q, k, a.g, w)) != hipSuccess) return e;
+    {
+        ProfScope ps(KID_MFMA_STATE, a.stream);
+        if ((e = allow_lds(mk_state_vec<3>, kStateLds)) != hipSuccess) return e;
+        StateArgs sa{v, w.khat_hi, nullptr, w.lamv, w.states, nullptr, a.m0, a.mT, w.khat_lo, d.dv, nvh};
+        hipLaunchKernelGGL(mk_state_vec<3>, dim3(D / 32 * d.BH() * nvh), dim3(kThreads), kStateLdsNoRem, a.stream, d, sa);
+    }
+    {
+        ProfScope ps(KID_MFMA_OUTPUT, a.stream);
+        if ((e = allow_lds(mk_output_vec, kOutVecLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(mk_output_vec, dim3(d.N, d.BH(), nvh), dim3(kThreads), kOutVecLds, a.stream, d, w.qhat_hi, w.qhat_lo, v,
+                           w.p_hi, w.p_lo, w.states, static_cast<uint16_t*>(a.o));
+    }
+    return hipGetLastError();
+}
+}  // namespace
+
 hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
+    if (d.kind == 3) return vec_fwd(d, a);
     Ws w = carve(d, a.ws, false);
     const dim3 grid(d.N, d.BH()), block(kThreads);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);

@@ -1,0 +1,153 @@
+// Device helpers shared by the MFMA kernel files: vector types, the 32x32x16 bf16 MFMA and the
+// operand access patterns built on its register layout (wave64, l = lane, half = l/32):
+//   A operand: lane holds A[m = l%32][k = 8*half + e],  e = 0..7
+//   B operand: lane holds B[k = 8*half + e][n = l%32]
+//   D result : lane holds D[m = 8*g + 4*half + j][n = l%32] in register 4*g + j
+#pragma once
+#include "lsm_internal.h"
+
+namespace lsm {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int C = 64;      // tokens per chunk
+constexpr int D = 128;     // d_k = d_v
+constexpr int LD = D + 8;  // row stride (elements) of a [*, 128] bf16 tile in LDS: 68 words, == 4 mod 32
+constexpr int LDP = C + 8; // row stride of a [*, 64] bf16 tile in LDS: 36 words, == 4 mod 32
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    f32x2 f = {lo, hi};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// 8 consecutive bf16 of row `row` starting at column `col` (16-byte aligned)
+__device__ __forceinline__ bf16x8 frag(const uint16_t* tile, int ld, int row, int col) {
+    return *reinterpret_cast<const bf16x8*>(tile + row * ld + col);
+}
+// k index in the permuted order of a D-layout operand: columns col0 + 4*half + {0..3} and col0 + 8 + 4*half + {0..3}
+__device__ __forceinline__ bf16x8 frag_perm(const uint16_t* tile, int ld, int row, int col0, int half) {
+    u32x2 lo = *reinterpret_cast<const u32x2*>(tile + row * ld + col0 + 4 * half);
+    u32x2 hi = *reinterpret_cast<const u32x2*>(tile + row * ld + col0 + 8 + 4 * half);
+    u32x4 v = {lo.x, lo.y, hi.x, hi.y};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// Token-major operand straight out of a row-major [token][feature] LDS tile with the LDS transpose
+// read: lane l receives feature col0 + l%32 of tokens row0 + 8*(l/32) + 0..7 (natural k order).
+// Each group of 16 lanes reads a 4-token x 16-feature patch as 8-byte pieces (lane r of the group:
+// token r/4, features 4*(r%4)..+3) and the hardware hands lane i of the group feature i, 4 tokens.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 frag_tr(const uint16_t* tile, int ld, int row0, int col0, int lane) {
+    const int r = lane & 15, nblk = (lane >> 4) & 1, half = lane >> 5;
+    const uint16_t* p = tile + (row0 + 8 * half + (r >> 2)) * ld + col0 + 16 * nblk + 4 * (r & 3);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ld));
+    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    u32x4 v = {l2.x, l2.y, h2.x, h2.y};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// registers 8*s .. 8*s+7 of a D-layout block as the operand of k-step s
+__device__ __forceinline__ bf16x8 pack_step(const f32x16& d, int s) {
+    u32x4 v = {pack2(d[8 * s + 0], d[8 * s + 1]), pack2(d[8 * s + 2], d[8 * s + 3]),
+               pack2(d[8 * s + 4], d[8 * s + 5]), pack2(d[8 * s + 6], d[8 * s + 7])};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// write a D-layout block as 8-byte pieces: dst[(n)][m0 + 8g + 4half + 0..3], row stride ld
+__device__ __forceinline__ void store_block_t(uint16_t* dst, int ld, int nrow, int m0, int half, const f32x16& d) {
+    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+        u32x2 v = {pack2(d[4 * g + 0], d[4 * g + 1]), pack2(d[4 * g + 2], d[4 * g + 3])};
+        *reinterpret_cast<u32x2*>(dst + nrow * ld + m0 + 8 * g + 4 * half) = v;
+    }
+}
+
+// same, as a bf16 head in `hi` and the bf16 remainder in `lo` (x = hi + lo to ~2^-17)
+__device__ __forceinline__ void store_block_t_split(uint16_t* hi, uint16_t* lo, int ld, int nrow, int m0, int half,
+                                                    const f32x16& d) {
+    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+        const uint32_t h0 = pack2(d[4 * g + 0], d[4 * g + 1]), h1 = pack2(d[4 * g + 2], d[4 * g + 3]);
+        u32x2 vh = {h0, h1};
+        u32x2 vl = {pack2(d[4 * g + 0] - bf16_lo(h0), d[4 * g + 1] - bf16_hi(h0)),
+                    pack2(d[4 * g + 2] - bf16_lo(h1), d[4 * g + 3] - bf16_hi(h1))};
+        *reinterpret_cast<u32x2*>(hi + nrow * ld + m0 + 8 * g + 4 * half) = vh;
+        *reinterpret_cast<u32x2*>(lo + nrow * ld + m0 + 8 * g + 4 * half) = vl;
+    }
+}
+
+// 64 x 128 bf16 tile: global rows [tok0, tok0+L) -> LDS (row stride LD), rows >= L zero
+__device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        u32x4 v = {0, 0, 0, 0};
+        if (row < L) v = *reinterpret_cast<const u32x4*>(src + (tok0 + row) * D + cp * 8);
+        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = v;
+    }
+}
+// LDS tile (row stride LD) rows [0, L) -> global
+__device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        if (row < L)
+            *reinterpret_cast<u32x4*>(dst + (tok0 + row) * D + cp * 8) =
+                *reinterpret_cast<const u32x4*>(src + row * LD + cp * 8);
+    }
+}
+
+// same as frag_tr, k in the permuted order of a D-layout operand: tokens row0 + 4*half + {0..3}
+// and row0 + 8 + 4*half + {0..3}
+__device__ __forceinline__ bf16x8 frag_tr_perm(const uint16_t* tile, int ld, int row0, int col0, int lane) {
+    const int r = lane & 15, nblk = (lane >> 4) & 1, half = lane >> 5;
+    const uint16_t* p = tile + (row0 + 4 * half + (r >> 2)) * ld + col0 + 16 * nblk + 4 * (r & 3);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * ld));
+    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    u32x4 v = {l2.x, l2.y, h2.x, h2.y};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// head and remainder operands (two k-steps each) of a D-layout block
+__device__ __forceinline__ void split_ops(const f32x16& d, bf16x8* hi, bf16x8* lo) {
+    f32x16 rem;
+    _Pragma("unroll") for (int x = 0; x < 16; x += 2) {
+        const uint32_t h = pack2(d[x], d[x + 1]);
+        rem[x] = d[x] - bf16_lo(h);
+        rem[x + 1] = d[x + 1] - bf16_hi(h);
+    }
+    hi[0] = pack_step(d, 0);
+    hi[1] = pack_step(d, 1);
+    lo[0] = pack_step(rem, 0);
+    lo[1] = pack_step(rem, 1);
+}
+
+struct PackedBlock { u32x2 v[4]; };  // a D-layout block rounded to bf16: v[g] = rows 8g + 4half + 0..3
+__device__ __forceinline__ PackedBlock pack_block(const f32x16& d) {
+    PackedBlock p;
+    _Pragma("unroll") for (int g = 0; g < 4; ++g)
+        p.v[g] = u32x2{pack2(d[4 * g + 0], d[4 * g + 1]), pack2(d[4 * g + 2], d[4 * g + 3])};
+    return p;
+}
+__device__ __forceinline__ void store_packed(uint16_t* dst, int ld, int nrow, int m0, int half, const PackedBlock& p) {
+    _Pragma("unroll") for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<u32x2*>(dst + nrow * ld + m0 + 8 * g + 4 * half) = p.v[g];
+}
+
+}  // namespace
+}  // namespace lsm
