@@ -89,6 +89,7 @@ constexpr int LDB = 40;  // row stride (elements) of a 64 x 32 B-side slice in L
 constexpr int kStateTile = C * LD + 2 * C * LDB;
 constexpr int kStateLds = (2 * kStateTile + 2 * 32 * LD) * 2;      // with the remainder plane
 constexpr int kStateLdsNoRem = (2 * kStateTile + 1 * 32 * LD) * 2; // without
+constexpr int kStateLdsTwin = (2 * kStateTile + 3 * 32 * LD) * 2;  // head, remainder and the untransposed twin
 
 struct StateRegs {  // one thread's share of a chunk on its way from global memory to LDS
     u32x4 a[4], b, blo;  // blo: remainder plane of the B slice (vector decay: both planes arrive precomputed)
@@ -106,6 +107,7 @@ struct StateArgs {
     const uint16_t* xb_lo;  // remainder plane of the decayed B-side operand
     int a_stride;           // row stride (elements) of the A-side operand = d_v
     int vh_count;           // 128-wide value slices per (b,h); each is scanned as a sequence of its own
+    uint16_t* states_twin;  // MODE 2 only: second copy of the head, untransposed (dS^T [v][i]), or NULL
 };
 
 // coalesced: the A side as whole 256-byte rows (16 lanes per row), the B side as 64-byte row slices.
@@ -189,6 +191,7 @@ __device__ __forceinline__ void state_store_plain(uint16_t* dst, const uint16_t*
 // and e^{b_C[i]} is one factor per lane; the A side is a 128-wide slice of the value-sized operand
 // (row stride d_v), each slice being scanned like a sequence of its own.
 //   MODE 3 (VEC only): forward states with the operands of MODE 1, stored S^T [v][i] like MODE 0.
+//   MODE 2 with VEC: states_twin, when given, receives a second copy dS^T [v][i] (for the dv kernel).
 template <int MODE, bool DEC, bool REM, bool VEC>
 __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& sa, int wg_id, int wg_count,
                                                 unsigned char* smem) {
@@ -199,6 +202,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     const float* __restrict__ lam = sa.lam;
     uint16_t* __restrict__ states = sa.states;
     uint16_t* __restrict__ states_rem = sa.states_rem;
+    uint16_t* __restrict__ states_twin = sa.states_twin;
     const float* __restrict__ edge_in = sa.edge_in;
     float* __restrict__ edge_out = sa.edge_out;
     uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);         // [2][kStateTile]
@@ -236,9 +240,8 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     const int first = MODE == 2 ? d.N - 1 : 0, step = MODE == 2 ? -1 : 1;
     auto bufA = [&](int k) { return tiles + (k & 1) * kStateTile; };
     auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
-    auto slot = [&](int k) {
-        return (size_t(seq) * d.N + (first + step * k)) * sz + (MODE == 3 ? size_t(32 * nb) : size_t(32 * nb) * D);
-    };
+    auto slot_plain = [&](int k) { return (size_t(seq) * d.N + (first + step * k)) * sz + size_t(32 * nb); };
+    auto slot = [&](int k) { return MODE == 3 ? slot_plain(k) : slot_plain(k) + size_t(32 * nb) * (D - 1); };
     const uint16_t* xav = xa + (VEC ? D * vh : 0);
     auto gload = [&](int c, StateRegs& r) {
         state_gload<DEC, VEC>(d, xav, xb, xb_lo, wts, lam, sa.a_stride, bh, c, 32 * nb, tid, r);
@@ -268,11 +271,16 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         gload(first + step * min(k + 4, d.N - 1), rl);
         // stage the state this chunk starts from (MODE 2: the gradient this chunk ends with)
         uint16_t* sh = stage;
-        if (MODE == 3) {
+        constexpr bool kTwin = VEC && MODE == 2;  // second copy, untransposed
+        if (MODE == 3 || (kTwin && states_twin)) {
+            uint16_t* sp = MODE == 3 ? sh : sh + 64 * LD;
             _Pragma("unroll") for (int x = 0; x < 16; ++x)
-                sh[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
-        } else if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
-        else store_block_t(sh, LD, n, 32 * mb, half, acc);
+                sp[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
+        }
+        if (MODE != 3) {
+            if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
+            else store_block_t(sh, LD, n, 32 * mb, half, acc);
+        }
         if (DEC) {
             _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[x] *= lam_cur;
         }
@@ -288,6 +296,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         if (MODE == 3) state_store_plain(states + slot(k), sh, mb, lane);
         else state_store(states + slot(k), sh, mb, lane);
         if (MODE != 3 && states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, lane);
+        if (kTwin && states_twin) state_store_plain(states_twin + slot_plain(k), sh + 64 * LD, mb, lane);
         lam_cur = lam_nxt;
         lam_nxt = rw.lam;
     };
@@ -657,10 +666,18 @@ __global__ __launch_bounds__(kThreads) void mk_state_vec(Dims d, StateArgs sa) {
     state_scan_body<MODE, true, false, true>(d, sa, blockIdx.x, gridDim.x, smem);
 }
 
+// both scans of the backward pass, vector decay kind (REM: also the remainder plane of S)
+template <bool REM>
+__global__ __launch_bounds__(kThreads) void mk_state_pair_vec(Dims d, StateArgs s1, StateArgs s2) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (blockIdx.y == 0) state_scan_body<1, true, REM, true>(d, s1, blockIdx.x, gridDim.x, smem);
+    else state_scan_body<2, true, REM, true>(d, s2, blockIdx.x, gridDim.x, smem);
+}
+
 #include "lsm_mfma_vec.h"
 
 struct Ws {
-    uint16_t *states, *dstates, *states_rem;
+    uint16_t *states, *dstates, *states_rem, *dstates_t, *dstates_rem;
     float *dg_tok, *wdec, *winc, *lam;
     // vector decay: decayed operand planes [BH*T][128], chunk decay totals [BH*N][128], scores [BH*N][64][64]
     uint16_t *khat_hi, *khat_lo, *qhat_hi, *qhat_lo, *p_hi, *p_lo;
@@ -675,6 +692,12 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
     const size_t st = align256(size_t(d.BH()) * (d.dv / D) * d.N * D * D * 2);
     w.states = reinterpret_cast<uint16_t*>(p + off); off += st;
     if (d.kind == 3) {
+        if (bwd) {
+            w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st;
+            w.dstates_t = reinterpret_cast<uint16_t*>(p + off); off += st;
+            w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += st;
+            w.dstates_rem = reinterpret_cast<uint16_t*>(p + off); off += st;
+        }
         const size_t plane = align256(size_t(d.BH()) * d.T * D * 2), sc = align256(size_t(d.BH()) * d.N * C * C * 2);
         uint16_t** planes[4] = {&w.khat_hi, &w.khat_lo, &w.qhat_hi, &w.qhat_lo};
         for (auto pp : planes) { *pp = reinterpret_cast<uint16_t*>(p + off); off += plane; }
@@ -707,7 +730,7 @@ bool mfma_supported(const Dims& d) {
     if (!(d.bf16 && d.C == C && d.dk == D)) return false;
     return d.kind == 3 ? d.dv % D == 0 : d.dv == D;
 }
-bool mfma_bwd_supported(const Dims& d) { return mfma_supported(d) && d.kind != 3; }
+bool mfma_bwd_supported(const Dims& d) { return mfma_supported(d); }
 
 size_t mfma_fwd_workspace(const Dims& d) { return carve(d, nullptr, false).bytes; }
 size_t mfma_bwd_workspace(const Dims& d) { return carve(d, nullptr, true).bytes; }
@@ -771,8 +794,8 @@ hipError_t vec_fwd(const Dims& d, const FwdArgs& a) {
     }
     {
         ProfScope ps(KID_MFMA_OUTPUT, a.stream);
-        if ((e = allow_lds(mk_output_vec, kOutVecLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL(mk_output_vec, dim3(d.N, d.BH(), nvh), dim3(kThreads), kOutVecLds, a.stream, d, w.qhat_hi, w.qhat_lo, v,
+        if ((e = allow_lds(mk_output_vec<false>, kOutVecLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(mk_output_vec<false>, dim3(d.N, d.BH(), nvh), dim3(kThreads), kOutVecLds, a.stream, d, w.qhat_hi, w.qhat_lo, v,
                            w.p_hi, w.p_lo, w.states, static_cast<uint16_t*>(a.o));
     }
     return hipGetLastError();
@@ -800,7 +823,48 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     return hipGetLastError();
 }
 
+namespace {
+hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
+    hipError_t e;
+    Ws w = carve(d, a.ws, true);
+    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    auto d_o = static_cast<const uint16_t*>(a.d_o);
+    const int nvh = d.dv / D;
+    if ((e = launch_vec_prep(d, a.stream, q, k, a.g, w)) != hipSuccess) return e;
+    {
+        ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
+        const StateArgs s1{v, w.khat_hi, nullptr, w.lamv, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr,
+                           w.khat_lo, d.dv, nvh};
+        const StateArgs s2{d_o, w.qhat_hi, nullptr, w.lamv, w.dstates, a.dg ? w.dstates_rem : nullptr, a.d_mT, a.d_m0,
+                           w.qhat_lo, d.dv, nvh, w.dstates_t};
+        const dim3 sgrid(D / 32 * d.BH() * nvh, 2);
+        if (a.dg) {
+            if ((e = allow_lds(mk_state_pair_vec<true>, kStateLdsTwin)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_state_pair_vec<true>, sgrid, dim3(kThreads), kStateLdsTwin, a.stream, d, s1, s2);
+        } else {
+            if ((e = allow_lds(mk_state_pair_vec<false>, kStateLdsTwin)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_state_pair_vec<false>, sgrid, dim3(kThreads), kStateLdsTwin, a.stream, d, s1, s2);
+        }
+    }
+    {
+        ProfScope ps(KID_MFMA_VEC_DV, a.stream);
+        if ((e = allow_lds(mk_output_vec<true>, kOutVecLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(mk_output_vec<true>, dim3(d.N, d.BH(), nvh), dim3(kThreads), kOutVecLds, a.stream, d, w.khat_hi,
+                           w.khat_lo, d_o, w.p_hi, w.p_lo, w.dstates_t, static_cast<uint16_t*>(a.dv));
+    }
+    {
+        ProfScope ps(KID_MFMA_GRAD, a.stream);
+        if ((e = allow_lds(mk_grad_vec, kGradVecLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(mk_grad_vec, dim3(d.N, d.BH()), dim3(kThreads), kGradVecLds, a.stream, d, q, k, v, d_o, a.g,
+                           w.states, a.dg ? w.states_rem : nullptr, w.dstates, w.dstates_rem, static_cast<uint16_t*>(a.dq),
+                           static_cast<uint16_t*>(a.dk), a.dg);
+    }
+    return hipGetLastError();
+}
+}  // namespace
+
 hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
+    if (d.kind == 3) return vec_bwd(d, a);
     Ws w = carve(d, a.ws, true);
     const dim3 grid(d.N, d.BH()), block(kThreads);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);

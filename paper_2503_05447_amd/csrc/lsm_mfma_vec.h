@@ -38,6 +38,42 @@ __device__ __forceinline__ void weigh8(const u32x4& raw, const float* w, u32x4& 
     }
 }
 
+// Chunk-local inclusive cumulative log-decay b [64][128] (fp32, row stride LDF) into LDS; tokens >= L
+// carry g = 0.  Called by all 256 threads; ends with a barrier.
+__device__ __forceinline__ void decay_tile(float* bt, const float* __restrict__ g, size_t tok0, int L, int tid) {
+    const int cp = tid & 15, r0 = tid >> 4;
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int row = r0 + 16 * it;
+        float4 g0 = {0.f, 0.f, 0.f, 0.f}, g1 = g0;
+        if (row < L) {
+            g0 = *reinterpret_cast<const float4*>(g + (tok0 + row) * D + cp * 8);
+            g1 = *reinterpret_cast<const float4*>(g + (tok0 + row) * D + cp * 8 + 4);
+        }
+        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8) = g0;
+        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8 + 4) = g1;
+    }
+    __syncthreads();
+    // inclusive scan along tokens, one feature column per thread, two halves of 32 tokens
+    const int i = tid & 127, hh = tid >> 7;
+    float run = 0.f;
+    for (int r = 32 * hh; r < 32 * hh + 32; ++r) {
+        run += bt[r * LDF + i];
+        bt[r * LDF + i] = run;
+    }
+    __syncthreads();
+    if (hh == 1) {
+        const float base = bt[31 * LDF + i];
+        for (int r = 32; r < 64; ++r) bt[r * LDF + i] += base;
+    }
+    __syncthreads();
+}
+// 8 consecutive floats of row `row` of the decay tile
+__device__ __forceinline__ void decay_row8(const float* bt, int row, int col, float* out) {
+    const float4 x0 = *reinterpret_cast<const float4*>(bt + row * LDF + col);
+    const float4 x1 = *reinterpret_cast<const float4*>(bt + row * LDF + col + 4);
+    out[0] = x0.x; out[1] = x0.y; out[2] = x0.z; out[3] = x0.w; out[4] = x1.x; out[5] = x1.y; out[6] = x1.z; out[7] = x1.w;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Per chunk (grid: N x BH): cumulative log-decay b [64][128]; the decayed operands of the state
 // passes  khat = k e^{b_C - b},  qhat = q e^{b}  as bf16 head and remainder planes [BH*T][128];
@@ -71,21 +107,16 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
     const int n = lane & 31, half = lane >> 5;
     const int cp = tid & 15, r0 = tid >> 4;  // this thread's feature piece (8 features) and first row; rows r0 + 16 it
 
-    // raw q, k pieces stay in registers for all levels; g goes to LDS for the scan along tokens
+    // raw q, k pieces stay in registers for all levels
     u32x4 qr[4], kr[4];
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int row = r0 + 16 * it;
-        float4 g0 = {0.f, 0.f, 0.f, 0.f}, g1 = g0;
         qr[it] = u32x4{0, 0, 0, 0};
         kr[it] = u32x4{0, 0, 0, 0};
         if (row < L) {
             qr[it] = *reinterpret_cast<const u32x4*>(q + (tok0 + row) * D + cp * 8);
             kr[it] = *reinterpret_cast<const u32x4*>(k + (tok0 + row) * D + cp * 8);
-            g0 = *reinterpret_cast<const float4*>(g + (tok0 + row) * D + cp * 8);
-            g1 = *reinterpret_cast<const float4*>(g + (tok0 + row) * D + cp * 8 + 4);
         }
-        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8) = g0;
-        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8 + 4) = g1;
     }
     // diagonal scores q_t . k_t: exact products, summed over this thread's 8 features, then over the
     // 16 threads that share the row (consecutive lanes)
@@ -96,32 +127,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
         _Pragma("unroll") for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
         if (cp == 0) diag[r0 + 16 * it] = s;
     }
-    __syncthreads();
-    {   // inclusive scan along tokens, one feature column per thread, two halves of 32 tokens
-        const int i = tid & 127, hh = tid >> 7;
-        float run = 0.f;
-        for (int r = 32 * hh; r < 32 * hh + 32; ++r) {
-            run += bt[r * LDF + i];
-            bt[r * LDF + i] = run;
-        }
-        __syncthreads();
-        if (hh == 1) {
-            const float base = bt[31 * LDF + i];
-            for (int r = 32; r < 64; ++r) bt[r * LDF + i] += base;
-        }
-    }
-    __syncthreads();
+    decay_tile(bt, g, tok0, L, tid);
     float bC[8];
-    {
-        const float4 x0 = *reinterpret_cast<const float4*>(bt + 63 * LDF + cp * 8);
-        const float4 x1 = *reinterpret_cast<const float4*>(bt + 63 * LDF + cp * 8 + 4);
-        bC[0] = x0.x; bC[1] = x0.y; bC[2] = x0.z; bC[3] = x0.w; bC[4] = x1.x; bC[5] = x1.y; bC[6] = x1.z; bC[7] = x1.w;
-    }
-    auto brow = [&](int row, float* out) {
-        const float4 x0 = *reinterpret_cast<const float4*>(bt + row * LDF + cp * 8);
-        const float4 x1 = *reinterpret_cast<const float4*>(bt + row * LDF + cp * 8 + 4);
-        out[0] = x0.x; out[1] = x0.y; out[2] = x0.z; out[3] = x0.w; out[4] = x1.x; out[5] = x1.y; out[6] = x1.z; out[7] = x1.w;
-    };
+    decay_row8(bt, 63, cp * 8, bC);
+    auto brow = [&](int row, float* out) { decay_row8(bt, row, cp * 8, out); };
     // decayed operands of the state passes
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int row = r0 + 16 * it;
@@ -265,9 +274,13 @@ __device__ __forceinline__ void load_scores(uint16_t* dst, const uint16_t* src, 
 // Output of one chunk for one 128-wide slice of the value dimension (grid: N x BH x d_v/128):
 //   O^T[v][j] = sum_i S^T[v][i] qhat_j[i] + sum_{r<=j} V^T[v][r] P[j][r]
 // with qhat and P from mk_vec_prep.  Wave w owns 32 value columns.
+// DV = true computes with the same structure the value gradient
+//   dv^T[v][r] = sum_i dS^T[v][i] khat_r[i] + sum_{j>=r} dO^T[v][j] P[j][r]
+// (states = dS^T, qhat = khat, v = d_o; P is read through the LDS transpose read).
 // LDS: qhat head (later the O stage) | qhat remainder | V slice | P head | P remainder
 constexpr int kOutVecLds = 3 * C * LD * 2 + 2 * C * LDP * 2;
 
+template <bool DV>
 __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint16_t* __restrict__ qhat,
                                                              const uint16_t* __restrict__ qhat_lo,
                                                              const uint16_t* __restrict__ v,
@@ -309,10 +322,18 @@ __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint1
             acc = mfma(sfrag[ks], frag(Q, LD, j, 16 * ks + 8 * half), acc);
             acc = mfma(sfrag[ks], frag(Ql, LD, j, 16 * ks + 8 * half), acc);
         }
-        _Pragma("unroll") for (int ks = 0; ks < 2 * (jb + 1); ++ks) {  // keys r >= 32 never reach queries j < 32
-            const bf16x8 vt = frag_tr(V, LD, 16 * ks, 32 * wave, lane);
-            acc = mfma(vt, frag(Ph, LDP, j, 16 * ks + 8 * half), acc);
-            acc = mfma(vt, frag(Pl, LDP, j, 16 * ks + 8 * half), acc);
+        if (!DV) {
+            _Pragma("unroll") for (int ks = 0; ks < 2 * (jb + 1); ++ks) {  // keys r >= 32 never reach queries j < 32
+                const bf16x8 vt = frag_tr(V, LD, 16 * ks, 32 * wave, lane);
+                acc = mfma(vt, frag(Ph, LDP, j, 16 * ks + 8 * half), acc);
+                acc = mfma(vt, frag(Pl, LDP, j, 16 * ks + 8 * half), acc);
+            }
+        } else {
+            _Pragma("unroll") for (int ks = 2 * jb; ks < 4; ++ks) {  // queries j < 32 never see keys r >= 32
+                const bf16x8 vt = frag_tr(V, LD, 16 * ks, 32 * wave, lane);
+                acc = mfma(vt, frag_tr(Ph, LDP, 16 * ks, 32 * jb, lane), acc);  // B[k = j][n = r] = P[j][r]
+                acc = mfma(vt, frag_tr(Pl, LDP, 16 * ks, 32 * jb, lane), acc);
+            }
         }
         res[jb] = pack_block(acc);
     }
@@ -320,4 +341,278 @@ __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint1
     _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) store_packed(Q, LD, 32 * jb + n, 32 * wave, half, res[jb]);
     __syncthreads();
     store_tile_strided(o, Q, tok0, L, d.dv, D * vh, tid);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dq, dk and the decay gradient of one chunk (grid: N x BH), vector decay kind.
+//   dA[j][r] = d_o_j . v_r  (r <= j),   Z[u][t] = dA[max(u,t)][min(u,t)]  (symmetric, 64 x 64)
+//   dq_j[i] = e^{b_j[i]} sum_v S[i][v] d_o_j[v]           + sum_{r<j} dA[j][r] k_r[i] e^{b_j[i]-b_r[i]} + dA[j][j] k_j[i]
+//   dk_r[i] = e^{b_C[i]-b_r[i]} sum_v dS[i][v] v_r[v]     + sum_{j>r} dA[j][r] q_j[i] e^{b_j[i]-b_r[i]} + dA[r][r] q_r[i]
+//   dg_t[i] = sum_{u>=t} (q_u[i] dq_u[i] - k_u[i] dk_u[i]) + sum_r k_r[i] dk_r^{inter}[i] + e^{b_C[i]} sum_v S[i][v] dS[i][v]
+// The intra sums use the level tiles W_s of mk_vec_prep: at level s every token t is on one side, and
+//   X_s[t][i] = sum_u Z_s[u][t] W_s[u][i]     (Z_s = Z restricted to the pairs of level s)
+// times the token's own level weight is its contribution to dq_t (t on the query side) or dk_t (key
+// side).  Wave w owns features [32w, 32w+32) of dq^T, dk^T (D layout: lane = token, registers =
+// features).  Z is built once (wave 0, 1: the diagonal 32-blocks, wave 2, 3: the off-diagonal ones),
+// summed over the 128-wide value slices, and kept in LDS as bf16 head + remainder.
+// LDS: b | Q | K | T0 (V slice, then W head, then dq stage) | T1 (d_o slice, W remainder, dk stage)
+//      | Z head | Z remainder | diagonal of dA | <S,dS> per feature
+constexpr int kGradVecLds = C * LDF * 4 + 4 * C * LD * 2 + 2 * C * LDP * 2 + C * 4 + D * 4;
+
+__global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_t* __restrict__ q,
+                                                           const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                           const uint16_t* __restrict__ d_o, const float* __restrict__ g,
+                                                           const uint16_t* __restrict__ states,
+                                                           const uint16_t* __restrict__ states_rem,
+                                                           const uint16_t* __restrict__ dstates,
+                                                           const uint16_t* __restrict__ dstates_rem,
+                                                           uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
+                                                           float* __restrict__ dg) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* bt = reinterpret_cast<float*>(smem);
+    uint16_t* Qr = reinterpret_cast<uint16_t*>(bt + C * LDF);
+    uint16_t* Kr = Qr + C * LD;
+    uint16_t* T0 = Kr + C * LD;
+    uint16_t* T1 = T0 + C * LD;
+    uint16_t* Zh = T1 + C * LD;
+    uint16_t* Zl = Zh + C * LDP;
+    float* zd = reinterpret_cast<float*>(Zl + C * LDP);  // [64]
+    float* zl = zd + C;                                  // [128]
+
+    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = c * C, L = min(C, d.T - t0);
+    const size_t tok0 = size_t(bh) * d.T + t0;
+    const int n = lane & 31, half = lane >> 5;
+    const int nvh = d.dv / D;
+    const bool want_dg = dg != nullptr;  // then states_rem and dstates_rem are present
+
+    load_tile(Qr, q, tok0, L, tid);
+    load_tile(Kr, k, tok0, L, tid);
+    decay_tile(bt, g, tok0, L, tid);
+
+    // ---- inter parts and Z, slice by slice of the value dimension
+    // aqr, akr: contributions of the remainder planes of S and dS; they enter the decay gradient only, so
+    // that dq and dk do not depend on whether it is asked for
+    f32x16 aq[2] = {{0}, {0}}, aqr[2] = {{0}, {0}}, ak[2] = {{0}, {0}}, akr[2] = {{0}, {0}};
+    f32x16 z0 = {0}, z1 = {0};
+    float zi = 0.f;
+    for (int vh = 0; vh < nvh; ++vh) {
+        if (vh > 0) __syncthreads();  // the previous slice is consumed
+        load_tile_strided(T0, v, tok0, L, d.dv, D * vh, tid);
+        load_tile_strided(T1, d_o, tok0, L, d.dv, D * vh, tid);
+        const size_t soff = ((size_t(bh) * nvh + vh) * d.N + c) * D * D + size_t(32 * wave + n) * D + 8 * half;
+        const uint16_t *S = states + soff, *dS = dstates + soff;
+        __syncthreads();
+        {
+            bf16x8 sf[8];
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) sf[ks] = *reinterpret_cast<const bf16x8*>(S + 16 * ks);
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                    aq[nb] = mfma(sf[ks], frag(T1, LD, 32 * nb + n, 16 * ks + 8 * half), aq[nb]);
+        }
+        if (want_dg) {
+            bf16x8 sf[8];
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                sf[ks] = *reinterpret_cast<const bf16x8*>(states_rem + soff + 16 * ks);
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                    aqr[nb] = mfma(sf[ks], frag(T1, LD, 32 * nb + n, 16 * ks + 8 * half), aqr[nb]);
+        }
+        {
+            bf16x8 sf[8];
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) sf[ks] = *reinterpret_cast<const bf16x8*>(dS + 16 * ks);
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                    ak[nb] = mfma(sf[ks], frag(T0, LD, 32 * nb + n, 16 * ks + 8 * half), ak[nb]);
+            if (want_dg) {  // <S, dS> over this lane's share of row i = 32 wave + n
+                bf16x8 sr[8];
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                    sr[ks] = *reinterpret_cast<const bf16x8*>(dstates_rem + soff + 16 * ks);
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                    const u32x4 a = *reinterpret_cast<const u32x4*>(S + 16 * ks);
+                    const u32x4 ar = *reinterpret_cast<const u32x4*>(states_rem + soff + 16 * ks);
+                    const u32x4 b = __builtin_bit_cast(u32x4, sf[ks]), br = __builtin_bit_cast(u32x4, sr[ks]);
+                    _Pragma("unroll") for (int p = 0; p < 4; ++p)
+                        zi += (bf16_lo(a[p]) + bf16_lo(ar[p])) * (bf16_lo(b[p]) + bf16_lo(br[p])) +
+                              (bf16_hi(a[p]) + bf16_hi(ar[p])) * (bf16_hi(b[p]) + bf16_hi(br[p]));
+                }
+                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                        akr[nb] = mfma(sr[ks], frag(T0, LD, 32 * nb + n, 16 * ks + 8 * half), akr[nb]);
+            }
+        }
+        {   // this wave's block of Z: rows of V and d_o as operands
+            const int rowv = wave == 1 ? 32 + n : n;               // V row: wave 0, 2, 3: 0.., wave 1: 32..
+            const int rowo = wave == 0 ? n : 32 + n;               // d_o row: wave 0: 0.., else 32..
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 fv = frag(T0, LD, rowv, 16 * ks + 8 * half), fo = frag(T1, LD, rowo, 16 * ks + 8 * half);
+                if (wave == 3) z0 = mfma(fo, fv, z0);              // D[m][n] = d_o_{32+m} . v_n
+                else z0 = mfma(fv, fo, z0);                        // D[m][n] = v_m . d_o_n
+                if (wave < 2) z1 = mfma(fo, fv, z1);               // D[m][n] = d_o_m . v_n
+            }
+        }
+    }
+    {   // Z[u][t] -> LDS rows t, head and remainder; diagonal of dA
+        const int ub = (wave == 1 || wave == 3) ? 1 : 0, tb = (wave == 1 || wave == 2) ? 1 : 0;
+        if (wave < 2) {
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                const int m = 8 * (x >> 2) + 4 * half + (x & 3);
+                if (m == n) zd[32 * wave + n] = z0[x];
+                z0[x] = m <= n ? z0[x] : z1[x];
+            }
+        }
+        store_block_t_split(Zh, Zl, LDP, 32 * tb + n, 32 * ub, half, z0);
+    }
+    // weights of the inter parts; the part of dg that needs dk^{inter}
+    f32x16 xk = {0};
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        const int t = 32 * nb + n;
+        _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
+            const int col = 32 * wave + 8 * gq + 4 * half;
+            const float4 b4 = *reinterpret_cast<const float4*>(bt + t * LDF + col);
+            const float4 c4 = *reinterpret_cast<const float4*>(bt + 63 * LDF + col);
+            const float bb[4] = {b4.x, b4.y, b4.z, b4.w}, cc[4] = {c4.x, c4.y, c4.z, c4.w};
+            const u32x2 kk = *reinterpret_cast<const u32x2*>(Kr + t * LD + col);
+            const float kf[4] = {bf16_lo(kk.x), bf16_hi(kk.x), bf16_lo(kk.y), bf16_hi(kk.y)};
+            _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
+                const int x = 4 * gq + jj;
+                const float wq = __expf(bb[jj]), wk = __expf(cc[jj] - bb[jj]);
+                aq[nb][x] *= wq;
+                aqr[nb][x] *= wq;
+                ak[nb][x] *= wk;
+                akr[nb][x] *= wk;
+                xk[x] += kf[jj] * (ak[nb][x] + akr[nb][x]);
+            }
+        }
+    }
+    if (want_dg) {
+        zi += __shfl_xor(zi, 32, 64);
+        if (half == 0) zl[32 * wave + n] = zi;
+    }
+
+    // ---- levels
+    const int cp = tid & 15, r0 = tid >> 4;
+    _Pragma("unroll") for (int lv = 0; lv < 6; ++lv) {
+        const int ls = 5 - lv;
+        __syncthreads();  // lv = 0: Z complete, V / d_o slices consumed; else: the previous level's tiles are read
+        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+            const int row = r0 + 16 * it;
+            bool qside;
+            const int ref = level_ref(row, ls, qside);
+            float b[8], br[8], w[8];
+            decay_row8(bt, row, cp * 8, b);
+            decay_row8(bt, ref, cp * 8, br);
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) w[e] = __expf(qside ? b[e] - br[e] : br[e] - b[e]);
+            const u32x4 raw = *reinterpret_cast<const u32x4*>((qside ? Qr : Kr) + row * LD + cp * 8);
+            u32x4 hi, lo;
+            weigh8(raw, w, hi, &lo);
+            *reinterpret_cast<u32x4*>(T0 + row * LD + cp * 8) = hi;
+            *reinterpret_cast<u32x4*>(T1 + row * LD + cp * 8) = lo;
+        }
+        __syncthreads();
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+            const int t = 32 * nb + n;
+            const int ub = ls == 5 ? 1 - nb : nb;  // the partners of level 32 sit in the other 32-block
+            f32x16 X = {0};
+            _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
+                const int u0 = 32 * ub + 16 * s2;
+                const int xr = (u0 + 8 * half) ^ t;
+                u32x4 mask;
+                _Pragma("unroll") for (int p = 0; p < 4; ++p)
+                    mask[p] = ((((xr ^ (2 * p)) >> ls) == 1) ? 0xffffu : 0u) | ((((xr ^ (2 * p + 1)) >> ls) == 1) ? 0xffff0000u : 0u);
+                u32x4 zh = *reinterpret_cast<const u32x4*>(Zh + t * LDP + u0 + 8 * half);
+                u32x4 zlo = *reinterpret_cast<const u32x4*>(Zl + t * LDP + u0 + 8 * half);
+                _Pragma("unroll") for (int p = 0; p < 4; ++p) {
+                    zh[p] &= mask[p];
+                    zlo[p] &= mask[p];
+                }
+                const bf16x8 bzh = __builtin_bit_cast(bf16x8, zh), bzl = __builtin_bit_cast(bf16x8, zlo);
+                const bf16x8 ah = frag_tr(T0, LD, u0, 32 * wave, lane), al = frag_tr(T1, LD, u0, 32 * wave, lane);
+                X = mfma(ah, bzh, X);
+                X = mfma(ah, bzl, X);
+                X = mfma(al, bzh, X);
+            }
+            bool qside;
+            const int ref = level_ref(t, ls, qside);
+            _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
+                const int col = 32 * wave + 8 * gq + 4 * half;
+                const float4 b4 = *reinterpret_cast<const float4*>(bt + t * LDF + col);
+                const float4 r4 = *reinterpret_cast<const float4*>(bt + ref * LDF + col);
+                const float bb[4] = {b4.x, b4.y, b4.z, b4.w}, rr[4] = {r4.x, r4.y, r4.z, r4.w};
+                _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
+                    const int x = 4 * gq + jj;
+                    const float val = X[x] * __expf(qside ? bb[jj] - rr[jj] : rr[jj] - bb[jj]);
+                    aq[nb][x] += qside ? val : 0.f;
+                    ak[nb][x] += qside ? 0.f : val;
+                }
+            }
+        }
+    }
+    // ---- diagonal pairs, then the decay gradient from the unrounded accumulators
+    f32x16 wd[2];
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        const int t = 32 * nb + n;
+        const float dd = zd[t];
+        _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
+            const int col = 32 * wave + 8 * gq + 4 * half;
+            const u32x2 qq = *reinterpret_cast<const u32x2*>(Qr + t * LD + col);
+            const u32x2 kk = *reinterpret_cast<const u32x2*>(Kr + t * LD + col);
+            const float qf[4] = {bf16_lo(qq.x), bf16_hi(qq.x), bf16_lo(qq.y), bf16_hi(qq.y)};
+            const float kf[4] = {bf16_lo(kk.x), bf16_hi(kk.x), bf16_lo(kk.y), bf16_hi(kk.y)};
+            _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
+                const int x = 4 * gq + jj;
+                aq[nb][x] += dd * kf[jj];
+                ak[nb][x] += dd * qf[jj];
+                wd[nb][x] = qf[jj] * (aq[nb][x] + aqr[nb][x]) - kf[jj] * (ak[nb][x] + akr[nb][x]);
+            }
+        }
+    }
+    __syncthreads();  // every wave is done with the level tiles and with b as weights
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        store_packed(T0, LD, 32 * nb + n, 32 * wave, half, pack_block(aq[nb]));
+        store_packed(T1, LD, 32 * nb + n, 32 * wave, half, pack_block(ak[nb]));
+    }
+    if (want_dg) {
+        // per feature (register): inclusive suffix sum over the tokens (lanes of one half), block 1 first
+        _Pragma("unroll") for (int nb = 1; nb >= 0; --nb) {
+            _Pragma("unroll") for (int off = 1; off < 32; off <<= 1) {
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                    const float y = __shfl_down(wd[nb][x], off, 32);
+                    wd[nb][x] += (n + off < 32) ? y : 0.f;
+                }
+            }
+            if (nb == 1) {
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                    const float total = __shfl(wd[1][x], 0, 32);  // all lanes take part in the exchange
+                    wd[0][x] += (n == 31) ? total : 0.f;
+                }
+            }
+        }
+        _Pragma("unroll") for (int off = 1; off < 32; off <<= 1) {
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) xk[x] += __shfl_xor(xk[x], off, 32);
+        }
+        _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
+            const int col = 32 * wave + 8 * gq + 4 * half;
+            const float4 c4 = *reinterpret_cast<const float4*>(bt + 63 * LDF + col);
+            const float4 z4 = *reinterpret_cast<const float4*>(zl + col);
+            const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, zz[4] = {z4.x, z4.y, z4.z, z4.w};
+            _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) xk[4 * gq + jj] += __expf(cc[jj]) * zz[jj];
+        }
+    }
+    __syncthreads();  // stages complete; b no longer needed
+    store_tile(dq, T0, tok0, L, tid);
+    store_tile(dk, T1, tok0, L, tid);
+    if (want_dg) {
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+            _Pragma("unroll") for (int gq = 0; gq < 4; ++gq)
+                *reinterpret_cast<float4*>(bt + (32 * nb + n) * LDF + 32 * wave + 8 * gq + 4 * half) =
+                    float4{wd[nb][4 * gq] + xk[4 * gq], wd[nb][4 * gq + 1] + xk[4 * gq + 1],
+                           wd[nb][4 * gq + 2] + xk[4 * gq + 2], wd[nb][4 * gq + 3] + xk[4 * gq + 3]};
+        __syncthreads();
+        _Pragma("unroll") for (int it = 0; it < 8; ++it) {
+            const int p = tid + kThreads * it, row = p >> 5, c4 = p & 31;
+            if (row < L)
+                *reinterpret_cast<float4*>(dg + (tok0 + row) * D + 4 * c4) = *reinterpret_cast<const float4*>(bt + row * LDF + 4 * c4);
+        }
+    }
 }
