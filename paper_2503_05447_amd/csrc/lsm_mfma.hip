@@ -1,5 +1,7 @@
 // MFMA kernel family of the chunkwise LSM path for gfx950: bf16 operands, fp32 accumulation,
-// chunk = 64 tokens, d_k = d_v = 128, decay kinds none / per-head / per-token scalar.
+// chunk = 64 tokens, d_k = 128.  This file: the state scans (all decay kinds) and the per-chunk
+// kernels of the decay kinds none / per-head / per-token scalar (d_v = 128); the per-chunk kernels
+// of the per-key-feature (vector) kind are in lsm_mfma_vec.h (d_v = 128 or 256).
 //
 // Algorithm 2 of the paper generalised to a decay, per (b,h) and chunk c with chunk-local
 // cumulative log-decay b_j:

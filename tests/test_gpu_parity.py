@@ -19,6 +19,7 @@ SHAPES = [
     (1, 1, 257, 128, 256, 128),   # chunk 128, tail of 1, d_v = 256
     (1, 2, 100, 64, 64, 16),      # chunk 16
     (1, 1, 96, 256, 64, 32),      # chunk 32, d_k = 256, exact multiple
+    (1, 2, 150, 128, 256, 64),    # two 128-wide value slices (vector kind: matrix-core path), tail of 22
 ]
 
 
@@ -34,7 +35,7 @@ def test_parity_weak_decay_with_states(kind, dtype, shape):
 
 @pytest.mark.parametrize("kind", [wl.KIND_HEAD, wl.KIND_SCALAR, wl.KIND_VECTOR])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("decay", ["default", "harsh"])
+@pytest.mark.parametrize("decay", ["default", "harsh", "strong4"])
 def test_parity_strong_decay_no_states(kind, dtype, decay):
     x = wl.make_inputs(2, 2, 300, 128, 128, kind, dtype=dtype, seed=200 + kind, decay=decay)
     rep = compare_case(x, 64)
