@@ -386,8 +386,43 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
     const int nvh = d.dv / D;
     const bool want_dg = dg != nullptr;  // then states_rem and dstates_rem are present
 
+    // Global loads are issued as early and as many at a time as the registers allow: with one
+    // workgroup per CU nothing else hides their latency.  Per value slice: the V and d_o tiles (via
+    // registers into LDS) and this wave's rows of S, dS and their remainder planes (MFMA A operands).
+    struct SliceRegs {
+        u32x4 tv[4], to[4];
+        bf16x8 s[8], sr[8], ds[8], dsr[8];
+    };
+    auto issue = [&](int vh, SliceRegs& r) {
+        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+            const int p = tid + kThreads * it, row = p >> 4, cpp = p & 15;
+            const size_t off = (tok0 + min(row, L - 1)) * d.dv + D * vh + cpp * 8;
+            const uint32_t keep = row < L ? 0xffffffffu : 0u;
+            u32x4 a = *reinterpret_cast<const u32x4*>(v + off), b = *reinterpret_cast<const u32x4*>(d_o + off);
+            r.tv[it] = u32x4{a.x & keep, a.y & keep, a.z & keep, a.w & keep};
+            r.to[it] = u32x4{b.x & keep, b.y & keep, b.z & keep, b.w & keep};
+        }
+        const size_t soff = ((size_t(bh) * nvh + vh) * d.N + c) * D * D + size_t(32 * wave + n) * D + 8 * half;
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+            r.s[ks] = *reinterpret_cast<const bf16x8*>(states + soff + 16 * ks);
+            r.ds[ks] = *reinterpret_cast<const bf16x8*>(dstates + soff + 16 * ks);
+            if (want_dg) {
+                r.sr[ks] = *reinterpret_cast<const bf16x8*>(states_rem + soff + 16 * ks);
+                r.dsr[ks] = *reinterpret_cast<const bf16x8*>(dstates_rem + soff + 16 * ks);
+            }
+        }
+    };
+    auto commit = [&](const SliceRegs& r) {
+        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+            const int p = tid + kThreads * it, row = p >> 4, cpp = p & 15;
+            *reinterpret_cast<u32x4*>(T0 + row * LD + cpp * 8) = r.tv[it];
+            *reinterpret_cast<u32x4*>(T1 + row * LD + cpp * 8) = r.to[it];
+        }
+    };
+    SliceRegs sr0;
     load_tile(Qr, q, tok0, L, tid);
     load_tile(Kr, k, tok0, L, tid);
+    issue(0, sr0);
     decay_tile(bt, g, tok0, L, tid);
 
     // ---- inter parts and Z, slice by slice of the value dimension
@@ -397,48 +432,29 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
     f32x16 z0 = {0}, z1 = {0};
     float zi = 0.f;
     for (int vh = 0; vh < nvh; ++vh) {
-        if (vh > 0) __syncthreads();  // the previous slice is consumed
-        load_tile_strided(T0, v, tok0, L, d.dv, D * vh, tid);
-        load_tile_strided(T1, d_o, tok0, L, d.dv, D * vh, tid);
-        const size_t soff = ((size_t(bh) * nvh + vh) * d.N + c) * D * D + size_t(32 * wave + n) * D + 8 * half;
-        const uint16_t *S = states + soff, *dS = dstates + soff;
+        if (vh > 0) {
+            __syncthreads();  // the previous slice is consumed
+            issue(vh, sr0);
+        }
+        commit(sr0);
         __syncthreads();
-        {
-            bf16x8 sf[8];
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) sf[ks] = *reinterpret_cast<const bf16x8*>(S + 16 * ks);
-            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                    aq[nb] = mfma(sf[ks], frag(T1, LD, 32 * nb + n, 16 * ks + 8 * half), aq[nb]);
-        }
-        if (want_dg) {
-            bf16x8 sf[8];
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                sf[ks] = *reinterpret_cast<const bf16x8*>(states_rem + soff + 16 * ks);
-            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                    aqr[nb] = mfma(sf[ks], frag(T1, LD, 32 * nb + n, 16 * ks + 8 * half), aqr[nb]);
-        }
-        {
-            bf16x8 sf[8];
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) sf[ks] = *reinterpret_cast<const bf16x8*>(dS + 16 * ks);
-            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                    ak[nb] = mfma(sf[ks], frag(T0, LD, 32 * nb + n, 16 * ks + 8 * half), ak[nb]);
-            if (want_dg) {  // <S, dS> over this lane's share of row i = 32 wave + n
-                bf16x8 sr[8];
-                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                    sr[ks] = *reinterpret_cast<const bf16x8*>(dstates_rem + soff + 16 * ks);
-                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                    const u32x4 a = *reinterpret_cast<const u32x4*>(S + 16 * ks);
-                    const u32x4 ar = *reinterpret_cast<const u32x4*>(states_rem + soff + 16 * ks);
-                    const u32x4 b = __builtin_bit_cast(u32x4, sf[ks]), br = __builtin_bit_cast(u32x4, sr[ks]);
-                    _Pragma("unroll") for (int p = 0; p < 4; ++p)
-                        zi += (bf16_lo(a[p]) + bf16_lo(ar[p])) * (bf16_lo(b[p]) + bf16_lo(br[p])) +
-                              (bf16_hi(a[p]) + bf16_hi(ar[p])) * (bf16_hi(b[p]) + bf16_hi(br[p]));
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 dof = frag(T1, LD, 32 * nb + n, 16 * ks + 8 * half), vf = frag(T0, LD, 32 * nb + n, 16 * ks + 8 * half);
+                aq[nb] = mfma(sr0.s[ks], dof, aq[nb]);
+                ak[nb] = mfma(sr0.ds[ks], vf, ak[nb]);
+                if (want_dg) {
+                    aqr[nb] = mfma(sr0.sr[ks], dof, aqr[nb]);
+                    akr[nb] = mfma(sr0.dsr[ks], vf, akr[nb]);
                 }
-                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-                    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                        akr[nb] = mfma(sr[ks], frag(T0, LD, 32 * nb + n, 16 * ks + 8 * half), akr[nb]);
+            }
+        if (want_dg) {  // <S, dS> over this lane's share of row i = 32 wave + n
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                const u32x4 a = __builtin_bit_cast(u32x4, sr0.s[ks]), ar = __builtin_bit_cast(u32x4, sr0.sr[ks]);
+                const u32x4 b = __builtin_bit_cast(u32x4, sr0.ds[ks]), br = __builtin_bit_cast(u32x4, sr0.dsr[ks]);
+                _Pragma("unroll") for (int p = 0; p < 4; ++p)
+                    zi += (bf16_lo(a[p]) + bf16_lo(ar[p])) * (bf16_lo(b[p]) + bf16_lo(br[p])) +
+                          (bf16_hi(a[p]) + bf16_hi(ar[p])) * (bf16_hi(b[p]) + bf16_hi(br[p]));
             }
         }
         {   // this wave's block of Z: rows of V and d_o as operands
