@@ -169,22 +169,24 @@ __device__ __forceinline__ void state_to_lds(const StateRegs& r, uint16_t* bufA,
     }
 }
 
-// One wave's staged 32 x 32 block -> global memory as 64-byte row pieces (4 lanes per row).  The wave
-// reads back only what it staged itself, and LDS serves a wave's accesses in order: no barrier.
-__device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage, int mb, int lane) {
-    _Pragma("unroll") for (int it = 0; it < 2; ++it) {
-        const int row = 16 * it + (lane >> 2), col = 32 * mb + 8 * (lane & 3);
-        *reinterpret_cast<u32x4*>(dst + row * D + col) = *reinterpret_cast<const u32x4*>(stage + row * LD + col);
-    }
+// Chunk states live in HBM "fragment-major": the 128 x 128 matrix X whose rows are the m index and
+// whose columns are the contraction index of the consumer's MFMA is stored as
+//     [row / 32][col / 16][(col / 8) % 2][row % 32][col % 8] ,
+// so that the A operand of k-step ks for the 32 rows of block w is one contiguous KiB with lane l
+// at byte 16 l: the per-chunk kernels read it with fully coalesced loads, and the scan writes
+// 512-byte runs.
+__device__ __forceinline__ size_t state_frag_off(int blk, int ks, int lane) {
+    return (size_t(blk * 8 + ks) * 64 + lane) * 8;
 }
-
-// One wave's staged block for the untransposed store of MODE 3: rows = this wave's 32 state rows m,
-// columns = the workgroup's 32 state columns n, written to dst[(32 mb + m)][n0 + n] as 64-byte pieces.
-__device__ __forceinline__ void state_store_plain(uint16_t* dst, const uint16_t* stage, int mb, int lane) {
+// One wave's staged 32 x 32 block -> global memory.  Stage row r = row r of the stored block `rowblk`,
+// stage columns 32 mb .. +31 = its columns 32 colblk .. +31.  The wave reads back only what it staged
+// itself, and LDS serves a wave's accesses in order: no barrier.
+__device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage, int mb, int rowblk, int colblk,
+                                            int lane) {
     _Pragma("unroll") for (int it = 0; it < 2; ++it) {
-        const int row = 16 * it + (lane >> 2), col = 8 * (lane & 3);
-        *reinterpret_cast<u32x4*>(dst + (32 * mb + row) * D + col) =
-            *reinterpret_cast<const u32x4*>(stage + row * LD + 32 * mb + col);
+        const int piece = 2 * it + (lane >> 5), ksl = piece >> 1, hf = piece & 1, r = lane & 31;
+        *reinterpret_cast<u32x4*>(dst + state_frag_off(rowblk, 2 * colblk + ksl, 32 * hf + r)) =
+            *reinterpret_cast<const u32x4*>(stage + r * LD + 32 * mb + 16 * ksl + 8 * hf);
     }
 }
 
@@ -242,8 +244,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     const int first = MODE == 2 ? d.N - 1 : 0, step = MODE == 2 ? -1 : 1;
     auto bufA = [&](int k) { return tiles + (k & 1) * kStateTile; };
     auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
-    auto slot_plain = [&](int k) { return (size_t(seq) * d.N + (first + step * k)) * sz + size_t(32 * nb); };
-    auto slot = [&](int k) { return MODE == 3 ? slot_plain(k) : slot_plain(k) + size_t(32 * nb) * (D - 1); };
+    auto slot = [&](int k) { return (size_t(seq) * d.N + (first + step * k)) * sz; };
     const uint16_t* xav = xa + (VEC ? D * vh : 0);
     auto gload = [&](int c, StateRegs& r) {
         state_gload<DEC, VEC>(d, xav, xb, xb_lo, wts, lam, sa.a_stride, bh, c, 32 * nb, tid, r);
@@ -295,10 +296,11 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         }
         __syncthreads();  // every wave is done with the tiles of chunk k
         state_to_lds<DEC, VEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
-        if (MODE == 3) state_store_plain(states + slot(k), sh, mb, lane);
-        else state_store(states + slot(k), sh, mb, lane);
-        if (MODE != 3 && states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, lane);
-        if (kTwin && states_twin) state_store_plain(states_twin + slot_plain(k), sh + 64 * LD, mb, lane);
+        // transposed staging: stage row = state column n (block nb); untransposed: stage row = state row m (block mb)
+        if (MODE == 3) state_store(states + slot(k), sh, mb, mb, nb, lane);
+        else state_store(states + slot(k), sh, mb, nb, mb, lane);
+        if (MODE != 3 && states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, nb, mb, lane);
+        if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
         lam_cur = lam_nxt;
         lam_nxt = rw.lam;
     };
@@ -410,7 +412,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     const uint16_t* St = states + (size_t(bh) * d.N + c) * D * D;
     bf16x8 sfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-        sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + (32 * wave + n) * D + 16 * ks + 8 * half);
+        sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + state_frag_off(wave, ks, lane));
 
     load_tile(Q, q, tok0, L, tid);
     load_tile(K, k, tok0, L, tid);
@@ -491,11 +493,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     // rows i in [32w, 32w+32) of S (and its remainder): A operands [m = i][k = v]
     bf16x8 sfrag[8], srfrag[8], dsfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-        sfrag[ks] = *reinterpret_cast<const bf16x8*>(S + (32 * wave + n) * D + 16 * ks + 8 * half);
-        dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + (32 * wave + n) * D + 16 * ks + 8 * half);
+        sfrag[ks] = *reinterpret_cast<const bf16x8*>(S + state_frag_off(wave, ks, lane));
+        dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane));
         if (want_dg)
-            srfrag[ks] = *reinterpret_cast<const bf16x8*>(states_rem + (S - states) + (32 * wave + n) * D + 16 * ks +
-                                                          8 * half);
+            srfrag[ks] = *reinterpret_cast<const bf16x8*>(states_rem + (S - states) + state_frag_off(wave, ks, lane));
     }
     load_tile(Q, q, tok0, L, tid);
     load_tile(K, k, tok0, L, tid);

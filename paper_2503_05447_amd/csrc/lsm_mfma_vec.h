@@ -304,7 +304,7 @@ __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint1
     const uint16_t* St = states + ((size_t(bh) * nvh + vh) * d.N + c) * D * D;
     bf16x8 sfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-        sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + (32 * wave + n) * D + 16 * ks + 8 * half);
+        sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + state_frag_off(wave, ks, lane));
 
     load_tile(Q, qhat, tok0, L, tid);
     load_tile(Ql, qhat_lo, tok0, L, tid);
@@ -402,13 +402,14 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
             r.tv[it] = u32x4{a.x & keep, a.y & keep, a.z & keep, a.w & keep};
             r.to[it] = u32x4{b.x & keep, b.y & keep, b.z & keep, b.w & keep};
         }
-        const size_t soff = ((size_t(bh) * nvh + vh) * d.N + c) * D * D + size_t(32 * wave + n) * D + 8 * half;
+        const size_t sbase = ((size_t(bh) * nvh + vh) * d.N + c) * D * D;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-            r.s[ks] = *reinterpret_cast<const bf16x8*>(states + soff + 16 * ks);
-            r.ds[ks] = *reinterpret_cast<const bf16x8*>(dstates + soff + 16 * ks);
+            const size_t soff = sbase + state_frag_off(wave, ks, lane);
+            r.s[ks] = *reinterpret_cast<const bf16x8*>(states + soff);
+            r.ds[ks] = *reinterpret_cast<const bf16x8*>(dstates + soff);
             if (want_dg) {
-                r.sr[ks] = *reinterpret_cast<const bf16x8*>(states_rem + soff + 16 * ks);
-                r.dsr[ks] = *reinterpret_cast<const bf16x8*>(dstates_rem + soff + 16 * ks);
+                r.sr[ks] = *reinterpret_cast<const bf16x8*>(states_rem + soff);
+                r.dsr[ks] = *reinterpret_cast<const bf16x8*>(dstates_rem + soff);
             }
         }
     };
