@@ -185,8 +185,9 @@ __device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage
                                             int lane) {
     _Pragma("unroll") for (int it = 0; it < 2; ++it) {
         const int piece = 2 * it + (lane >> 5), ksl = piece >> 1, hf = piece & 1, r = lane & 31;
-        *reinterpret_cast<u32x4*>(dst + state_frag_off(rowblk, 2 * colblk + ksl, 32 * hf + r)) =
-            *reinterpret_cast<const u32x4*>(stage + r * LD + 32 * mb + 16 * ksl + 8 * hf);
+        // written once, read by a later kernel: keep it from displacing the shared input tiles in L2
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + r * LD + 32 * mb + 16 * ksl + 8 * hf),
+                                    reinterpret_cast<u32x4*>(dst + state_frag_off(rowblk, 2 * colblk + ksl, 32 * hf + r)));
     }
 }
 
@@ -412,7 +413,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     const uint16_t* St = states + (size_t(bh) * d.N + c) * D * D;
     bf16x8 sfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-        sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + state_frag_off(wave, ks, lane));
+        sfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(St + state_frag_off(wave, ks, lane)));
 
     load_tile(Q, q, tok0, L, tid);
     load_tile(K, k, tok0, L, tid);
@@ -493,10 +494,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     // rows i in [32w, 32w+32) of S (and its remainder): A operands [m = i][k = v]
     bf16x8 sfrag[8], srfrag[8], dsfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-        sfrag[ks] = *reinterpret_cast<const bf16x8*>(S + state_frag_off(wave, ks, lane));
-        dsfrag[ks] = *reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane));
+        sfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(S + state_frag_off(wave, ks, lane)));
+        dsfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane)));
         if (want_dg)
-            srfrag[ks] = *reinterpret_cast<const bf16x8*>(states_rem + (S - states) + state_frag_off(wave, ks, lane));
+            srfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(states_rem + (S - states) + state_frag_off(wave, ks, lane)));
     }
     load_tile(Q, q, tok0, L, tid);
     load_tile(K, k, tok0, L, tid);

@@ -96,7 +96,7 @@ __device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, si
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         u32x4 v = {0, 0, 0, 0};
-        if (row < L) v = *reinterpret_cast<const u32x4*>(src + (tok0 + row) * D + cp * 8);
+        if (row < L) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + row) * D + cp * 8));
         *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = v;
     }
 }
@@ -105,8 +105,8 @@ __device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, s
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         if (row < L)
-            *reinterpret_cast<u32x4*>(dst + (tok0 + row) * D + cp * 8) =
-                *reinterpret_cast<const u32x4*>(src + row * LD + cp * 8);
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
+                                        reinterpret_cast<u32x4*>(dst + (tok0 + row) * D + cp * 8));
     }
 }
 
