@@ -97,6 +97,7 @@ struct StateRegs {  // one thread's share of a chunk on its way from global memo
     u32x4 a[4], b, blo;  // blo: remainder plane of the B slice (vector decay: both planes arrive precomputed)
     float w;             // weight of the B-slice row this thread carries
     float lam;           // e^{b_C}: one per chunk, or (vector decay) the one of this lane's state column
+    int L;               // valid tokens of the chunk; rows beyond are zeroed on the way to LDS
 };
 
 struct StateArgs {
@@ -124,18 +125,16 @@ __device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, c
     const int astride = VEC ? a_stride : D;
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        u32x4 v = *reinterpret_cast<const u32x4*>(xa + (tok0 + min(row, L - 1)) * astride + cp * 8);
-        const uint32_t keep = row < L ? 0xffffffffu : 0u;
-        r.a[it] = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
+        r.a[it] = *reinterpret_cast<const u32x4*>(xa + (tok0 + min(row, L - 1)) * astride + cp * 8);
     }
+    // nothing is computed on the loaded values here (the ragged tail is zeroed when they go to LDS): an
+    // ALU operation at this point would make the wave wait for the load it has just issued
+    r.L = L;
     const int row = tid >> 2, cp = tid & 3;
     const size_t boff = (tok0 + min(row, L - 1)) * D + fb0 + cp * 8;
-    u32x4 v = *reinterpret_cast<const u32x4*>(xb + boff);
-    const uint32_t keep = row < L ? 0xffffffffu : 0u;
-    r.b = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
+    r.b = *reinterpret_cast<const u32x4*>(xb + boff);
     if (VEC) {
-        v = *reinterpret_cast<const u32x4*>(xb_lo + boff);
-        r.blo = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
+        r.blo = *reinterpret_cast<const u32x4*>(xb_lo + boff);
         r.lam = lam[(size_t(bh) * d.N + c) * D + fb0 + (tid & 31)];
     } else if (DEC) {
         r.w = wts[(size_t(bh) * d.N + c) * C + row];
@@ -148,16 +147,20 @@ template <bool DEC, bool VEC>
 __device__ __forceinline__ void state_to_lds(const StateRegs& r, uint16_t* bufA, uint16_t* bufB, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        *reinterpret_cast<u32x4*>(bufA + row * LD + cp * 8) = r.a[it];
+        const uint32_t keep = row < r.L ? 0xffffffffu : 0u;
+        *reinterpret_cast<u32x4*>(bufA + row * LD + cp * 8) =
+            u32x4{r.a[it].x & keep, r.a[it].y & keep, r.a[it].z & keep, r.a[it].w & keep};
     }
     uint16_t* dst = bufB + (tid >> 2) * LDB + (tid & 3) * 8;
+    const uint32_t keep = (tid >> 2) < r.L ? 0xffffffffu : 0u;
+    const u32x4 rb = {r.b.x & keep, r.b.y & keep, r.b.z & keep, r.b.w & keep};
     if (VEC) {
-        *reinterpret_cast<u32x4*>(dst) = r.b;
-        *reinterpret_cast<u32x4*>(dst + C * LDB) = r.blo;
+        *reinterpret_cast<u32x4*>(dst) = rb;
+        *reinterpret_cast<u32x4*>(dst + C * LDB) = u32x4{r.blo.x & keep, r.blo.y & keep, r.blo.z & keep, r.blo.w & keep};
     } else if (DEC) {
         u32x4 hi, lo;
         _Pragma("unroll") for (int p = 0; p < 4; ++p) {
-            const float x0 = bf16_lo(r.b[p]) * r.w, x1 = bf16_hi(r.b[p]) * r.w;
+            const float x0 = bf16_lo(rb[p]) * r.w, x1 = bf16_hi(rb[p]) * r.w;
             const uint32_t h = pack2(x0, x1);
             hi[p] = h;
             lo[p] = pack2(x0 - bf16_lo(h), x1 - bf16_hi(h));
@@ -165,7 +168,7 @@ __device__ __forceinline__ void state_to_lds(const StateRegs& r, uint16_t* bufA,
         *reinterpret_cast<u32x4*>(dst) = hi;
         *reinterpret_cast<u32x4*>(dst + C * LDB) = lo;
     } else {
-        *reinterpret_cast<u32x4*>(dst) = r.b;
+        *reinterpret_cast<u32x4*>(dst) = rb;
     }
 }
 
@@ -181,13 +184,16 @@ __device__ __forceinline__ size_t state_frag_off(int blk, int ks, int lane) {
 // One wave's staged 32 x 32 block -> global memory.  Stage row r = row r of the stored block `rowblk`,
 // stage columns 32 mb .. +31 = its columns 32 colblk .. +31.  The wave reads back only what it staged
 // itself, and LDS serves a wave's accesses in order: no barrier.
+template <bool STREAM = true>
 __device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage, int mb, int rowblk, int colblk,
                                             int lane) {
     _Pragma("unroll") for (int it = 0; it < 2; ++it) {
         const int piece = 2 * it + (lane >> 5), ksl = piece >> 1, hf = piece & 1, r = lane & 31;
+        const u32x4 val = *reinterpret_cast<const u32x4*>(stage + r * LD + 32 * mb + 16 * ksl + 8 * hf);
+        u32x4* p = reinterpret_cast<u32x4*>(dst + state_frag_off(rowblk, 2 * colblk + ksl, 32 * hf + r));
         // written once, read by a later kernel: keep it from displacing the shared input tiles in L2
-        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + r * LD + 32 * mb + 16 * ksl + 8 * hf),
-                                    reinterpret_cast<u32x4*>(dst + state_frag_off(rowblk, 2 * colblk + ksl, 32 * hf + r)));
+        if (STREAM) __builtin_nontemporal_store(val, p);
+        else *p = val;
     }
 }
 
@@ -298,7 +304,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         __syncthreads();  // every wave is done with the tiles of chunk k
         state_to_lds<DEC, VEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
         // transposed staging: stage row = state column n (block nb); untransposed: stage row = state row m (block mb)
-        if (MODE == 3) state_store(states + slot(k), sh, mb, mb, nb, lane);
+        if (MODE == 3) state_store<false>(states + slot(k), sh, mb, mb, nb, lane);
         else state_store(states + slot(k), sh, mb, nb, mb, lane);
         if (MODE != 3 && states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, nb, mb, lane);
         if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
