@@ -123,6 +123,14 @@ __device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, c
     const int t0 = c * C, L = min(C, d.T - t0);
     const size_t tok0 = size_t(bh) * d.T + t0;
     const int astride = VEC ? a_stride : D;
+    // the scalars first: they are copied between iterations once the set is consumed, and being the
+    // oldest loads of the set they are then known to have arrived
+    if (VEC) {
+        r.lam = lam[(size_t(bh) * d.N + c) * D + fb0 + (tid & 31)];
+    } else if (DEC) {
+        r.w = wts[(size_t(bh) * d.N + c) * C + (tid >> 2)];
+        r.lam = lam[size_t(bh) * d.N + c];
+    }
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         r.a[it] = *reinterpret_cast<const u32x4*>(xa + (tok0 + min(row, L - 1)) * astride + cp * 8);
@@ -133,13 +141,7 @@ __device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, c
     const int row = tid >> 2, cp = tid & 3;
     const size_t boff = (tok0 + min(row, L - 1)) * D + fb0 + cp * 8;
     r.b = *reinterpret_cast<const u32x4*>(xb + boff);
-    if (VEC) {
-        r.blo = *reinterpret_cast<const u32x4*>(xb_lo + boff);
-        r.lam = lam[(size_t(bh) * d.N + c) * D + fb0 + (tid & 31)];
-    } else if (DEC) {
-        r.w = wts[(size_t(bh) * d.N + c) * C + row];
-        r.lam = lam[size_t(bh) * d.N + c];
-    }
+    if (VEC) r.blo = *reinterpret_cast<const u32x4*>(xb_lo + boff);
 }
 // The B slice carries the decay: each row is multiplied by its token's weight in fp32 and stored as a
 // bf16 head plus a bf16 remainder, once per workgroup.
