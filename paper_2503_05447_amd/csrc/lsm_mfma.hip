@@ -119,17 +119,18 @@ struct StateArgs {
 template <bool DEC, bool VEC>
 __device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, const uint16_t* xb,
                                             const uint16_t* xb_lo, const float* wts, const float* lam, int a_stride,
-                                            int bh, int c, int fb0, int tid, StateRegs& r) {
+                                            int bh, int c, int clam, int fb0, int tid, StateRegs& r) {
     const int t0 = c * C, L = min(C, d.T - t0);
     const size_t tok0 = size_t(bh) * d.T + t0;
     const int astride = VEC ? a_stride : D;
-    // the scalars first: they are copied between iterations once the set is consumed, and being the
-    // oldest loads of the set they are then known to have arrived
+    // The set of chunk c carries e^{b_C} of chunk `clam`, the one that is being accumulated when this
+    // set goes to LDS: the factor is then read from a set that has arrived, and no loaded value is
+    // copied from iteration to iteration (such a copy waits for every load in flight).
     if (VEC) {
-        r.lam = lam[(size_t(bh) * d.N + c) * D + fb0 + (tid & 31)];
+        r.lam = lam[(size_t(bh) * d.N + clam) * D + fb0 + (tid & 31)];
     } else if (DEC) {
         r.w = wts[(size_t(bh) * d.N + c) * C + (tid >> 2)];
-        r.lam = lam[size_t(bh) * d.N + c];
+        r.lam = lam[size_t(bh) * d.N + clam];
     }
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
@@ -255,24 +256,23 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
     auto slot = [&](int k) { return (size_t(seq) * d.N + (first + step * k)) * sz; };
     const uint16_t* xav = xa + (VEC ? D * vh : 0);
-    auto gload = [&](int c, StateRegs& r) {
-        state_gload<DEC, VEC>(d, xav, xb, xb_lo, wts, lam, sa.a_stride, bh, c, 32 * nb, tid, r);
+    auto gload = [&](int kc, StateRegs& r) {
+        // the kc-th chunk of the walk (clamped at the end); it goes to LDS during iteration kc - 2
+        const int c = first + step * min(kc, d.N - 1), clam = first + step * min(max(kc - 2, 0), d.N - 1);
+        state_gload<DEC, VEC>(d, xav, xb, xb_lo, wts, lam, sa.a_stride, bh, c, clam, 32 * nb, tid, r);
     };
 
     // prologue: chunks 0 and 1 -> LDS, chunk 2 in flight.  Global loads are issued two iterations
     // before their data is written to LDS: one iteration is shorter than a trip to HBM.
     StateRegs r0, r1, r2;
-    float lam_cur = 1.f, lam_nxt = 1.f;
-    gload(first, r0);
-    if (d.N > 1) gload(first + step, r1);
+    gload(0, r0);
+    if (d.N > 1) gload(1, r1);
     state_to_lds<DEC, VEC>(r0, bufA(0), bufB(0), tid);
-    lam_cur = r0.lam;
     if (d.N > 1) {
         state_to_lds<DEC, VEC>(r1, bufA(1), bufB(1), tid);
-        lam_nxt = r1.lam;
     }
-    gload(first + step * min(2, d.N - 1), r0);
-    gload(first + step * min(3, d.N - 1), r1);
+    gload(2, r0);
+    gload(3, r1);
     __syncthreads();
 
     // One chunk, straight-line code: rw holds chunk k+2 (loaded three iterations ago, written to LDS
@@ -280,7 +280,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     // buffer nobody reads).  The three register sets rotate by unrolling, never by copying: a copy
     // would wait for the load issued in the same iteration.
     auto iteration = [&](int k, StateRegs& rw, StateRegs& rl) {
-        gload(first + step * min(k + 4, d.N - 1), rl);
+        gload(k + 4, rl);
         // stage the state this chunk starts from (MODE 2: the gradient this chunk ends with)
         uint16_t* sh = stage;
         constexpr bool kTwin = VEC && MODE == 2;  // second copy, untransposed
@@ -294,6 +294,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
             else store_block_t(sh, LD, n, 32 * mb, half, acc);
         }
         if (DEC) {
+            const float lam_cur = rw.lam;
             _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[x] *= lam_cur;
         }
         // acc[m][n] += sum_t A[t][32mb + m] * Bw[t][n]: both operands read token-major out of LDS
@@ -310,8 +311,6 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         else state_store(states + slot(k), sh, mb, nb, mb, lane);
         if (MODE != 3 && states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, nb, mb, lane);
         if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
-        lam_cur = lam_nxt;
-        lam_nxt = rw.lam;
     };
     int k = 0;
     for (; k + 2 < d.N; k += 3) {
