@@ -138,6 +138,30 @@ def main():
                      "algorithmic_bytes_per_launch": abytes},
     }
 
+    if pkg.kernel_path(p) == 1 and kind != wl.KIND_VECTOR:
+        # Intra-chunk phase apart from HBM: the forward per-chunk kernel with its compute phase repeated on
+        # LDS-resident tiles; the time of one pass is the slope between two repeat counts.
+        R = 33
+        o_mb = torch.empty_like(last[0][0])
+        pkg.lsm_chunk_fwd(q, k, v, g, kind, C, m0, workspace=ws)   # the workspace holds the chunk states again
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws, 1, C)
+        ev[0].record(); pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws, 1, C); ev[1].record()
+        ev[2].record(); pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws, R, C); ev[3].record()
+        torch.cuda.synchronize()
+        t1_ms, tR_ms = ev[0].elapsed_time(ev[1]), ev[2].elapsed_time(ev[3])
+        pass_s = (tR_ms - t1_ms) / (R - 1) * 1e-3
+        chunks = B * H * ((T + C - 1) // C)
+        alg = chunks * (2 * C * C * (dk + dv) + 2 * C * dk * dv)          # dense C x C block + Q S_c (Algorithm 2)
+        # issued MFMA 32x32x16 per chunk: Q S_c 4 x 16, three score blocks x 8, A V with head + remainder 4 x 12
+        issued = chunks * 136 * 2 * 32 * 32 * 16
+        result["intra_chunk_microbench"] = {
+            "what": "forward per-chunk kernel (scores, mask/decay, A V, Q S_c), compute phase repeated on LDS-resident tiles",
+            "repeats": R, "ms_one_pass": pass_s * 1e3, "ms_streamed_kernel": t1_ms,
+            "algorithmic_tflops": alg / pass_s / 1e12, "algorithmic_frac_of_mfma_peak": alg / pass_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "issued_mfma_tflops": issued / pass_s / 1e12, "issued_frac_of_mfma_peak": issued / pass_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "same_output_as_forward": bool(torch.equal(o_mb, last[0][0]))}
+
     if not args.no_cpu_baseline or not args.no_check:
         from oracle import lsm_oracle_bwd, lsm_oracle_fwd, oracle_threads
         # bounded sample: the first `nb` batch elements of the same workload (all heads, full T)

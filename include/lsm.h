@@ -132,6 +132,19 @@ int lsm_profile_start(void);
 int lsm_profile_stop(int* kernel_ids, float* milliseconds, int capacity);
 const char* lsm_kernel_name(int kernel_id);
 
+/*
+ * Benchmark aid (not part of the method): the intra-chunk kernel of the forward (masked decayed scores
+ * times V plus Q times the chunk state; Algorithm 2, O_intra + O_inter) with its compute phase repeated
+ * `repeats` times on the tiles resident in LDS, so that the arithmetic rate of the intra-chunk phase can
+ * be measured apart from the HBM traffic that bounds the streamed kernel.  Only for parameter sets with
+ * lsm_kernel_path() == 1 and a decay kind other than LSM_DECAY_VECTOR (else LSM_ERR_UNSUPPORTED).
+ * `workspace` must be the one a preceding lsm_chunk_fwd() call with the same parameters and inputs
+ * used (it holds the chunk states); `o` is overwritten with the same values that call produced.
+ */
+int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, const void* v,
+                          const float* log_decay, void* o, void* workspace, size_t workspace_bytes,
+                          int repeats, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* lsm_status_string(int status);
 

@@ -57,6 +57,8 @@ def library():
     lib.lsm_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
     lib.lsm_kernel_name.restype = ctypes.c_char_p
     lib.lsm_kernel_name.argtypes = [ctypes.c_int]
+    lib.lsm_bench_intra_chunk.restype = ctypes.c_int
+    lib.lsm_bench_intra_chunk.argtypes = [pp] + [vp] * 6 + [sz, ctypes.c_int, vp]
     _lib = lib
     return lib
 
@@ -157,6 +159,17 @@ def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None
     if rc != 0:
         raise LsmError(rc, "lsm_chunk_fwd")
     return o, final
+
+
+def lsm_bench_intra_chunk(q, k, v, log_decay, decay_kind, o, workspace, repeats, chunk_size=64, stream=None):
+    """Benchmark aid: the intra-chunk forward kernel with its compute phase repeated ``repeats`` times.
+
+    ``workspace`` must be the one a preceding lsm_chunk_fwd call on the same inputs used."""
+    p, _, _ = _setup(q, k, v, log_decay, decay_kind, chunk_size)
+    rc = library().lsm_bench_intra_chunk(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(o),
+                                         _ptr(workspace), workspace.numel(), int(repeats), _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_bench_intra_chunk")
 
 
 def lsm_chunk_bwd(q, k, v, log_decay, decay_kind, d_o, chunk_size=64, init_state=None, d_final_state=None,

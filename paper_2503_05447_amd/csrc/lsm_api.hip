@@ -142,6 +142,21 @@ int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void*
     return e == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
 }
 
+int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
+                          void* o, void* workspace, size_t workspace_bytes, int repeats, void* stream) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !o) return LSM_ERR_NULL;
+    if ((d.kind == LSM_DECAY_NONE) != (log_decay == nullptr)) return LSM_ERR_NULL;
+    if (!lsm::mfma_supported(d) || d.kind == LSM_DECAY_VECTOR || repeats < 1) return LSM_ERR_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_decay) || misaligned(workspace))
+        return LSM_ERR_ALIGN;
+    if (!workspace || workspace_bytes < lsm_chunk_fwd_workspace_bytes(p)) return LSM_ERR_WORKSPACE;
+    lsm::FwdArgs a{q, k, v, log_decay, nullptr, o, nullptr, workspace, static_cast<hipStream_t>(stream)};
+    return lsm::mfma_intra_bench(d, a, repeats) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
+}
+
 int lsm_chunk_bwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
                   const float* init_state, const void* d_o, const float* d_final_state, void* dq, void* dk,
                   void* dv, float* d_log_decay, float* d_init_state, void* workspace, size_t workspace_bytes,

@@ -66,5 +66,8 @@ size_t mfma_fwd_workspace(const Dims& d);
 size_t mfma_bwd_workspace(const Dims& d);
 hipError_t mfma_fwd(const Dims& d, const FwdArgs& a);
 hipError_t mfma_bwd(const Dims& d, const BwdArgs& a);
+// benchmark aid: the output kernel alone with its compute phase repeated `reps` times (scalar decay kinds);
+// the workspace must hold the chunk states of a preceding mfma_fwd call on the same inputs
+hipError_t mfma_intra_bench(const Dims& d, const FwdArgs& a, int reps);
 
 }  // namespace lsm

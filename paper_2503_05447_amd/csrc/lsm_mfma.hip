@@ -391,19 +391,31 @@ __device__ __forceinline__ float row_dot(const uint16_t* X, int tok, int wave, i
 
 // ---------------------------------------------------------------------------------------------
 // Output of one chunk:  O^T[v][j] = e^{b_j} sum_i S^T[v][i] q_j[i] + sum_{r<=j} V^T[v][r] P[j][r],
-// P[j][r] = (q_j . k_r) e^{b_j - b_r}.   Wave w owns v in [32w, 32w+32) and computes every 32 x 32
-// block of P it needs itself: the block stays in its accumulator registers and is fed to the next
-// MFMA as the B operand (bf16 head + bf16 remainder: an output that one key dominates would
-// otherwise carry the full 2^-9 rounding of its score), V^T coming from the LDS transpose read in
-// the matching k order.  No LDS copy of P, no barrier between the two products.
+// P[j][r] = (q_j . k_r) e^{b_j - b_r}.   Wave w owns v in [32w, 32w+32): the inter part with the state
+// rows as A operand straight from global memory, then the intra part with V^T from the LDS transpose
+// read.  Each of the three 32 x 32 blocks of P is computed by ONE wave (mask and decay on its
+// accumulators) and handed to the others through LDS as a bf16 head plus a bf16 remainder (an output
+// that one key dominates would otherwise carry the full 2^-9 rounding of its score); the head goes
+// over the Q tile and the remainder over the K tile, both dead by then, so the kernel stays at 52 KiB
+// of LDS.  (SHARED = false keeps the earlier variant in which every wave computes all score blocks
+// itself and feeds them to the next MFMA from registers: no exchange, but four times the score MFMAs.)
 // LDS: Q | K (later the O stage) | V (64 x LD each) | bs
+// REPEAT (benchmark aid): the compute phase runs `reps` times on the tiles resident in LDS, so that
+// the rate of the intra-chunk arithmetic can be measured without the HBM traffic that bounds the
+// streamed kernel; the stored result is that of the last pass, identical to reps = 1.
 constexpr int kOutLds = 3 * C * LD * 2 + C * 4;
+constexpr int kOutLdsRepeat = kOutLds + 2 * C * LDP * 2;
+#ifndef LSM_SHARED_SCORES
+#define LSM_SHARED_SCORES 1
+#endif
+constexpr bool kSharedScores = LSM_SHARED_SCORES;
 
+template <bool REPEAT, bool SHARED>
 __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ k,
                                                          const uint16_t* __restrict__ v, const float* __restrict__ g,
                                                          const uint16_t* __restrict__ states,
-                                                         uint16_t* __restrict__ o) {
+                                                         uint16_t* __restrict__ o, int reps) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = Q + C * LD;
@@ -429,6 +441,41 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     __syncthreads();
 
     PackedBlock res[2];
+    // SHARED: each of the three score blocks is computed by one wave and handed to the others through
+    // LDS (head over the Q tile, remainder over the K tile, both dead by then; the repeat variant, which
+    // needs Q and K again, has room of its own behind bs).
+    uint16_t* Ph = REPEAT ? reinterpret_cast<uint16_t*>(bs + C) : Q;
+    uint16_t* Pl = REPEAT ? Ph + C * LDP : K;
+    for (int rep = 0; rep < (REPEAT ? reps : 1); ++rep) {
+    if (REPEAT) asm volatile("" ::: "memory");  // the tiles are read again in every pass
+    if (SHARED) {
+        f32x16 acc[2], P = {0};
+        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+            const int j = 32 * jb + n;
+            acc[jb] = f32x16{0};
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                acc[jb] = mfma(sfrag[ks], frag(Q, LD, j, 16 * ks + 8 * half), acc[jb]);
+            const float w = __expf(bs[j]);
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[jb][x] *= w;
+        }
+        const int pjb = wave ? 1 : 0, prb = wave == 2 ? 1 : 0;  // wave 0: (0,0), wave 1: (1,0), wave 2: (1,1)
+        if (wave < 3) {
+            P = score_block(K, 32 * prb, Q, 32 * pjb, n, half);  // D[m = r][n = j] = k_r . q_j
+            decay_mask<true>(P, 32 * prb, 32 * pjb + n, bs, half);
+        }
+        __syncthreads();  // every wave is done with Q and K (and, in a repeated pass, with the previous P)
+        if (wave < 3) store_block_t_split(Ph, Pl, LDP, 32 * pjb + n, 32 * prb, half, P);
+        __syncthreads();
+        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+            const int j = 32 * jb + n;
+            _Pragma("unroll") for (int ks = 0; ks < 2 * (jb + 1); ++ks) {  // keys r >= 32 never reach queries j < 32
+                const bf16x8 vt = frag_tr(V, LD, 16 * ks, 32 * wave, lane);
+                acc[jb] = mfma(vt, frag(Ph, LDP, j, 16 * ks + 8 * half), acc[jb]);
+                acc[jb] = mfma(vt, frag(Pl, LDP, j, 16 * ks + 8 * half), acc[jb]);
+            }
+            res[jb] = pack_block(acc[jb]);
+        }
+    } else
     _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
         const int j = 32 * jb + n;
         f32x16 acc = {0};
@@ -449,7 +496,8 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
             }
         res[jb] = pack_block(acc);
     }
-    __syncthreads();  // every wave is done with K
+    }
+    __syncthreads();  // every wave is done with K (SHARED: with the score tiles)
     _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) store_packed(stage, LD, 32 * jb + n, 32 * wave, half, res[jb]);
     __syncthreads();
     store_tile(o, stage, tok0, L, tid);
@@ -819,7 +867,7 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     const dim3 grid(d.N, d.BH()), block(kThreads);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     hipError_t e;
-    if ((e = allow_lds(mk_output, kOutLds)) != hipSuccess) return e;
+    if ((e = allow_lds((mk_output<false, kSharedScores>), kOutLds)) != hipSuccess) return e;
     launch_prep(d, a.stream, a.g, w);
     {
         ProfScope ps(KID_MFMA_STATE, a.stream);
@@ -828,8 +876,8 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     }
     {
         ProfScope ps(KID_MFMA_OUTPUT, a.stream);
-        hipLaunchKernelGGL(mk_output, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
-                           static_cast<uint16_t*>(a.o));
+        hipLaunchKernelGGL((mk_output<false, kSharedScores>), grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
+                           static_cast<uint16_t*>(a.o), 1);
     }
     return hipGetLastError();
 }
@@ -873,6 +921,18 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
     return hipGetLastError();
 }
 }  // namespace
+
+hipError_t mfma_intra_bench(const Dims& d, const FwdArgs& a, int reps) {
+    if (d.kind == 3 || !mfma_supported(d)) return hipErrorInvalidValue;
+    Ws w = carve(d, a.ws, false);
+    hipError_t e;
+    if ((e = allow_lds((mk_output<true, kSharedScores>), kOutLdsRepeat)) != hipSuccess) return e;
+    ProfScope ps(KID_MFMA_OUTPUT, a.stream);
+    hipLaunchKernelGGL((mk_output<true, kSharedScores>), dim3(d.N, d.BH()), dim3(kThreads), kOutLdsRepeat, a.stream, d,
+                       static_cast<const uint16_t*>(a.q), static_cast<const uint16_t*>(a.k),
+                       static_cast<const uint16_t*>(a.v), a.g, w.states, static_cast<uint16_t*>(a.o), reps);
+    return hipGetLastError();
+}
 
 hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     if (d.kind == 3) return vec_bwd(d, a);

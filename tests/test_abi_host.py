@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported():
     lib = pkg.library()
     names = declared_symbols()
     assert {"lsm_chunk_fwd", "lsm_chunk_bwd", "lsm_chunk_fwd_workspace_bytes", "lsm_chunk_bwd_workspace_bytes",
-            "lsm_status_string", "lsm_version", "lsm_kernel_path"} <= set(names)
+            "lsm_status_string", "lsm_version", "lsm_kernel_path", "lsm_bench_intra_chunk"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert lib.lsm_version() >= 1
