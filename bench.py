@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--no-microbench", action="store_true",
+                    help="skip the LDS-resident intra-chunk micro-benchmark (profiling runs: it launches the output kernel again)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -138,7 +140,7 @@ def main():
                      "algorithmic_bytes_per_launch": abytes},
     }
 
-    if pkg.kernel_path(p) == 1 and kind != wl.KIND_VECTOR:
+    if pkg.kernel_path(p) == 1 and kind != wl.KIND_VECTOR and not args.no_microbench:
         # Intra-chunk phase apart from HBM: the forward per-chunk kernel with its compute phase repeated on
         # LDS-resident tiles; the time of one pass is the slope between two repeat counts.
         R = 33
