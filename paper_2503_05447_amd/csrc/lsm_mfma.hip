@@ -563,39 +563,26 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     const float bC = bs[C - 1];
 
     PackedBlock resq[2], resk[2], resv[2];
-    // ---- dq^T[i][j], i in this wave's slice
+    // ---- inter parts of dq^T[i][j] and dk^T[i][r], i in this wave's slice
+    f32x16 aq[2] = {{0}, {0}}, aqr[2] = {{0}, {0}}, ak[2] = {{0}, {0}};  // aqr: remainder of S, enters the decay gradient only
+    float pk_inter[2] = {0.f, 0.f};
     _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        const int tok = 32 * nb + n;  // j
-        f32x16 aq = {0}, aqr = {0};   // aqr: remainder of S, enters the decay gradient only
+        const int tok = 32 * nb + n;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
             const bf16x8 dof = frag(dO, LD, tok, 16 * ks + 8 * half);
-            aq = mfma(sfrag[ks], dof, aq);
-            if (want_dg) aqr = mfma(srfrag[ks], dof, aqr);
+            aq[nb] = mfma(sfrag[ks], dof, aq[nb]);
+            if (want_dg) aqr[nb] = mfma(srfrag[ks], dof, aqr[nb]);
+            ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
         }
-        const float wq = __expf(bs[tok]);
-        _Pragma("unroll") for (int x = 0; x < 16; ++x) aq[x] *= wq;
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)
-            if (rb <= nb) {
-                f32x16 G = score_block(V, 32 * rb, dO, 32 * nb, n, half);  // D[m = r][n = j] = v_r . d_o_j
-                decay_mask<true>(G, 32 * rb, tok, bs, half);
-                bf16x8 hi[2], lo[2];
-                split_ops(G, hi, lo);
-                _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
-                    const bf16x8 kt = frag_tr_perm(K, LD, 32 * rb + 16 * s2, 32 * wave, lane);
-                    aq = mfma(kt, hi[s2], aq);
-                    aq = mfma(kt, lo[s2], aq);
-                }
-            }
-        if (want_dg) {
-            f32x16 full = aq;
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) full[x] += wq * aqr[x];
-            float pq = row_dot(Q, tok, wave, half, full);
-            pq += __shfl_xor(pq, 32, 64);
-            if (half == 0) red[(wave * 3 + 0) * 64 + tok] = pq;
+        const float wq = __expf(bs[tok]), wk = __expf(bC - bs[tok]);
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+            aq[nb][x] *= wq;
+            aqr[nb][x] *= wq;
+            ak[nb][x] *= wk;
         }
-        resq[nb] = pack_block(aq);
+        if (want_dg) pk_inter[nb] = row_dot(K, tok, wave, half, ak[nb]);
     }
-    // ---- <S, dS> over this wave's rows, then dk^T[i][r]
+    // ---- <S, dS> over this wave's rows
     if (want_dg) {
         float z = 0.f;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
@@ -607,36 +594,53 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
         for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
         if (lane == 0) zred[wave] = z;
     }
+    // ---- G = (dO V^T) * D: each of its three 32 x 32 blocks is computed by one wave (wave 0: (0,0),
+    // wave 1: (1,0), wave 2: (1,1)) and handed to the others as head + remainder through the V tile,
+    // which nothing reads between here and the dS hand-over of the dv phase.  Rows j; columns r of the
+    // head in 0..63, of the remainder in 64..127 (one 64 x 128 tile).
+    constexpr int LDG = LD;
+    uint16_t* Gh = V;
+    uint16_t* Gl = V + C;
+    {
+        f32x16 G = {0};
+        const int pjb = wave ? 1 : 0, prb = wave == 2 ? 1 : 0;
+        if (wave < 3) {
+            G = score_block(V, 32 * prb, dO, 32 * pjb, n, half);  // D[m = r][n = j] = v_r . d_o_j
+            decay_mask<true>(G, 32 * prb, 32 * pjb + n, bs, half);
+        }
+        __syncthreads();  // every wave is done with V
+        if (wave < 3) store_block_t_split(Gh, Gl, LDG, 32 * pjb + n, 32 * prb, half, G);
+        __syncthreads();
+    }
     _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        const int tok = 32 * nb + n;  // r
-        f32x16 ak = {0};
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak);
-        const float wk = __expf(bC - bs[tok]);
-        _Pragma("unroll") for (int x = 0; x < 16; ++x) ak[x] *= wk;
-        float pk_inter = 0.f;
-        if (want_dg) pk_inter = row_dot(K, tok, wave, half, ak);
-        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb)
-            if (jb >= nb) {
-                f32x16 Gt = score_block(dO, 32 * jb, V, 32 * nb, n, half);  // D[m = j][n = r] = d_o_j . v_r
-                decay_mask<false>(Gt, 32 * jb, tok, bs, half);
-                bf16x8 hi[2], lo[2];
-                split_ops(Gt, hi, lo);
-                _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
-                    const bf16x8 qt = frag_tr_perm(Q, LD, 32 * jb + 16 * s2, 32 * wave, lane);
-                    ak = mfma(qt, hi[s2], ak);
-                    ak = mfma(qt, lo[s2], ak);
-                }
-            }
+        const int tok = 32 * nb + n;
+        // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r]: keys r >= 32 never reach queries j < 32
+        _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {
+            const bf16x8 kt = frag_tr(K, LD, 16 * ks, 32 * wave, lane);
+            aq[nb] = mfma(kt, frag(Gh, LDG, tok, 16 * ks + 8 * half), aq[nb]);
+            aq[nb] = mfma(kt, frag(Gl, LDG, tok, 16 * ks + 8 * half), aq[nb]);
+        }
+        // dk^T[i][r] += sum_{j>=r} Q^T[i][j] G[j][r]: queries j < 32 never see keys r >= 32
+        _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+            const bf16x8 qt = frag_tr(Q, LD, 16 * ks, 32 * wave, lane);
+            ak[nb] = mfma(qt, frag_tr(Gh, LDG, 16 * ks, 32 * nb, lane), ak[nb]);  // B[k = j][n = r] = G[j][r]
+            ak[nb] = mfma(qt, frag_tr(Gl, LDG, 16 * ks, 32 * nb, lane), ak[nb]);
+        }
         if (want_dg) {
-            float pk = row_dot(K, tok, wave, half, ak);
+            f32x16 full = aq[nb];
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) full[x] += aqr[nb][x];
+            float pq = row_dot(Q, tok, wave, half, full), pk = row_dot(K, tok, wave, half, ak[nb]);
+            pq += __shfl_xor(pq, 32, 64);
             pk += __shfl_xor(pk, 32, 64);
-            pk_inter += __shfl_xor(pk_inter, 32, 64);
+            const float pi = pk_inter[nb] + __shfl_xor(pk_inter[nb], 32, 64);
             if (half == 0) {
+                red[(wave * 3 + 0) * 64 + tok] = pq;
                 red[(wave * 3 + 1) * 64 + tok] = pk;
-                red[(wave * 3 + 2) * 64 + tok] = pk_inter;
+                red[(wave * 3 + 2) * 64 + tok] = pi;
             }
         }
-        resk[nb] = pack_block(ak);
+        resq[nb] = pack_block(aq[nb]);
+        resk[nb] = pack_block(ak[nb]);
     }
     // ---- dv^T[v][r], v in this wave's slice.  The inter part contracts over the rows i of dS, which
     // the four waves hold as their A fragments: they are handed over through the V tile (dead by now),
