@@ -645,10 +645,19 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     // ---- dv^T[v][r], v in this wave's slice.  The inter part contracts over the rows i of dS, which
     // the four waves hold as their A fragments: they are handed over through the V tile (dead by now),
     // 64 rows at a time, and read back token-major with the LDS transpose read.
+    // The intra part needs As = (Q K^T) * D: like G, one wave per block, handed over through the Q tile
+    // (dead once the dk products are done) at the barriers of the dS hand-over.
     {
         f32x16 av[2] = {{0}, {0}};
+        f32x16 As = {0};
+        const int pjb = wave ? 1 : 0, prb = wave == 2 ? 1 : 0;
+        if (wave < 3) {
+            As = score_block(K, 32 * prb, Q, 32 * pjb, n, half);  // D[m = r][n = j] = k_r . q_j
+            decay_mask<true>(As, 32 * prb, 32 * pjb + n, bs, half);
+        }
         _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {
-            __syncthreads();  // hf = 0: every wave is done with V; hf = 1: done with the first 64 rows
+            __syncthreads();  // hf = 0: every wave is done with V (G) and Q; hf = 1: done with the first 64 rows
+            if (hf == 0 && wave < 3) store_block_t_split(Q, Q + C, LD, 32 * pjb + n, 32 * prb, half, As);
             if ((wave >> 1) == hf) {
                 _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
                     *reinterpret_cast<bf16x8*>(V + (32 * (wave & 1) + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
@@ -664,18 +673,12 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
             const int r = 32 * nb + n;
             const float wk = __expf(bC - bs[r]);
             _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
-            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb)
-                if (jb >= nb) {
-                    f32x16 As = score_block(Q, 32 * jb, K, 32 * nb, n, half);  // D[m = j][n = r] = q_j . k_r
-                    decay_mask<false>(As, 32 * jb, r, bs, half);
-                    bf16x8 hi[2], lo[2];
-                    split_ops(As, hi, lo);
-                    _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
-                        const bf16x8 dot = frag_tr_perm(dO, LD, 32 * jb + 16 * s2, 32 * wave, lane);
-                        av[nb] = mfma(dot, hi[s2], av[nb]);
-                        av[nb] = mfma(dot, lo[s2], av[nb]);
-                    }
-                }
+            // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]: queries j < 32 never see keys r >= 32
+            _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+                const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
+                av[nb] = mfma(dot, frag_tr(Q, LD, 16 * ks, 32 * nb, lane), av[nb]);      // B[k = j][n = r] = As[j][r]
+                av[nb] = mfma(dot, frag_tr(Q, LD, 16 * ks, C + 32 * nb, lane), av[nb]);  // remainder
+            }
             resv[nb] = pack_block(av[nb]);
         }
     }
