@@ -428,15 +428,20 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     const size_t tok0 = size_t(bh) * d.T + t0;
     const int n = lane & 31, half = lane >> 5;
 
+    // tiles first, state rows after them (loads return in order; the rows are needed only by the MFMAs)
+    TileRegs tq, tk, tv;
+    tile_gload(tq, q, tok0, L, tid);
+    tile_gload(tk, k, tok0, L, tid);
+    tile_gload(tv, v, tok0, L, tid);
     // state rows of this wave straight from global memory: A operand [m = v][k = i]
     const uint16_t* St = states + (size_t(bh) * d.N + c) * D * D;
     bf16x8 sfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
         sfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(St + state_frag_off(wave, ks, lane)));
 
-    load_tile(Q, q, tok0, L, tid);
-    load_tile(K, k, tok0, L, tid);
-    load_tile(V, v, tok0, L, tid);
+    tile_commit(Q, tq, L, tid);
+    tile_commit(K, tk, L, tid);
+    tile_commit(V, tv, L, tid);
     cumulative_decay(d, g, bh, t0, L, bs, tid);
     __syncthreads();
 
@@ -546,6 +551,14 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     const uint16_t* dS = dstates + (size_t(bh) * d.N + c) * D * D;
     const bool want_dg = dg_tok != nullptr;  // then states_rem is present
 
+    // The tiles are requested first and the state rows after them: loads return in order, so the tiles
+    // can go to LDS (and the barrier be reached) while the state rows, needed only by the first MFMAs,
+    // are still on their way.
+    TileRegs tq, tk, tv, to;
+    tile_gload(tq, q, tok0, L, tid);
+    tile_gload(tk, k, tok0, L, tid);
+    tile_gload(tv, v, tok0, L, tid);
+    tile_gload(to, d_o, tok0, L, tid);
     // rows i in [32w, 32w+32) of S (and its remainder): A operands [m = i][k = v]
     bf16x8 sfrag[8], srfrag[8], dsfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
@@ -554,10 +567,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
         if (want_dg)
             srfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(states_rem + (S - states) + state_frag_off(wave, ks, lane)));
     }
-    load_tile(Q, q, tok0, L, tid);
-    load_tile(K, k, tok0, L, tid);
-    load_tile(V, v, tok0, L, tid);
-    load_tile(dO, d_o, tok0, L, tid);
+    tile_commit(Q, tq, L, tid);
+    tile_commit(K, tk, L, tid);
+    tile_commit(V, tv, L, tid);
+    tile_commit(dO, to, L, tid);
     cumulative_decay(d, g, bh, t0, L, bs, tid);
     __syncthreads();
     const float bC = bs[C - 1];

@@ -100,6 +100,21 @@ __device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, si
         *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = v;
     }
 }
+// the same in two steps: global -> registers (no operation on the loaded values), registers -> LDS
+struct TileRegs { u32x4 v[4]; };
+__device__ __forceinline__ void tile_gload(TileRegs& r, const uint16_t* src, size_t tok0, int L, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        r.v[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + min(row, L - 1)) * D + cp * 8));
+    }
+}
+__device__ __forceinline__ void tile_commit(uint16_t* dst, const TileRegs& r, int L, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        const uint32_t keep = row < L ? 0xffffffffu : 0u;
+        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{r.v[it].x & keep, r.v[it].y & keep, r.v[it].z & keep, r.v[it].w & keep};
+    }
+}
 // LDS tile (row stride LD) rows [0, L) -> global
 __device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
