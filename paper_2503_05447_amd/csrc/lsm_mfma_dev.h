@@ -95,9 +95,9 @@ __device__ __forceinline__ void store_block_t_split(uint16_t* hi, uint16_t* lo, 
 __device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        u32x4 v = {0, 0, 0, 0};
-        if (row < L) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + row) * D + cp * 8));
-        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = v;
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + min(row, L - 1)) * D + cp * 8));
+        const uint32_t keep = row < L ? 0xffffffffu : 0u;  // branch-free: a branch around a load drains the load queue
+        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
     }
 }
 // the same in two steps: global -> registers (no operation on the loaded values), registers -> LDS

@@ -44,13 +44,15 @@ __device__ __forceinline__ void decay_tile(float* bt, const float* __restrict__ 
     const int cp = tid & 15, r0 = tid >> 4;
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int row = r0 + 16 * it;
-        float4 g0 = {0.f, 0.f, 0.f, 0.f}, g1 = g0;
-        if (row < L) {
-            g0 = *reinterpret_cast<const float4*>(g + (tok0 + row) * D + cp * 8);
-            g1 = *reinterpret_cast<const float4*>(g + (tok0 + row) * D + cp * 8 + 4);
-        }
-        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8) = g0;
-        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8 + 4) = g1;
+        // branch-free (rows beyond the ragged end read the last valid row and are zeroed): a branch
+        // around a load makes the wave wait for every load in flight
+        const float* src = g + (tok0 + min(row, L - 1)) * D + cp * 8;
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 g0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src));
+        const f32x4 g1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + 4));
+        const float keep = row < L ? 1.f : 0.f;
+        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8) = float4{g0.x * keep, g0.y * keep, g0.z * keep, g0.w * keep};
+        *reinterpret_cast<float4*>(bt + row * LDF + cp * 8 + 4) = float4{g1.x * keep, g1.y * keep, g1.z * keep, g1.w * keep};
     }
     __syncthreads();
     // inclusive scan along tokens, one feature column per thread, two halves of 32 tokens
@@ -111,12 +113,14 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
     u32x4 qr[4], kr[4];
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int row = r0 + 16 * it;
-        qr[it] = u32x4{0, 0, 0, 0};
-        kr[it] = u32x4{0, 0, 0, 0};
-        if (row < L) {
-            qr[it] = *reinterpret_cast<const u32x4*>(q + (tok0 + row) * D + cp * 8);
-            kr[it] = *reinterpret_cast<const u32x4*>(k + (tok0 + row) * D + cp * 8);
-        }
+        qr[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + (tok0 + min(row, L - 1)) * D + cp * 8));
+        kr[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k + (tok0 + min(row, L - 1)) * D + cp * 8));
+    }
+    decay_tile(bt, g, tok0, L, tid);
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {  // zero the ragged tail (after the loads have been issued)
+        const uint32_t keep = r0 + 16 * it < L ? 0xffffffffu : 0u;
+        qr[it] = u32x4{qr[it].x & keep, qr[it].y & keep, qr[it].z & keep, qr[it].w & keep};
+        kr[it] = u32x4{kr[it].x & keep, kr[it].y & keep, kr[it].z & keep, kr[it].w & keep};
     }
     // diagonal scores q_t . k_t: exact products, summed over this thread's 8 features, then over the
     // 16 threads that share the row (consecutive lanes)
@@ -125,9 +129,8 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
         _Pragma("unroll") for (int p = 0; p < 4; ++p)
             s += bf16_lo(qr[it][p]) * bf16_lo(kr[it][p]) + bf16_hi(qr[it][p]) * bf16_hi(kr[it][p]);
         _Pragma("unroll") for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-        if (cp == 0) diag[r0 + 16 * it] = s;
+        if (cp == 0) diag[r0 + 16 * it] = s;  // read after the barriers of the level loop
     }
-    decay_tile(bt, g, tok0, L, tid);
     float bC[8];
     decay_row8(bt, 63, cp * 8, bC);
     auto brow = [&](int row, float* out) { decay_row8(bt, row, cp * 8, out); };
@@ -248,9 +251,10 @@ __device__ __forceinline__ void load_tile_strided(uint16_t* dst, const uint16_t*
                                                   int col0, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        u32x4 v = {0, 0, 0, 0};
-        if (row < L) v = *reinterpret_cast<const u32x4*>(src + (tok0 + row) * stride + col0 + cp * 8);
-        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = v;
+        const u32x4 v = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4*>(src + (tok0 + min(row, L - 1)) * stride + col0 + cp * 8));
+        const uint32_t keep = row < L ? 0xffffffffu : 0u;
+        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
     }
 }
 __device__ __forceinline__ void store_tile_strided(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int stride,
@@ -258,8 +262,8 @@ __device__ __forceinline__ void store_tile_strided(uint16_t* dst, const uint16_t
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         if (row < L)
-            *reinterpret_cast<u32x4*>(dst + (tok0 + row) * stride + col0 + cp * 8) =
-                *reinterpret_cast<const u32x4*>(src + row * LD + cp * 8);
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
+                                        reinterpret_cast<u32x4*>(dst + (tok0 + row) * stride + col0 + cp * 8));
     }
 }
 // 64 x 64 bf16 matrix (dense rows) -> LDS tile with row stride LDP
