@@ -27,16 +27,18 @@ namespace lsm {
 namespace {
 
 
-// Chunk-local inclusive cumulative log-decay b_j, j = 0..63, into LDS (tokens >= L carry g = 0).
-// Called by all threads; only wave 0 works.  Caller synchronises afterwards.
-__device__ __forceinline__ void cumulative_decay(const Dims& d, const float* g, int bh, int t0, int L, float* bs,
-                                                 int tid) {
+// Log-decay of this lane's token (every wave loads, only wave 0's value is used).  To be called
+// BEFORE the kernel's other global loads: loads return in order, so waiting for this one later
+// leaves the younger ones in flight, whereas as the youngest it would drain the whole queue.
+__device__ __forceinline__ float decay_gload(const Dims& d, const float* g, int bh, int t0, int L, int lane) {
+    if (d.kind == 0) return 0.f;
+    return g[d.kind == 1 ? size_t(bh % d.H) : size_t(bh) * d.T + t0 + min(lane, L - 1)];
+}
+// Chunk-local inclusive cumulative log-decay b_j, j = 0..63, into LDS (tokens >= L carry g = 0) from
+// the values of decay_gload.  Called by all threads; only wave 0 works.  Caller synchronises afterwards.
+__device__ __forceinline__ void cumulative_decay(float gval, int L, float* bs, int tid) {
     if (tid >= 64) return;
-    float x = 0.f;
-    if (tid < L) {
-        if (d.kind == 1) x = g[bh % d.H];
-        else if (d.kind == 2) x = g[size_t(bh) * d.T + t0 + tid];
-    }
+    float x = tid < L ? gval : 0.f;
     for (int off = 1; off < 64; off <<= 1) {
         const float y = __shfl_up(x, off, 64);
         if (tid >= off) x += y;
@@ -428,7 +430,9 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     const size_t tok0 = size_t(bh) * d.T + t0;
     const int n = lane & 31, half = lane >> 5;
 
-    // tiles first, state rows after them (loads return in order; the rows are needed only by the MFMAs)
+    // decay first, then the tiles, the state rows after them (loads return in order; the rows are
+    // needed only by the MFMAs)
+    const float gval = decay_gload(d, g, bh, t0, L, lane);
     TileRegs tq, tk, tv;
     tile_gload(tq, q, tok0, L, tid);
     tile_gload(tk, k, tok0, L, tid);
@@ -442,7 +446,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     tile_commit(Q, tq, L, tid);
     tile_commit(K, tk, L, tid);
     tile_commit(V, tv, L, tid);
-    cumulative_decay(d, g, bh, t0, L, bs, tid);
+    cumulative_decay(gval, L, bs, tid);
     __syncthreads();
 
     PackedBlock res[2];
@@ -526,6 +530,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
 //      per-wave partial row dots) | zred
 constexpr int kGradLds = 4 * C * LD * 2 + C * 4 + 4 * 64 * 3 * 4 + 64;
 
+template <bool WANT_DG>  // decay gradient asked for: then states_rem and dg_tok are present
 __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* __restrict__ q,
                                                        const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                        const uint16_t* __restrict__ d_o, const float* __restrict__ g,
@@ -549,11 +554,12 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     const int n = lane & 31, half = lane >> 5;
     const uint16_t* S = states + (size_t(bh) * d.N + c) * D * D;
     const uint16_t* dS = dstates + (size_t(bh) * d.N + c) * D * D;
-    const bool want_dg = dg_tok != nullptr;  // then states_rem is present
+    constexpr bool want_dg = WANT_DG;
 
     // The tiles are requested first and the state rows after them: loads return in order, so the tiles
     // can go to LDS (and the barrier be reached) while the state rows, needed only by the first MFMAs,
     // are still on their way.
+    const float gval = decay_gload(d, g, bh, t0, L, lane);
     TileRegs tq, tk, tv, to;
     tile_gload(tq, q, tok0, L, tid);
     tile_gload(tk, k, tok0, L, tid);
@@ -571,7 +577,7 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     tile_commit(K, tk, L, tid);
     tile_commit(V, tv, L, tid);
     tile_commit(dO, to, L, tid);
-    cumulative_decay(d, g, bh, t0, L, bs, tid);
+    cumulative_decay(gval, L, bs, tid);
     __syncthreads();
     const float bC = bs[C - 1];
 
@@ -961,7 +967,8 @@ hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     auto d_o = static_cast<const uint16_t*>(a.d_o);
     hipError_t e;
-    if ((e = allow_lds(mk_grad, kGradLds)) != hipSuccess) return e;
+    if ((e = allow_lds(mk_grad<true>, kGradLds)) != hipSuccess) return e;
+    if ((e = allow_lds(mk_grad<false>, kGradLds)) != hipSuccess) return e;
     launch_prep(d, a.stream, a.g, w);
     {
         ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
@@ -973,9 +980,14 @@ hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     if (a.dg) dg_tok = d.kind == 1 ? w.dg_tok : a.dg;  // per-token scalar decay: written in place
     {
         ProfScope ps(KID_MFMA_GRAD, a.stream);
-        hipLaunchKernelGGL(mk_grad, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem,
-                           w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
-                           static_cast<uint16_t*>(a.dv), dg_tok);
+        if (dg_tok)
+            hipLaunchKernelGGL(mk_grad<true>, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem,
+                               w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
+                               static_cast<uint16_t*>(a.dv), dg_tok);
+        else
+            hipLaunchKernelGGL(mk_grad<false>, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem,
+                               w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
+                               static_cast<uint16_t*>(a.dv), dg_tok);
     }
     if (a.dg && d.kind == 1) {
         ProfScope ps(KID_HEAD_REDUCE, a.stream);
