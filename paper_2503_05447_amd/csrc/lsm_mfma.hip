@@ -84,7 +84,8 @@ __global__ __launch_bounds__(64) void mk_decay_prep(Dims d, const float* __restr
 // The loop is software-pipelined: the operands of chunk c+1 are turned, weighted and packed while
 // the accumulation of chunk c is in the matrix pipe; loads run kStatePrefetch chunks ahead.
 // edge_in = M_0 (or d M_T), edge_out = M_T (or d M_0), fp32 [i][v], either may be NULL.
-// states_rem (may be NULL) receives the bf16 remainder S - bf16(S) in the same layout: the decay
+// states_rem (may be NULL) receives the remainder S - bf16(S) in the same layout (scalar decay kinds:
+// as 8-bit floats, vector kind: as bf16): the decay
 // gradient contracts q_u S d_o_u^T into one scalar per token, where the 2^-9 rounding of a state that
 // a single token dominates is visible.
 constexpr int LDB = 40;  // row stride (elements) of a 64 x 32 B-side slice in LDS
@@ -202,6 +203,16 @@ __device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage
     }
 }
 
+// the remainder plane of the scalar decay kinds: one byte per element (see store_block_t_split8), same
+// fragment-major element order, 8 bytes per lane and k-step
+__device__ __forceinline__ void state_store8(uint8_t* dst, const uint8_t* stage, int mb, int rowblk, int colblk, int lane) {
+    _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+        const int piece = 2 * it + (lane >> 5), ksl = piece >> 1, hf = piece & 1, r = lane & 31;
+        const u32x2 val = *reinterpret_cast<const u32x2*>(stage + r * LD + 32 * mb + 16 * ksl + 8 * hf);
+        __builtin_nontemporal_store(val, reinterpret_cast<u32x2*>(dst + state_frag_off(rowblk, 2 * colblk + ksl, 32 * hf + r)));
+    }
+}
+
 // VEC (per-key-feature decay): the decayed operand (k e^{b_C-b} or q e^{b}) arrives precomputed as a
 // head and a remainder plane and is always the B side, so that a state column n is one key feature i
 // and e^{b_C[i]} is one factor per lane; the A side is a 128-wide slice of the value-sized operand
@@ -292,7 +303,8 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
                 sp[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
         }
         if (MODE != 3) {
-            if (states_rem) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
+            if (states_rem && VEC) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
+            else if (states_rem) store_block_t_split8(sh, reinterpret_cast<uint8_t*>(sh + 32 * LD), LD, n, 32 * mb, half, acc);
             else store_block_t(sh, LD, n, 32 * mb, half, acc);
         }
         if (DEC) {
@@ -311,7 +323,10 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         // transposed staging: stage row = state column n (block nb); untransposed: stage row = state row m (block mb)
         if (MODE == 3) state_store<false>(states + slot(k), sh, mb, mb, nb, lane);
         else state_store(states + slot(k), sh, mb, nb, mb, lane);
-        if (MODE != 3 && states_rem) state_store(states_rem + slot(k), sh + 32 * LD, mb, nb, mb, lane);
+        if (MODE != 3 && states_rem) {
+            if (VEC) state_store(states_rem + slot(k), sh + 32 * LD, mb, nb, mb, lane);
+            else state_store8(reinterpret_cast<uint8_t*>(states_rem) + slot(k), reinterpret_cast<const uint8_t*>(sh + 32 * LD), mb, nb, mb, lane);
+        }
         if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
     };
     int k = 0;
@@ -571,7 +586,8 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
         sfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(S + state_frag_off(wave, ks, lane)));
         dsfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane)));
         if (want_dg)
-            srfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(states_rem + (S - states) + state_frag_off(wave, ks, lane)));
+            srfrag[ks] = rem8_to_bf16(__builtin_nontemporal_load(reinterpret_cast<const u32x2*>(
+                reinterpret_cast<const uint8_t*>(states_rem) + (S - states) + state_frag_off(wave, ks, lane))));
     }
     tile_commit(Q, tq, L, tid);
     tile_commit(K, tk, L, tid);
@@ -593,10 +609,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
             if (want_dg) aqr[nb] = mfma(srfrag[ks], dof, aqr[nb]);
             ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
         }
-        const float wq = __expf(bs[tok]), wk = __expf(bC - bs[tok]);
+        const float wq = __expf(bs[tok]), wk = __expf(bC - bs[tok]), wqr = wq * kRem8Unscale;
         _Pragma("unroll") for (int x = 0; x < 16; ++x) {
             aq[nb][x] *= wq;
-            aqr[nb][x] *= wq;
+            aqr[nb][x] *= wqr;
             ak[nb][x] *= wk;
         }
         if (want_dg) pk_inter[nb] = row_dot(K, tok, wave, half, ak[nb]);
@@ -608,7 +624,8 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
             u32x4 a = __builtin_bit_cast(u32x4, sfrag[ks]), b = __builtin_bit_cast(u32x4, dsfrag[ks]);
             u32x4 ar = __builtin_bit_cast(u32x4, srfrag[ks]);
             _Pragma("unroll") for (int p = 0; p < 4; ++p)
-                z += (bf16_lo(a[p]) + bf16_lo(ar[p])) * bf16_lo(b[p]) + (bf16_hi(a[p]) + bf16_hi(ar[p])) * bf16_hi(b[p]);
+                z += (bf16_lo(a[p]) + kRem8Unscale * bf16_lo(ar[p])) * bf16_lo(b[p]) +
+                     (bf16_hi(a[p]) + kRem8Unscale * bf16_hi(ar[p])) * bf16_hi(b[p]);
         }
         for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
         if (lane == 0) zred[wave] = z;
@@ -793,7 +810,7 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
         return w;
     }
     if (bwd) { w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st; }
-    if (bwd && d.kind != 0) { w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += st; }
+    if (bwd && d.kind != 0) { w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2); }  // one byte per element
     if (d.kind != 0) {
         w.wdec = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * C * 4);
         w.winc = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * C * 4);
