@@ -84,8 +84,7 @@ __global__ __launch_bounds__(64) void mk_decay_prep(Dims d, const float* __restr
 // The loop is software-pipelined: the operands of chunk c+1 are turned, weighted and packed while
 // the accumulation of chunk c is in the matrix pipe; loads run kStatePrefetch chunks ahead.
 // edge_in = M_0 (or d M_T), edge_out = M_T (or d M_0), fp32 [i][v], either may be NULL.
-// states_rem (may be NULL) receives the remainder S - bf16(S) in the same layout (scalar decay kinds:
-// as 8-bit floats, vector kind: as bf16): the decay
+// states_rem (may be NULL) receives the remainder S - bf16(S) in the same layout as 8-bit floats: the decay
 // gradient contracts q_u S d_o_u^T into one scalar per token, where the 2^-9 rounding of a state that
 // a single token dominates is visible.
 constexpr int LDB = 40;  // row stride (elements) of a 64 x 32 B-side slice in LDS
@@ -203,7 +202,7 @@ __device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage
     }
 }
 
-// the remainder plane of the scalar decay kinds: one byte per element (see store_block_t_split8), same
+// the remainder plane: one byte per element (see store_block_t_split8), same
 // fragment-major element order, 8 bytes per lane and k-step
 __device__ __forceinline__ void state_store8(uint8_t* dst, const uint8_t* stage, int mb, int rowblk, int colblk, int lane) {
     _Pragma("unroll") for (int it = 0; it < 2; ++it) {
@@ -303,8 +302,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
                 sp[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
         }
         if (MODE != 3) {
-            if (states_rem && VEC) store_block_t_split(sh, sh + 32 * LD, LD, n, 32 * mb, half, acc);
-            else if (states_rem) store_block_t_split8(sh, reinterpret_cast<uint8_t*>(sh + 32 * LD), LD, n, 32 * mb, half, acc);
+            if (states_rem) store_block_t_split8(sh, reinterpret_cast<uint8_t*>(sh + 32 * LD), LD, n, 32 * mb, half, acc);
             else store_block_t(sh, LD, n, 32 * mb, half, acc);
         }
         if (DEC) {
@@ -324,8 +322,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         if (MODE == 3) state_store<false>(states + slot(k), sh, mb, mb, nb, lane);
         else state_store(states + slot(k), sh, mb, nb, mb, lane);
         if (MODE != 3 && states_rem) {
-            if (VEC) state_store(states_rem + slot(k), sh + 32 * LD, mb, nb, mb, lane);
-            else state_store8(reinterpret_cast<uint8_t*>(states_rem) + slot(k), reinterpret_cast<const uint8_t*>(sh + 32 * LD), mb, nb, mb, lane);
+            state_store8(reinterpret_cast<uint8_t*>(states_rem) + slot(k), reinterpret_cast<const uint8_t*>(sh + 32 * LD), mb, nb, mb, lane);
         }
         if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
     };
@@ -797,8 +794,8 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
         if (bwd) {
             w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st;
             w.dstates_t = reinterpret_cast<uint16_t*>(p + off); off += st;
-            w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += st;
-            w.dstates_rem = reinterpret_cast<uint16_t*>(p + off); off += st;
+            w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2);  // one byte per element
+            w.dstates_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2);
         }
         const size_t plane = align256(size_t(d.BH()) * d.T * D * 2), sc = align256(size_t(d.BH()) * d.N * C * C * 2);
         uint16_t** planes[4] = {&w.khat_hi, &w.khat_lo, &w.qhat_hi, &w.qhat_lo};

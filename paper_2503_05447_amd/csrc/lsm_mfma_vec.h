@@ -395,7 +395,8 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
     // registers into LDS) and this wave's rows of S, dS and their remainder planes (MFMA A operands).
     struct SliceRegs {
         u32x4 tv[4], to[4];
-        bf16x8 s[8], sr[8], ds[8], dsr[8];
+        bf16x8 s[8], ds[8];
+        u32x2 sr[8], dsr[8];  // remainder planes: 8-bit floats, still scaled by 2^8
     };
     auto issue = [&](int vh, SliceRegs& r) {
         _Pragma("unroll") for (int it = 0; it < 4; ++it) {
@@ -412,8 +413,8 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
             r.s[ks] = *reinterpret_cast<const bf16x8*>(states + soff);
             r.ds[ks] = *reinterpret_cast<const bf16x8*>(dstates + soff);
             if (want_dg) {
-                r.sr[ks] = *reinterpret_cast<const bf16x8*>(states_rem + soff);
-                r.dsr[ks] = *reinterpret_cast<const bf16x8*>(dstates_rem + soff);
+                r.sr[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(states_rem) + soff));
+                r.dsr[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(dstates_rem) + soff));
             }
         }
     };
@@ -449,17 +450,17 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
                 aq[nb] = mfma(sr0.s[ks], dof, aq[nb]);
                 ak[nb] = mfma(sr0.ds[ks], vf, ak[nb]);
                 if (want_dg) {
-                    aqr[nb] = mfma(sr0.sr[ks], dof, aqr[nb]);
-                    akr[nb] = mfma(sr0.dsr[ks], vf, akr[nb]);
+                    aqr[nb] = mfma(rem8_to_bf16(sr0.sr[ks]), dof, aqr[nb]);
+                    akr[nb] = mfma(rem8_to_bf16(sr0.dsr[ks]), vf, akr[nb]);
                 }
             }
         if (want_dg) {  // <S, dS> over this lane's share of row i = 32 wave + n
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                const u32x4 a = __builtin_bit_cast(u32x4, sr0.s[ks]), ar = __builtin_bit_cast(u32x4, sr0.sr[ks]);
-                const u32x4 b = __builtin_bit_cast(u32x4, sr0.ds[ks]), br = __builtin_bit_cast(u32x4, sr0.dsr[ks]);
+                const u32x4 a = __builtin_bit_cast(u32x4, sr0.s[ks]), ar = __builtin_bit_cast(u32x4, rem8_to_bf16(sr0.sr[ks]));
+                const u32x4 b = __builtin_bit_cast(u32x4, sr0.ds[ks]), br = __builtin_bit_cast(u32x4, rem8_to_bf16(sr0.dsr[ks]));
                 _Pragma("unroll") for (int p = 0; p < 4; ++p)
-                    zi += (bf16_lo(a[p]) + bf16_lo(ar[p])) * (bf16_lo(b[p]) + bf16_lo(br[p])) +
-                          (bf16_hi(a[p]) + bf16_hi(ar[p])) * (bf16_hi(b[p]) + bf16_hi(br[p]));
+                    zi += (bf16_lo(a[p]) + kRem8Unscale * bf16_lo(ar[p])) * (bf16_lo(b[p]) + kRem8Unscale * bf16_lo(br[p])) +
+                          (bf16_hi(a[p]) + kRem8Unscale * bf16_hi(ar[p])) * (bf16_hi(b[p]) + kRem8Unscale * bf16_hi(br[p]));
             }
         }
         {   // this wave's block of Z: rows of V and d_o as operands
@@ -499,9 +500,9 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
                 const int x = 4 * gq + jj;
                 const float wq = __expf(bb[jj]), wk = __expf(cc[jj] - bb[jj]);
                 aq[nb][x] *= wq;
-                aqr[nb][x] *= wq;
+                aqr[nb][x] *= wq * kRem8Unscale;
                 ak[nb][x] *= wk;
-                akr[nb][x] *= wk;
+                akr[nb][x] *= wk * kRem8Unscale;
                 xk[x] += kf[jj] * (ak[nb][x] + akr[nb][x]);
             }
         }
