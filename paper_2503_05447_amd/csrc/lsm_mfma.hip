@@ -738,17 +738,24 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
             const float y = __shfl_down(sfx, off, 64);
             if (tid + off < 64) sfx += y;
         }
-        if (tid < L) dg_tok[tok0 + tid] = sfx + tail + __expf(bC) * z;
+        float dgv = tid < L ? sfx + tail + __expf(bC) * z : 0.f;
+        if (d.kind == 1) {
+            // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
+            for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
+            if (tid == 0) dg_tok[size_t(bh) * d.N + c] = dgv;
+        } else if (tid < L) {
+            dg_tok[tok0 + tid] = dgv;
+        }
     }
 }
 
-// dg[h] = sum_{b,t} dg_tok[b,h,t] in a fixed order (grid: H)
+// dg[h] = sum over batch elements and chunks of the per-chunk sums dg_chunk[b,h,c], in a fixed order (grid: H)
 __global__ void mk_head_reduce(Dims d, const float* __restrict__ dg_tok, float* __restrict__ dg) {
     __shared__ float part[kThreads];
     const int h = blockIdx.x;
     float s = 0.f;
-    const size_t nn = size_t(d.B) * d.T;
-    for (size_t e = threadIdx.x; e < nn; e += blockDim.x) s += dg_tok[((e / d.T) * d.H + h) * d.T + e % d.T];
+    const size_t nn = size_t(d.B) * d.N;
+    for (size_t e = threadIdx.x; e < nn; e += blockDim.x) s += dg_tok[((e / d.N) * d.H + h) * d.N + e % d.N];
     part[threadIdx.x] = s;
     __syncthreads();
     for (int w = kThreads / 2; w > 0; w >>= 1) {
@@ -813,7 +820,7 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
         w.winc = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * C * 4);
         w.lam = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * 4);
     }
-    if (bwd && d.kind == 1) { w.dg_tok = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.T * 4); }
+    if (bwd && d.kind == 1) { w.dg_tok = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * 4); }  // per-chunk sums
     w.bytes = off;
     return w;
 }
