@@ -164,6 +164,37 @@ def main():
             "issued_mfma_tflops": issued / pass_s / 1e12, "issued_frac_of_mfma_peak": issued / pass_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             "same_output_as_forward": bool(torch.equal(o_mb, last[0][0]))}
 
+    if not args.no_microbench:
+        # Recurrent decoding step (lsm_step) on the heads of this workload: state read + written once per step.
+        dec = {}
+        for Bd in (16, 256):
+            qd = torch.randn(Bd, H, dk, device=dev).to(tdt)
+            kd = torch.randn(Bd, H, dk, device=dev).to(tdt) / dk ** 0.5
+            vd = torch.randn(Bd, H, dv, device=dev).to(tdt)
+            gd = {wl.KIND_NONE: None, wl.KIND_HEAD: g}.get(kind, None)
+            if kind == wl.KIND_SCALAR:
+                gd = -torch.rand(Bd, H, device=dev)
+            elif kind == wl.KIND_VECTOR:
+                gd = -torch.rand(Bd, H, dk, device=dev)
+            st = torch.zeros(Bd, H, dk, dv, device=dev)
+            od = torch.empty(Bd, H, dv, device=dev, dtype=tdt)
+            nst = 200
+            for _ in range(20):
+                pkg.lsm_step(qd, kd, vd, gd, kind, st, od)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(nst):
+                pkg.lsm_step(qd, kd, vd, gd, kind, st, od)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / nst
+            state_bytes = Bd * H * dk * dv * 8
+            dec["batch_%d" % Bd] = {"us_per_step": us, "tokens_per_s": Bd / (us * 1e-6),
+                                    "state_GBps": state_bytes / (us * 1e-6) / 1e9, "state_bytes_per_step": state_bytes}
+        result["decode_step"] = {"what": "lsm_step, one token per sequence, H=%d d_k=%d d_v=%d, back-to-back launches on one stream "
+                                         "(launch overhead included); state_GBps = fp32 state read + written per step" % (H, dk, dv),
+                                 **dec}
+
     if not args.no_cpu_baseline or not args.no_check:
         from oracle import lsm_oracle_bwd, lsm_oracle_fwd, oracle_threads
         # bounded sample: the first `nb` batch elements of the same workload (all heads, full T)

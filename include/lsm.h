@@ -110,6 +110,22 @@ int lsm_chunk_bwd(const lsm_params* p,
                   float* d_log_decay, float* d_init_state,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * One recurrent step, the constant-memory form of the same recurrence used for decoding (Eq. 5 with the
+ * rank-1 update of Table 1, one token):  for every (b,h)
+ *     state <- diag(a) state + k^T v ,      o = q state .
+ *   q, k        [B,H,d_k]  dtype          in
+ *   v           [B,H,d_v]  dtype          in
+ *   log_decay   NONE: NULL;  HEAD: [H];  SCALAR: [B,H];  VECTOR: [B,H,d_k];  fp32, <= 0      in
+ *   state       [B,H,d_k,d_v] fp32, updated in place                                          in/out
+ *   o           [B,H,d_v]  dtype          out
+ * p->T and p->chunk_size are not used (they must still be valid; pass T = 1).  No workspace.  T calls of
+ * lsm_step from init_state give the o and final_state of lsm_chunk_fwd over the same T tokens, up to rounding.
+ */
+int lsm_step(const lsm_params* p,
+             const void* q, const void* k, const void* v, const float* log_decay,
+             float* state, void* o, void* stream);
+
 /* Scratch the calls above need, in bytes; 0 if *p is invalid.  Host-only, no HIP call. */
 size_t lsm_chunk_fwd_workspace_bytes(const lsm_params* p);
 size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p);

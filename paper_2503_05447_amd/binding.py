@@ -57,6 +57,8 @@ def library():
     lib.lsm_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
     lib.lsm_kernel_name.restype = ctypes.c_char_p
     lib.lsm_kernel_name.argtypes = [ctypes.c_int]
+    lib.lsm_step.restype = ctypes.c_int
+    lib.lsm_step.argtypes = [pp] + [vp] * 7
     lib.lsm_bench_intra_chunk.restype = ctypes.c_int
     lib.lsm_bench_intra_chunk.argtypes = [pp] + [vp] * 6 + [sz, ctypes.c_int, vp]
     _lib = lib
@@ -159,6 +161,36 @@ def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None
     if rc != 0:
         raise LsmError(rc, "lsm_chunk_fwd")
     return o, final
+
+
+def lsm_step(q, k, v, log_decay, decay_kind, state, o=None, stream=None):
+    """One recurrent step: ``state`` [B,H,d_k,d_v] fp32 is updated in place, returns o [B,H,d_v].
+
+    q, k [B,H,d_k], v [B,H,d_v]; log_decay None / [H] / [B,H] / [B,H,d_k] by decay kind."""
+    import torch
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    tdt = {torch.float32: 0, torch.bfloat16: 1}[q.dtype]
+    p = make_params(B, H, 1, dk, dv, 64, decay_kind, tdt)
+    _check(q, (B, H, dk), q.dtype, "q"); _check(k, (B, H, dk), q.dtype, "k"); _check(v, (B, H, dv), q.dtype, "v")
+    gshape = {DECAY_NONE: None, DECAY_HEAD: (H,), DECAY_SCALAR: (B, H), DECAY_VECTOR: (B, H, dk)}[decay_kind]
+    if gshape is None:
+        if log_decay is not None:
+            raise ValueError("log_decay must be None for DECAY_NONE")
+    else:
+        _check(log_decay, gshape, torch.float32, "log_decay")
+        if log_decay is None:
+            raise ValueError("log_decay is required for this decay kind")
+    _check(state, (B, H, dk, dv), torch.float32, "state")
+    if state is None:
+        raise ValueError("state is required")
+    if o is None:
+        o = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
+    rc = library().lsm_step(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(state), _ptr(o),
+                            _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_step")
+    return o
 
 
 def lsm_bench_intra_chunk(q, k, v, log_decay, decay_kind, o, workspace, repeats, chunk_size=64, stream=None):

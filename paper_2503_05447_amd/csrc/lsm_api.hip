@@ -101,7 +101,7 @@ const char* lsm_kernel_name(int kernel_id) {
     static const char* names[lsm::KID_COUNT] = {
         "generic_cumsum", "generic_chunk_state", "generic_scan", "generic_output", "generic_chunk_dstate",
         "generic_reverse_scan", "generic_grad", "head_reduce", "mfma_state_scan_fwd", "mfma_output",
-        "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep", "mfma_vector_decay_dv"};
+        "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep", "mfma_vector_decay_dv", "recurrent_step"};
     return kernel_id >= 0 && kernel_id < lsm::KID_COUNT ? names[kernel_id] : "unknown";
 }
 
@@ -155,6 +155,19 @@ int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, con
     if (!workspace || workspace_bytes < lsm_chunk_fwd_workspace_bytes(p)) return LSM_ERR_WORKSPACE;
     lsm::FwdArgs a{q, k, v, log_decay, nullptr, o, nullptr, workspace, static_cast<hipStream_t>(stream)};
     return lsm::mfma_intra_bench(d, a, repeats) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
+}
+
+int lsm_step(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay, float* state,
+             void* o, void* stream) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !o || !state) return LSM_ERR_NULL;
+    if ((d.kind == LSM_DECAY_NONE) != (log_decay == nullptr)) return LSM_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_decay) || misaligned(state))
+        return LSM_ERR_ALIGN;
+    return lsm::step(d, q, k, v, log_decay, state, o, static_cast<hipStream_t>(stream)) == hipSuccess ? LSM_OK
+                                                                                                    : LSM_ERR_LAUNCH;
 }
 
 int lsm_chunk_bwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,

@@ -42,7 +42,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 // Kernel identifiers reported by the optional per-kernel timing (lsm_profile_start / _stop).
 enum KernelId {
     KID_GEN_CUMSUM = 0, KID_GEN_STATE, KID_GEN_SCAN, KID_GEN_OUTPUT, KID_GEN_DSTATE, KID_GEN_RSCAN, KID_GEN_GRAD,
-    KID_HEAD_REDUCE, KID_MFMA_STATE, KID_MFMA_OUTPUT, KID_MFMA_STATE_BWD, KID_MFMA_DSTATE, KID_MFMA_GRAD, KID_MFMA_PREP, KID_MFMA_VEC_PREP, KID_MFMA_VEC_DV, KID_COUNT
+    KID_HEAD_REDUCE, KID_MFMA_STATE, KID_MFMA_OUTPUT, KID_MFMA_STATE_BWD, KID_MFMA_DSTATE, KID_MFMA_GRAD, KID_MFMA_PREP, KID_MFMA_VEC_PREP, KID_MFMA_VEC_DV, KID_STEP, KID_COUNT
 };
 // Bracket a kernel launch with events when timing is switched on (no-ops otherwise).
 void prof_begin(int kernel_id, hipStream_t stream);
@@ -69,5 +69,9 @@ hipError_t mfma_bwd(const Dims& d, const BwdArgs& a);
 // benchmark aid: the output kernel alone with its compute phase repeated `reps` times (scalar decay kinds);
 // the workspace must hold the chunk states of a preceding mfma_fwd call on the same inputs
 hipError_t mfma_intra_bench(const Dims& d, const FwdArgs& a, int reps);
+
+// Recurrent single-token step (decoding): state updated in place, T of the Dims ignored.
+hipError_t step(const Dims& d, const void* q, const void* k, const void* v, const float* g, float* state, void* o,
+                hipStream_t stream);
 
 }  // namespace lsm

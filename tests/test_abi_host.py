@@ -68,6 +68,19 @@ def test_error_codes_are_reached_before_any_launch():
     assert fwd(P(), ws=None) == ERR_WS
     assert fwd(P(), wsb=16) == ERR_WS
     assert bwd(P(), wsb=16) == ERR_WS
+    # recurrent step and benchmark aid: same checks, before any HIP call
+    vp = ctypes.c_void_p
+    lib = pkg.library()
+    step = lambda p, q=0x1000, g=0x4000, st=0x5000: lib.lsm_step(ctypes.byref(p), vp(q), vp(0x2000), vp(0x3000), vp(g), vp(st),
+                                                                  vp(0x6000), vp(None))
+    assert step(P(T=1), q=None) == ERR_NULL
+    assert step(P(T=1), st=None) == ERR_NULL
+    assert step(P(T=1), g=None) == ERR_NULL
+    assert step(P(T=1, decay_kind=0)) == ERR_NULL
+    assert step(P(T=1, d_k=96)) == ERR_UNSUP
+    assert step(P(T=1), st=0x5004) == ERR_ALIGN
+    assert lib.lsm_bench_intra_chunk(ctypes.byref(P()), vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000), vp(0x5000),
+                                     vp(0x10000), 1 << 40, 4, vp(None)) == ERR_UNSUP   # d = 64 is not on the MFMA path
     assert pkg.library().lsm_chunk_fwd(None, *([ctypes.c_void_p(None)] * 8), 0, ctypes.c_void_p(None)) == ERR_NULL
 
 
