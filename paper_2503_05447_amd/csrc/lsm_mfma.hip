@@ -16,11 +16,9 @@
 //   D result : lane holds D[m = 8*g + 4*half + j][n = l%32] in register 4*g + j
 // Tiles arrive feature-contiguous ([token][feature] rows).  A contraction over FEATURES reads its
 // operands as 16-byte row pieces (frag).  A contraction over TOKENS reads them with the LDS transpose
-// read (frag_tr: lane = feature, 8 tokens), which needs no transposed copy.  A D-layout result can
-// feed the next MFMA directly from registers as an operand whose k index runs over its rows in the
-// order 4*half + {0..3}, 8 + 4*half + {0..3}; the partner operand is then read in the same order
-// (frag_perm / frag_tr_perm).  Rounded products (scores, decayed operands, states where it matters)
-// are carried as a bf16 head plus a bf16 remainder and cost two MFMAs.
+// read (frag_tr: lane = feature, 8 tokens), which needs no transposed copy.  Rounded products (scores,
+// decayed operands, states where it matters) are carried as a bf16 head plus a bf16 remainder and
+// cost two MFMAs.
 #include "lsm_mfma_dev.h"
 
 namespace lsm {
@@ -411,20 +409,15 @@ __device__ __forceinline__ float row_dot(const uint16_t* X, int tok, int wave, i
 // accumulators) and handed to the others through LDS as a bf16 head plus a bf16 remainder (an output
 // that one key dominates would otherwise carry the full 2^-9 rounding of its score); the head goes
 // over the Q tile and the remainder over the K tile, both dead by then, so the kernel stays at 52 KiB
-// of LDS.  (SHARED = false keeps the earlier variant in which every wave computes all score blocks
-// itself and feeds them to the next MFMA from registers: no exchange, but four times the score MFMAs.)
+// of LDS.
 // LDS: Q | K (later the O stage) | V (64 x LD each) | bs
 // REPEAT (benchmark aid): the compute phase runs `reps` times on the tiles resident in LDS, so that
 // the rate of the intra-chunk arithmetic can be measured without the HBM traffic that bounds the
 // streamed kernel; the stored result is that of the last pass, identical to reps = 1.
 constexpr int kOutLds = 3 * C * LD * 2 + C * 4;
 constexpr int kOutLdsRepeat = kOutLds + 2 * C * LDP * 2;
-#ifndef LSM_SHARED_SCORES
-#define LSM_SHARED_SCORES 1
-#endif
-constexpr bool kSharedScores = LSM_SHARED_SCORES;
 
-template <bool REPEAT, bool SHARED>
+template <bool REPEAT>
 __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ k,
                                                          const uint16_t* __restrict__ v, const float* __restrict__ g,
@@ -462,14 +455,13 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     __syncthreads();
 
     PackedBlock res[2];
-    // SHARED: each of the three score blocks is computed by one wave and handed to the others through
-    // LDS (head over the Q tile, remainder over the K tile, both dead by then; the repeat variant, which
-    // needs Q and K again, has room of its own behind bs).
+    // each of the three score blocks is computed by one wave and handed to the others through LDS (head
+    // over the Q tile, remainder over the K tile, both dead by then; the repeat variant, which needs Q
+    // and K again, has room of its own behind bs)
     uint16_t* Ph = REPEAT ? reinterpret_cast<uint16_t*>(bs + C) : Q;
     uint16_t* Pl = REPEAT ? Ph + C * LDP : K;
     for (int rep = 0; rep < (REPEAT ? reps : 1); ++rep) {
-    if (REPEAT) asm volatile("" ::: "memory");  // the tiles are read again in every pass
-    if (SHARED) {
+        if (REPEAT) asm volatile("" ::: "memory");  // the tiles are read again in every pass
         f32x16 acc[2], P = {0};
         _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
             const int j = 32 * jb + n;
@@ -496,29 +488,8 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
             }
             res[jb] = pack_block(acc[jb]);
         }
-    } else
-    _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-        const int j = 32 * jb + n;
-        f32x16 acc = {0};
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) acc = mfma(sfrag[ks], frag(Q, LD, j, 16 * ks + 8 * half), acc);
-        const float w = __expf(bs[j]);
-        _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[x] *= w;
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)
-            if (rb <= jb) {  // keys r >= 32 never reach queries j < 32
-                f32x16 P = score_block(K, 32 * rb, Q, 32 * jb, n, half);  // D[m = r][n = j] = k_r . q_j
-                decay_mask<true>(P, 32 * rb, j, bs, half);
-                bf16x8 hi[2], lo[2];
-                split_ops(P, hi, lo);
-                _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
-                    const bf16x8 vt = frag_tr_perm(V, LD, 32 * rb + 16 * s2, 32 * wave, lane);
-                    acc = mfma(vt, hi[s2], acc);
-                    acc = mfma(vt, lo[s2], acc);
-                }
-            }
-        res[jb] = pack_block(acc);
     }
-    }
-    __syncthreads();  // every wave is done with K (SHARED: with the score tiles)
+    __syncthreads();  // every wave is done with the score tiles
     _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) store_packed(stage, LD, 32 * jb + n, 32 * wave, half, res[jb]);
     __syncthreads();
     store_tile(o, stage, tok0, L, tid);
@@ -532,12 +503,12 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
 //   dk^T[i][r] = e^{b_C-b_r} sum_v dS[i][v] v_r[v]   + sum_j Q^T[i][j] G[j][r]
 //   dv^T[v][r] = e^{b_C-b_r} sum_i dS^T[v][i] k_r[i] + sum_j dO^T[v][j] As[j][r]
 //   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + sum_r k_r.dk_r^{inter} + e^{b_C} <S, dS>
-// Wave w owns i (and v) in [32w, 32w+32) and never exchanges data with the other waves before the
-// final staging: every 32 x 32 block of G, G^T and As it needs is computed by the wave itself and
-// consumed straight from its accumulator registers (as the B operand of the next MFMA, head and
-// remainder), the partner operand K^T / Q^T / dO^T coming from the LDS transpose read in the
-// matching k order.  That costs three times the score MFMAs but no LDS space, no LDS round trip and
-// no barrier, and lets two workgroups share a CU.
+// Wave w owns i (and v) in [32w, 32w+32).  The inter parts come first (state rows as A operands from
+// global memory, scaled on the accumulators).  G and As are each computed once per workgroup, one
+// wave per 32 x 32 block (mask and decay on its accumulators), and parked as bf16 head + remainder in
+// a tile that is dead at that point: G in the V tile (dq reads it by rows, dk through the LDS
+// transpose read, so G^T is never formed), As in the Q tile for dv.  K^T, Q^T and dO^T come from
+// transpose reads of the row-major tiles.
 // LDS: Q | K | V | dO (64 x LD; later stages of dq, dk, dv) | bs (64) | red (4 x 3 x 64 floats:
 //      per-wave partial row dots) | zred
 constexpr int kGradLds = 4 * C * LD * 2 + C * 4 + 4 * 64 * 3 * 4 + 64;
@@ -914,7 +885,7 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     const dim3 grid(d.N, d.BH()), block(kThreads);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     hipError_t e;
-    if ((e = allow_lds((mk_output<false, kSharedScores>), kOutLds)) != hipSuccess) return e;
+    if ((e = allow_lds(mk_output<false>, kOutLds)) != hipSuccess) return e;
     launch_prep(d, a.stream, a.g, w);
     {
         ProfScope ps(KID_MFMA_STATE, a.stream);
@@ -923,7 +894,7 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     }
     {
         ProfScope ps(KID_MFMA_OUTPUT, a.stream);
-        hipLaunchKernelGGL((mk_output<false, kSharedScores>), grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
+        hipLaunchKernelGGL(mk_output<false>, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
                            static_cast<uint16_t*>(a.o), 1);
     }
     return hipGetLastError();
@@ -973,9 +944,9 @@ hipError_t mfma_intra_bench(const Dims& d, const FwdArgs& a, int reps) {
     if (d.kind == 3 || !mfma_supported(d)) return hipErrorInvalidValue;
     Ws w = carve(d, a.ws, false);
     hipError_t e;
-    if ((e = allow_lds((mk_output<true, kSharedScores>), kOutLdsRepeat)) != hipSuccess) return e;
+    if ((e = allow_lds(mk_output<true>, kOutLdsRepeat)) != hipSuccess) return e;
     ProfScope ps(KID_MFMA_OUTPUT, a.stream);
-    hipLaunchKernelGGL((mk_output<true, kSharedScores>), dim3(d.N, d.BH()), dim3(kThreads), kOutLdsRepeat, a.stream, d,
+    hipLaunchKernelGGL(mk_output<true>, dim3(d.N, d.BH()), dim3(kThreads), kOutLdsRepeat, a.stream, d,
                        static_cast<const uint16_t*>(a.q), static_cast<const uint16_t*>(a.k),
                        static_cast<const uint16_t*>(a.v), a.g, w.states, static_cast<uint16_t*>(a.o), reps);
     return hipGetLastError();

@@ -39,14 +39,6 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ bf16x8 frag(const uint16_t* tile, int ld, int row, int col) {
     return *reinterpret_cast<const bf16x8*>(tile + row * ld + col);
 }
-// k index in the permuted order of a D-layout operand: columns col0 + 4*half + {0..3} and col0 + 8 + 4*half + {0..3}
-__device__ __forceinline__ bf16x8 frag_perm(const uint16_t* tile, int ld, int row, int col0, int half) {
-    u32x2 lo = *reinterpret_cast<const u32x2*>(tile + row * ld + col0 + 4 * half);
-    u32x2 hi = *reinterpret_cast<const u32x2*>(tile + row * ld + col0 + 8 + 4 * half);
-    u32x4 v = {lo.x, lo.y, hi.x, hi.y};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
 // Token-major operand straight out of a row-major [token][feature] LDS tile with the LDS transpose
 // read: lane l receives feature col0 + l%32 of tokens row0 + 8*(l/32) + 0..7 (natural k order).
 // Each group of 16 lanes reads a 4-token x 16-feature patch as 8-byte pieces (lane r of the group:
@@ -60,13 +52,6 @@ __device__ __forceinline__ bf16x8 frag_tr(const uint16_t* tile, int ld, int row0
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ld));
     u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
     u32x4 v = {l2.x, l2.y, h2.x, h2.y};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-// registers 8*s .. 8*s+7 of a D-layout block as the operand of k-step s
-__device__ __forceinline__ bf16x8 pack_step(const f32x16& d, int s) {
-    u32x4 v = {pack2(d[8 * s + 0], d[8 * s + 1]), pack2(d[8 * s + 2], d[8 * s + 3]),
-               pack2(d[8 * s + 4], d[8 * s + 5]), pack2(d[8 * s + 6], d[8 * s + 7])};
     return __builtin_bit_cast(bf16x8, v);
 }
 
@@ -152,33 +137,6 @@ __device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, s
             __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
                                         reinterpret_cast<u32x4*>(dst + (tok0 + row) * D + cp * 8));
     }
-}
-
-// same as frag_tr, k in the permuted order of a D-layout operand: tokens row0 + 4*half + {0..3}
-// and row0 + 8 + 4*half + {0..3}
-__device__ __forceinline__ bf16x8 frag_tr_perm(const uint16_t* tile, int ld, int row0, int col0, int lane) {
-    const int r = lane & 15, nblk = (lane >> 4) & 1, half = lane >> 5;
-    const uint16_t* p = tile + (row0 + 4 * half + (r >> 2)) * ld + col0 + 16 * nblk + 4 * (r & 3);
-    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * ld));
-    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-    u32x4 v = {l2.x, l2.y, h2.x, h2.y};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-// head and remainder operands (two k-steps each) of a D-layout block
-__device__ __forceinline__ void split_ops(const f32x16& d, bf16x8* hi, bf16x8* lo) {
-    f32x16 rem;
-    _Pragma("unroll") for (int x = 0; x < 16; x += 2) {
-        const uint32_t h = pack2(d[x], d[x + 1]);
-        rem[x] = d[x] - bf16_lo(h);
-        rem[x + 1] = d[x + 1] - bf16_hi(h);
-    }
-    hi[0] = pack_step(d, 0);
-    hi[1] = pack_step(d, 1);
-    lo[0] = pack_step(rem, 0);
-    lo[1] = pack_step(rem, 1);
 }
 
 struct PackedBlock { u32x2 v[4]; };  // a D-layout block rounded to bf16: v[g] = rows 8g + 4half + 0..3

@@ -17,9 +17,6 @@
 
 constexpr int LDF = D + 4;  // row stride (floats) of the fp32 [64][128] cumulative-decay tile in LDS
 
-// log2 of the level s at which the pair (a, b) of chunk-local token indices is handled; a != b
-__device__ __forceinline__ int pair_level(int a, int b) { return 31 - __clz(a ^ b); }
-
 // weight exponent of token t at level s = 1 << ls:  q side (odd block): b_t - b_{m-1};  k side: b_{e} - b_t
 // with e the last token of t's own block.  Returns the reference row and sets `qside`.
 __device__ __forceinline__ int level_ref(int t, int ls, bool& qside) {
