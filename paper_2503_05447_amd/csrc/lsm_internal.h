@@ -7,13 +7,64 @@
 
 namespace lsm {
 
-// Problem geometry handed to every launcher.  N = ceil(T / C) chunks per sequence.
+// Problem geometry handed to every launcher.  N = ceil(T / C) chunks per sequence; for packed
+// variable-length input (cu != NULL, B = 1) N is the total chunk count over all sequences, T the
+// total token count, and no chunk straddles two sequences.
 struct Dims {
     int B, H, T, dk, dv, C, N, kind;
-    bool bf16;  // element type of q,k,v,o and their gradients
+    bool bf16;    // element type of q,k,v,o and their gradients
+    int layout;   // 0: [B,H,T,d] (head-major), 1: [B,T,H,d] (token-major); same for per-token decays
+    int nseq;     // packed variable-length input: number of sequences, else 0
+    const int* cu;      // [nseq + 1] first token of each sequence (device memory), cu[nseq] = T
+    const int* cstart;  // [nseq + 1] first chunk of each sequence (device memory, written by the library)
     __host__ __device__ int BH() const { return B * H; }
     __host__ __device__ int dkd() const { return kind == 3 ? dk : 1; }  // decay values per token
+    __host__ __device__ int seqs() const { return nseq ? nseq * H : B * H; }  // independent recurrences
 };
+
+// Where one chunk of one (b,h) lives.
+struct ChunkPos {
+    int t0, L;      // first token and number of valid tokens (L <= 0: no such chunk)
+    size_t tok0;    // row of the first token in the caller's q/k/v/o arrays (rows of d_k or d_v elements)
+    int ts;         // rows between consecutive tokens there
+    size_t wtok0;   // first token in the library's own per-token arrays ([BH][T] order)
+    size_t slot;    // this chunk in the library's per-chunk arrays ([BH][N] order)
+};
+__device__ __forceinline__ ChunkPos chunk_pos_at(const Dims& d, int bh, int t0, int L, int c) {
+    ChunkPos p;
+    p.t0 = t0;
+    p.L = L;
+    p.ts = d.layout ? d.H : 1;
+    p.tok0 = d.layout ? (size_t(bh / d.H) * d.T + t0) * d.H + bh % d.H : size_t(bh) * d.T + t0;
+    p.wtok0 = size_t(bh) * d.T + t0;
+    p.slot = size_t(bh) * d.N + c;
+    return p;
+}
+// chunk c (grid index) of (b,h); packed input: c counts chunks over all sequences
+__device__ __forceinline__ ChunkPos chunk_pos(const Dims& d, int c, int bh) {
+    if (!d.cu) return chunk_pos_at(d, bh, c * d.C, min(d.C, d.T - c * d.C), c);
+    int lo = 0, hi = d.nseq;  // last s with cstart[s] <= c
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (d.cstart[mid] <= c) lo = mid; else hi = mid;
+    }
+    if (c >= d.cstart[d.nseq]) return chunk_pos_at(d, bh, 0, 0, c);
+    const int t0 = d.cu[lo] + d.C * (c - d.cstart[lo]);
+    return chunk_pos_at(d, bh, t0, min(d.C, d.cu[lo + 1] - t0), c);
+}
+// Walk of one recurrence: q-th of Dims::seqs().  Sets the (b,h) index, the index of its edge states,
+// the first chunk and the chunk count.
+struct SeqWalk { int bh, edge, c0, n, tbeg, tend; };
+__device__ __forceinline__ SeqWalk seq_walk(const Dims& d, int q) {
+    if (!d.cu) return SeqWalk{q, q, 0, d.N, 0, d.T};
+    const int s = q / d.H;
+    return SeqWalk{q % d.H, q, d.cstart[s], d.cstart[s + 1] - d.cstart[s], d.cu[s], d.cu[s + 1]};
+}
+// k-th chunk of a walk
+__device__ __forceinline__ ChunkPos walk_pos(const Dims& d, const SeqWalk& w, int k) {
+    const int t0 = w.tbeg + k * d.C;
+    return chunk_pos_at(d, w.bh, t0, min(d.C, w.tend - t0), w.c0 + k);
+}
 
 // Pointers of one forward call (device memory).
 struct FwdArgs {
@@ -36,6 +87,9 @@ struct BwdArgs {
     void* ws;
     hipStream_t stream;
 };
+
+// first chunk of every sequence of a packed variable-length input: cstart[s] = sum_{s' < s} ceil(len_s' / C)
+hipError_t launch_chunk_starts(const Dims& d, int* cstart, hipStream_t stream);
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 

@@ -28,9 +28,9 @@ namespace {
 // Log-decay of this lane's token (every wave loads, only wave 0's value is used).  To be called
 // BEFORE the kernel's other global loads: loads return in order, so waiting for this one later
 // leaves the younger ones in flight, whereas as the youngest it would drain the whole queue.
-__device__ __forceinline__ float decay_gload(const Dims& d, const float* g, int bh, int t0, int L, int lane) {
+__device__ __forceinline__ float decay_gload(const Dims& d, const float* g, int bh, const ChunkPos& cp, int lane) {
     if (d.kind == 0) return 0.f;
-    return g[d.kind == 1 ? size_t(bh % d.H) : size_t(bh) * d.T + t0 + min(lane, L - 1)];
+    return g[d.kind == 1 ? size_t(bh % d.H) : cp.tok0 + size_t(min(lane, cp.L - 1)) * cp.ts];
 }
 // Chunk-local inclusive cumulative log-decay b_j, j = 0..63, into LDS (tokens >= L carry g = 0) from
 // the values of decay_gload.  Called by all threads; only wave 0 works.  Caller synchronises afterwards.
@@ -51,18 +51,20 @@ __device__ __forceinline__ void cumulative_decay(float gval, int L, float* bs, i
 __global__ __launch_bounds__(64) void mk_decay_prep(Dims d, const float* __restrict__ g, float* __restrict__ wdec,
                                                     float* __restrict__ winc, float* __restrict__ lam) {
     const int c = blockIdx.x, bh = blockIdx.y, lane = threadIdx.x;
-    const int t0 = c * C, L = min(C, d.T - t0);
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L;
+    if (L <= 0) return;
     float x = 0.f;
-    if (lane < L) x = d.kind == 1 ? g[bh % d.H] : g[size_t(bh) * d.T + t0 + lane];
+    if (lane < L) x = d.kind == 1 ? g[bh % d.H] : g[cp.tok0 + size_t(lane) * cp.ts];
     for (int off = 1; off < 64; off <<= 1) {
         const float y = __shfl_up(x, off, 64);
         if (lane >= off) x += y;
     }
     const float bC = __shfl(x, 63, 64);
-    const size_t base = (size_t(bh) * d.N + c) * C;
+    const size_t base = cp.slot * C;
     wdec[base + lane] = __expf(bC - x);
     winc[base + lane] = __expf(x);
-    if (lane == 0) lam[size_t(bh) * d.N + c] = __expf(bC);
+    if (lane == 0) lam[cp.slot] = __expf(bC);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -119,28 +121,28 @@ struct StateArgs {
 template <bool DEC, bool VEC>
 __device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, const uint16_t* xb,
                                             const uint16_t* xb_lo, const float* wts, const float* lam, int a_stride,
-                                            int bh, int c, int clam, int fb0, int tid, StateRegs& r) {
-    const int t0 = c * C, L = min(C, d.T - t0);
-    const size_t tok0 = size_t(bh) * d.T + t0;
+                                            const ChunkPos& cp, size_t lamslot, int fb0, int tid, StateRegs& r) {
+    const int L = cp.L;
     const int astride = VEC ? a_stride : D;
-    // The set of chunk c carries e^{b_C} of chunk `clam`, the one that is being accumulated when this
-    // set goes to LDS: the factor is then read from a set that has arrived, and no loaded value is
+    // The set of this chunk carries e^{b_C} of chunk `lamslot`, the one that is being accumulated when
+    // this set goes to LDS: the factor is then read from a set that has arrived, and no loaded value is
     // copied from iteration to iteration (such a copy waits for every load in flight).
     if (VEC) {
-        r.lam = lam[(size_t(bh) * d.N + clam) * D + fb0 + (tid & 31)];
+        r.lam = lam[lamslot * D + fb0 + (tid & 31)];
     } else if (DEC) {
-        r.w = wts[(size_t(bh) * d.N + c) * C + (tid >> 2)];
-        r.lam = lam[size_t(bh) * d.N + clam];
+        r.w = wts[cp.slot * C + (tid >> 2)];
+        r.lam = lam[lamslot];
     }
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        r.a[it] = *reinterpret_cast<const u32x4*>(xa + (tok0 + min(row, L - 1)) * astride + cp * 8);
+        const int p = tid + kThreads * it, row = p >> 4, cpp = p & 15;
+        r.a[it] = *reinterpret_cast<const u32x4*>(xa + (cp.tok0 + size_t(min(row, L - 1)) * cp.ts) * astride + cpp * 8);
     }
     // nothing is computed on the loaded values here (the ragged tail is zeroed when they go to LDS): an
     // ALU operation at this point would make the wave wait for the load it has just issued
     r.L = L;
-    const int row = tid >> 2, cp = tid & 3;
-    const size_t boff = (tok0 + min(row, L - 1)) * D + fb0 + cp * 8;
+    const int row = min(tid >> 2, L - 1), cpp = tid & 3;
+    // vector decay: the decayed operand comes from the library's own planes ([BH*T][128] order)
+    const size_t boff = (VEC ? cp.wtok0 + row : cp.tok0 + size_t(row) * cp.ts) * D + fb0 + cpp * 8;
     r.b = *reinterpret_cast<const u32x4*>(xb + boff);
     if (VEC) r.blo = *reinterpret_cast<const u32x4*>(xb_lo + boff);
 }
@@ -246,7 +248,9 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
             seq = (full >> 2) + ((id - full) >> 2);
         }
     }
-    const int bh = VEC ? seq / sa.vh_count : seq, vh = VEC ? seq % sa.vh_count : 0;
+    const int vh = VEC ? seq % sa.vh_count : 0, nvh = VEC ? sa.vh_count : 1;
+    const SeqWalk walk = seq_walk(d, VEC ? seq / sa.vh_count : seq);
+    const int cnt = walk.n;  // chunks to walk
     const int tid = threadIdx.x, lane = tid & 63, mb = tid >> 6;
     const int n = lane & 31, half = lane >> 5;
     constexpr int sz = D * D;
@@ -255,30 +259,42 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     // acc[4g+j] = state element (m = 32mb + 8g + 4half + j, n = 32nb + lane%32); MODE 0: m = i, else m = v
     f32x16 acc = {0};
     if (edge_in) {
-        const float* e = edge_in + size_t(bh) * D * erow + D * vh;
+        const float* e = edge_in + size_t(walk.edge) * D * erow + D * vh;
         _Pragma("unroll") for (int r = 0; r < 16; ++r) {
             const int mm = 32 * mb + 8 * (r >> 2) + 4 * half + (r & 3), nn = 32 * nb + n;
             acc[r] = MODE == 0 ? e[mm * erow + nn] : e[nn * erow + mm];
         }
     }
-    const int first = MODE == 2 ? d.N - 1 : 0, step = MODE == 2 ? -1 : 1;
+    const int first = MODE == 2 ? cnt - 1 : 0, step = MODE == 2 ? -1 : 1;
     auto bufA = [&](int k) { return tiles + (k & 1) * kStateTile; };
     auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
-    auto slot = [&](int k) { return (size_t(seq) * d.N + (first + step * k)) * sz; };
+    auto slot = [&](int k) { return ((size_t(walk.bh) * d.N + walk.c0 + (first + step * k)) * nvh + vh) * sz; };
     const uint16_t* xav = xa + (VEC ? D * vh : 0);
     auto gload = [&](int kc, StateRegs& r) {
         // the kc-th chunk of the walk (clamped at the end); it goes to LDS during iteration kc - 2
-        const int c = first + step * min(kc, d.N - 1), clam = first + step * min(max(kc - 2, 0), d.N - 1);
-        state_gload<DEC, VEC>(d, xav, xb, xb_lo, wts, lam, sa.a_stride, bh, c, clam, 32 * nb, tid, r);
+        const int c = first + step * min(kc, cnt - 1), clam = first + step * min(max(kc - 2, 0), cnt - 1);
+        state_gload<DEC, VEC>(d, xav, xb, xb_lo, wts, lam, sa.a_stride, walk_pos(d, walk, c),
+                              size_t(walk.bh) * d.N + walk.c0 + clam, 32 * nb, tid, r);
     };
 
     // prologue: chunks 0 and 1 -> LDS, chunk 2 in flight.  Global loads are issued two iterations
     // before their data is written to LDS: one iteration is shorter than a trip to HBM.
     StateRegs r0, r1, r2;
+    if (cnt <= 0) {  // an empty sequence of a packed input: the state passes through
+        if (edge_out) {
+            float* e = edge_out + size_t(walk.edge) * D * erow + D * vh;
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                const int mm = 32 * mb + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * nb + n;
+                if (MODE == 0) e[mm * erow + nn] = acc[x];
+                else e[nn * erow + mm] = acc[x];
+            }
+        }
+        return;
+    }
     gload(0, r0);
-    if (d.N > 1) gload(1, r1);
+    if (cnt > 1) gload(1, r1);
     state_to_lds<DEC, VEC>(r0, bufA(0), bufB(0), tid);
-    if (d.N > 1) {
+    if (cnt > 1) {
         state_to_lds<DEC, VEC>(r1, bufA(1), bufB(1), tid);
     }
     gload(2, r0);
@@ -325,16 +341,16 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
     };
     int k = 0;
-    for (; k + 2 < d.N; k += 3) {
+    for (; k + 2 < cnt; k += 3) {
         iteration(k, r0, r2);
         iteration(k + 1, r1, r0);
         iteration(k + 2, r2, r1);
     }
-    if (k < d.N) iteration(k, r0, r2);
-    if (k + 1 < d.N) iteration(k + 1, r1, r0);
+    if (k < cnt) iteration(k, r0, r2);
+    if (k + 1 < cnt) iteration(k + 1, r1, r0);
     __syncthreads();
     if (edge_out) {
-        float* e = edge_out + size_t(bh) * D * erow + D * vh;
+        float* e = edge_out + size_t(walk.edge) * D * erow + D * vh;
         _Pragma("unroll") for (int x = 0; x < 16; ++x) {
             const int mm = 32 * mb + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * nb + n;
             if (MODE == 0) e[mm * erow + nn] = acc[x];
@@ -431,19 +447,22 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     uint16_t* stage = K;
 
     const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = c * C, L = min(C, d.T - t0);
-    const size_t tok0 = size_t(bh) * d.T + t0;
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L;
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = cp.tok0;
+    const int ts = cp.ts;
     const int n = lane & 31, half = lane >> 5;
 
     // decay first, then the tiles, the state rows after them (loads return in order; the rows are
     // needed only by the MFMAs)
-    const float gval = decay_gload(d, g, bh, t0, L, lane);
+    const float gval = decay_gload(d, g, bh, cp, lane);
     TileRegs tq, tk, tv;
-    tile_gload(tq, q, tok0, L, tid);
-    tile_gload(tk, k, tok0, L, tid);
-    tile_gload(tv, v, tok0, L, tid);
+    tile_gload(tq, q, tok0, ts, L, tid);
+    tile_gload(tk, k, tok0, ts, L, tid);
+    tile_gload(tv, v, tok0, ts, L, tid);
     // state rows of this wave straight from global memory: A operand [m = v][k = i]
-    const uint16_t* St = states + (size_t(bh) * d.N + c) * D * D;
+    const uint16_t* St = states + cp.slot * D * D;
     bf16x8 sfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
         sfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(St + state_frag_off(wave, ks, lane)));
@@ -492,7 +511,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     __syncthreads();  // every wave is done with the score tiles
     _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) store_packed(stage, LD, 32 * jb + n, 32 * wave, half, res[jb]);
     __syncthreads();
-    store_tile(o, stage, tok0, L, tid);
+    store_tile(o, stage, tok0, ts, L, tid);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -532,22 +551,25 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
     float* zred = red + 4 * 3 * 64;  // [wave]: partial <S, dS>
 
     const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = c * C, L = min(C, d.T - t0);
-    const size_t tok0 = size_t(bh) * d.T + t0;
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L;
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = cp.tok0;
+    const int ts = cp.ts;
     const int n = lane & 31, half = lane >> 5;
-    const uint16_t* S = states + (size_t(bh) * d.N + c) * D * D;
-    const uint16_t* dS = dstates + (size_t(bh) * d.N + c) * D * D;
+    const uint16_t* S = states + cp.slot * D * D;
+    const uint16_t* dS = dstates + cp.slot * D * D;
     constexpr bool want_dg = WANT_DG;
 
     // The tiles are requested first and the state rows after them: loads return in order, so the tiles
     // can go to LDS (and the barrier be reached) while the state rows, needed only by the first MFMAs,
     // are still on their way.
-    const float gval = decay_gload(d, g, bh, t0, L, lane);
+    const float gval = decay_gload(d, g, bh, cp, lane);
     TileRegs tq, tk, tv, to;
-    tile_gload(tq, q, tok0, L, tid);
-    tile_gload(tk, k, tok0, L, tid);
-    tile_gload(tv, v, tok0, L, tid);
-    tile_gload(to, d_o, tok0, L, tid);
+    tile_gload(tq, q, tok0, ts, L, tid);
+    tile_gload(tk, k, tok0, ts, L, tid);
+    tile_gload(tv, v, tok0, ts, L, tid);
+    tile_gload(to, d_o, tok0, ts, L, tid);
     // rows i in [32w, 32w+32) of S (and its remainder): A operands [m = i][k = v]
     bf16x8 sfrag[8], srfrag[8], dsfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
@@ -693,9 +715,9 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
         store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
     }
     __syncthreads();
-    store_tile(dq, Q, tok0, L, tid);
-    store_tile(dk, K, tok0, L, tid);
-    store_tile(dv, V, tok0, L, tid);
+    store_tile(dq, Q, tok0, ts, L, tid);
+    store_tile(dk, K, tok0, ts, L, tid);
+    store_tile(dv, V, tok0, ts, L, tid);
     if (want_dg && tid < 64) {
         // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
         float w = 0.f, tail = 0.f, z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
@@ -713,9 +735,9 @@ __global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* _
         if (d.kind == 1) {
             // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
             for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
-            if (tid == 0) dg_tok[size_t(bh) * d.N + c] = dgv;
+            if (tid == 0) dg_tok[cp.slot] = dgv;
         } else if (tid < L) {
-            dg_tok[tok0 + tid] = dgv;
+            dg_tok[tok0 + size_t(tid) * ts] = dgv;
         }
     }
 }
@@ -725,8 +747,9 @@ __global__ void mk_head_reduce(Dims d, const float* __restrict__ dg_tok, float* 
     __shared__ float part[kThreads];
     const int h = blockIdx.x;
     float s = 0.f;
-    const size_t nn = size_t(d.B) * d.N;
-    for (size_t e = threadIdx.x; e < nn; e += blockDim.x) s += dg_tok[((e / d.N) * d.H + h) * d.N + e % d.N];
+    const int nc = d.cu ? d.cstart[d.nseq] : d.N;  // packed input: d.N is an upper bound, the rest was never written
+    const size_t nn = size_t(d.B) * nc;
+    for (size_t e = threadIdx.x; e < nn; e += blockDim.x) s += dg_tok[((e / nc) * d.H + h) * d.N + e % nc];
     part[threadIdx.x] = s;
     __syncthreads();
     for (int w = kThreads / 2; w > 0; w >>= 1) {

@@ -106,20 +106,21 @@ __device__ __forceinline__ bf16x8 rem8_to_bf16(u32x2 raw) {
 }
 
 // 64 x 128 bf16 tile: global rows [tok0, tok0+L) -> LDS (row stride LD), rows >= L zero
-__device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
+// (tok0 = row of the first token in src, ts = rows between consecutive tokens)
+__device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + min(row, L - 1)) * D + cp * 8));
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + size_t(min(row, L - 1)) * ts) * D + cp * 8));
         const uint32_t keep = row < L ? 0xffffffffu : 0u;  // branch-free: a branch around a load drains the load queue
         *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
     }
 }
 // the same in two steps: global -> registers (no operation on the loaded values), registers -> LDS
 struct TileRegs { u32x4 v[4]; };
-__device__ __forceinline__ void tile_gload(TileRegs& r, const uint16_t* src, size_t tok0, int L, int tid) {
+__device__ __forceinline__ void tile_gload(TileRegs& r, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        r.v[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + min(row, L - 1)) * D + cp * 8));
+        r.v[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + size_t(min(row, L - 1)) * ts) * D + cp * 8));
     }
 }
 __device__ __forceinline__ void tile_commit(uint16_t* dst, const TileRegs& r, int L, int tid) {
@@ -130,12 +131,12 @@ __device__ __forceinline__ void tile_commit(uint16_t* dst, const TileRegs& r, in
     }
 }
 // LDS tile (row stride LD) rows [0, L) -> global
-__device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int tid) {
+__device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         if (row < L)
             __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
-                                        reinterpret_cast<u32x4*>(dst + (tok0 + row) * D + cp * 8));
+                                        reinterpret_cast<u32x4*>(dst + (tok0 + size_t(row) * ts) * D + cp * 8));
     }
 }
 

@@ -37,13 +37,13 @@ __device__ __forceinline__ void weigh8(const u32x4& raw, const float* w, u32x4& 
 
 // Chunk-local inclusive cumulative log-decay b [64][128] (fp32, row stride LDF) into LDS; tokens >= L
 // carry g = 0.  Called by all 256 threads; ends with a barrier.
-__device__ __forceinline__ void decay_tile(float* bt, const float* __restrict__ g, size_t tok0, int L, int tid) {
+__device__ __forceinline__ void decay_tile(float* bt, const float* __restrict__ g, size_t tok0, int ts, int L, int tid) {
     const int cp = tid & 15, r0 = tid >> 4;
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int row = r0 + 16 * it;
         // branch-free (rows beyond the ragged end read the last valid row and are zeroed): a branch
         // around a load makes the wave wait for every load in flight
-        const float* src = g + (tok0 + min(row, L - 1)) * D + cp * 8;
+        const float* src = g + (tok0 + size_t(min(row, L - 1)) * ts) * D + cp * 8;
         typedef float f32x4 __attribute__((ext_vector_type(4)));
         const f32x4 g0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src));
         const f32x4 g1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + 4));
@@ -101,8 +101,11 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
     float* diag = reinterpret_cast<float*>(smem + kPrepLdsMain);      // [64]
 
     const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = c * C, L = min(C, d.T - t0);
-    const size_t tok0 = size_t(bh) * d.T + t0;
+    const ChunkPos pos = chunk_pos(d, c, bh);
+    const int L = pos.L;
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = pos.tok0, wtok0 = pos.wtok0;
+    const int ts = pos.ts;
     const int n = lane & 31, half = lane >> 5;
     const int cp = tid & 15, r0 = tid >> 4;  // this thread's feature piece (8 features) and first row; rows r0 + 16 it
 
@@ -110,10 +113,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
     u32x4 qr[4], kr[4];
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int row = r0 + 16 * it;
-        qr[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + (tok0 + min(row, L - 1)) * D + cp * 8));
-        kr[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k + (tok0 + min(row, L - 1)) * D + cp * 8));
+        qr[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + (tok0 + size_t(min(row, L - 1)) * ts) * D + cp * 8));
+        kr[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k + (tok0 + size_t(min(row, L - 1)) * ts) * D + cp * 8));
     }
-    decay_tile(bt, g, tok0, L, tid);
+    decay_tile(bt, g, tok0, ts, L, tid);
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {  // zero the ragged tail (after the loads have been issued)
         const uint32_t keep = r0 + 16 * it < L ? 0xffffffffu : 0u;
         qr[it] = u32x4{qr[it].x & keep, qr[it].y & keep, qr[it].z & keep, qr[it].w & keep};
@@ -143,14 +146,14 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
         u32x4 hi, lo;
         if (row < L) {
             weigh8(kr[it], wk, hi, &lo);
-            *reinterpret_cast<u32x4*>(khat_hi + (tok0 + row) * D + cp * 8) = hi;
-            *reinterpret_cast<u32x4*>(khat_lo + (tok0 + row) * D + cp * 8) = lo;
+            *reinterpret_cast<u32x4*>(khat_hi + (wtok0 + row) * D + cp * 8) = hi;
+            *reinterpret_cast<u32x4*>(khat_lo + (wtok0 + row) * D + cp * 8) = lo;
             weigh8(qr[it], wq, hi, &lo);
-            *reinterpret_cast<u32x4*>(qhat_hi + (tok0 + row) * D + cp * 8) = hi;
-            *reinterpret_cast<u32x4*>(qhat_lo + (tok0 + row) * D + cp * 8) = lo;
+            *reinterpret_cast<u32x4*>(qhat_hi + (wtok0 + row) * D + cp * 8) = hi;
+            *reinterpret_cast<u32x4*>(qhat_lo + (wtok0 + row) * D + cp * 8) = lo;
         }
     }
-    if (tid < D) lamv[(size_t(bh) * d.N + c) * D + tid] = __expf(bt[63 * LDF + tid]);
+    if (tid < D) lamv[pos.slot * D + tid] = __expf(bt[63 * LDF + tid]);
 
     // levels: wave w accumulates, masked, the partial Gram blocks it is responsible for
     //   accD: diagonal 32-block (w & 1), feature range 64 (w >> 1) .. + 64     (levels 16 .. 1)
@@ -235,7 +238,7 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
             hi[p >> 2][p & 3] = h;
             lo[p >> 2][p & 3] = pack2(val[2 * p] - bf16_lo(h), val[2 * p + 1] - bf16_hi(h));
         }
-        const size_t off = (size_t(bh) * d.N + c) * C * C + j * C + rbase;
+        const size_t off = pos.slot * C * C + j * C + rbase;
         *reinterpret_cast<u32x4*>(p_hi + off) = hi[0];
         *reinterpret_cast<u32x4*>(p_hi + off + 8) = hi[1];
         *reinterpret_cast<u32x4*>(p_lo + off) = lo[0];
@@ -244,23 +247,23 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
 }
 
 // 64 x 128 bf16 tile out of rows of `stride` elements starting at column `col0`; rows >= L zero
-__device__ __forceinline__ void load_tile_strided(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int stride,
+__device__ __forceinline__ void load_tile_strided(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int stride,
                                                   int col0, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         const u32x4 v = __builtin_nontemporal_load(
-            reinterpret_cast<const u32x4*>(src + (tok0 + min(row, L - 1)) * stride + col0 + cp * 8));
+            reinterpret_cast<const u32x4*>(src + (tok0 + size_t(min(row, L - 1)) * ts) * stride + col0 + cp * 8));
         const uint32_t keep = row < L ? 0xffffffffu : 0u;
         *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
     }
 }
-__device__ __forceinline__ void store_tile_strided(uint16_t* dst, const uint16_t* src, size_t tok0, int L, int stride,
+__device__ __forceinline__ void store_tile_strided(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int stride,
                                                    int col0, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
         if (row < L)
             __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
-                                        reinterpret_cast<u32x4*>(dst + (tok0 + row) * stride + col0 + cp * 8));
+                                        reinterpret_cast<u32x4*>(dst + (tok0 + size_t(row) * ts) * stride + col0 + cp * 8));
     }
 }
 // 64 x 64 bf16 matrix (dense rows) -> LDS tile with row stride LDP
@@ -298,19 +301,22 @@ __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint1
 
     const int c = blockIdx.x, bh = blockIdx.y, vh = blockIdx.z, nvh = gridDim.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = c * C, L = min(C, d.T - t0);
-    const size_t tok0 = size_t(bh) * d.T + t0;
+    const ChunkPos pos = chunk_pos(d, c, bh);
+    const int L = pos.L;
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = pos.tok0, wtok0 = pos.wtok0;
+    const int ts = pos.ts;
     const int n = lane & 31, half = lane >> 5;
 
-    const uint16_t* St = states + ((size_t(bh) * nvh + vh) * d.N + c) * D * D;
+    const uint16_t* St = states + (pos.slot * nvh + vh) * D * D;
     bf16x8 sfrag[8];
     _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
         sfrag[ks] = *reinterpret_cast<const bf16x8*>(St + state_frag_off(wave, ks, lane));
 
-    load_tile(Q, qhat, tok0, L, tid);
-    load_tile(Ql, qhat_lo, tok0, L, tid);
-    load_tile_strided(V, v, tok0, L, d.dv, D * vh, tid);
-    const size_t poff = (size_t(bh) * d.N + c) * C * C;
+    load_tile(Q, qhat, wtok0, 1, L, tid);  // the library's own planes
+    load_tile(Ql, qhat_lo, wtok0, 1, L, tid);
+    load_tile_strided(V, v, tok0, ts, L, d.dv, D * vh, tid);
+    const size_t poff = pos.slot * C * C;
     load_scores(Ph, p_hi + poff, tid);
     load_scores(Pl, p_lo + poff, tid);
     __syncthreads();
@@ -341,7 +347,7 @@ __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint1
     __syncthreads();  // every wave is done with Q
     _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) store_packed(Q, LD, 32 * jb + n, 32 * wave, half, res[jb]);
     __syncthreads();
-    store_tile_strided(o, Q, tok0, L, d.dv, D * vh, tid);
+    store_tile_strided(o, Q, tok0, ts, L, d.dv, D * vh, tid);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -381,8 +387,11 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
     float* zl = zd + C;                                  // [128]
 
     const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = c * C, L = min(C, d.T - t0);
-    const size_t tok0 = size_t(bh) * d.T + t0;
+    const ChunkPos pos = chunk_pos(d, c, bh);
+    const int L = pos.L;
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = pos.tok0, wtok0 = pos.wtok0;
+    const int ts = pos.ts;
     const int n = lane & 31, half = lane >> 5;
     const int nvh = d.dv / D;
     const bool want_dg = dg != nullptr;  // then states_rem and dstates_rem are present
@@ -398,13 +407,13 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
     auto issue = [&](int vh, SliceRegs& r) {
         _Pragma("unroll") for (int it = 0; it < 4; ++it) {
             const int p = tid + kThreads * it, row = p >> 4, cpp = p & 15;
-            const size_t off = (tok0 + min(row, L - 1)) * d.dv + D * vh + cpp * 8;
+            const size_t off = (tok0 + size_t(min(row, L - 1)) * ts) * d.dv + D * vh + cpp * 8;
             const uint32_t keep = row < L ? 0xffffffffu : 0u;
             u32x4 a = *reinterpret_cast<const u32x4*>(v + off), b = *reinterpret_cast<const u32x4*>(d_o + off);
             r.tv[it] = u32x4{a.x & keep, a.y & keep, a.z & keep, a.w & keep};
             r.to[it] = u32x4{b.x & keep, b.y & keep, b.z & keep, b.w & keep};
         }
-        const size_t sbase = ((size_t(bh) * nvh + vh) * d.N + c) * D * D;
+        const size_t sbase = (pos.slot * nvh + vh) * D * D;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
             const size_t soff = sbase + state_frag_off(wave, ks, lane);
             r.s[ks] = *reinterpret_cast<const bf16x8*>(states + soff);
@@ -423,10 +432,10 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
         }
     };
     SliceRegs sr0;
-    load_tile(Qr, q, tok0, L, tid);
-    load_tile(Kr, k, tok0, L, tid);
+    load_tile(Qr, q, tok0, ts, L, tid);
+    load_tile(Kr, k, tok0, ts, L, tid);
     issue(0, sr0);
-    decay_tile(bt, g, tok0, L, tid);
+    decay_tile(bt, g, tok0, ts, L, tid);
 
     // ---- inter parts and Z, slice by slice of the value dimension
     // aqr, akr: contributions of the remainder planes of S and dS; they enter the decay gradient only, so
@@ -619,8 +628,8 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
         }
     }
     __syncthreads();  // stages complete; b no longer needed
-    store_tile(dq, T0, tok0, L, tid);
-    store_tile(dk, T1, tok0, L, tid);
+    store_tile(dq, T0, tok0, ts, L, tid);
+    store_tile(dk, T1, tok0, ts, L, tid);
     if (want_dg) {
         _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
             _Pragma("unroll") for (int gq = 0; gq < 4; ++gq)
@@ -631,7 +640,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
         _Pragma("unroll") for (int it = 0; it < 8; ++it) {
             const int p = tid + kThreads * it, row = p >> 5, c4 = p & 31;
             if (row < L)
-                *reinterpret_cast<float4*>(dg + (tok0 + row) * D + 4 * c4) = *reinterpret_cast<const float4*>(bt + row * LDF + 4 * c4);
+                *reinterpret_cast<float4*>(dg + (tok0 + size_t(row) * ts) * D + 4 * c4) = *reinterpret_cast<const float4*>(bt + row * LDF + 4 * c4);
         }
     }
 }
