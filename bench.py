@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--layout", type=int, default=0, choices=(0, 1),
+                    help="0: [B,H,T,d] as BASELINE.json's configurations are written; 1: the same data token-major [B,T,H,d]")
     ap.add_argument("--no-microbench", action="store_true",
                     help="skip the LDS-resident intra-chunk micro-benchmark (profiling runs: it launches the output kernel again)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -77,9 +79,14 @@ def main():
     ws = torch.empty(max(pkg.lsm_chunk_fwd_workspace_bytes(p), pkg.lsm_chunk_bwd_workspace_bytes(p), 256),
                      dtype=torch.uint8, device=dev)
 
+    if args.layout == 1:   # the same values, token-major
+        q, k, v, d_o = (t_.transpose(1, 2).contiguous() for t_ in (q, k, v, d_o))
+        if kind in (wl.KIND_SCALAR, wl.KIND_VECTOR):
+            g = g.transpose(1, 2).contiguous()
+
     def step():
-        out = pkg.lsm_chunk_fwd(q, k, v, g, kind, C, m0, workspace=ws)
-        grads = pkg.lsm_chunk_bwd(q, k, v, g, kind, d_o, C, m0, workspace=ws) if backward else None
+        out = pkg.lsm_chunk_fwd(q, k, v, g, kind, C, m0, workspace=ws, layout=args.layout)
+        grads = pkg.lsm_chunk_bwd(q, k, v, g, kind, d_o, C, m0, workspace=ws, layout=args.layout) if backward else None
         return out, grads
 
     if args.copy_calibration:
@@ -131,7 +138,8 @@ def main():
         "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": cfg["name"], "B": B, "H": H, "T": T, "d_k": dk, "d_v": dv, "chunk": C,
                    "decay_kind": wl.KIND_NAMES[kind], "passes": "fwd+bwd" if backward else "fwd",
-                   "kernel_path": "mfma" if pkg.kernel_path(p) == 1 else "generic"},
+                   "kernel_path": "mfma" if pkg.kernel_path(p) == 1 else "generic",
+                   "layout": "BTHD" if args.layout else "BHTD"},
         "tflops": tflops, "mfma_peak_frac": tflops / MFMA_BF16_PEAK_TFLOPS,
         "hbm_frac_whole_step": algorithmic_bytes_per_token_head(cfg, "both" if backward else "fwd") * th / sec / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kavg,
@@ -140,7 +148,7 @@ def main():
                      "algorithmic_bytes_per_launch": abytes},
     }
 
-    if pkg.kernel_path(p) == 1 and kind != wl.KIND_VECTOR and not args.no_microbench:
+    if pkg.kernel_path(p) == 1 and kind != wl.KIND_VECTOR and not args.no_microbench and args.layout == 0:
         # Intra-chunk phase apart from HBM: the forward per-chunk kernel with its compute phase repeated on
         # LDS-resident tiles; the time of one pass is the slope between two repeat counts.
         R = 33
@@ -213,6 +221,11 @@ def main():
                                   "seconds": c1 - c0}
         if not args.no_check:
             (o, mT), grads = last
+            if args.layout == 1:   # back to the order of the oracle's arrays
+                o = o.transpose(1, 2)
+                if grads:
+                    grads = {n_: (t_.transpose(1, 2) if (t_ is not None and t_.dim() >= 3 and n_ != "d_init_state") else t_)
+                             for n_, t_ in grads.items()}
             def err(got, ref, ulp):
                 got = got.float().cpu().numpy().astype(np.float64)
                 e = np.maximum(np.abs(got - ref) - ulp * np.abs(ref), 0).max()

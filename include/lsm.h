@@ -61,6 +61,12 @@ typedef enum {
     LSM_ERR_LAUNCH      = -6  /* HIP reported an error when the kernels were enqueued            */
 } lsm_status;
 
+/* Memory order of q, k, v, o, d_o, dq, dk, dv and of the per-token decays and their gradient. */
+typedef enum {
+    LSM_LAYOUT_BHTD = 0, /* [B,H,T,d]: head-major (per-token scalar decay [B,H,T])                        */
+    LSM_LAYOUT_BTHD = 1  /* [B,T,H,d]: token-major, as a fused QKV projection leaves it (decay [B,T,H])    */
+} lsm_layout;
+
 typedef struct {
     uint32_t struct_size; /* = sizeof(lsm_params) */
     int32_t  B, H, T;     /* batch, heads, tokens per sequence (any T >= 1; the last chunk may be ragged) */
@@ -68,15 +74,27 @@ typedef struct {
     int32_t  chunk_size;  /* C: tokens per chunk of Algorithm 2 (size of the quadratic block)    */
     int32_t  decay_kind;  /* lsm_decay_kind                                                      */
     int32_t  dtype;       /* lsm_dtype                                                           */
+    int32_t  layout;      /* lsm_layout                                                          */
+    /*
+     * Packed variable-length input (the paper's handling of batches of unequal sequences: one
+     * continuous token axis, the state starting afresh at every sequence boundary).  n_seq = 0: B
+     * sequences of T tokens each.  n_seq > 0: B must be 1, T is the total token count and
+     * cu_seqlens (DEVICE pointer, n_seq + 1 ints, 16-byte aligned) holds the first token of each
+     * sequence, cu_seqlens[0] = 0 <= ... <= cu_seqlens[n_seq] = T (content not checked).  Every
+     * sequence is chunked on its own, so no chunk straddles a boundary; init_state, final_state and
+     * their gradients are then [n_seq,H,d_k,d_v].  The result equals n_seq separate calls.
+     */
+    int32_t  n_seq;
+    const int32_t* cu_seqlens;
 } lsm_params;
 
 /*
  * Forward (Algorithm 2 with decay; Eq. 5; Table 1).
- *   q, k        [B,H,T,d_k]  dtype          in
- *   v           [B,H,T,d_v]  dtype          in
- *   log_decay   per decay_kind, fp32, finite and <= 0 (not checked)      in
- *   init_state  NULL (= zeros) or [B,H,d_k,d_v] fp32: M_0                in
- *   o           [B,H,T,d_v]  dtype          out
+ *   q, k        [B,H,T,d_k]  dtype          in      (shapes as written are for LSM_LAYOUT_BHTD; with
+ *   v           [B,H,T,d_v]  dtype          in       LSM_LAYOUT_BTHD the H and T axes of q, k, v, o and of
+ *   log_decay   per decay_kind, fp32, finite and <= 0 (not checked)      in      the per-token decays swap)
+ *   init_state  NULL (= zeros) or [B,H,d_k,d_v] fp32: M_0                in      ([n_seq,H,d_k,d_v] for packed input,
+ *   o           [B,H,T,d_v]  dtype          out                                   as are the other three states)
  *   final_state NULL (not wanted) or [B,H,d_k,d_v] fp32: M_T             out
  *   workspace   device scratch of at least lsm_chunk_fwd_workspace_bytes(p); contents undefined after the call
  *   stream      hipStream_t, NULL = the default stream
@@ -164,7 +182,7 @@ int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, con
 /* Static, NUL-terminated description of a status code. */
 const char* lsm_status_string(int status);
 
-/* ABI version, bumped when a signature or struct changes. */
+/* ABI version, bumped when a signature or struct changes (2: layout and packed input in lsm_params). */
 int lsm_version(void);
 
 #ifdef __cplusplus

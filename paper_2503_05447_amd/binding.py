@@ -12,6 +12,7 @@ from . import build as _build
 
 DECAY_NONE, DECAY_HEAD, DECAY_SCALAR, DECAY_VECTOR = 0, 1, 2, 3
 DTYPE_F32, DTYPE_BF16 = 0, 1
+LAYOUT_BHTD, LAYOUT_BTHD = 0, 1
 
 
 class LsmError(RuntimeError):
@@ -23,7 +24,8 @@ class LsmError(RuntimeError):
 class _Params(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("B", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("T", ctypes.c_int32), ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32),
-                ("chunk_size", ctypes.c_int32), ("decay_kind", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("chunk_size", ctypes.c_int32), ("decay_kind", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("layout", ctypes.c_int32), ("n_seq", ctypes.c_int32), ("cu_seqlens", ctypes.c_void_p)]
 
 
 _lib = None
@@ -69,8 +71,9 @@ def _status_string(status):
     return library().lsm_status_string(int(status)).decode()
 
 
-def make_params(B, H, T, d_k, d_v, chunk_size, decay_kind, dtype):
-    return _Params(ctypes.sizeof(_Params), B, H, T, d_k, d_v, chunk_size, decay_kind, dtype)
+def make_params(B, H, T, d_k, d_v, chunk_size, decay_kind, dtype, layout=LAYOUT_BHTD, n_seq=0, cu_seqlens=None):
+    """cu_seqlens: device address (int) of n_seq + 1 int32 sequence starts, or None."""
+    return _Params(ctypes.sizeof(_Params), B, H, T, d_k, d_v, chunk_size, decay_kind, dtype, layout, n_seq, cu_seqlens)
 
 
 def lsm_chunk_fwd_workspace_bytes(params):
@@ -112,7 +115,7 @@ def _check(t, shape, dtype, name):
                          % (name, tuple(shape), dtype, tuple(t.shape), t.dtype, t.device))
 
 
-def _setup(q, k, v, log_decay, decay_kind, chunk_size):
+def _setup(q, k, v, log_decay, decay_kind, chunk_size, layout=LAYOUT_BHTD, cu_seqlens=None):
     import torch
     if q.dtype == torch.float32:
         dt = DTYPE_F32
@@ -120,20 +123,31 @@ def _setup(q, k, v, log_decay, decay_kind, chunk_size):
         dt = DTYPE_BF16
     else:
         raise ValueError("q must be float32 or bfloat16")
-    B, H, T, dk = q.shape
+    if layout == LAYOUT_BTHD:
+        B, T, H, dk = q.shape
+    else:
+        B, H, T, dk = q.shape
     dv = v.shape[-1]
-    _check(q, (B, H, T, dk), q.dtype, "q")
-    _check(k, (B, H, T, dk), q.dtype, "k")
-    _check(v, (B, H, T, dv), q.dtype, "v")
-    gshape = {DECAY_NONE: None, DECAY_HEAD: (H,), DECAY_SCALAR: (B, H, T), DECAY_VECTOR: (B, H, T, dk)}[decay_kind]
+    tshape = (lambda d_: (B, T, H, d_)) if layout == LAYOUT_BTHD else (lambda d_: (B, H, T, d_))
+    _check(q, tshape(dk), q.dtype, "q")
+    _check(k, tshape(dk), q.dtype, "k")
+    _check(v, tshape(dv), q.dtype, "v")
+    gshape = {DECAY_NONE: None, DECAY_HEAD: (H,), DECAY_SCALAR: tshape(dk)[:3], DECAY_VECTOR: tshape(dk)}[decay_kind]
     if gshape is not None:
         if log_decay is None:
             raise ValueError("log_decay required for this decay kind")
         _check(log_decay, gshape, torch.float32, "log_decay")
     elif log_decay is not None:
         raise ValueError("log_decay must be None for DECAY_NONE")
-    p = make_params(B, H, T, dk, dv, chunk_size, decay_kind, dt)
-    return p, (B, H, T, dk, dv), gshape
+    n_seq, cu_ptr = 0, None
+    if cu_seqlens is not None:
+        if B != 1:
+            raise ValueError("packed variable-length input needs B == 1")
+        n_seq = cu_seqlens.numel() - 1
+        _check(cu_seqlens, (n_seq + 1,), torch.int32, "cu_seqlens")
+        cu_ptr = cu_seqlens.data_ptr()
+    p = make_params(B, H, T, dk, dv, chunk_size, decay_kind, dt, layout, n_seq, cu_ptr)
+    return p, (n_seq or B, H, T, dk, dv), gshape
 
 
 def _stream_handle(stream):
@@ -143,18 +157,20 @@ def _stream_handle(stream):
 
 
 def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None,
-                  want_final_state=True, workspace=None, stream=None):
+                  want_final_state=True, workspace=None, stream=None, layout=LAYOUT_BHTD, cu_seqlens=None):
     """o, final_state = chunkwise forward of M_t = diag(a_t) M_{t-1} + k_t^T v_t, o_t = q_t M_t.
 
+    layout: LAYOUT_BHTD ([B,H,T,d]) or LAYOUT_BTHD ([B,T,H,d]).  cu_seqlens (int32 device tensor of
+    n_seq + 1 sequence starts, B == 1): packed variable-length input; states are then [n_seq,H,d_k,d_v].
     Enqueues on ``stream`` (default: torch's current stream) and returns without synchronising.
     """
     import torch
-    p, (B, H, T, dk, dv), _ = _setup(q, k, v, log_decay, decay_kind, chunk_size)
+    p, (B, H, T, dk, dv), _ = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens)
     _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
     need = lsm_chunk_fwd_workspace_bytes(p)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    o = torch.empty((B, H, T, dv), dtype=q.dtype, device=q.device)
+    o = torch.empty_like(v)
     final = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
     rc = library().lsm_chunk_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(init_state),
                                  _ptr(o), _ptr(final), _ptr(workspace), workspace.numel(), _stream_handle(stream))
@@ -205,13 +221,14 @@ def lsm_bench_intra_chunk(q, k, v, log_decay, decay_kind, o, workspace, repeats,
 
 
 def lsm_chunk_bwd(q, k, v, log_decay, decay_kind, d_o, chunk_size=64, init_state=None, d_final_state=None,
-                  want_d_log_decay=True, want_d_init_state=True, workspace=None, stream=None):
+                  want_d_log_decay=True, want_d_init_state=True, workspace=None, stream=None,
+                  layout=LAYOUT_BHTD, cu_seqlens=None):
     """dict(dq, dk, dv, dg, d_init_state): chunkwise backward of <o, d_o> + <M_T, d_final_state>."""
     import torch
-    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_decay, decay_kind, chunk_size)
+    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens)
     _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
     _check(d_final_state, (B, H, dk, dv), torch.float32, "d_final_state")
-    _check(d_o, (B, H, T, dv), q.dtype, "d_o")
+    _check(d_o, tuple(v.shape), q.dtype, "d_o")
     need = lsm_chunk_bwd_workspace_bytes(p)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)

@@ -44,18 +44,35 @@ int check_params(const lsm_params* p, lsm::Dims* d) {
     if (!dim_ok(p->d_k) || !dim_ok(p->d_v) || !chunk_ok(p->chunk_size)) return LSM_ERR_UNSUPPORTED;
     // index arithmetic inside the kernels is 64-bit, grid dimensions are not
     const long long bh = (long long)p->B * p->H;
-    const long long n = ((long long)p->T + p->chunk_size - 1) / p->chunk_size;
-    if (bh > 65535 || n > 0x7fffffffLL || bh * p->T > (1LL << 40)) return LSM_ERR_SHAPE;
+    if (p->layout != LSM_LAYOUT_BHTD && p->layout != LSM_LAYOUT_BTHD) return LSM_ERR_UNSUPPORTED;
+    if (p->n_seq < 0 || (p->n_seq > 0 && p->B != 1)) return LSM_ERR_SHAPE;
+    if ((p->n_seq > 0) != (p->cu_seqlens != nullptr)) return LSM_ERR_NULL;
+    if (misaligned(p->cu_seqlens)) return LSM_ERR_ALIGN;
+    // packed input: every sequence adds at most one ragged chunk to the count
+    const long long n = ((long long)p->T + p->chunk_size - 1) / p->chunk_size + p->n_seq;
+    const long long seqs = p->n_seq ? (long long)p->n_seq * p->H : bh;
+    if (bh > 65535 || seqs > 65535 || n > 0x7fffffffLL || bh * p->T > (1LL << 40)) return LSM_ERR_SHAPE;
     d->B = p->B; d->H = p->H; d->T = p->T; d->dk = p->d_k; d->dv = p->d_v; d->C = p->chunk_size;
     d->N = int(n); d->kind = p->decay_kind; d->bf16 = p->dtype == LSM_DTYPE_BF16;
+    d->layout = p->layout; d->nseq = p->n_seq; d->cu = p->cu_seqlens; d->cstart = nullptr;
     return LSM_OK;
+}
+
+// packed input: the first bytes of the workspace hold the first chunk of every sequence
+size_t table_bytes(const lsm::Dims& d) { return d.nseq ? lsm::align256(size_t(d.nseq + 1) * sizeof(int)) : 0; }
+hipError_t prepare_tables(lsm::Dims& d, void*& workspace, hipStream_t stream) {
+    if (!d.nseq) return hipSuccess;
+    int* cstart = static_cast<int*>(workspace);
+    workspace = static_cast<char*>(workspace) + table_bytes(d);
+    d.cstart = cstart;
+    return lsm::launch_chunk_starts(d, cstart, stream);
 }
 
 }  // namespace
 
 extern "C" {
 
-int lsm_version(void) { return 1; }
+int lsm_version(void) { return 2; }
 
 const char* lsm_status_string(int status) {
     switch (status) {
@@ -115,13 +132,13 @@ int lsm_kernel_path(const lsm_params* p) {
 size_t lsm_chunk_fwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK) return 0;
-    return lsm::mfma_supported(d) ? lsm::mfma_fwd_workspace(d) : lsm::generic_fwd_workspace(d);
+    return table_bytes(d) + (lsm::mfma_supported(d) ? lsm::mfma_fwd_workspace(d) : lsm::generic_fwd_workspace(d));
 }
 
 size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK) return 0;
-    return lsm::mfma_bwd_supported(d) ? lsm::mfma_bwd_workspace(d) : lsm::generic_bwd_workspace(d);
+    return table_bytes(d) + (lsm::mfma_bwd_supported(d) ? lsm::mfma_bwd_workspace(d) : lsm::generic_bwd_workspace(d));
 }
 
 int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
@@ -137,6 +154,7 @@ int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void*
         return LSM_ERR_ALIGN;
     const size_t need = lsm_chunk_fwd_workspace_bytes(p);
     if (!workspace || workspace_bytes < need) return LSM_ERR_WORKSPACE;
+    if (prepare_tables(d, workspace, static_cast<hipStream_t>(stream)) != hipSuccess) return LSM_ERR_LAUNCH;
     lsm::FwdArgs a{q, k, v, log_decay, init_state, o, final_state, workspace, static_cast<hipStream_t>(stream)};
     const hipError_t e = lsm::mfma_supported(d) ? lsm::mfma_fwd(d, a) : lsm::generic_fwd(d, a);
     return e == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
@@ -149,7 +167,7 @@ int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, con
     if (rc != LSM_OK) return rc;
     if (!q || !k || !v || !o) return LSM_ERR_NULL;
     if ((d.kind == LSM_DECAY_NONE) != (log_decay == nullptr)) return LSM_ERR_NULL;
-    if (!lsm::mfma_supported(d) || d.kind == LSM_DECAY_VECTOR || repeats < 1) return LSM_ERR_UNSUPPORTED;
+    if (!lsm::mfma_supported(d) || d.kind == LSM_DECAY_VECTOR || repeats < 1 || d.nseq) return LSM_ERR_UNSUPPORTED;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_decay) || misaligned(workspace))
         return LSM_ERR_ALIGN;
     if (!workspace || workspace_bytes < lsm_chunk_fwd_workspace_bytes(p)) return LSM_ERR_WORKSPACE;
@@ -164,6 +182,7 @@ int lsm_step(const lsm_params* p, const void* q, const void* k, const void* v, c
     if (rc != LSM_OK) return rc;
     if (!q || !k || !v || !o || !state) return LSM_ERR_NULL;
     if ((d.kind == LSM_DECAY_NONE) != (log_decay == nullptr)) return LSM_ERR_NULL;
+    if (d.nseq) return LSM_ERR_UNSUPPORTED;  // one token per sequence: nothing to pack (the layout is immaterial for T = 1)
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_decay) || misaligned(state))
         return LSM_ERR_ALIGN;
     return lsm::step(d, q, k, v, log_decay, state, o, static_cast<hipStream_t>(stream)) == hipSuccess ? LSM_OK
@@ -186,6 +205,7 @@ int lsm_chunk_bwd(const lsm_params* p, const void* q, const void* k, const void*
         return LSM_ERR_ALIGN;
     const size_t need = lsm_chunk_bwd_workspace_bytes(p);
     if (!workspace || workspace_bytes < need) return LSM_ERR_WORKSPACE;
+    if (prepare_tables(d, workspace, static_cast<hipStream_t>(stream)) != hipSuccess) return LSM_ERR_LAUNCH;
     lsm::BwdArgs a{q, k, v, log_decay, init_state, d_o, d_final_state, dq, dk, dv, d_log_decay, d_init_state,
                    workspace, static_cast<hipStream_t>(stream)};
     const hipError_t e = lsm::mfma_bwd_supported(d) ? lsm::mfma_bwd(d, a) : lsm::generic_bwd(d, a);

@@ -41,14 +41,15 @@ __device__ __forceinline__ float expd(bsum_t x) { return expf(float(x)); }
 // b_j = sum_{r<=j, r in chunk} g_r   (grid: N x BH)
 __global__ void k_cumsum(Dims d, const float* __restrict__ g, bsum_t* __restrict__ bcum) {
     const int c = blockIdx.x, bh = blockIdx.y, h = bh % d.H;
-    const int t0 = c * d.C, L = min(d.C, d.T - t0), dkd = d.dkd();
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L, dkd = d.dkd();
     for (int i = threadIdx.x; i < dkd; i += blockDim.x) {
         bsum_t b = 0.0;
         for (int j = 0; j < L; ++j) {
-            size_t tok = size_t(bh) * d.T + t0 + j;
+            const size_t tok = cp.tok0 + size_t(j) * cp.ts;  // in the caller's arrays
             float gv = d.kind == 1 ? g[h] : (d.kind == 2 ? g[tok] : g[tok * d.dk + i]);
             b += gv;
-            bcum[tok * dkd + i] = b;
+            bcum[(cp.wtok0 + j) * dkd + i] = b;
         }
     }
 }
@@ -59,9 +60,12 @@ template <typename TIO, int MODE>
 __global__ void k_local_state(Dims d, const TIO* __restrict__ x, const TIO* __restrict__ y,
                               const bsum_t* __restrict__ bcum, float* __restrict__ out) {
     const int c = blockIdx.x, bh = blockIdx.y;
-    const int t0 = c * d.C, L = min(d.C, d.T - t0), dkd = d.dkd();
-    const size_t tok0 = size_t(bh) * d.T + t0;
-    float* dst = out + (size_t(bh) * d.N + c) * d.dk * d.dv;
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L, dkd = d.dkd();
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = cp.wtok0;                              // token index in the library's own arrays
+    auto U = [&](int r) { return cp.tok0 + size_t(r) * cp.ts; };  // row of token r in the caller's arrays
+    float* dst = out + cp.slot * d.dk * d.dv;
     for (int e = threadIdx.x; e < d.dk * d.dv; e += blockDim.x) {
         const int i = e / d.dv, j = e % d.dv;
         const bsum_t bC = bval(bcum, tok0 + L - 1, dkd, i);
@@ -69,7 +73,7 @@ __global__ void k_local_state(Dims d, const TIO* __restrict__ x, const TIO* __re
         for (int r = 0; r < L; ++r) {
             const bsum_t br = bval(bcum, tok0 + r, dkd, i);
             const float w = MODE == 0 ? expd(bC - br) : expd(br);
-            acc += to_f32(x[(tok0 + r) * d.dk + i]) * w * to_f32(y[(tok0 + r) * d.dv + j]);
+            acc += to_f32(x[U(r) * d.dk + i]) * w * to_f32(y[U(r) * d.dv + j]);
         }
         dst[e] = acc;
     }
@@ -82,40 +86,42 @@ __global__ void k_local_state(Dims d, const TIO* __restrict__ x, const TIO* __re
 template <bool REVERSE>
 __global__ void k_scan(Dims d, const bsum_t* __restrict__ bcum, float* __restrict__ states,
                        const float* __restrict__ edge_in, float* __restrict__ edge_out) {
-    const int bh = blockIdx.y, dkd = d.dkd();
+    const SeqWalk w = seq_walk(d, blockIdx.y);  // grid.y = Dims::seqs()
+    const int dkd = d.dkd();
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     const int sz = d.dk * d.dv;
     if (e >= sz) return;
     const int i = e / d.dv;
-    float s = edge_in ? edge_in[size_t(bh) * sz + e] : 0.f;
-    for (int n = 0; n < d.N; ++n) {
-        const int c = REVERSE ? d.N - 1 - n : n;
-        const int tlast = min(d.T, (c + 1) * d.C) - 1;
-        const float lam = expd(bval(bcum, size_t(bh) * d.T + tlast, dkd, i));
-        float* slot = states + (size_t(bh) * d.N + c) * sz + e;
+    float s = edge_in ? edge_in[size_t(w.edge) * sz + e] : 0.f;
+    for (int n = 0; n < w.n; ++n) {
+        const ChunkPos cp = walk_pos(d, w, REVERSE ? w.n - 1 - n : n);
+        const float lam = expd(bval(bcum, cp.wtok0 + cp.L - 1, dkd, i));
+        float* slot = states + cp.slot * sz + e;
         const float u = *slot;
         *slot = s;
         s = lam * s + u;
     }
-    if (edge_out) edge_out[size_t(bh) * sz + e] = s;
+    if (edge_out) edge_out[size_t(w.edge) * sz + e] = s;
 }
 
 // A_jr = sum_i q_ji k_ri e^{b_ji - b_ri}  for r <= j  (0 otherwise), into LDS [C*C]
 template <typename TIO>
-__device__ void scores_to_lds(const Dims& d, const TIO* q, const TIO* k, const bsum_t* bcum, size_t tok0,
+__device__ void scores_to_lds(const Dims& d, const TIO* q, const TIO* k, const bsum_t* bcum, const ChunkPos& cp,
                               int L, float* A) {
     const int dkd = d.dkd();
+    const size_t tok0 = cp.wtok0;
+    auto U = [&](int r) { return cp.tok0 + size_t(r) * cp.ts; };
     for (int e = threadIdx.x; e < L * L; e += blockDim.x) {
         const int j = e / L, r = e % L;
         float acc = 0.f;
         if (r <= j) {
             if (dkd == 1) {
                 for (int i = 0; i < d.dk; ++i)
-                    acc += to_f32(q[(tok0 + j) * d.dk + i]) * to_f32(k[(tok0 + r) * d.dk + i]);
+                    acc += to_f32(q[U(j) * d.dk + i]) * to_f32(k[U(r) * d.dk + i]);
                 acc *= expd(bval(bcum, tok0 + j, 1, 0) - bval(bcum, tok0 + r, 1, 0));
             } else {
                 for (int i = 0; i < d.dk; ++i)
-                    acc += to_f32(q[(tok0 + j) * d.dk + i]) * to_f32(k[(tok0 + r) * d.dk + i]) *
+                    acc += to_f32(q[U(j) * d.dk + i]) * to_f32(k[U(r) * d.dk + i]) *
                            expd(bcum[(tok0 + j) * dkd + i] - bcum[(tok0 + r) * dkd + i]);
             }
         }
@@ -130,18 +136,21 @@ __global__ void k_output(Dims d, const TIO* __restrict__ q, const TIO* __restric
     extern __shared__ float lds[];
     float* A = lds;
     const int c = blockIdx.x, bh = blockIdx.y;
-    const int t0 = c * d.C, L = min(d.C, d.T - t0), dkd = d.dkd();
-    const size_t tok0 = size_t(bh) * d.T + t0;
-    const float* S = states + (size_t(bh) * d.N + c) * d.dk * d.dv;
-    scores_to_lds(d, q, k, bcum, tok0, L, A);
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L, dkd = d.dkd();
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = cp.wtok0;                              // token index in the library's own arrays
+    auto U = [&](int r) { return cp.tok0 + size_t(r) * cp.ts; };  // row of token r in the caller's arrays
+    const float* S = states + cp.slot * d.dk * d.dv;
+    scores_to_lds(d, q, k, bcum, cp, L, A);
     __syncthreads();
     for (int e = threadIdx.x; e < L * d.dv; e += blockDim.x) {
         const int j = e / d.dv, col = e % d.dv;
         float acc = 0.f;
-        for (int r = 0; r <= j; ++r) acc += A[j * d.C + r] * to_f32(v[(tok0 + r) * d.dv + col]);
+        for (int r = 0; r <= j; ++r) acc += A[j * d.C + r] * to_f32(v[U(r) * d.dv + col]);
         for (int i = 0; i < d.dk; ++i)
-            acc += to_f32(q[(tok0 + j) * d.dk + i]) * expd(bval(bcum, tok0 + j, dkd, i)) * S[i * d.dv + col];
-        from_f32(&o[(tok0 + j) * d.dv + col], acc);
+            acc += to_f32(q[U(j) * d.dk + i]) * expd(bval(bcum, tok0 + j, dkd, i)) * S[i * d.dv + col];
+        from_f32(&o[U(j) * d.dv + col], acc);
     }
 }
 
@@ -164,19 +173,22 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
     float* A = lds;
     float* dA = lds + d.C * d.C;
     const int c = blockIdx.x, bh = blockIdx.y;
-    const int t0 = c * d.C, L = min(d.C, d.T - t0), dkd = d.dkd();
-    const size_t tok0 = size_t(bh) * d.T + t0;
-    const float* S = states + (size_t(bh) * d.N + c) * d.dk * d.dv;
-    const float* dS = dstates + (size_t(bh) * d.N + c) * d.dk * d.dv;
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L, dkd = d.dkd();
+    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
+    const size_t tok0 = cp.wtok0;                              // token index in the library's own arrays
+    auto U = [&](int r) { return cp.tok0 + size_t(r) * cp.ts; };  // row of token r in the caller's arrays
+    const float* S = states + cp.slot * d.dk * d.dv;
+    const float* dS = dstates + cp.slot * d.dk * d.dv;
     const bool want_dg = dg != nullptr || dg_tok != nullptr;
 
-    scores_to_lds(d, q, k, bcum, tok0, L, A);
+    scores_to_lds(d, q, k, bcum, cp, L, A);
     for (int e = threadIdx.x; e < L * L; e += blockDim.x) {
         const int j = e / L, r = e % L;
         float acc = 0.f;
         if (r <= j)
             for (int col = 0; col < d.dv; ++col)
-                acc += to_f32(d_o[(tok0 + j) * d.dv + col]) * to_f32(v[(tok0 + r) * d.dv + col]);
+                acc += to_f32(d_o[U(j) * d.dv + col]) * to_f32(v[U(r) * d.dv + col]);
         dA[j * d.C + r] = acc;
     }
     __syncthreads();
@@ -185,12 +197,12 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
     for (int e = threadIdx.x; e < L * d.dv; e += blockDim.x) {
         const int r = e / d.dv, col = e % d.dv;
         float acc = 0.f;
-        for (int j = r; j < L; ++j) acc += A[j * d.C + r] * to_f32(d_o[(tok0 + j) * d.dv + col]);
+        for (int j = r; j < L; ++j) acc += A[j * d.C + r] * to_f32(d_o[U(j) * d.dv + col]);
         for (int i = 0; i < d.dk; ++i) {
             const float w = expd(bval(bcum, tok0 + L - 1, dkd, i) - bval(bcum, tok0 + r, dkd, i));
-            acc += to_f32(k[(tok0 + r) * d.dk + i]) * w * dS[i * d.dv + col];
+            acc += to_f32(k[U(r) * d.dk + i]) * w * dS[i * d.dv + col];
         }
-        from_f32(&dv[(tok0 + r) * d.dv + col], acc);
+        from_f32(&dv[U(r) * d.dv + col], acc);
     }
     // dq, dk and the per-token terms of the decay gradient
     for (int e = threadIdx.x; e < L * d.dk; e += blockDim.x) {
@@ -199,21 +211,21 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
         const bsum_t bC = bval(bcum, tok0 + L - 1, dkd, i);
         float q_inter = 0.f, k_inter = 0.f;
         for (int col = 0; col < d.dv; ++col) {
-            q_inter += to_f32(d_o[(tok0 + t) * d.dv + col]) * S[i * d.dv + col];
-            k_inter += to_f32(v[(tok0 + t) * d.dv + col]) * dS[i * d.dv + col];
+            q_inter += to_f32(d_o[U(t) * d.dv + col]) * S[i * d.dv + col];
+            k_inter += to_f32(v[U(t) * d.dv + col]) * dS[i * d.dv + col];
         }
         q_inter *= expd(bt);
         k_inter *= expd(bC - bt);
         float q_intra = 0.f, k_intra = 0.f;
         for (int r = 0; r <= t; ++r)
-            q_intra += dA[t * d.C + r] * expd(bt - bval(bcum, tok0 + r, dkd, i)) * to_f32(k[(tok0 + r) * d.dk + i]);
+            q_intra += dA[t * d.C + r] * expd(bt - bval(bcum, tok0 + r, dkd, i)) * to_f32(k[U(r) * d.dk + i]);
         for (int j = t; j < L; ++j)
-            k_intra += dA[j * d.C + t] * expd(bval(bcum, tok0 + j, dkd, i) - bt) * to_f32(q[(tok0 + j) * d.dk + i]);
+            k_intra += dA[j * d.C + t] * expd(bval(bcum, tok0 + j, dkd, i) - bt) * to_f32(q[U(j) * d.dk + i]);
         const float dqv = q_inter + q_intra, dkv = k_inter + k_intra;
-        from_f32(&dq[(tok0 + t) * d.dk + i], dqv);
-        from_f32(&dk[(tok0 + t) * d.dk + i], dkv);
+        from_f32(&dq[U(t) * d.dk + i], dqv);
+        from_f32(&dk[U(t) * d.dk + i], dkv);
         if (want_dg) {
-            const float qv = to_f32(q[(tok0 + t) * d.dk + i]), kv = to_f32(k[(tok0 + t) * d.dk + i]);
+            const float qv = to_f32(q[U(t) * d.dk + i]), kv = to_f32(k[U(t) * d.dk + i]);
             wq[(tok0 + t) * d.dk + i] = qv * dqv - kv * dkv;
             wk[(tok0 + t) * d.dk + i] = kv * k_inter;
         }
@@ -228,7 +240,7 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
         for (int r = 0; r < L; ++r) run += wk[(tok0 + r) * d.dk + i];
         for (int t = L - 1; t >= 0; --t) {
             run += wq[(tok0 + t) * d.dk + i];
-            if (d.kind == 3) dg[(tok0 + t) * d.dk + i] = run;
+            if (d.kind == 3) dg[U(t) * d.dk + i] = run;
             else wq[(tok0 + t) * d.dk + i] = run;
         }
     }
@@ -237,7 +249,7 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
     for (int t = threadIdx.x; t < L; t += blockDim.x) {
         float s = 0.f;
         for (int i = 0; i < d.dk; ++i) s += wq[(tok0 + t) * d.dk + i];
-        if (d.kind == 2) dg[tok0 + t] = s;
+        if (d.kind == 2) dg[U(t)] = s;
         else dg_tok[tok0 + t] = s;
     }
 }
@@ -299,7 +311,7 @@ hipError_t fwd_t(const Dims& d, const FwdArgs& a) {
     auto q = static_cast<const TIO*>(a.q), k = static_cast<const TIO*>(a.k), v = static_cast<const TIO*>(a.v);
     if (d.kind != 0) { ProfScope ps(KID_GEN_CUMSUM, a.stream); hipLaunchKernelGGL(k_cumsum, grid, block, 0, a.stream, d, a.g, w.bcum); }
     { ProfScope ps(KID_GEN_STATE, a.stream); hipLaunchKernelGGL((k_local_state<TIO, 0>), grid, block, 0, a.stream, d, k, v, w.bcum, w.states); }
-    { ProfScope ps(KID_GEN_SCAN, a.stream); hipLaunchKernelGGL((k_scan<false>), dim3((sz + kThreads - 1) / kThreads, d.BH()), block, 0, a.stream, d, w.bcum,
+    { ProfScope ps(KID_GEN_SCAN, a.stream); hipLaunchKernelGGL((k_scan<false>), dim3((sz + kThreads - 1) / kThreads, d.seqs()), block, 0, a.stream, d, w.bcum,
                        w.states, a.m0, a.mT); }
     const size_t lds = size_t(d.C) * d.C * 4;
     if (lds > 48 * 1024) {
@@ -317,7 +329,7 @@ hipError_t bwd_t(const Dims& d, const BwdArgs& a) {
     WsBwd w = carve_bwd(d, a.ws);
     const dim3 grid(d.N, d.BH()), block(kThreads);
     const int sz = d.dk * d.dv;
-    const dim3 sgrid((sz + kThreads - 1) / kThreads, d.BH());
+    const dim3 sgrid((sz + kThreads - 1) / kThreads, d.seqs());
     auto q = static_cast<const TIO*>(a.q), k = static_cast<const TIO*>(a.k), v = static_cast<const TIO*>(a.v);
     auto d_o = static_cast<const TIO*>(a.d_o);
     const size_t lds = size_t(d.C) * d.C * 8;
@@ -345,6 +357,23 @@ hipError_t bwd_t(const Dims& d, const BwdArgs& a) {
 }
 
 }  // namespace
+
+namespace {
+// packed input: cstart[s] = sum over earlier sequences of ceil(len / C)  (one thread; n_seq is small)
+__global__ void k_chunk_starts(Dims d, int* __restrict__ cstart) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int c = 0;
+    cstart[0] = 0;
+    for (int s = 0; s < d.nseq; ++s) {
+        c += (d.cu[s + 1] - d.cu[s] + d.C - 1) / d.C;
+        cstart[s + 1] = c;
+    }
+}
+}  // namespace
+hipError_t launch_chunk_starts(const Dims& d, int* cstart, hipStream_t stream) {
+    hipLaunchKernelGGL(k_chunk_starts, dim3(1), dim3(64), 0, stream, d, cstart);
+    return hipGetLastError();
+}
 
 size_t generic_fwd_workspace(const Dims& d) { return carve_fwd(d, nullptr).bytes; }
 size_t generic_bwd_workspace(const Dims& d) { return carve_bwd(d, nullptr).bytes; }

@@ -838,7 +838,7 @@ size_t mfma_bwd_workspace(const Dims& d) { return carve(d, nullptr, true).bytes;
 namespace {
 template <int MODE>
 hipError_t launch_state(const Dims& d, hipStream_t st, const StateArgs& sa) {
-    const dim3 sgrid(D / 32 * d.BH()), block(kThreads);
+    const dim3 sgrid(D / 32 * d.seqs()), block(kThreads);
     const int lds = kStateLdsNoRem;
     hipError_t e;
     if (d.kind == 0) {
@@ -852,7 +852,7 @@ hipError_t launch_state(const Dims& d, hipStream_t st, const StateArgs& sa) {
 }
 template <bool DEC, bool REM>
 hipError_t launch_state_pair_t(const Dims& d, hipStream_t st, const StateArgs& s1, const StateArgs& s2) {
-    const dim3 sgrid(D / 32 * d.BH(), 2), block(kThreads);
+    const dim3 sgrid(D / 32 * d.seqs(), 2), block(kThreads);
     const int lds = REM ? kStateLds : kStateLdsNoRem;
     const hipError_t e = allow_lds(mk_state_pair<DEC, REM>, kStateLds);
     if (e != hipSuccess) return e;
@@ -890,7 +890,7 @@ hipError_t vec_fwd(const Dims& d, const FwdArgs& a) {
         ProfScope ps(KID_MFMA_STATE, a.stream);
         if ((e = allow_lds(mk_state_vec<3>, kStateLds)) != hipSuccess) return e;
         StateArgs sa{v, w.khat_hi, nullptr, w.lamv, w.states, nullptr, a.m0, a.mT, w.khat_lo, d.dv, nvh};
-        hipLaunchKernelGGL(mk_state_vec<3>, dim3(D / 32 * d.BH() * nvh), dim3(kThreads), kStateLdsNoRem, a.stream, d, sa);
+        hipLaunchKernelGGL(mk_state_vec<3>, dim3(D / 32 * d.seqs() * nvh), dim3(kThreads), kStateLdsNoRem, a.stream, d, sa);
     }
     {
         ProfScope ps(KID_MFMA_OUTPUT, a.stream);
@@ -937,7 +937,7 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
                            w.khat_lo, d.dv, nvh};
         const StateArgs s2{d_o, w.qhat_hi, nullptr, w.lamv, w.dstates, a.dg ? w.dstates_rem : nullptr, a.d_mT, a.d_m0,
                            w.qhat_lo, d.dv, nvh, w.dstates_t};
-        const dim3 sgrid(D / 32 * d.BH() * nvh, 2);
+        const dim3 sgrid(D / 32 * d.seqs() * nvh, 2);
         if (a.dg) {
             if ((e = allow_lds(mk_state_pair_vec<true>, kStateLdsTwin)) != hipSuccess) return e;
             hipLaunchKernelGGL(mk_state_pair_vec<true>, sgrid, dim3(kThreads), kStateLdsTwin, a.stream, d, s1, s2);

@@ -68,6 +68,13 @@ def test_error_codes_are_reached_before_any_launch():
     assert fwd(P(), ws=None) == ERR_WS
     assert fwd(P(), wsb=16) == ERR_WS
     assert bwd(P(), wsb=16) == ERR_WS
+    # layout and packed variable-length input
+    assert fwd(P(layout=2)) == ERR_UNSUP
+    assert fwd(P(n_seq=2, cu_seqlens=0x20000)) == ERR_SHAPE            # packed input needs B == 1
+    assert fwd(P(B=1, n_seq=2)) == ERR_NULL                            # cu_seqlens missing
+    assert fwd(P(B=1, cu_seqlens=0x20000)) == ERR_NULL                 # cu_seqlens without n_seq
+    assert fwd(P(B=1, n_seq=2, cu_seqlens=0x20004)) == ERR_ALIGN
+    assert fwd(P(B=1, n_seq=-1)) == ERR_SHAPE
     # recurrent step and benchmark aid: same checks, before any HIP call
     vp = ctypes.c_void_p
     lib = pkg.library()
@@ -95,6 +102,7 @@ def test_workspace_queries_and_status_strings():
     assert pkg.kernel_path(P(d_k=3)) < 0
     # workspace grows with the number of chunks
     assert pkg.lsm_chunk_fwd_workspace_bytes(P(T=6400)) > f
+    assert pkg.lsm_chunk_fwd_workspace_bytes(P(B=1, n_seq=3, cu_seqlens=0x20000)) > pkg.lsm_chunk_fwd_workspace_bytes(P(B=1))
     for s in range(0, -7, -1):
         assert len(binding._status_string(s)) > 1
     assert binding._status_string(-99) == "unknown status"
