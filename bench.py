@@ -206,7 +206,7 @@ def main():
     if not args.no_cpu_baseline or not args.no_check:
         from oracle import lsm_oracle_bwd, lsm_oracle_fwd, oracle_threads
         # bounded sample: the first `nb` batch elements of the same workload (all heads, full T)
-        nb = max(1, min(B, (1 << 18) // (H * T) or 1))
+        nb = max(1, min(B, (1 << 20) // (H * T) or 1))
         sl = slice(0, nb)
         gs = x["g"] if (x["g"] is None or kind == wl.KIND_HEAD) else x["g"][sl]
         m0s = None if x["m0"] is None else x["m0"][sl]
