@@ -955,7 +955,7 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
     {
         ProfScope ps(KID_MFMA_GRAD, a.stream);
         if ((e = allow_lds(mk_grad_vec, kGradVecLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL(mk_grad_vec, dim3(d.N, d.BH()), dim3(kThreads), kGradVecLds, a.stream, d, q, k, v, d_o, a.g,
+        hipLaunchKernelGGL(mk_grad_vec, dim3(d.N, d.BH()), dim3(kGradVecThreads), kGradVecLds, a.stream, d, q, k, v, d_o, a.g,
                            w.states, a.dg ? w.states_rem : nullptr, w.dstates, w.dstates_rem, static_cast<uint16_t*>(a.dq),
                            static_cast<uint16_t*>(a.dk), a.dg);
     }

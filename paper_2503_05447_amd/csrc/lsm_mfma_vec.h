@@ -359,22 +359,29 @@ __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint1
 // The intra sums use the level tiles W_s of mk_vec_prep: at level s every token t is on one side, and
 //   X_s[t][i] = sum_u Z_s[u][t] W_s[u][i]     (Z_s = Z restricted to the pairs of level s)
 // times the token's own level weight is its contribution to dq_t (t on the query side) or dk_t (key
-// side).  Wave w owns features [32w, 32w+32) of dq^T, dk^T (D layout: lane = token, registers =
-// features).  Z is built once (wave 0, 1: the diagonal 32-blocks, wave 2, 3: the off-diagonal ones),
-// summed over the 128-wide value slices, and kept in LDS as bf16 head + remainder.
+// side).  Eight waves: wave (w, nb) owns features [32w, 32w+32) of dq^T, dk^T for the tokens
+// [32nb, 32nb+32) (D layout: lane = token, registers = features), so that two waves share a SIMD
+// and the long per-element weight arithmetic of one overlaps the waits of the other.  Z is built
+// once (waves 0..3: one 32 x 32 block each), summed over the 128-wide value slices, and kept in LDS
+// as bf16 head + remainder.
 // LDS: b | Q | K | T0 (V slice, then W head, then dq stage) | T1 (d_o slice, W remainder, dk stage)
-//      | Z head | Z remainder | diagonal of dA | <S,dS> per feature
-constexpr int kGradVecLds = C * LDF * 4 + 4 * C * LD * 2 + 2 * C * LDP * 2 + C * 4 + D * 4;
+//      | Z head | Z remainder | diagonal of dA | <S,dS> per feature | exchange between the two token blocks
+//      | second level-tile buffer (head, remainder)        -- 155 KiB in all
+constexpr int kGradVecThreads = 512;
+constexpr int kGradVecLds = C * LDF * 4 + 6 * C * LD * 2 + 2 * C * LDP * 2 + C * 4 + D * 4 + 3 * 4 * 32 * 4;
 
-__global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_t* __restrict__ q,
-                                                           const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                           const uint16_t* __restrict__ d_o, const float* __restrict__ g,
-                                                           const uint16_t* __restrict__ states,
-                                                           const uint16_t* __restrict__ states_rem,
-                                                           const uint16_t* __restrict__ dstates,
-                                                           const uint16_t* __restrict__ dstates_rem,
-                                                           uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
-                                                           float* __restrict__ dg) {
+__global__ __launch_bounds__(kGradVecThreads, 1) void mk_grad_vec(Dims d, const uint16_t* __restrict__ q,
+                                                                  const uint16_t* __restrict__ k,
+                                                                  const uint16_t* __restrict__ v,
+                                                                  const uint16_t* __restrict__ d_o,
+                                                                  const float* __restrict__ g,
+                                                                  const uint16_t* __restrict__ states,
+                                                                  const uint16_t* __restrict__ states_rem,
+                                                                  const uint16_t* __restrict__ dstates,
+                                                                  const uint16_t* __restrict__ dstates_rem,
+                                                                  uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
+                                                                  float* __restrict__ dg) {
+    constexpr int NT = kGradVecThreads;
     extern __shared__ __align__(16) unsigned char smem[];
     float* bt = reinterpret_cast<float*>(smem);
     uint16_t* Qr = reinterpret_cast<uint16_t*>(bt + C * LDF);
@@ -385,62 +392,105 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
     uint16_t* Zl = Zh + C * LDP;
     float* zd = reinterpret_cast<float*>(Zl + C * LDP);  // [64]
     float* zl = zd + C;                                  // [128]
+    float* xch = zl + D;                                 // [3][4][32]: block-1 totals of the running sum, tail sums of both blocks
+    uint16_t* W1 = reinterpret_cast<uint16_t*>(xch + 3 * 4 * 32);  // second level-tile buffer: head | remainder
 
-    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wave = wv & 3, nb = wv >> 2;  // feature block, token block
     const ChunkPos pos = chunk_pos(d, c, bh);
     const int L = pos.L;
     if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
-    const size_t tok0 = pos.tok0, wtok0 = pos.wtok0;
+    const size_t tok0 = pos.tok0;
     const int ts = pos.ts;
     const int n = lane & 31, half = lane >> 5;
+    const int t = 32 * nb + n;  // this lane's token
     const int nvh = d.dv / D;
     const bool want_dg = dg != nullptr;  // then states_rem and dstates_rem are present
 
-    // Global loads are issued as early and as many at a time as the registers allow: with one
-    // workgroup per CU nothing else hides their latency.  Per value slice: the V and d_o tiles (via
-    // registers into LDS) and this wave's rows of S, dS and their remainder planes (MFMA A operands).
+    // 64 x 128 tiles move as 1024 16-byte pieces, two per thread
+    auto tile_rows = [&](int it, int& row, int& cpp) { const int p = tid + NT * it; row = p >> 4; cpp = p & 15; };
     struct SliceRegs {
-        u32x4 tv[4], to[4];
+        u32x4 tv[2], to[2];
         bf16x8 s[8], ds[8];
         u32x2 sr[8], dsr[8];  // remainder planes: 8-bit floats, still scaled by 2^8
     };
     auto issue = [&](int vh, SliceRegs& r) {
-        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-            const int p = tid + kThreads * it, row = p >> 4, cpp = p & 15;
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+            int row, cpp;
+            tile_rows(it, row, cpp);
             const size_t off = (tok0 + size_t(min(row, L - 1)) * ts) * d.dv + D * vh + cpp * 8;
-            const uint32_t keep = row < L ? 0xffffffffu : 0u;
-            u32x4 a = *reinterpret_cast<const u32x4*>(v + off), b = *reinterpret_cast<const u32x4*>(d_o + off);
-            r.tv[it] = u32x4{a.x & keep, a.y & keep, a.z & keep, a.w & keep};
-            r.to[it] = u32x4{b.x & keep, b.y & keep, b.z & keep, b.w & keep};
+            r.tv[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v + off));
+            r.to[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(d_o + off));
         }
+        // this wave's rows of S, dS (both token blocks read the same rows) and their 8-bit remainder planes
         const size_t sbase = (pos.slot * nvh + vh) * D * D;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
             const size_t soff = sbase + state_frag_off(wave, ks, lane);
             r.s[ks] = *reinterpret_cast<const bf16x8*>(states + soff);
             r.ds[ks] = *reinterpret_cast<const bf16x8*>(dstates + soff);
             if (want_dg) {
-                r.sr[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(states_rem) + soff));
-                r.dsr[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(dstates_rem) + soff));
+                r.sr[ks] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(states_rem) + soff);
+                r.dsr[ks] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(dstates_rem) + soff);
             }
         }
     };
     auto commit = [&](const SliceRegs& r) {
-        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-            const int p = tid + kThreads * it, row = p >> 4, cpp = p & 15;
-            *reinterpret_cast<u32x4*>(T0 + row * LD + cpp * 8) = r.tv[it];
-            *reinterpret_cast<u32x4*>(T1 + row * LD + cpp * 8) = r.to[it];
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+            int row, cpp;
+            tile_rows(it, row, cpp);
+            const uint32_t keep = row < L ? 0xffffffffu : 0u;
+            *reinterpret_cast<u32x4*>(T0 + row * LD + cpp * 8) = u32x4{r.tv[it].x & keep, r.tv[it].y & keep, r.tv[it].z & keep, r.tv[it].w & keep};
+            *reinterpret_cast<u32x4*>(T1 + row * LD + cpp * 8) = u32x4{r.to[it].x & keep, r.to[it].y & keep, r.to[it].z & keep, r.to[it].w & keep};
         }
     };
+    // ---- q, k, g and the first value slice: every load issued before the first wait
     SliceRegs sr0;
-    load_tile(Qr, q, tok0, ts, L, tid);
-    load_tile(Kr, k, tok0, ts, L, tid);
-    issue(0, sr0);
-    decay_tile(bt, g, tok0, ts, L, tid);
+    {
+        u32x4 tq[2], tk[2];
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        f32x4 tg[2][2];
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+            int row, cpp;
+            tile_rows(it, row, cpp);
+            const size_t roff = (tok0 + size_t(min(row, L - 1)) * ts) * D + cpp * 8;
+            tq[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + roff));
+            tk[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k + roff));
+            tg[it][0] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + roff));
+            tg[it][1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + roff + 4));
+        }
+        issue(0, sr0);
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+            int row, cpp;
+            tile_rows(it, row, cpp);
+            const uint32_t keep = row < L ? 0xffffffffu : 0u;
+            const float kf = row < L ? 1.f : 0.f;
+            *reinterpret_cast<u32x4*>(Qr + row * LD + cpp * 8) = u32x4{tq[it].x & keep, tq[it].y & keep, tq[it].z & keep, tq[it].w & keep};
+            *reinterpret_cast<u32x4*>(Kr + row * LD + cpp * 8) = u32x4{tk[it].x & keep, tk[it].y & keep, tk[it].z & keep, tk[it].w & keep};
+            *reinterpret_cast<float4*>(bt + row * LDF + cpp * 8) = float4{tg[it][0].x * kf, tg[it][0].y * kf, tg[it][0].z * kf, tg[it][0].w * kf};
+            *reinterpret_cast<float4*>(bt + row * LDF + cpp * 8 + 4) = float4{tg[it][1].x * kf, tg[it][1].y * kf, tg[it][1].z * kf, tg[it][1].w * kf};
+        }
+    }
+    __syncthreads();
+    {   // inclusive scan of g along tokens: one feature column per thread, four quarters of 16 tokens
+        const int i = tid & 127, hq = tid >> 7;
+        float run = 0.f;
+        for (int r = 16 * hq; r < 16 * hq + 16; ++r) {
+            run += bt[r * LDF + i];
+            bt[r * LDF + i] = run;
+        }
+        __syncthreads();
+        float base = 0.f;
+        for (int qq = 0; qq < hq; ++qq) base += bt[(16 * qq + 15) * LDF + i];
+        __syncthreads();
+        if (hq > 0)
+            for (int r = 16 * hq; r < 16 * hq + 16; ++r) bt[r * LDF + i] += base;
+    }
+    __syncthreads();
 
     // ---- inter parts and Z, slice by slice of the value dimension
     // aqr, akr: contributions of the remainder planes of S and dS; they enter the decay gradient only, so
     // that dq and dk do not depend on whether it is asked for
-    f32x16 aq[2] = {{0}, {0}}, aqr[2] = {{0}, {0}}, ak[2] = {{0}, {0}}, akr[2] = {{0}, {0}};
+    f32x16 aq = {0}, aqr = {0}, ak = {0}, akr = {0};
     f32x16 z0 = {0}, z1 = {0};
     float zi = 0.f;
     for (int vh = 0; vh < nvh; ++vh) {
@@ -450,42 +500,41 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
         }
         commit(sr0);
         __syncthreads();
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 dof = frag(T1, LD, 32 * nb + n, 16 * ks + 8 * half), vf = frag(T0, LD, 32 * nb + n, 16 * ks + 8 * half);
-                aq[nb] = mfma(sr0.s[ks], dof, aq[nb]);
-                ak[nb] = mfma(sr0.ds[ks], vf, ak[nb]);
-                if (want_dg) {
-                    aqr[nb] = mfma(rem8_to_bf16(sr0.sr[ks]), dof, aqr[nb]);
-                    akr[nb] = mfma(rem8_to_bf16(sr0.dsr[ks]), vf, akr[nb]);
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 sf = sr0.s[ks], dsf = sr0.ds[ks];
+            const bf16x8 dof = frag(T1, LD, t, 16 * ks + 8 * half), vf = frag(T0, LD, t, 16 * ks + 8 * half);
+            aq = mfma(sf, dof, aq);
+            ak = mfma(dsf, vf, ak);
+            if (want_dg) {
+                const bf16x8 srf = rem8_to_bf16(sr0.sr[ks]), dsrf = rem8_to_bf16(sr0.dsr[ks]);
+                aqr = mfma(srf, dof, aqr);
+                akr = mfma(dsrf, vf, akr);
+                if (nb == 0) {  // <S, dS> over this lane's share of row i = 32 wave + n
+                    const u32x4 a = __builtin_bit_cast(u32x4, sf), ar = __builtin_bit_cast(u32x4, srf);
+                    const u32x4 b = __builtin_bit_cast(u32x4, dsf), br = __builtin_bit_cast(u32x4, dsrf);
+                    _Pragma("unroll") for (int p = 0; p < 4; ++p)
+                        zi += (bf16_lo(a[p]) + kRem8Unscale * bf16_lo(ar[p])) * (bf16_lo(b[p]) + kRem8Unscale * bf16_lo(br[p])) +
+                              (bf16_hi(a[p]) + kRem8Unscale * bf16_hi(ar[p])) * (bf16_hi(b[p]) + kRem8Unscale * bf16_hi(br[p]));
                 }
             }
-        if (want_dg) {  // <S, dS> over this lane's share of row i = 32 wave + n
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                const u32x4 a = __builtin_bit_cast(u32x4, sr0.s[ks]), ar = __builtin_bit_cast(u32x4, rem8_to_bf16(sr0.sr[ks]));
-                const u32x4 b = __builtin_bit_cast(u32x4, sr0.ds[ks]), br = __builtin_bit_cast(u32x4, rem8_to_bf16(sr0.dsr[ks]));
-                _Pragma("unroll") for (int p = 0; p < 4; ++p)
-                    zi += (bf16_lo(a[p]) + kRem8Unscale * bf16_lo(ar[p])) * (bf16_lo(b[p]) + kRem8Unscale * bf16_lo(br[p])) +
-                          (bf16_hi(a[p]) + kRem8Unscale * bf16_hi(ar[p])) * (bf16_hi(b[p]) + kRem8Unscale * bf16_hi(br[p]));
-            }
         }
-        {   // this wave's block of Z: rows of V and d_o as operands
-            const int rowv = wave == 1 ? 32 + n : n;               // V row: wave 0, 2, 3: 0.., wave 1: 32..
-            const int rowo = wave == 0 ? n : 32 + n;               // d_o row: wave 0: 0.., else 32..
+        if (wv < 4) {  // this wave's block of Z: rows of V and d_o as operands
+            const int rowv = wv == 1 ? 32 + n : n;               // V row: wave 0, 2, 3: 0.., wave 1: 32..
+            const int rowo = wv == 0 ? n : 32 + n;               // d_o row: wave 0: 0.., else 32..
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
                 const bf16x8 fv = frag(T0, LD, rowv, 16 * ks + 8 * half), fo = frag(T1, LD, rowo, 16 * ks + 8 * half);
-                if (wave == 3) z0 = mfma(fo, fv, z0);              // D[m][n] = d_o_{32+m} . v_n
-                else z0 = mfma(fv, fo, z0);                        // D[m][n] = v_m . d_o_n
-                if (wave < 2) z1 = mfma(fo, fv, z1);               // D[m][n] = d_o_m . v_n
+                if (wv == 3) z0 = mfma(fo, fv, z0);              // D[m][n] = d_o_{32+m} . v_n
+                else z0 = mfma(fv, fo, z0);                      // D[m][n] = v_m . d_o_n
+                if (wv < 2) z1 = mfma(fo, fv, z1);               // D[m][n] = d_o_m . v_n
             }
         }
     }
-    {   // Z[u][t] -> LDS rows t, head and remainder; diagonal of dA
-        const int ub = (wave == 1 || wave == 3) ? 1 : 0, tb = (wave == 1 || wave == 2) ? 1 : 0;
-        if (wave < 2) {
+    if (wv < 4) {  // Z[u][t] -> LDS rows t, head and remainder; diagonal of dA
+        const int ub = (wv == 1 || wv == 3) ? 1 : 0, tb = (wv == 1 || wv == 2) ? 1 : 0;
+        if (wv < 2) {
             _Pragma("unroll") for (int x = 0; x < 16; ++x) {
                 const int m = 8 * (x >> 2) + 4 * half + (x & 3);
-                if (m == n) zd[32 * wave + n] = z0[x];
+                if (m == n) zd[32 * wv + n] = z0[x];
                 z0[x] = m <= n ? z0[x] : z1[x];
             }
         }
@@ -493,38 +542,40 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
     }
     // weights of the inter parts; the part of dg that needs dk^{inter}
     f32x16 xk = {0};
-    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        const int t = 32 * nb + n;
-        _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
-            const int col = 32 * wave + 8 * gq + 4 * half;
-            const float4 b4 = *reinterpret_cast<const float4*>(bt + t * LDF + col);
-            const float4 c4 = *reinterpret_cast<const float4*>(bt + 63 * LDF + col);
-            const float bb[4] = {b4.x, b4.y, b4.z, b4.w}, cc[4] = {c4.x, c4.y, c4.z, c4.w};
-            const u32x2 kk = *reinterpret_cast<const u32x2*>(Kr + t * LD + col);
-            const float kf[4] = {bf16_lo(kk.x), bf16_hi(kk.x), bf16_lo(kk.y), bf16_hi(kk.y)};
-            _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
-                const int x = 4 * gq + jj;
-                const float wq = __expf(bb[jj]), wk = __expf(cc[jj] - bb[jj]);
-                aq[nb][x] *= wq;
-                aqr[nb][x] *= wq * kRem8Unscale;
-                ak[nb][x] *= wk;
-                akr[nb][x] *= wk * kRem8Unscale;
-                xk[x] += kf[jj] * (ak[nb][x] + akr[nb][x]);
-            }
+    _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
+        const int col = 32 * wave + 8 * gq + 4 * half;
+        const float4 b4 = *reinterpret_cast<const float4*>(bt + t * LDF + col);
+        const float4 c4 = *reinterpret_cast<const float4*>(bt + 63 * LDF + col);
+        const float bb[4] = {b4.x, b4.y, b4.z, b4.w}, cc[4] = {c4.x, c4.y, c4.z, c4.w};
+        const u32x2 kk = *reinterpret_cast<const u32x2*>(Kr + t * LD + col);
+        const float kf[4] = {bf16_lo(kk.x), bf16_hi(kk.x), bf16_lo(kk.y), bf16_hi(kk.y)};
+        _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
+            const int x = 4 * gq + jj;
+            const float wq = __expf(bb[jj]), wk = __expf(cc[jj] - bb[jj]);
+            aq[x] *= wq;
+            aqr[x] *= wq * kRem8Unscale;
+            ak[x] *= wk;
+            akr[x] *= wk * kRem8Unscale;
+            xk[x] = kf[jj] * (ak[x] + akr[x]);
         }
     }
-    if (want_dg) {
+    if (want_dg && nb == 0) {
         zi += __shfl_xor(zi, 32, 64);
         if (half == 0) zl[32 * wave + n] = zi;
     }
 
-    // ---- levels
-    const int cp = tid & 15, r0 = tid >> 4;
-    _Pragma("unroll") for (int lv = 0; lv < 6; ++lv) {
+    // ---- levels.  The level tiles are double-buffered, and the two waves of a SIMD (same features,
+    // token blocks 0 and 1) take the two halves of an iteration in opposite order: while one builds
+    // the tile of the next level (exponentials on the vector ALU) the other contracts the current one
+    // (LDS reads, MFMA), instead of both queueing for the same unit.
+    const int cp = tid & 15, r0 = tid >> 4;  // W rows r0 and r0 + 32, features 8 cp .. + 7
+    auto Wh = [&](int lv) { return (lv & 1) ? W1 : T0; };
+    auto Wl = [&](int lv) { return (lv & 1) ? W1 + C * LD : T1; };
+    auto build = [&](int lv) {
         const int ls = 5 - lv;
-        __syncthreads();  // lv = 0: Z complete, V / d_o slices consumed; else: the previous level's tiles are read
-        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-            const int row = r0 + 16 * it;
+        uint16_t *wh = Wh(lv), *wl = Wl(lv);
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+            const int row = r0 + 32 * it;
             bool qside;
             const int ref = level_ref(row, ls, qside);
             float b[8], br[8], w[8];
@@ -534,52 +585,64 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
             const u32x4 raw = *reinterpret_cast<const u32x4*>((qside ? Qr : Kr) + row * LD + cp * 8);
             u32x4 hi, lo;
             weigh8(raw, w, hi, &lo);
-            *reinterpret_cast<u32x4*>(T0 + row * LD + cp * 8) = hi;
-            *reinterpret_cast<u32x4*>(T1 + row * LD + cp * 8) = lo;
+            *reinterpret_cast<u32x4*>(wh + row * LD + cp * 8) = hi;
+            *reinterpret_cast<u32x4*>(wl + row * LD + cp * 8) = lo;
         }
-        __syncthreads();
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            const int t = 32 * nb + n;
-            const int ub = ls == 5 ? 1 - nb : nb;  // the partners of level 32 sit in the other 32-block
-            f32x16 X = {0};
-            _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
-                const int u0 = 32 * ub + 16 * s2;
-                const int xr = (u0 + 8 * half) ^ t;
-                u32x4 mask;
-                _Pragma("unroll") for (int p = 0; p < 4; ++p)
-                    mask[p] = ((((xr ^ (2 * p)) >> ls) == 1) ? 0xffffu : 0u) | ((((xr ^ (2 * p + 1)) >> ls) == 1) ? 0xffff0000u : 0u);
-                u32x4 zh = *reinterpret_cast<const u32x4*>(Zh + t * LDP + u0 + 8 * half);
-                u32x4 zlo = *reinterpret_cast<const u32x4*>(Zl + t * LDP + u0 + 8 * half);
-                _Pragma("unroll") for (int p = 0; p < 4; ++p) {
-                    zh[p] &= mask[p];
-                    zlo[p] &= mask[p];
-                }
-                const bf16x8 bzh = __builtin_bit_cast(bf16x8, zh), bzl = __builtin_bit_cast(bf16x8, zlo);
-                const bf16x8 ah = frag_tr(T0, LD, u0, 32 * wave, lane), al = frag_tr(T1, LD, u0, 32 * wave, lane);
-                X = mfma(ah, bzh, X);
-                X = mfma(ah, bzl, X);
-                X = mfma(al, bzh, X);
+    };
+    auto contract = [&](int lv) {
+        const int ls = 5 - lv;
+        const uint16_t *wh = Wh(lv), *wl = Wl(lv);
+        const int ub = ls == 5 ? 1 - nb : nb;  // the partners of level 32 sit in the other 32-block
+        f32x16 X = {0};
+        _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {
+            const int u0 = 32 * ub + 16 * s2;
+            const int xr = (u0 + 8 * half) ^ t;
+            u32x4 mask;
+            _Pragma("unroll") for (int p = 0; p < 4; ++p)
+                mask[p] = ((((xr ^ (2 * p)) >> ls) == 1) ? 0xffffu : 0u) | ((((xr ^ (2 * p + 1)) >> ls) == 1) ? 0xffff0000u : 0u);
+            u32x4 zh = *reinterpret_cast<const u32x4*>(Zh + t * LDP + u0 + 8 * half);
+            u32x4 zlo = *reinterpret_cast<const u32x4*>(Zl + t * LDP + u0 + 8 * half);
+            _Pragma("unroll") for (int p = 0; p < 4; ++p) {
+                zh[p] &= mask[p];
+                zlo[p] &= mask[p];
             }
-            bool qside;
-            const int ref = level_ref(t, ls, qside);
-            _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
-                const int col = 32 * wave + 8 * gq + 4 * half;
-                const float4 b4 = *reinterpret_cast<const float4*>(bt + t * LDF + col);
-                const float4 r4 = *reinterpret_cast<const float4*>(bt + ref * LDF + col);
-                const float bb[4] = {b4.x, b4.y, b4.z, b4.w}, rr[4] = {r4.x, r4.y, r4.z, r4.w};
-                _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
-                    const int x = 4 * gq + jj;
-                    const float val = X[x] * __expf(qside ? bb[jj] - rr[jj] : rr[jj] - bb[jj]);
-                    aq[nb][x] += qside ? val : 0.f;
-                    ak[nb][x] += qside ? 0.f : val;
-                }
+            const bf16x8 bzh = __builtin_bit_cast(bf16x8, zh), bzl = __builtin_bit_cast(bf16x8, zlo);
+            const bf16x8 ah = frag_tr(wh, LD, u0, 32 * wave, lane), al = frag_tr(wl, LD, u0, 32 * wave, lane);
+            X = mfma(ah, bzh, X);
+            X = mfma(ah, bzl, X);
+            X = mfma(al, bzh, X);
+        }
+        bool qside;
+        const int ref = level_ref(t, ls, qside);
+        _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
+            const int col = 32 * wave + 8 * gq + 4 * half;
+            const float4 b4 = *reinterpret_cast<const float4*>(bt + t * LDF + col);
+            const float4 r4 = *reinterpret_cast<const float4*>(bt + ref * LDF + col);
+            const float bb[4] = {b4.x, b4.y, b4.z, b4.w}, rr[4] = {r4.x, r4.y, r4.z, r4.w};
+            _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
+                const int x = 4 * gq + jj;
+                const float val = X[x] * __expf(qside ? bb[jj] - rr[jj] : rr[jj] - bb[jj]);
+                aq[x] += qside ? val : 0.f;
+                ak[x] += qside ? 0.f : val;
             }
         }
+    };
+    __syncthreads();  // Z complete, V / d_o slices consumed
+    build(0);
+    __syncthreads();
+    _Pragma("unroll") for (int lv = 0; lv < 6; ++lv) {
+        if (nb == 0) {
+            if (lv < 5) build(lv + 1);
+            contract(lv);
+        } else {
+            contract(lv);
+            if (lv < 5) build(lv + 1);
+        }
+        __syncthreads();  // the next tile is complete, this one is free again
     }
     // ---- diagonal pairs, then the decay gradient from the unrounded accumulators
-    f32x16 wd[2];
-    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        const int t = 32 * nb + n;
+    f32x16 wd;
+    {
         const float dd = zd[t];
         _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
             const int col = 32 * wave + 8 * gq + 4 * half;
@@ -589,56 +652,70 @@ __global__ __launch_bounds__(kThreads, 1) void mk_grad_vec(Dims d, const uint16_
             const float kf[4] = {bf16_lo(kk.x), bf16_hi(kk.x), bf16_lo(kk.y), bf16_hi(kk.y)};
             _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
                 const int x = 4 * gq + jj;
-                aq[nb][x] += dd * kf[jj];
-                ak[nb][x] += dd * qf[jj];
-                wd[nb][x] = qf[jj] * (aq[nb][x] + aqr[nb][x]) - kf[jj] * (ak[nb][x] + akr[nb][x]);
+                aq[x] += dd * kf[jj];
+                ak[x] += dd * qf[jj];
+                wd[x] = qf[jj] * (aq[x] + aqr[x]) - kf[jj] * (ak[x] + akr[x]);
             }
         }
     }
-    __syncthreads();  // every wave is done with the level tiles and with b as weights
-    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        store_packed(T0, LD, 32 * nb + n, 32 * wave, half, pack_block(aq[nb]));
-        store_packed(T1, LD, 32 * nb + n, 32 * wave, half, pack_block(ak[nb]));
-    }
+    // (the barrier that ends the level loop: every wave is done with the level tiles)
+    store_packed(T0, LD, t, 32 * wave, half, pack_block(aq));
+    store_packed(T1, LD, t, 32 * wave, half, pack_block(ak));
     if (want_dg) {
-        // per feature (register): inclusive suffix sum over the tokens (lanes of one half), block 1 first
-        _Pragma("unroll") for (int nb = 1; nb >= 0; --nb) {
-            _Pragma("unroll") for (int off = 1; off < 32; off <<= 1) {
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-                    const float y = __shfl_down(wd[nb][x], off, 32);
-                    wd[nb][x] += (n + off < 32) ? y : 0.f;
-                }
-            }
-            if (nb == 1) {
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-                    const float total = __shfl(wd[1][x], 0, 32);  // all lanes take part in the exchange
-                    wd[0][x] += (n == 31) ? total : 0.f;
-                }
+        // per feature (register): inclusive suffix sum over this wave's 32 tokens (lanes of one half), the
+        // sum of this wave's tail terms; both go to the other token block through LDS
+        _Pragma("unroll") for (int off = 1; off < 32; off <<= 1) {
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                const float y = __shfl_down(wd[x], off, 32);
+                wd[x] += (n + off < 32) ? y : 0.f;
             }
         }
         _Pragma("unroll") for (int off = 1; off < 32; off <<= 1) {
             _Pragma("unroll") for (int x = 0; x < 16; ++x) xk[x] += __shfl_xor(xk[x], off, 32);
         }
+        if (n == 0) {
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                const int f = 8 * (x >> 2) + 4 * half + (x & 3);
+                if (nb == 1) xch[(0 * 4 + wave) * 32 + f] = wd[x];   // total of token block 1
+                xch[((1 + nb) * 4 + wave) * 32 + f] = xk[x];           // tail sum of this block
+            }
+        }
+    }
+    __syncthreads();  // stages and exchange complete; b no longer needed as weights
+    {
+        int row, cpp;
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {
+            tile_rows(it, row, cpp);
+            if (row < L) {
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(T0 + row * LD + cpp * 8),
+                                            reinterpret_cast<u32x4*>(dq + (tok0 + size_t(row) * ts) * D + cpp * 8));
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(T1 + row * LD + cpp * 8),
+                                            reinterpret_cast<u32x4*>(dk + (tok0 + size_t(row) * ts) * D + cpp * 8));
+            }
+        }
+    }
+    if (want_dg) {
+        float add[16];
         _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {
             const int col = 32 * wave + 8 * gq + 4 * half;
             const float4 c4 = *reinterpret_cast<const float4*>(bt + 63 * LDF + col);
             const float4 z4 = *reinterpret_cast<const float4*>(zl + col);
             const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, zz[4] = {z4.x, z4.y, z4.z, z4.w};
-            _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) xk[4 * gq + jj] += __expf(cc[jj]) * zz[jj];
+            _Pragma("unroll") for (int jj = 0; jj < 4; ++jj) {
+                const int x = 4 * gq + jj, f = 8 * gq + 4 * half + jj;
+                // tail over all 64 tokens (block 0 first), the state term, and for block 0 the running sum of block 1
+                add[x] = (xch[(1 * 4 + wave) * 32 + f] + xch[(2 * 4 + wave) * 32 + f]) + __expf(cc[jj]) * zz[jj] +
+                         (nb == 0 ? xch[(0 * 4 + wave) * 32 + f] : 0.f);
+            }
         }
-    }
-    __syncthreads();  // stages complete; b no longer needed
-    store_tile(dq, T0, tok0, ts, L, tid);
-    store_tile(dk, T1, tok0, ts, L, tid);
-    if (want_dg) {
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-            _Pragma("unroll") for (int gq = 0; gq < 4; ++gq)
-                *reinterpret_cast<float4*>(bt + (32 * nb + n) * LDF + 32 * wave + 8 * gq + 4 * half) =
-                    float4{wd[nb][4 * gq] + xk[4 * gq], wd[nb][4 * gq + 1] + xk[4 * gq + 1],
-                           wd[nb][4 * gq + 2] + xk[4 * gq + 2], wd[nb][4 * gq + 3] + xk[4 * gq + 3]};
+        __syncthreads();  // every wave has read b and the exchange area: b becomes the dg stage
+        _Pragma("unroll") for (int gq = 0; gq < 4; ++gq)
+            *reinterpret_cast<float4*>(bt + t * LDF + 32 * wave + 8 * gq + 4 * half) =
+                float4{wd[4 * gq] + add[4 * gq], wd[4 * gq + 1] + add[4 * gq + 1], wd[4 * gq + 2] + add[4 * gq + 2],
+                       wd[4 * gq + 3] + add[4 * gq + 3]};
         __syncthreads();
-        _Pragma("unroll") for (int it = 0; it < 8; ++it) {
-            const int p = tid + kThreads * it, row = p >> 5, c4 = p & 31;
+        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+            const int p = tid + NT * it, row = p >> 5, c4 = p & 31;
             if (row < L)
                 *reinterpret_cast<float4*>(dg + (tok0 + size_t(row) * ts) * D + 4 * c4) = *reinterpret_cast<const float4*>(bt + row * LDF + 4 * c4);
         }
