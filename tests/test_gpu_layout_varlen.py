@@ -135,3 +135,37 @@ def test_packed_sequences_against_oracle(kind):
         check(n, host(r[n]), cat_t(n), "bf16")
     check("dg", host(r["dg"]), cat_t("dg"), "bf16")
     check("d_init_state", host(r["d_init_state"]), np.concatenate(ref["d_m0"], axis=0), "bf16")
+
+
+@pytest.mark.parametrize("case", [("bf16", wl.KIND_SCALAR, 128, 128), ("bf16", wl.KIND_VECTOR, 128, 256), ("f32", wl.KIND_SCALAR, 64, 64)])
+def test_packed_input_with_an_empty_sequence(case):
+    """A sequence of length zero passes its initial state (and the gradient of its final state) through."""
+    import torch
+    import paper_2503_05447_amd as pkg
+    dtype, kind, dk, dv = case
+    lens = [70, 0, 33]
+    T, H, n = sum(lens), 2, len(lens)
+    x = wl.make_inputs(1, H, T, dk, dv, kind, dtype=dtype, seed=970, decay="weak")
+    rng = np.random.default_rng(971)
+    x["m0"] = (rng.standard_normal((n, H, dk, dv)) * 0.1).astype(np.float32)
+    x["d_mT"] = (rng.standard_normal((n, H, dk, dv)) * 0.1).astype(np.float32)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    t = to_device(x)
+    cu_d = torch.from_numpy(cu).to(t["q"].device)
+    o, mT = pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"], t["g"], kind, 64, t["m0"], cu_seqlens=cu_d)
+    r = pkg.lsm_chunk_bwd(t["q"], t["k"], t["v"], t["g"], kind, t["d_o"], 64, t["m0"], t["d_mT"], cu_seqlens=cu_d)
+    torch.cuda.synchronize()
+    assert torch.equal(mT[1], t["m0"][1]) and torch.equal(r["d_init_state"][1], t["d_mT"][1])
+    for s_, (lo, hi) in enumerate(zip(cu[:-1], cu[1:])):
+        if hi == lo:
+            continue
+        m0s, dms = t["m0"][s_:s_ + 1].contiguous(), t["d_mT"][s_:s_ + 1].contiguous()
+        o_s, mT_s = pkg.lsm_chunk_fwd(piece(t["q"], lo, hi), piece(t["k"], lo, hi), piece(t["v"], lo, hi), piece(t["g"], lo, hi),
+                                      kind, 64, m0s)
+        r_s = pkg.lsm_chunk_bwd(piece(t["q"], lo, hi), piece(t["k"], lo, hi), piece(t["v"], lo, hi), piece(t["g"], lo, hi), kind,
+                                piece(t["d_o"], lo, hi), 64, m0s, dms)
+        torch.cuda.synchronize()
+        assert torch.equal(o[:, :, lo:hi], o_s) and torch.equal(mT[s_:s_ + 1], mT_s)
+        for key in ("dq", "dk", "dv", "dg"):
+            assert torch.equal(r[key][:, :, lo:hi], r_s[key]), key
+        assert torch.equal(r["d_init_state"][s_:s_ + 1], r_s["d_init_state"])
