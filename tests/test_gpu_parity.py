@@ -20,6 +20,7 @@ SHAPES = [
     (1, 2, 100, 64, 64, 16),      # chunk 16
     (1, 1, 96, 256, 64, 32),      # chunk 32, d_k = 256, exact multiple
     (1, 2, 150, 128, 256, 64),    # two 128-wide value slices (vector kind: matrix-core path), tail of 22
+    (3, 3, 100, 128, 128, 64),    # B*H = 9: not a multiple of the 8 XCDs (tail of the workgroup-id decoding)
 ]
 
 
