@@ -40,13 +40,17 @@ def algorithmic_flops_per_token_head(cfg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--layout", type=int, default=0, choices=(0, 1),
                     help="0: [B,H,T,d] as BASELINE.json's configurations are written; 1: the same data token-major [B,T,H,d]")
+    ap.add_argument("--states", choices=("recompute", "saved"), default="saved",
+                    help="chunk states of the backward pass: kept by the forward call in the shared workspace (where "
+                         "the library finds that faster), or computed again from the inputs; the other mode is timed "
+                         "too and reported beside the headline")
     ap.add_argument("--no-microbench", action="store_true",
                     help="skip the LDS-resident intra-chunk micro-benchmark (profiling runs: it launches the output kernel again)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -75,18 +79,24 @@ def main():
     g, m0 = mv(x["g"], torch.float32), mv(x["m0"], torch.float32)
     kind, C = cfg["kind"], cfg["chunk"]
     B, H, T, dk, dv = cfg["B"], cfg["H"], cfg["T"], cfg["dk"], cfg["dv"]
-    p = pkg.make_params(B, H, T, dk, dv, C, kind, 1 if cfg["dtype"] == "bf16" else 0)
-    ws = torch.empty(max(pkg.lsm_chunk_fwd_workspace_bytes(p), pkg.lsm_chunk_bwd_workspace_bytes(p), 256),
-                     dtype=torch.uint8, device=dev)
+    saved = args.states == "saved"
+    p = pkg.make_params(B, H, T, dk, dv, C, kind, 1 if cfg["dtype"] == "bf16" else 0,
+                        flags=pkg.FLAG_SAVE_STATES if saved else 0)
+    p_keep = pkg.make_params(B, H, T, dk, dv, C, kind, 1 if cfg["dtype"] == "bf16" else 0, flags=pkg.FLAG_SAVE_STATES)
+    ws = torch.empty(max(pkg.lsm_chunk_fwd_workspace_bytes(p), pkg.lsm_chunk_bwd_workspace_bytes(p),
+                         pkg.lsm_chunk_fwd_workspace_bytes(p_keep), 256), dtype=torch.uint8, device=dev)
+    # what the library does with the request (it recomputes where keeping the states would be slower)
+    kept = {True: "saved by the forward call", False: "recomputed"}
 
     if args.layout == 1:   # the same values, token-major
         q, k, v, d_o = (t_.transpose(1, 2).contiguous() for t_ in (q, k, v, d_o))
         if kind in (wl.KIND_SCALAR, wl.KIND_VECTOR):
             g = g.transpose(1, 2).contiguous()
 
-    def step():
-        out = pkg.lsm_chunk_fwd(q, k, v, g, kind, C, m0, workspace=ws, layout=args.layout)
-        grads = pkg.lsm_chunk_bwd(q, k, v, g, kind, d_o, C, m0, workspace=ws, layout=args.layout) if backward else None
+    def step(saved=saved):
+        out = pkg.lsm_chunk_fwd(q, k, v, g, kind, C, m0, workspace=ws, layout=args.layout, save_states=saved)
+        grads = pkg.lsm_chunk_bwd(q, k, v, g, kind, d_o, C, m0, workspace=ws, layout=args.layout,
+                                  states_saved=saved) if backward else None
         return out, grads
 
     if args.copy_calibration:
@@ -100,14 +110,22 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    pkg.lsm_profile_start()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         last = step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = pkg.lsm_profile_stop()
     sec = (t1 - t0) / args.steps
+    # Per-kernel durations: the same K steps once more with a pair of HIP events around every launch, on
+    # the launch stream.  The events keep consecutive kernels from overlapping and cost several percent of
+    # a step, so this pass is timed on its own (ms_per_step_with_events) and not reported as the throughput.
+    pkg.lsm_profile_start()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec_events = (time.perf_counter() - t2) / args.steps
+    prof = pkg.lsm_profile_stop()
     tokens = B * T
     th = B * H * T
 
@@ -139,14 +157,27 @@ def main():
         "config": {"workload": cfg["name"], "B": B, "H": H, "T": T, "d_k": dk, "d_v": dv, "chunk": C,
                    "decay_kind": wl.KIND_NAMES[kind], "passes": "fwd+bwd" if backward else "fwd",
                    "kernel_path": "mfma" if pkg.kernel_path(p) == 1 else "generic",
-                   "layout": "BTHD" if args.layout else "BHTD"},
+                   "layout": "BTHD" if args.layout else "BHTD", "bwd_states": kept[pkg.keeps_states(p) == 1]},
         "tflops": tflops, "mfma_peak_frac": tflops / MFMA_BF16_PEAK_TFLOPS,
         "hbm_frac_whole_step": algorithmic_bytes_per_token_head(cfg, "both" if backward else "fwd") * th / sec / 1e9 / HBM_PEAK_GBS,
-        "kernel_ms": kavg,
+        "kernel_ms": kavg, "ms_per_step_with_events": sec_events * 1e3,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": abytes},
     }
+
+    if backward and not args.no_microbench:   # the same steps with the other treatment of the chunk states
+        for _ in range(args.warmup):
+            step(not saved)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(not saved)
+        torch.cuda.synchronize()
+        sec2 = (time.perf_counter() - t0) / args.steps
+        other = kept[False] if saved else kept[pkg.keeps_states(p_keep) == 1]
+        result["other_bwd_states"] = {"bwd_states": other, "ms_per_step": sec2 * 1e3, "value": tokens / sec2,
+                                      "unit": "tokens/s"}
 
     if pkg.kernel_path(p) == 1 and kind != wl.KIND_VECTOR and not args.no_microbench and args.layout == 0:
         # Intra-chunk phase apart from HBM: the forward per-chunk kernel with its compute phase repeated on

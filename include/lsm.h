@@ -67,6 +67,25 @@ typedef enum {
     LSM_LAYOUT_BTHD = 1  /* [B,T,H,d]: token-major, as a fused QKV projection leaves it (decay [B,T,H])    */
 } lsm_layout;
 
+/*
+ * lsm_params.flags.
+ * LSM_FLAG_SAVE_STATES: the chunk states that the forward call computes anyway are kept for the
+ * backward call instead of being computed again there (the usual trade of memory for recomputation
+ * in training).  Set it in the params of BOTH calls.  Contract: the two calls get the same params,
+ * the same q, k, v, log_decay and init_state, and the same workspace buffer, of at least
+ * lsm_chunk_fwd_workspace_bytes(p) (with the flag set, both size queries return one figure that
+ * covers both calls), and nothing else writes to that buffer between them; lsm_chunk_bwd then reads
+ * what lsm_chunk_fwd left there and is wrong if the buffer was touched.  The flag is a permission:
+ * shapes served by kernels that keep nothing recompute as usual, and so do the scalar decay kinds
+ * when there are fewer than 40 independent recurrences (B*H, or n_seq*H): the two scans of the
+ * recomputing backward pass then hide each other's latency, which is worth more than the saved
+ * work.  Both calls take the decision from the params alone, so they always agree.
+ * LSM_FLAG_SAVE_ALWAYS (only together with LSM_FLAG_SAVE_STATES) switches that size rule off.
+ * Results agree with those of the recomputing path to rounding (the states are accumulated in a
+ * different operand order), not bit for bit.
+ */
+typedef enum { LSM_FLAG_SAVE_STATES = 1, LSM_FLAG_SAVE_ALWAYS = 2 } lsm_flags;
+
 typedef struct {
     uint32_t struct_size; /* = sizeof(lsm_params) */
     int32_t  B, H, T;     /* batch, heads, tokens per sequence (any T >= 1; the last chunk may be ragged) */
@@ -85,6 +104,7 @@ typedef struct {
      * their gradients are then [n_seq,H,d_k,d_v].  The result equals n_seq separate calls.
      */
     int32_t  n_seq;
+    int32_t  flags;       /* bitwise OR of lsm_flags; 0 = none                                   */
     const int32_t* cu_seqlens;
 } lsm_params;
 
@@ -111,7 +131,8 @@ int lsm_chunk_fwd(const lsm_params* p,
  * Backward of  L = <o, d_o> + <M_T, d_final_state>  (the paper states no
  * backward; it is the adjoint of the forward above, evaluated chunkwise with a
  * reverse scan over chunk-state gradients).  Chunk states are recomputed from
- * the inputs; nothing saved by the forward call is needed.
+ * the inputs; nothing saved by the forward call is needed (unless
+ * LSM_FLAG_SAVE_STATES is set, see lsm_flags).
  *   q,k,v,log_decay,init_state   as in the forward                         in
  *   d_o            [B,H,T,d_v] dtype                                       in
  *   d_final_state  NULL (= zeros) or [B,H,d_k,d_v] fp32                    in
@@ -179,10 +200,14 @@ int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, con
                           const float* log_decay, void* o, void* workspace, size_t workspace_bytes,
                           int repeats, void* stream);
 
+/* 1 if, for these params, lsm_chunk_fwd keeps its chunk states for lsm_chunk_bwd (see lsm_flags), 0 if the
+ * backward call recomputes them, a negative lsm_status for invalid params. */
+int lsm_keeps_states(const lsm_params* p);
+
 /* Static, NUL-terminated description of a status code. */
 const char* lsm_status_string(int status);
 
-/* ABI version, bumped when a signature or struct changes (2: layout and packed input in lsm_params). */
+/* ABI version, bumped when a signature or struct changes (2: layout and packed input in lsm_params; 3: flags). */
 int lsm_version(void);
 
 #ifdef __cplusplus

@@ -13,6 +13,7 @@ from . import build as _build
 DECAY_NONE, DECAY_HEAD, DECAY_SCALAR, DECAY_VECTOR = 0, 1, 2, 3
 DTYPE_F32, DTYPE_BF16 = 0, 1
 LAYOUT_BHTD, LAYOUT_BTHD = 0, 1
+FLAG_SAVE_STATES, FLAG_SAVE_ALWAYS = 1, 2
 
 
 class LsmError(RuntimeError):
@@ -25,7 +26,8 @@ class _Params(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("B", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("T", ctypes.c_int32), ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32),
                 ("chunk_size", ctypes.c_int32), ("decay_kind", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("layout", ctypes.c_int32), ("n_seq", ctypes.c_int32), ("cu_seqlens", ctypes.c_void_p)]
+                ("layout", ctypes.c_int32), ("n_seq", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("cu_seqlens", ctypes.c_void_p)]
 
 
 _lib = None
@@ -59,6 +61,8 @@ def library():
     lib.lsm_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
     lib.lsm_kernel_name.restype = ctypes.c_char_p
     lib.lsm_kernel_name.argtypes = [ctypes.c_int]
+    lib.lsm_keeps_states.restype = ctypes.c_int
+    lib.lsm_keeps_states.argtypes = [pp]
     lib.lsm_step.restype = ctypes.c_int
     lib.lsm_step.argtypes = [pp] + [vp] * 7
     lib.lsm_bench_intra_chunk.restype = ctypes.c_int
@@ -71,9 +75,11 @@ def _status_string(status):
     return library().lsm_status_string(int(status)).decode()
 
 
-def make_params(B, H, T, d_k, d_v, chunk_size, decay_kind, dtype, layout=LAYOUT_BHTD, n_seq=0, cu_seqlens=None):
+def make_params(B, H, T, d_k, d_v, chunk_size, decay_kind, dtype, layout=LAYOUT_BHTD, n_seq=0, cu_seqlens=None,
+                flags=0):
     """cu_seqlens: device address (int) of n_seq + 1 int32 sequence starts, or None."""
-    return _Params(ctypes.sizeof(_Params), B, H, T, d_k, d_v, chunk_size, decay_kind, dtype, layout, n_seq, cu_seqlens)
+    return _Params(ctypes.sizeof(_Params), B, H, T, d_k, d_v, chunk_size, decay_kind, dtype, layout, n_seq, flags,
+                   cu_seqlens)
 
 
 def lsm_chunk_fwd_workspace_bytes(params):
@@ -87,6 +93,11 @@ def lsm_chunk_bwd_workspace_bytes(params):
 def kernel_path(params):
     """1 = MFMA kernels, 0 = generic fp32-arithmetic kernels, < 0 = invalid parameters."""
     return int(library().lsm_kernel_path(ctypes.byref(params)))
+
+
+def keeps_states(params):
+    """1 = the forward call keeps its chunk states for the backward call, 0 = the backward call recomputes them."""
+    return int(library().lsm_keeps_states(ctypes.byref(params)))
 
 
 def lsm_profile_start():
@@ -115,7 +126,14 @@ def _check(t, shape, dtype, name):
                          % (name, tuple(shape), dtype, tuple(t.shape), t.dtype, t.device))
 
 
-def _setup(q, k, v, log_decay, decay_kind, chunk_size, layout=LAYOUT_BHTD, cu_seqlens=None):
+def _save_flags(save):
+    """False: none; True: keep the states where the library finds it faster; "always": wherever it can."""
+    if not save:
+        return 0
+    return FLAG_SAVE_STATES | (FLAG_SAVE_ALWAYS if save == "always" else 0)
+
+
+def _setup(q, k, v, log_decay, decay_kind, chunk_size, layout=LAYOUT_BHTD, cu_seqlens=None, flags=0):
     import torch
     if q.dtype == torch.float32:
         dt = DTYPE_F32
@@ -146,7 +164,7 @@ def _setup(q, k, v, log_decay, decay_kind, chunk_size, layout=LAYOUT_BHTD, cu_se
         n_seq = cu_seqlens.numel() - 1
         _check(cu_seqlens, (n_seq + 1,), torch.int32, "cu_seqlens")
         cu_ptr = cu_seqlens.data_ptr()
-    p = make_params(B, H, T, dk, dv, chunk_size, decay_kind, dt, layout, n_seq, cu_ptr)
+    p = make_params(B, H, T, dk, dv, chunk_size, decay_kind, dt, layout, n_seq, cu_ptr, flags)
     return p, (n_seq or B, H, T, dk, dv), gshape
 
 
@@ -156,16 +174,34 @@ def _stream_handle(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def lsm_chunk_workspace(q, k, v, log_decay, decay_kind, chunk_size=64, layout=LAYOUT_BHTD, cu_seqlens=None,
+                        save_states=True):
+    """A workspace tensor large enough for both the forward and the backward call on these inputs."""
+    import torch
+    p, _, _ = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens,
+                     _save_flags(save_states))
+    need = max(lsm_chunk_fwd_workspace_bytes(p), lsm_chunk_bwd_workspace_bytes(p), 256)
+    return torch.empty(need, dtype=torch.uint8, device=q.device)
+
+
 def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None,
-                  want_final_state=True, workspace=None, stream=None, layout=LAYOUT_BHTD, cu_seqlens=None):
+                  want_final_state=True, workspace=None, stream=None, layout=LAYOUT_BHTD, cu_seqlens=None,
+                  save_states=False):
     """o, final_state = chunkwise forward of M_t = diag(a_t) M_{t-1} + k_t^T v_t, o_t = q_t M_t.
+
+    save_states: keep the chunk states in ``workspace`` (required then, see lsm_chunk_workspace) for a
+    following lsm_chunk_bwd(..., workspace=the same tensor, states_saved=<the same value>) on the same
+    inputs.  True leaves the choice to the library (it recomputes where that is faster), "always" does not.
 
     layout: LAYOUT_BHTD ([B,H,T,d]) or LAYOUT_BTHD ([B,T,H,d]).  cu_seqlens (int32 device tensor of
     n_seq + 1 sequence starts, B == 1): packed variable-length input; states are then [n_seq,H,d_k,d_v].
     Enqueues on ``stream`` (default: torch's current stream) and returns without synchronising.
     """
     import torch
-    p, (B, H, T, dk, dv), _ = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens)
+    if save_states and workspace is None:
+        raise ValueError("save_states needs a caller-owned workspace that is passed on to lsm_chunk_bwd")
+    p, (B, H, T, dk, dv), _ = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens,
+                                     _save_flags(save_states))
     _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
     need = lsm_chunk_fwd_workspace_bytes(p)
     if workspace is None:
@@ -222,10 +258,16 @@ def lsm_bench_intra_chunk(q, k, v, log_decay, decay_kind, o, workspace, repeats,
 
 def lsm_chunk_bwd(q, k, v, log_decay, decay_kind, d_o, chunk_size=64, init_state=None, d_final_state=None,
                   want_d_log_decay=True, want_d_init_state=True, workspace=None, stream=None,
-                  layout=LAYOUT_BHTD, cu_seqlens=None):
-    """dict(dq, dk, dv, dg, d_init_state): chunkwise backward of <o, d_o> + <M_T, d_final_state>."""
+                  layout=LAYOUT_BHTD, cu_seqlens=None, states_saved=False):
+    """dict(dq, dk, dv, dg, d_init_state): chunkwise backward of <o, d_o> + <M_T, d_final_state>.
+
+    states_saved: ``workspace`` is the tensor that lsm_chunk_fwd(..., save_states=True) filled for the same
+    inputs and nothing has written to it since; the chunk states are then read from it, not recomputed."""
     import torch
-    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens)
+    if states_saved and workspace is None:
+        raise ValueError("states_saved needs the workspace of the forward call")
+    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens,
+                                          _save_flags(states_saved))
     _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
     _check(d_final_state, (B, H, dk, dv), torch.float32, "d_final_state")
     _check(d_o, tuple(v.shape), q.dtype, "d_o")

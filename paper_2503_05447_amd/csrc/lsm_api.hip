@@ -45,6 +45,8 @@ int check_params(const lsm_params* p, lsm::Dims* d) {
     // index arithmetic inside the kernels is 64-bit, grid dimensions are not
     const long long bh = (long long)p->B * p->H;
     if (p->layout != LSM_LAYOUT_BHTD && p->layout != LSM_LAYOUT_BTHD) return LSM_ERR_UNSUPPORTED;
+    if (p->flags & ~(LSM_FLAG_SAVE_STATES | LSM_FLAG_SAVE_ALWAYS)) return LSM_ERR_UNSUPPORTED;
+    if ((p->flags & LSM_FLAG_SAVE_ALWAYS) && !(p->flags & LSM_FLAG_SAVE_STATES)) return LSM_ERR_UNSUPPORTED;
     if (p->n_seq < 0 || (p->n_seq > 0 && p->B != 1)) return LSM_ERR_SHAPE;
     if ((p->n_seq > 0) != (p->cu_seqlens != nullptr)) return LSM_ERR_NULL;
     if (misaligned(p->cu_seqlens)) return LSM_ERR_ALIGN;
@@ -55,6 +57,12 @@ int check_params(const lsm_params* p, lsm::Dims* d) {
     d->B = p->B; d->H = p->H; d->T = p->T; d->dk = p->d_k; d->dv = p->d_v; d->C = p->chunk_size;
     d->N = int(n); d->kind = p->decay_kind; d->bf16 = p->dtype == LSM_DTYPE_BF16;
     d->layout = p->layout; d->nseq = p->n_seq; d->cu = p->cu_seqlens; d->cstart = nullptr;
+    // Only the matrix-core kernels keep states between the two calls; elsewhere the flag changes nothing.
+    // Scalar kinds with few recurrences: a lone scan leaves most of the chip idle, and the recomputing
+    // backward pass, which runs its two scans side by side, is the faster one (measured: it wins at 32
+    // recurrences, loses at 48).
+    d->save = (p->flags & LSM_FLAG_SAVE_STATES) != 0 && lsm::mfma_supported(*d) &&
+              (d->kind == LSM_DECAY_VECTOR || d->seqs() >= 40 || (p->flags & LSM_FLAG_SAVE_ALWAYS) != 0);
     return LSM_OK;
 }
 
@@ -72,7 +80,7 @@ hipError_t prepare_tables(lsm::Dims& d, void*& workspace, hipStream_t stream) {
 
 extern "C" {
 
-int lsm_version(void) { return 2; }
+int lsm_version(void) { return 3; }
 
 const char* lsm_status_string(int status) {
     switch (status) {
@@ -129,16 +137,35 @@ int lsm_kernel_path(const lsm_params* p) {
     return lsm::mfma_supported(d) ? 1 : 0;
 }
 
+namespace {
+size_t fwd_bytes(const lsm::Dims& d) {
+    return table_bytes(d) + (lsm::mfma_supported(d) ? lsm::mfma_fwd_workspace(d) : lsm::generic_fwd_workspace(d));
+}
+size_t bwd_bytes(const lsm::Dims& d) {
+    return table_bytes(d) + (lsm::mfma_bwd_supported(d) ? lsm::mfma_bwd_workspace(d) : lsm::generic_bwd_workspace(d));
+}
+}  // namespace
+
+// With LSM_FLAG_SAVE_STATES one buffer serves both calls, so both queries return the same figure.
+int lsm_keeps_states(const lsm_params* p) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    return d.save ? 1 : 0;
+}
+
 size_t lsm_chunk_fwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK) return 0;
-    return table_bytes(d) + (lsm::mfma_supported(d) ? lsm::mfma_fwd_workspace(d) : lsm::generic_fwd_workspace(d));
+    if (p->flags & LSM_FLAG_SAVE_STATES) return fwd_bytes(d) > bwd_bytes(d) ? fwd_bytes(d) : bwd_bytes(d);
+    return fwd_bytes(d);
 }
 
 size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK) return 0;
-    return table_bytes(d) + (lsm::mfma_bwd_supported(d) ? lsm::mfma_bwd_workspace(d) : lsm::generic_bwd_workspace(d));
+    if (p->flags & LSM_FLAG_SAVE_STATES) return fwd_bytes(d) > bwd_bytes(d) ? fwd_bytes(d) : bwd_bytes(d);
+    return bwd_bytes(d);
 }
 
 int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,

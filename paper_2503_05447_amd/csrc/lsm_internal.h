@@ -17,6 +17,7 @@ struct Dims {
     int nseq;     // packed variable-length input: number of sequences, else 0
     const int* cu;      // [nseq + 1] first token of each sequence (device memory), cu[nseq] = T
     const int* cstart;  // [nseq + 1] first chunk of each sequence (device memory, written by the library)
+    bool save;    // the forward call leaves its chunk states in the workspace and the backward call reads them
     __host__ __device__ int BH() const { return B * H; }
     __host__ __device__ int dkd() const { return kind == 3 ? dk : 1; }  // decay values per token
     __host__ __device__ int seqs() const { return nseq ? nseq * H : B * H; }  // independent recurrences

@@ -218,7 +218,9 @@ __device__ __forceinline__ void state_store8(uint8_t* dst, const uint8_t* stage,
 // (row stride d_v), each slice being scanned like a sequence of its own.
 //   MODE 3 (VEC only): forward states with the operands of MODE 1, stored S^T [v][i] like MODE 0.
 //   MODE 2 with VEC: states_twin, when given, receives a second copy dS^T [v][i] (for the dv kernel).
-template <int MODE, bool DEC, bool REM, bool VEC>
+//   SAVE (MODE 3 only): the forward scan also leaves what the backward pass needs of it, the states in
+//   the order MODE 1 stores them (S [i][v], into states_twin) and their 8-bit remainder plane (states_rem).
+template <int MODE, bool DEC, bool REM, bool VEC, bool SAVE = false>
 __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& sa, int wg_id, int wg_count,
                                                 unsigned char* smem) {
     const uint16_t* __restrict__ xa = sa.xa;
@@ -319,6 +321,10 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
             if (states_rem) store_block_t_split8(sh, reinterpret_cast<uint8_t*>(sh + 32 * LD), LD, n, 32 * mb, half, acc);
             else store_block_t(sh, LD, n, 32 * mb, half, acc);
         }
+        if (SAVE) {
+            if (states_rem) store_block_t_split8(sh + 32 * LD, reinterpret_cast<uint8_t*>(sh + 64 * LD), LD, n, 32 * mb, half, acc);
+            else store_block_t(sh + 32 * LD, LD, n, 32 * mb, half, acc);
+        }
         if (DEC) {
             const float lam_cur = rw.lam;
             _Pragma("unroll") for (int x = 0; x < 16; ++x) acc[x] *= lam_cur;
@@ -339,6 +345,11 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
             state_store8(reinterpret_cast<uint8_t*>(states_rem) + slot(k), reinterpret_cast<const uint8_t*>(sh + 32 * LD), mb, nb, mb, lane);
         }
         if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
+        if (SAVE) {
+            state_store(states_twin + slot(k), sh + 32 * LD, mb, nb, mb, lane);
+            if (states_rem)
+                state_store8(reinterpret_cast<uint8_t*>(states_rem) + slot(k), reinterpret_cast<const uint8_t*>(sh + 64 * LD), mb, nb, mb, lane);
+        }
     };
     int k = 0;
     for (; k + 2 < cnt; k += 3) {
@@ -359,10 +370,10 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     }
 }
 
-template <int MODE, bool DEC>
+template <int MODE, bool DEC, bool SAVE = false>
 __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, StateArgs sa) {
     extern __shared__ __align__(16) unsigned char smem[];
-    state_scan_body<MODE, DEC, false, false>(d, sa, blockIdx.x, gridDim.x, smem);
+    state_scan_body<MODE, DEC, false, false, SAVE>(d, sa, blockIdx.x, gridDim.x, smem);
 }
 
 // The two scans of the backward pass (states forward in time, state gradients backward in time) are
@@ -760,10 +771,16 @@ __global__ void mk_head_reduce(Dims d, const float* __restrict__ dg_tok, float* 
 }
 
 // the forward state scan of the vector decay kind
-template <int MODE>
+template <int MODE, bool SAVE = false>
 __global__ __launch_bounds__(kThreads) void mk_state_vec(Dims d, StateArgs sa) {
     extern __shared__ __align__(16) unsigned char smem[];
-    state_scan_body<MODE, true, false, true>(d, sa, blockIdx.x, gridDim.x, smem);
+    state_scan_body<MODE, true, false, true, SAVE>(d, sa, blockIdx.x, gridDim.x, smem);
+}
+
+// the reverse scan alone (the states come from the forward call)
+__global__ __launch_bounds__(kThreads) void mk_state_vec_rev(Dims d, StateArgs sa) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    state_scan_body<2, true, true, true>(d, sa, blockIdx.x, gridDim.x, smem);
 }
 
 // both scans of the backward pass, vector decay kind (REM: also the remainder plane of S)
@@ -778,6 +795,7 @@ __global__ __launch_bounds__(kThreads) void mk_state_pair_vec(Dims d, StateArgs 
 
 struct Ws {
     uint16_t *states, *dstates, *states_rem, *dstates_t, *dstates_rem;
+    uint16_t* states_t;  // what the forward output kernel reads (S^T [v][i]); = states unless the states are saved
     float *dg_tok, *wdec, *winc, *lam;
     // vector decay: decayed operand planes [BH*T][128], chunk decay totals [BH*N][128], scores [BH*N][64][64]
     uint16_t *khat_hi, *khat_lo, *qhat_hi, *qhat_lo, *p_hi, *p_lo;
@@ -785,12 +803,16 @@ struct Ws {
     size_t bytes;
 };
 
+// With saved states (d.save) the forward and the backward call share one workspace: the backward
+// carving, followed by the plane of transposed states that only the forward call uses.
 Ws carve(const Dims& d, void* ws, bool bwd) {
     char* p = static_cast<char*>(ws);
     size_t off = 0;
     Ws w{};
     const size_t st = align256(size_t(d.BH()) * (d.dv / D) * d.N * D * D * 2);
+    if (d.save) bwd = true;
     w.states = reinterpret_cast<uint16_t*>(p + off); off += st;
+    w.states_t = w.states;
     if (d.kind == 3) {
         if (bwd) {
             w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st;
@@ -804,6 +826,7 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
         w.p_hi = reinterpret_cast<uint16_t*>(p + off); off += sc;
         w.p_lo = reinterpret_cast<uint16_t*>(p + off); off += sc;
         w.lamv = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * D * 4);
+        if (d.save) { w.states_t = reinterpret_cast<uint16_t*>(p + off); off += st; }
         w.bytes = off;
         return w;
     }
@@ -815,6 +838,7 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
         w.lam = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * 4);
     }
     if (bwd && d.kind == 1) { w.dg_tok = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * 4); }  // per-chunk sums
+    if (d.save) { w.states_t = reinterpret_cast<uint16_t*>(p + off); off += st; }
     w.bytes = off;
     return w;
 }
@@ -847,6 +871,19 @@ hipError_t launch_state(const Dims& d, hipStream_t st, const StateArgs& sa) {
     } else {
         if ((e = allow_lds(mk_state_seq<MODE, true>, kStateLds)) != hipSuccess) return e;
         hipLaunchKernelGGL((mk_state_seq<MODE, true>), sgrid, block, lds, st, d, sa);
+    }
+    return hipSuccess;
+}
+// forward scan that also leaves the states (and, with a decay, their remainder plane) for the backward pass
+hipError_t launch_state_save(const Dims& d, hipStream_t st, const StateArgs& sa) {
+    const dim3 sgrid(D / 32 * d.seqs()), block(kThreads);
+    hipError_t e;
+    if (d.kind == 0) {
+        if ((e = allow_lds(mk_state_seq<3, false, true>, kStateLdsTwin)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_state_seq<3, false, true>), sgrid, block, kStateLdsTwin, st, d, sa);
+    } else {
+        if ((e = allow_lds(mk_state_seq<3, true, true>, kStateLdsTwin)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_state_seq<3, true, true>), sgrid, block, kStateLdsTwin, st, d, sa);
     }
     return hipSuccess;
 }
@@ -889,14 +926,21 @@ hipError_t vec_fwd(const Dims& d, const FwdArgs& a) {
     {
         ProfScope ps(KID_MFMA_STATE, a.stream);
         if ((e = allow_lds(mk_state_vec<3>, kStateLds)) != hipSuccess) return e;
-        StateArgs sa{v, w.khat_hi, nullptr, w.lamv, w.states, nullptr, a.m0, a.mT, w.khat_lo, d.dv, nvh};
-        hipLaunchKernelGGL(mk_state_vec<3>, dim3(D / 32 * d.seqs() * nvh), dim3(kThreads), kStateLdsNoRem, a.stream, d, sa);
+        const dim3 sgrid(D / 32 * d.seqs() * nvh);
+        if (d.save) {
+            if ((e = allow_lds(mk_state_vec<3, true>, kStateLdsTwin)) != hipSuccess) return e;
+            StateArgs sa{v, w.khat_hi, nullptr, w.lamv, w.states_t, w.states_rem, a.m0, a.mT, w.khat_lo, d.dv, nvh, w.states};
+            hipLaunchKernelGGL((mk_state_vec<3, true>), sgrid, dim3(kThreads), kStateLdsTwin, a.stream, d, sa);
+        } else {
+            StateArgs sa{v, w.khat_hi, nullptr, w.lamv, w.states, nullptr, a.m0, a.mT, w.khat_lo, d.dv, nvh};
+            hipLaunchKernelGGL(mk_state_vec<3>, sgrid, dim3(kThreads), kStateLdsNoRem, a.stream, d, sa);
+        }
     }
     {
         ProfScope ps(KID_MFMA_OUTPUT, a.stream);
         if ((e = allow_lds(mk_output_vec<false>, kOutVecLds)) != hipSuccess) return e;
         hipLaunchKernelGGL(mk_output_vec<false>, dim3(d.N, d.BH(), nvh), dim3(kThreads), kOutVecLds, a.stream, d, w.qhat_hi, w.qhat_lo, v,
-                           w.p_hi, w.p_lo, w.states, static_cast<uint16_t*>(a.o));
+                           w.p_hi, w.p_lo, w.states_t, static_cast<uint16_t*>(a.o));
     }
     return hipGetLastError();
 }
@@ -912,12 +956,16 @@ hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
     launch_prep(d, a.stream, a.g, w);
     {
         ProfScope ps(KID_MFMA_STATE, a.stream);
-        if ((e = launch_state<0>(d, a.stream, StateArgs{k, v, w.wdec, w.lam, w.states, nullptr, a.m0, a.mT})) != hipSuccess)
+        if (d.save) {
+            const StateArgs sa{v, k, w.wdec, w.lam, w.states_t, d.kind ? w.states_rem : nullptr, a.m0, a.mT, nullptr, 0, 0, w.states};
+            if ((e = launch_state_save(d, a.stream, sa)) != hipSuccess) return e;
+        } else if ((e = launch_state<0>(d, a.stream, StateArgs{k, v, w.wdec, w.lam, w.states, nullptr, a.m0, a.mT})) != hipSuccess) {
             return e;
+        }
     }
     {
         ProfScope ps(KID_MFMA_OUTPUT, a.stream);
-        hipLaunchKernelGGL(mk_output<false>, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states,
+        hipLaunchKernelGGL(mk_output<false>, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states_t,
                            static_cast<uint16_t*>(a.o), 1);
     }
     return hipGetLastError();
@@ -930,8 +978,14 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     auto d_o = static_cast<const uint16_t*>(a.d_o);
     const int nvh = d.dv / D;
-    if ((e = launch_vec_prep(d, a.stream, q, k, a.g, w)) != hipSuccess) return e;
-    {
+    if (!d.save && (e = launch_vec_prep(d, a.stream, q, k, a.g, w)) != hipSuccess) return e;
+    if (d.save) {  // the decayed operand planes, the scores and the states are the forward call's
+        ProfScope ps(KID_MFMA_DSTATE, a.stream);
+        const StateArgs s2{d_o, w.qhat_hi, nullptr, w.lamv, w.dstates, a.dg ? w.dstates_rem : nullptr, a.d_mT, a.d_m0,
+                           w.qhat_lo, d.dv, nvh, w.dstates_t};
+        if ((e = allow_lds(mk_state_vec_rev, kStateLdsTwin)) != hipSuccess) return e;
+        hipLaunchKernelGGL(mk_state_vec_rev, dim3(D / 32 * d.seqs() * nvh), dim3(kThreads), kStateLdsTwin, a.stream, d, s2);
+    } else {
         ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
         const StateArgs s1{v, w.khat_hi, nullptr, w.lamv, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr,
                            w.khat_lo, d.dv, nvh};
@@ -984,8 +1038,12 @@ hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     hipError_t e;
     if ((e = allow_lds(mk_grad<true>, kGradLds)) != hipSuccess) return e;
     if ((e = allow_lds(mk_grad<false>, kGradLds)) != hipSuccess) return e;
-    launch_prep(d, a.stream, a.g, w);
-    {
+    if (d.save) {  // decay tables and states are the forward call's: only the reverse scan runs
+        ProfScope ps(KID_MFMA_DSTATE, a.stream);
+        if ((e = launch_state<2>(d, a.stream, StateArgs{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0})) != hipSuccess)
+            return e;
+    } else {
+        launch_prep(d, a.stream, a.g, w);
         ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
         const StateArgs s1{v, k, w.wdec, w.lam, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr};
         const StateArgs s2{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0};
