@@ -145,7 +145,8 @@ def main():
     traffic = None
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-            traffic = json.load(f).get(cfg["name"], {}).get(dominant)
+            key = cfg["name"] + ("" if pkg.keeps_states(p) == 1 else "_recompute")
+            traffic = json.load(f).get(key, {}).get(dominant)
     except (OSError, ValueError):
         pass
 
