@@ -9,17 +9,18 @@ from lsm_testlib import to_device
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("keep", [False, "always"])
 @pytest.mark.parametrize("kind", [wl.KIND_SCALAR, wl.KIND_VECTOR])
-def test_forward_backward_replayed_from_a_graph(kind):
+def test_forward_backward_replayed_from_a_graph(kind, keep):
+    """keep: the forward call leaves its chunk states in the workspace for the backward call."""
     import torch
     import paper_2503_05447_amd as pkg
     x = wl.make_inputs(2, 2, 200, 128, 128, kind, dtype="bf16", seed=990 + kind, decay="weak", init_state=True, d_final=True)
     t = to_device(x)
-    p = pkg.make_params(2, 2, 200, 128, 128, 64, kind, 1)
-    ws = torch.empty(max(pkg.lsm_chunk_fwd_workspace_bytes(p), pkg.lsm_chunk_bwd_workspace_bytes(p)), dtype=torch.uint8,
-                     device=t["q"].device)
-    run = lambda: (pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"], t["g"], kind, 64, t["m0"], workspace=ws),
-                   pkg.lsm_chunk_bwd(t["q"], t["k"], t["v"], t["g"], kind, t["d_o"], 64, t["m0"], t["d_mT"], workspace=ws))
+    ws = pkg.lsm_chunk_workspace(t["q"], t["k"], t["v"], t["g"], kind, save_states=keep)
+    run = lambda: (pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"], t["g"], kind, 64, t["m0"], workspace=ws, save_states=keep),
+                   pkg.lsm_chunk_bwd(t["q"], t["k"], t["v"], t["g"], kind, t["d_o"], 64, t["m0"], t["d_mT"], workspace=ws,
+                                     states_saved=keep))
     (o_e, m_e), r_e = run()
     torch.cuda.synchronize()
     eager = [o_e.clone(), m_e.clone()] + [r_e[n].clone() for n in ("dq", "dk", "dv", "dg", "d_init_state")]
