@@ -66,14 +66,29 @@ __global__ void k_local_state(Dims d, const TIO* __restrict__ x, const TIO* __re
     const size_t tok0 = cp.wtok0;                              // token index in the library's own arrays
     auto U = [&](int r) { return cp.tok0 + size_t(r) * cp.ts; };  // row of token r in the caller's arrays
     float* dst = out + cp.slot * d.dk * d.dv;
+    // scalar kinds: the weight depends on the token only, one table per chunk instead of an exp per product
+    __shared__ float wtok[128];
+    if (dkd == 1) {
+        const bsum_t bC = bval(bcum, tok0 + L - 1, 1, 0);
+        for (int r = threadIdx.x; r < L; r += blockDim.x) {
+            const bsum_t br = bval(bcum, tok0 + r, 1, 0);
+            wtok[r] = MODE == 0 ? expd(bC - br) : expd(br);
+        }
+        __syncthreads();
+    }
     for (int e = threadIdx.x; e < d.dk * d.dv; e += blockDim.x) {
         const int i = e / d.dv, j = e % d.dv;
-        const bsum_t bC = bval(bcum, tok0 + L - 1, dkd, i);
         float acc = 0.f;
-        for (int r = 0; r < L; ++r) {
-            const bsum_t br = bval(bcum, tok0 + r, dkd, i);
-            const float w = MODE == 0 ? expd(bC - br) : expd(br);
-            acc += to_f32(x[U(r) * d.dk + i]) * w * to_f32(y[U(r) * d.dv + j]);
+        if (dkd == 1) {
+            _Pragma("unroll 8")
+            for (int r = 0; r < L; ++r) acc += to_f32(x[U(r) * d.dk + i]) * wtok[r] * to_f32(y[U(r) * d.dv + j]);
+        } else {
+            const bsum_t bC = bval(bcum, tok0 + L - 1, dkd, i);
+            for (int r = 0; r < L; ++r) {
+                const bsum_t br = bval(bcum, tok0 + r, dkd, i);
+                const float w = MODE == 0 ? expd(bC - br) : expd(br);
+                acc += to_f32(x[U(r) * d.dk + i]) * w * to_f32(y[U(r) * d.dv + j]);
+            }
         }
         dst[e] = acc;
     }
@@ -116,6 +131,7 @@ __device__ void scores_to_lds(const Dims& d, const TIO* q, const TIO* k, const b
         float acc = 0.f;
         if (r <= j) {
             if (dkd == 1) {
+                _Pragma("unroll 8")
                 for (int i = 0; i < d.dk; ++i)
                     acc += to_f32(q[U(j) * d.dk + i]) * to_f32(k[U(r) * d.dk + i]);
                 acc *= expd(bval(bcum, tok0 + j, 1, 0) - bval(bcum, tok0 + r, 1, 0));
@@ -147,9 +163,17 @@ __global__ void k_output(Dims d, const TIO* __restrict__ q, const TIO* __restric
     for (int e = threadIdx.x; e < L * d.dv; e += blockDim.x) {
         const int j = e / d.dv, col = e % d.dv;
         float acc = 0.f;
+        _Pragma("unroll 8")
         for (int r = 0; r <= j; ++r) acc += A[j * d.C + r] * to_f32(v[U(r) * d.dv + col]);
-        for (int i = 0; i < d.dk; ++i)
-            acc += to_f32(q[U(j) * d.dk + i]) * expd(bval(bcum, tok0 + j, dkd, i)) * S[i * d.dv + col];
+        if (dkd == 1) {  // one decay factor per token
+            float inter = 0.f;
+            _Pragma("unroll 8")
+            for (int i = 0; i < d.dk; ++i) inter += to_f32(q[U(j) * d.dk + i]) * S[i * d.dv + col];
+            acc += expd(bval(bcum, tok0 + j, 1, 0)) * inter;
+        } else {
+            for (int i = 0; i < d.dk; ++i)
+                acc += to_f32(q[U(j) * d.dk + i]) * expd(bval(bcum, tok0 + j, dkd, i)) * S[i * d.dv + col];
+        }
         from_f32(&o[U(j) * d.dv + col], acc);
     }
 }
@@ -187,6 +211,7 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
         const int j = e / L, r = e % L;
         float acc = 0.f;
         if (r <= j)
+            _Pragma("unroll 8")
             for (int col = 0; col < d.dv; ++col)
                 acc += to_f32(d_o[U(j) * d.dv + col]) * to_f32(v[U(r) * d.dv + col]);
         dA[j * d.C + r] = acc;
@@ -197,10 +222,18 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
     for (int e = threadIdx.x; e < L * d.dv; e += blockDim.x) {
         const int r = e / d.dv, col = e % d.dv;
         float acc = 0.f;
+        _Pragma("unroll 8")
         for (int j = r; j < L; ++j) acc += A[j * d.C + r] * to_f32(d_o[U(j) * d.dv + col]);
-        for (int i = 0; i < d.dk; ++i) {
-            const float w = expd(bval(bcum, tok0 + L - 1, dkd, i) - bval(bcum, tok0 + r, dkd, i));
-            acc += to_f32(k[U(r) * d.dk + i]) * w * dS[i * d.dv + col];
+        if (dkd == 1) {  // one decay factor per token
+            float inter = 0.f;
+            _Pragma("unroll 8")
+            for (int i = 0; i < d.dk; ++i) inter += to_f32(k[U(r) * d.dk + i]) * dS[i * d.dv + col];
+            acc += expd(bval(bcum, tok0 + L - 1, 1, 0) - bval(bcum, tok0 + r, 1, 0)) * inter;
+        } else {
+            for (int i = 0; i < d.dk; ++i) {
+                const float w = expd(bval(bcum, tok0 + L - 1, dkd, i) - bval(bcum, tok0 + r, dkd, i));
+                acc += to_f32(k[U(r) * d.dk + i]) * w * dS[i * d.dv + col];
+            }
         }
         from_f32(&dv[U(r) * d.dv + col], acc);
     }
@@ -210,6 +243,7 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
         const bsum_t bt = bval(bcum, tok0 + t, dkd, i);
         const bsum_t bC = bval(bcum, tok0 + L - 1, dkd, i);
         float q_inter = 0.f, k_inter = 0.f;
+        _Pragma("unroll 8")
         for (int col = 0; col < d.dv; ++col) {
             q_inter += to_f32(d_o[U(t) * d.dv + col]) * S[i * d.dv + col];
             k_inter += to_f32(v[U(t) * d.dv + col]) * dS[i * d.dv + col];
