@@ -203,6 +203,11 @@ def main():
             "algorithmic_tflops": alg / pass_s / 1e12, "algorithmic_frac_of_mfma_peak": alg / pass_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             "issued_mfma_tflops": issued / pass_s / 1e12, "issued_frac_of_mfma_peak": issued / pass_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             "same_output_as_forward": bool(torch.equal(o_mb, o_plain))}
+        try:   # the matrix-pipe utilisation the hardware counters give for the same launches (collected under rocprofv3)
+            with open(os.path.join(ROOT, "profiles", "mfma_counters.json")) as f:
+                result["intra_chunk_microbench"]["rocprof_counters"] = json.load(f).get(cfg["name"] + "_intra_chunk_microbench")
+        except (OSError, ValueError):
+            pass
 
     if not args.no_microbench:
         # Recurrent decoding step (lsm_step) on the heads of this workload: state read + written once per step.
