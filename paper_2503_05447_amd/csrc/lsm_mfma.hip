@@ -202,13 +202,42 @@ __device__ __forceinline__ void state_store(uint16_t* dst, const uint16_t* stage
     }
 }
 
-// the remainder plane: one byte per element (see store_block_t_split8), same
-// fragment-major element order, 8 bytes per lane and k-step
-__device__ __forceinline__ void state_store8(uint8_t* dst, const uint8_t* stage, int mb, int rowblk, int colblk, int lane) {
-    _Pragma("unroll") for (int it = 0; it < 2; ++it) {
-        const int piece = 2 * it + (lane >> 5), ksl = piece >> 1, hf = piece & 1, r = lane & 31;
-        const u32x2 val = *reinterpret_cast<const u32x2*>(stage + r * LD + 32 * mb + 16 * ksl + 8 * hf);
-        __builtin_nontemporal_store(val, reinterpret_cast<u32x2*>(dst + state_frag_off(rowblk, 2 * colblk + ksl, 32 * hf + r)));
+// The same block -> global memory without LDS, for the transposed order (stored row = the lane's column
+// n, stored columns = the block's rows m).  In D layout lanes l and l + 32 hold complementary halves
+// (4 + 4 rows) of every group of 8 rows; one v_permlane32_swap per dword hands each lane a whole group:
+// the lower lanes the even groups, the upper lanes the odd ones, i.e. exactly the 16 bytes that lane
+// 32 hf + n of fragment (rowblk, 2 mb + q) holds, and a wave stores one contiguous KiB per instruction.
+__device__ __forceinline__ void state_store_direct(uint16_t* dst, int rowblk, int mb, int lane, const f32x16& acc) {
+    _Pragma("unroll") for (int q = 0; q < 2; ++q) {
+        const uint32_t a0 = pack2(acc[8 * q + 0], acc[8 * q + 1]), a1 = pack2(acc[8 * q + 2], acc[8 * q + 3]);
+        const uint32_t b0 = pack2(acc[8 * q + 4], acc[8 * q + 5]), b1 = pack2(acc[8 * q + 6], acc[8 * q + 7]);
+        const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+        const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+        const u32x4 val = {s0[0], s1[0], s0[1], s1[1]};
+        __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(dst + state_frag_off(rowblk, 2 * mb + q, lane)));
+    }
+}
+// with the 8-bit remainder plane: (x - head) * 2^8 as an 8-bit float, same element order, one byte each
+__device__ __forceinline__ void state_store_direct_split8(uint16_t* dst, uint8_t* dst8, int rowblk, int mb, int lane,
+                                                          const f32x16& acc) {
+    _Pragma("unroll") for (int q = 0; q < 2; ++q) {
+        uint32_t h[4];
+        int r8[2];
+        _Pragma("unroll") for (int gg = 0; gg < 2; ++gg) {
+            const int x = 8 * q + 4 * gg;
+            h[2 * gg] = pack2(acc[x], acc[x + 1]);
+            h[2 * gg + 1] = pack2(acc[x + 2], acc[x + 3]);
+            int v = __builtin_amdgcn_cvt_pk_bf8_f32((acc[x] - bf16_lo(h[2 * gg])) * kRem8Scale,
+                                                    (acc[x + 1] - bf16_hi(h[2 * gg])) * kRem8Scale, 0, false);
+            r8[gg] = __builtin_amdgcn_cvt_pk_bf8_f32((acc[x + 2] - bf16_lo(h[2 * gg + 1])) * kRem8Scale,
+                                                     (acc[x + 3] - bf16_hi(h[2 * gg + 1])) * kRem8Scale, v, true);
+        }
+        const auto s0 = __builtin_amdgcn_permlane32_swap(h[0], h[2], false, false);
+        const auto s1 = __builtin_amdgcn_permlane32_swap(h[1], h[3], false, false);
+        const auto sr = __builtin_amdgcn_permlane32_swap(uint32_t(r8[0]), uint32_t(r8[1]), false, false);
+        const size_t off = state_frag_off(rowblk, 2 * mb + q, lane);
+        __builtin_nontemporal_store(u32x4{s0[0], s1[0], s0[1], s1[1]}, reinterpret_cast<u32x4*>(dst + off));
+        __builtin_nontemporal_store(u32x2{sr[0], sr[1]}, reinterpret_cast<u32x2*>(dst8 + off));
     }
 }
 
@@ -317,13 +346,11 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
             _Pragma("unroll") for (int x = 0; x < 16; ++x)
                 sp[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
         }
-        if (MODE != 3) {
-            if (states_rem) store_block_t_split8(sh, reinterpret_cast<uint8_t*>(sh + 32 * LD), LD, n, 32 * mb, half, acc);
-            else store_block_t(sh, LD, n, 32 * mb, half, acc);
-        }
-        if (SAVE) {
-            if (states_rem) store_block_t_split8(sh + 32 * LD, reinterpret_cast<uint8_t*>(sh + 64 * LD), LD, n, 32 * mb, half, acc);
-            else store_block_t(sh + 32 * LD, LD, n, 32 * mb, half, acc);
+        // the transposed order needs no staging: registers -> global memory
+        if (MODE != 3 || SAVE) {
+            uint16_t* tdst = (MODE == 3 ? states_twin : states) + slot(k);
+            if (states_rem) state_store_direct_split8(tdst, reinterpret_cast<uint8_t*>(states_rem) + slot(k), nb, mb, lane, acc);
+            else state_store_direct(tdst, nb, mb, lane, acc);
         }
         if (DEC) {
             const float lam_cur = rw.lam;
@@ -340,16 +367,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         state_to_lds<DEC, VEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
         // transposed staging: stage row = state column n (block nb); untransposed: stage row = state row m (block mb)
         if (MODE == 3) state_store<false>(states + slot(k), sh, mb, mb, nb, lane);
-        else state_store(states + slot(k), sh, mb, nb, mb, lane);
-        if (MODE != 3 && states_rem) {
-            state_store8(reinterpret_cast<uint8_t*>(states_rem) + slot(k), reinterpret_cast<const uint8_t*>(sh + 32 * LD), mb, nb, mb, lane);
-        }
         if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
-        if (SAVE) {
-            state_store(states_twin + slot(k), sh + 32 * LD, mb, nb, mb, lane);
-            if (states_rem)
-                state_store8(reinterpret_cast<uint8_t*>(states_rem) + slot(k), reinterpret_cast<const uint8_t*>(sh + 64 * LD), mb, nb, mb, lane);
-        }
     };
     int k = 0;
     for (; k + 2 < cnt; k += 3) {

@@ -81,19 +81,6 @@ __device__ __forceinline__ void store_block_t_split(uint16_t* hi, uint16_t* lo, 
 // of their underflow: x = head + 2^-8 * rem8 to about 2^-12 relative, in three bytes per element.
 constexpr float kRem8Scale = 256.f, kRem8Unscale = 1.f / 256.f;
 typedef float f32x2v __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ void store_block_t_split8(uint16_t* hi, uint8_t* lo8, int ld, int nrow, int m0, int half,
-                                                     const f32x16& d) {
-    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-        const uint32_t h0 = pack2(d[4 * g + 0], d[4 * g + 1]), h1 = pack2(d[4 * g + 2], d[4 * g + 3]);
-        u32x2 vh = {h0, h1};
-        *reinterpret_cast<u32x2*>(hi + nrow * ld + m0 + 8 * g + 4 * half) = vh;
-        int v = __builtin_amdgcn_cvt_pk_bf8_f32((d[4 * g + 0] - bf16_lo(h0)) * kRem8Scale,
-                                                (d[4 * g + 1] - bf16_hi(h0)) * kRem8Scale, 0, false);
-        v = __builtin_amdgcn_cvt_pk_bf8_f32((d[4 * g + 2] - bf16_lo(h1)) * kRem8Scale,
-                                            (d[4 * g + 3] - bf16_hi(h1)) * kRem8Scale, v, true);
-        *reinterpret_cast<int*>(lo8 + nrow * ld + m0 + 8 * g + 4 * half) = v;  // byte tile, row stride ld bytes
-    }
-}
 // 8 such bytes -> bf16 operand (exact: the 8-bit values have two mantissa bits); still scaled by 2^8
 __device__ __forceinline__ bf16x8 rem8_to_bf16(u32x2 raw) {
     u32x4 v;
