@@ -827,7 +827,12 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
     char* p = static_cast<char*>(ws);
     size_t off = 0;
     Ws w{};
-    const size_t st = align256(size_t(d.BH()) * (d.dv / D) * d.N * D * D * 2);
+    // Planes are read and written at the same relative offsets by the same workgroups.  Plane sizes are
+    // powers of two for the usual shapes, and starts that far apart map equal offsets to the same memory
+    // channels (measured: the scan that writes three planes ran a third slower at such a placement), so
+    // every plane is followed by a pad that moves the next one to other channels.
+    constexpr size_t kSkew = 17 * 256;
+    const size_t st = align256(size_t(d.BH()) * (d.dv / D) * d.N * D * D * 2) + kSkew;
     if (d.save) bwd = true;
     w.states = reinterpret_cast<uint16_t*>(p + off); off += st;
     w.states_t = w.states;
@@ -835,10 +840,10 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
         if (bwd) {
             w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st;
             w.dstates_t = reinterpret_cast<uint16_t*>(p + off); off += st;
-            w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2);  // one byte per element
-            w.dstates_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2);
+            w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2) + kSkew;  // one byte per element
+            w.dstates_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2) + kSkew;
         }
-        const size_t plane = align256(size_t(d.BH()) * d.T * D * 2), sc = align256(size_t(d.BH()) * d.N * C * C * 2);
+        const size_t plane = align256(size_t(d.BH()) * d.T * D * 2) + kSkew, sc = align256(size_t(d.BH()) * d.N * C * C * 2) + kSkew;
         uint16_t** planes[4] = {&w.khat_hi, &w.khat_lo, &w.qhat_hi, &w.qhat_lo};
         for (auto pp : planes) { *pp = reinterpret_cast<uint16_t*>(p + off); off += plane; }
         w.p_hi = reinterpret_cast<uint16_t*>(p + off); off += sc;
@@ -849,7 +854,7 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
         return w;
     }
     if (bwd) { w.dstates = reinterpret_cast<uint16_t*>(p + off); off += st; }
-    if (bwd && d.kind != 0) { w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2); }  // one byte per element
+    if (bwd && d.kind != 0) { w.states_rem = reinterpret_cast<uint16_t*>(p + off); off += align256(st / 2) + kSkew; }  // one byte per element
     if (d.kind != 0) {
         w.wdec = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * C * 4);
         w.winc = reinterpret_cast<float*>(p + off); off += align256(size_t(d.BH()) * d.N * C * 4);
