@@ -71,8 +71,7 @@ __global__ __launch_bounds__(64) void mk_decay_prep(Dims d, const float* __restr
 // Chunk states and the scan over chunks, fused: one wave owns a 32 x 32 block of the d_k x d_v
 // state in MFMA accumulators (fp32) and walks the chunks of its sequence in order,
 //     S_{c+1} = e^{b_C} S_c + sum_r (k_r e^{b_C - b_r})^T v_r ,
-// writing the bf16 copy of S_c that the per-chunk kernels consume before each update.  The
-// 16 waves of a (b,h) pair are independent (no LDS traffic between them, no barrier).
+// writing the bf16 copy of S_c that the per-chunk kernels consume before each update.
 //   MODE 0: forward states, stored S^T [v][i]   (A side = k decayed, B side = v)
 //   MODE 1: backward recomputation, stored S [i][v]   (A side = v, B side = k decayed)
 //   MODE 2: reverse scan of state gradients, stored dS [i][v]: slot c receives the gradient of the
@@ -81,19 +80,19 @@ __global__ __launch_bounds__(64) void mk_decay_prep(Dims d, const float* __restr
 // Both operands of the token contraction come from identity turns, so their k order agrees.  The
 // decayed operand is split into a bf16 head and a bf16 remainder (two MFMAs) so that the rounding of
 // k * w does not show in a state that one token dominates.  DEC = false (no decay) skips all of it.
-// The loop is software-pipelined: the operands of chunk c+1 are turned, weighted and packed while
-// the accumulation of chunk c is in the matrix pipe; loads run kStatePrefetch chunks ahead.
+// The loop is software-pipelined: global loads run three chunks ahead in rotating register sets, the
+// tiles of the next two chunks sit in LDS (weighted and split on the way in) while this one is contracted.
 // edge_in = M_0 (or d M_T), edge_out = M_T (or d M_0), fp32 [i][v], either may be NULL.
 // states_rem (may be NULL) receives the remainder S - bf16(S) in the same layout as 8-bit floats: the decay
 // gradient contracts q_u S d_o_u^T into one scalar per token, where the 2^-9 rounding of a state that
 // a single token dominates is visible.
 constexpr int LDB = 40;  // row stride (elements) of a 64 x 32 B-side slice in LDS
 // LDS: 2 x (A tile 64 x LD | B slice head 64 x LDB | B slice remainder 64 x LDB) for chunks k+1, k+2
-//      | stage head | stage remainder, 32 x LD each (every wave stages and stores its own block)
+//      | one 32 x LD stage for the scans that also store a block untransposed (the transposed order
+//        leaves straight from the registers, see state_store_direct)
 constexpr int kStateTile = C * LD + 2 * C * LDB;
-constexpr int kStateLds = (2 * kStateTile + 2 * 32 * LD) * 2;      // with the remainder plane
-constexpr int kStateLdsNoRem = (2 * kStateTile + 1 * 32 * LD) * 2; // without
-constexpr int kStateLdsTwin = (2 * kStateTile + 3 * 32 * LD) * 2;  // head, remainder and the untransposed twin
+constexpr int kStateLdsNone = 2 * kStateTile * 2;                  // transposed stores only
+constexpr int kStateLdsPlain = (2 * kStateTile + 32 * LD) * 2;     // with the stage of an untransposed copy
 
 struct StateRegs {  // one thread's share of a chunk on its way from global memory to LDS
     u32x4 a[4], b, blo;  // blo: remainder plane of the B slice (vector decay: both planes arrive precomputed)
@@ -263,7 +262,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     const float* __restrict__ edge_in = sa.edge_in;
     float* __restrict__ edge_out = sa.edge_out;
     uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);         // [2][kStateTile]
-    uint16_t* stage = tiles + 2 * kStateTile;                    // [2][32 * LD]: head, remainder
+    uint16_t* stage = tiles + 2 * kStateTile;                    // [32 * LD]: the untransposed copy, if any
     // The four workgroups of a sequence read the same A-side rows.  Workgroups are dealt to the 8
     // XCDs round-robin by linear id, so the id is decoded such that those four share an XCD (and
     // its L2): id = xcd + 8 * (4 * (seq / 8) + nb), seq = xcd + 8 * (seq / 8).
@@ -342,9 +341,8 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         uint16_t* sh = stage;
         constexpr bool kTwin = VEC && MODE == 2;  // second copy, untransposed
         if (MODE == 3 || (kTwin && states_twin)) {
-            uint16_t* sp = MODE == 3 ? sh : sh + 64 * LD;
             _Pragma("unroll") for (int x = 0; x < 16; ++x)
-                sp[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
+                sh[(8 * (x >> 2) + 4 * half + (x & 3)) * LD + 32 * mb + n] = uint16_t(pack2(acc[x], 0.f));
         }
         // the transposed order needs no staging: registers -> global memory
         if (MODE != 3 || SAVE) {
@@ -365,9 +363,9 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
         }
         __syncthreads();  // every wave is done with the tiles of chunk k
         state_to_lds<DEC, VEC>(rw, bufA(k), bufB(k), tid);  // chunk k+2; read again two barriers from now
-        // transposed staging: stage row = state column n (block nb); untransposed: stage row = state row m (block mb)
+        // the untransposed copy: stage row = state row m (block mb), stage columns = state columns (block nb)
         if (MODE == 3) state_store<false>(states + slot(k), sh, mb, mb, nb, lane);
-        if (kTwin && states_twin) state_store(states_twin + slot(k), sh + 64 * LD, mb, mb, nb, lane);
+        if (kTwin && states_twin) state_store(states_twin + slot(k), sh, mb, mb, nb, lane);
     };
     int k = 0;
     for (; k + 2 < cnt; k += 3) {
@@ -886,13 +884,13 @@ namespace {
 template <int MODE>
 hipError_t launch_state(const Dims& d, hipStream_t st, const StateArgs& sa) {
     const dim3 sgrid(D / 32 * d.seqs()), block(kThreads);
-    const int lds = kStateLdsNoRem;
+    const int lds = kStateLdsNone;
     hipError_t e;
     if (d.kind == 0) {
-        if ((e = allow_lds(mk_state_seq<MODE, false>, kStateLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_state_seq<MODE, false>, lds)) != hipSuccess) return e;
         hipLaunchKernelGGL((mk_state_seq<MODE, false>), sgrid, block, lds, st, d, sa);
     } else {
-        if ((e = allow_lds(mk_state_seq<MODE, true>, kStateLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_state_seq<MODE, true>, lds)) != hipSuccess) return e;
         hipLaunchKernelGGL((mk_state_seq<MODE, true>), sgrid, block, lds, st, d, sa);
     }
     return hipSuccess;
@@ -902,19 +900,19 @@ hipError_t launch_state_save(const Dims& d, hipStream_t st, const StateArgs& sa)
     const dim3 sgrid(D / 32 * d.seqs()), block(kThreads);
     hipError_t e;
     if (d.kind == 0) {
-        if ((e = allow_lds(mk_state_seq<3, false, true>, kStateLdsTwin)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_state_seq<3, false, true>), sgrid, block, kStateLdsTwin, st, d, sa);
+        if ((e = allow_lds(mk_state_seq<3, false, true>, kStateLdsPlain)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_state_seq<3, false, true>), sgrid, block, kStateLdsPlain, st, d, sa);
     } else {
-        if ((e = allow_lds(mk_state_seq<3, true, true>, kStateLdsTwin)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_state_seq<3, true, true>), sgrid, block, kStateLdsTwin, st, d, sa);
+        if ((e = allow_lds(mk_state_seq<3, true, true>, kStateLdsPlain)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_state_seq<3, true, true>), sgrid, block, kStateLdsPlain, st, d, sa);
     }
     return hipSuccess;
 }
 template <bool DEC, bool REM>
 hipError_t launch_state_pair_t(const Dims& d, hipStream_t st, const StateArgs& s1, const StateArgs& s2) {
     const dim3 sgrid(D / 32 * d.seqs(), 2), block(kThreads);
-    const int lds = REM ? kStateLds : kStateLdsNoRem;
-    const hipError_t e = allow_lds(mk_state_pair<DEC, REM>, kStateLds);
+    const int lds = kStateLdsNone;
+    const hipError_t e = allow_lds(mk_state_pair<DEC, REM>, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((mk_state_pair<DEC, REM>), sgrid, block, lds, st, d, s1, s2);
     return hipSuccess;
@@ -948,15 +946,15 @@ hipError_t vec_fwd(const Dims& d, const FwdArgs& a) {
     if ((e = launch_vec_prep(d, a.stream, q, k, a.g, w)) != hipSuccess) return e;
     {
         ProfScope ps(KID_MFMA_STATE, a.stream);
-        if ((e = allow_lds(mk_state_vec<3>, kStateLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_state_vec<3>, kStateLdsPlain)) != hipSuccess) return e;
         const dim3 sgrid(D / 32 * d.seqs() * nvh);
         if (d.save) {
-            if ((e = allow_lds(mk_state_vec<3, true>, kStateLdsTwin)) != hipSuccess) return e;
+            if ((e = allow_lds(mk_state_vec<3, true>, kStateLdsPlain)) != hipSuccess) return e;
             StateArgs sa{v, w.khat_hi, nullptr, w.lamv, w.states_t, w.states_rem, a.m0, a.mT, w.khat_lo, d.dv, nvh, w.states};
-            hipLaunchKernelGGL((mk_state_vec<3, true>), sgrid, dim3(kThreads), kStateLdsTwin, a.stream, d, sa);
+            hipLaunchKernelGGL((mk_state_vec<3, true>), sgrid, dim3(kThreads), kStateLdsPlain, a.stream, d, sa);
         } else {
             StateArgs sa{v, w.khat_hi, nullptr, w.lamv, w.states, nullptr, a.m0, a.mT, w.khat_lo, d.dv, nvh};
-            hipLaunchKernelGGL(mk_state_vec<3>, sgrid, dim3(kThreads), kStateLdsNoRem, a.stream, d, sa);
+            hipLaunchKernelGGL(mk_state_vec<3>, sgrid, dim3(kThreads), kStateLdsPlain, a.stream, d, sa);
         }
     }
     {
@@ -1006,8 +1004,8 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
         ProfScope ps(KID_MFMA_DSTATE, a.stream);
         const StateArgs s2{d_o, w.qhat_hi, nullptr, w.lamv, w.dstates, a.dg ? w.dstates_rem : nullptr, a.d_mT, a.d_m0,
                            w.qhat_lo, d.dv, nvh, w.dstates_t};
-        if ((e = allow_lds(mk_state_vec_rev, kStateLdsTwin)) != hipSuccess) return e;
-        hipLaunchKernelGGL(mk_state_vec_rev, dim3(D / 32 * d.seqs() * nvh), dim3(kThreads), kStateLdsTwin, a.stream, d, s2);
+        if ((e = allow_lds(mk_state_vec_rev, kStateLdsPlain)) != hipSuccess) return e;
+        hipLaunchKernelGGL(mk_state_vec_rev, dim3(D / 32 * d.seqs() * nvh), dim3(kThreads), kStateLdsPlain, a.stream, d, s2);
     } else {
         ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
         const StateArgs s1{v, w.khat_hi, nullptr, w.lamv, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr,
@@ -1016,11 +1014,11 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
                            w.qhat_lo, d.dv, nvh, w.dstates_t};
         const dim3 sgrid(D / 32 * d.seqs() * nvh, 2);
         if (a.dg) {
-            if ((e = allow_lds(mk_state_pair_vec<true>, kStateLdsTwin)) != hipSuccess) return e;
-            hipLaunchKernelGGL(mk_state_pair_vec<true>, sgrid, dim3(kThreads), kStateLdsTwin, a.stream, d, s1, s2);
+            if ((e = allow_lds(mk_state_pair_vec<true>, kStateLdsPlain)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_state_pair_vec<true>, sgrid, dim3(kThreads), kStateLdsPlain, a.stream, d, s1, s2);
         } else {
-            if ((e = allow_lds(mk_state_pair_vec<false>, kStateLdsTwin)) != hipSuccess) return e;
-            hipLaunchKernelGGL(mk_state_pair_vec<false>, sgrid, dim3(kThreads), kStateLdsTwin, a.stream, d, s1, s2);
+            if ((e = allow_lds(mk_state_pair_vec<false>, kStateLdsPlain)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_state_pair_vec<false>, sgrid, dim3(kThreads), kStateLdsPlain, a.stream, d, s1, s2);
         }
     }
     {
