@@ -214,6 +214,9 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
             _Pragma("unroll 8")
             for (int col = 0; col < d.dv; ++col)
                 acc += to_f32(d_o[U(j) * d.dv + col]) * to_f32(v[U(r) * d.dv + col]);
+        // scalar kinds: the decay of a score depends on the token pair only, so G = dA * D is formed here
+        // once and the loops below contain no exponential
+        if (dkd == 1 && r <= j) acc *= expd(bval(bcum, tok0 + j, 1, 0) - bval(bcum, tok0 + r, 1, 0));
         dA[j * d.C + r] = acc;
     }
     __syncthreads();
@@ -251,10 +254,17 @@ __global__ void k_grad(Dims d, const TIO* __restrict__ q, const TIO* __restrict_
         q_inter *= expd(bt);
         k_inter *= expd(bC - bt);
         float q_intra = 0.f, k_intra = 0.f;
-        for (int r = 0; r <= t; ++r)
-            q_intra += dA[t * d.C + r] * expd(bt - bval(bcum, tok0 + r, dkd, i)) * to_f32(k[U(r) * d.dk + i]);
-        for (int j = t; j < L; ++j)
-            k_intra += dA[j * d.C + t] * expd(bval(bcum, tok0 + j, dkd, i) - bt) * to_f32(q[U(j) * d.dk + i]);
+        if (dkd == 1) {  // dA already carries the decay
+            _Pragma("unroll 8")
+            for (int r = 0; r <= t; ++r) q_intra += dA[t * d.C + r] * to_f32(k[U(r) * d.dk + i]);
+            _Pragma("unroll 8")
+            for (int j = t; j < L; ++j) k_intra += dA[j * d.C + t] * to_f32(q[U(j) * d.dk + i]);
+        } else {
+            for (int r = 0; r <= t; ++r)
+                q_intra += dA[t * d.C + r] * expd(bt - bval(bcum, tok0 + r, dkd, i)) * to_f32(k[U(r) * d.dk + i]);
+            for (int j = t; j < L; ++j)
+                k_intra += dA[j * d.C + t] * expd(bval(bcum, tok0 + j, dkd, i) - bt) * to_f32(q[U(j) * d.dk + i]);
+        }
         const float dqv = q_inter + q_intra, dkv = k_inter + k_intra;
         from_f32(&dq[U(t) * d.dk + i], dqv);
         from_f32(&dk[U(t) * d.dk + i], dkv);
