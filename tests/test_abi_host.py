@@ -56,6 +56,7 @@ def test_error_codes_are_reached_before_any_launch():
     assert bwd(P(), dq=None) == ERR_NULL
     assert fwd(P(T=0)) == ERR_SHAPE
     assert fwd(P(B=-1)) == ERR_SHAPE
+    assert fwd(P(B=256, H=256)) == ERR_SHAPE                  # B * H beyond the largest grid dimension (65535)
     bad = P(); bad.struct_size = 12
     assert fwd(bad) == ERR_SHAPE
     assert fwd(P(d_k=96)) == ERR_UNSUP

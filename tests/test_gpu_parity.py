@@ -148,3 +148,30 @@ def test_kind_embeddings_on_gpu():
         assert rel_err(host(a), host(b)) <= 1e-4
     assert rel_err(host(r_s["dg"]).sum((0, 2)), host(r_h["dg"])) <= 1e-4
     assert rel_err(host(r_v["dg"]).sum(-1), host(r_s["dg"])) <= 1e-4
+
+
+@pytest.mark.parametrize("case", [("bf16", 128), ("f32", 64)])
+def test_largest_batch_times_heads(case):
+    """B * H = 65535, the largest the grids allow (the ABI rejects more), short sequences: a sample of
+    (b,h) pairs against the oracle, the rest must at least be finite."""
+    import torch
+    from lsm_testlib import oracle_all, select_heads
+    dtype, dd = case
+    B, H, T = 255, 257, 3
+    x = wl.make_inputs(B, H, T, dd, dd, wl.KIND_SCALAR, dtype=dtype, seed=77, decay="weak", init_state=True, d_final=True)
+    t = to_device(x)
+    o, mT = gpu_forward(x, 64, t)
+    r = gpu_backward(x, 64, t)
+    torch.cuda.synchronize()
+    for a in (o, mT, r["dq"], r["dk"], r["dv"], r["dg"], r["d_init_state"]):
+        assert bool(torch.isfinite(a.float()).all())
+    pairs = [(0, 0), (131, 200), (254, 256)]
+    y = select_heads(x, pairs)
+    o_ref, mT_ref, r_ref = oracle_all(y)
+    ib, ih = [p[0] for p in pairs], [p[1] for p in pairs]
+    pick = lambda a: host(a[ib, ih][None])
+    check("o", pick(o), o_ref, dtype)
+    check("final_state", pick(mT), mT_ref, dtype)
+    for key in ("dq", "dk", "dv", "dg"):
+        check(key, pick(r[key]), r_ref[key], dtype)
+    check("d_init_state", pick(r["d_init_state"]), r_ref["d_m0"], dtype)
