@@ -185,11 +185,12 @@ def main():
         # LDS-resident tiles; the time of one pass is the slope between two repeat counts.
         R = 33
         o_mb = torch.empty_like(last[0][0])
-        o_plain, _ = pkg.lsm_chunk_fwd(q, k, v, g, kind, C, m0, workspace=ws)   # the workspace holds the chunk states again
+        o_plain, _ = pkg.lsm_chunk_fwd(q, k, v, g, kind, C, None, workspace=ws)
+        ws_mb = pkg.lsm_bench_intra_chunk_workspace(q, k, v, g, kind, C)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws, 1, C)
-        ev[0].record(); pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws, 1, C); ev[1].record()
-        ev[2].record(); pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws, R, C); ev[3].record()
+        pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws_mb, 1, C)
+        ev[0].record(); pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws_mb, 1, C); ev[1].record()
+        ev[2].record(); pkg.lsm_bench_intra_chunk(q, k, v, g, kind, o_mb, ws_mb, R, C); ev[3].record()
         torch.cuda.synchronize()
         t1_ms, tR_ms = ev[0].elapsed_time(ev[1]), ev[2].elapsed_time(ev[3])
         pass_s = (tR_ms - t1_ms) / (R - 1) * 1e-3
@@ -202,7 +203,7 @@ def main():
             "repeats": R, "ms_one_pass": pass_s * 1e3, "ms_streamed_kernel": t1_ms,
             "algorithmic_tflops": alg / pass_s / 1e12, "algorithmic_frac_of_mfma_peak": alg / pass_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             "issued_mfma_tflops": issued / pass_s / 1e12, "issued_frac_of_mfma_peak": issued / pass_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-            "same_output_as_forward": bool(torch.equal(o_mb, o_plain))}
+            "max_abs_diff_to_forward": float((o_mb.float() - o_plain.float()).abs().max())}
         try:   # the matrix-pipe utilisation the hardware counters give for the same launches (collected under rocprofv3)
             with open(os.path.join(ROOT, "profiles", "mfma_counters.json")) as f:
                 result["intra_chunk_microbench"]["rocprof_counters"] = json.load(f).get(cfg["name"] + "_intra_chunk_microbench")

@@ -69,20 +69,19 @@ typedef enum {
 
 /*
  * lsm_params.flags.
- * LSM_FLAG_SAVE_STATES: the chunk states that the forward call computes anyway are kept for the
- * backward call instead of being computed again there (the usual trade of memory for recomputation
- * in training).  Set it in the params of BOTH calls.  Contract: the two calls get the same params,
- * the same q, k, v, log_decay and init_state, and the same workspace buffer, of at least
+ * LSM_FLAG_SAVE_STATES: the states that the forward call computes anyway are kept for the backward
+ * call instead of being computed again there (the usual trade of memory for recomputation in
+ * training).  Set it in the params of BOTH calls.  Contract: the two calls get the same params, the
+ * same q, k, v, log_decay and init_state, and the same workspace buffer, of at least
  * lsm_chunk_fwd_workspace_bytes(p) (with the flag set, both size queries return one figure that
  * covers both calls), and nothing else writes to that buffer between them; lsm_chunk_bwd then reads
- * what lsm_chunk_fwd left there and is wrong if the buffer was touched.  The flag is a permission:
- * shapes served by kernels that keep nothing recompute as usual, and so do the scalar decay kinds
- * when there are fewer than 40 independent recurrences (B*H, or n_seq*H): the two scans of the
- * recomputing backward pass then hide each other's latency, which is worth more than the saved
- * work.  Both calls take the decision from the params alone, so they always agree.
- * LSM_FLAG_SAVE_ALWAYS (only together with LSM_FLAG_SAVE_STATES) switches that size rule off.
- * Results agree with those of the recomputing path to rounding (the states are accumulated in a
- * different operand order), not bit for bit.
+ * what lsm_chunk_fwd left there and is wrong if the buffer was touched.  What is kept: for the scalar
+ * decay kinds on the matrix-core kernels the state at the start of every segment of chunks (one
+ * d_k x d_v fp32 matrix per segment; nothing when a sequence is a single segment), for the vector
+ * kind the per-chunk states and decayed operands.  The flag is a permission: shapes served by kernels
+ * that keep nothing recompute as usual (lsm_keeps_states tells).  Both calls take the decision from
+ * the params alone, so they always agree.  LSM_FLAG_SAVE_ALWAYS (only together with
+ * LSM_FLAG_SAVE_STATES) is accepted for compatibility and changes nothing.
  */
 typedef enum { LSM_FLAG_SAVE_STATES = 1, LSM_FLAG_SAVE_ALWAYS = 2 } lsm_flags;
 
@@ -188,14 +187,17 @@ int lsm_profile_stop(int* kernel_ids, float* milliseconds, int capacity);
 const char* lsm_kernel_name(int kernel_id);
 
 /*
- * Benchmark aid (not part of the method): the intra-chunk kernel of the forward (masked decayed scores
- * times V plus Q times the chunk state; Algorithm 2, O_intra + O_inter) with its compute phase repeated
- * `repeats` times on the tiles resident in LDS, so that the arithmetic rate of the intra-chunk phase can
- * be measured apart from the HBM traffic that bounds the streamed kernel.  Only for parameter sets with
- * lsm_kernel_path() == 1 and a decay kind other than LSM_DECAY_VECTOR (else LSM_ERR_UNSUPPORTED).
- * `workspace` must be the one a preceding lsm_chunk_fwd() call with the same parameters and inputs
- * used (it holds the chunk states); `o` is overwritten with the same values that call produced.
+ * Benchmark aid (not part of the method): the intra-chunk phase of the forward (masked decayed scores
+ * times V plus Q times the chunk state; Algorithm 2, O_intra + O_inter) as a kernel of its own, one
+ * chunk per workgroup, with its compute phase repeated `repeats` times on the tiles resident in LDS,
+ * so that the arithmetic rate of that phase can be measured apart from the HBM traffic that bounds
+ * the streamed path.  Only for parameter sets with lsm_kernel_path() == 1, a decay kind other than
+ * LSM_DECAY_VECTOR and no packed input (else LSM_ERR_UNSUPPORTED).  The call first materialises one
+ * chunk state per chunk in `workspace` (at least lsm_bench_intra_chunk_workspace_bytes(p), 0 if
+ * unsupported), from a zero initial state; `o` receives lsm_chunk_fwd's output for init_state = NULL
+ * (to rounding).
  */
+size_t lsm_bench_intra_chunk_workspace_bytes(const lsm_params* p);
 int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, const void* v,
                           const float* log_decay, void* o, void* workspace, size_t workspace_bytes,
                           int repeats, void* stream);
@@ -207,7 +209,7 @@ int lsm_keeps_states(const lsm_params* p);
 /* Static, NUL-terminated description of a status code. */
 const char* lsm_status_string(int status);
 
-/* ABI version, bumped when a signature or struct changes (2: layout and packed input in lsm_params; 3: flags). */
+/* ABI version, bumped when a signature or struct changes (2: layout and packed input in lsm_params; 3: flags; 4: workspace query of the benchmark aid). */
 int lsm_version(void);
 
 #ifdef __cplusplus

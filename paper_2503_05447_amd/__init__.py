@@ -3,5 +3,5 @@ from .binding import (  # noqa: F401
     DECAY_NONE, DECAY_HEAD, DECAY_SCALAR, DECAY_VECTOR, LAYOUT_BHTD, LAYOUT_BTHD, FLAG_SAVE_STATES, FLAG_SAVE_ALWAYS,
     LsmError, library, kernel_path, keeps_states, lsm_chunk_fwd, lsm_chunk_bwd, lsm_bench_intra_chunk, lsm_step,
     lsm_chunk_fwd_workspace_bytes, lsm_chunk_bwd_workspace_bytes, make_params,
-    lsm_profile_start, lsm_profile_stop, lsm_chunk_workspace,
+    lsm_profile_start, lsm_profile_stop, lsm_chunk_workspace, lsm_bench_intra_chunk_workspace,
 )

@@ -65,6 +65,8 @@ def library():
     lib.lsm_keeps_states.argtypes = [pp]
     lib.lsm_step.restype = ctypes.c_int
     lib.lsm_step.argtypes = [pp] + [vp] * 7
+    lib.lsm_bench_intra_chunk_workspace_bytes.restype = sz
+    lib.lsm_bench_intra_chunk_workspace_bytes.argtypes = [pp]
     lib.lsm_bench_intra_chunk.restype = ctypes.c_int
     lib.lsm_bench_intra_chunk.argtypes = [pp] + [vp] * 6 + [sz, ctypes.c_int, vp]
     _lib = lib
@@ -248,12 +250,21 @@ def lsm_step(q, k, v, log_decay, decay_kind, state, o=None, stream=None):
 def lsm_bench_intra_chunk(q, k, v, log_decay, decay_kind, o, workspace, repeats, chunk_size=64, stream=None):
     """Benchmark aid: the intra-chunk forward kernel with its compute phase repeated ``repeats`` times.
 
-    ``workspace`` must be the one a preceding lsm_chunk_fwd call on the same inputs used."""
+    ``workspace``: at least lsm_bench_intra_chunk_workspace(...) bytes (None: allocated here)."""
     p, _, _ = _setup(q, k, v, log_decay, decay_kind, chunk_size)
+    if workspace is None:
+        workspace = lsm_bench_intra_chunk_workspace(q, k, v, log_decay, decay_kind, chunk_size)
     rc = library().lsm_bench_intra_chunk(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(o),
                                          _ptr(workspace), workspace.numel(), int(repeats), _stream_handle(stream))
     if rc != 0:
         raise LsmError(rc, "lsm_bench_intra_chunk")
+
+
+def lsm_bench_intra_chunk_workspace(q, k, v, log_decay, decay_kind, chunk_size=64):
+    import torch
+    p, _, _ = _setup(q, k, v, log_decay, decay_kind, chunk_size)
+    need = int(library().lsm_bench_intra_chunk_workspace_bytes(ctypes.byref(p)))
+    return torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
 
 
 def lsm_chunk_bwd(q, k, v, log_decay, decay_kind, d_o, chunk_size=64, init_state=None, d_final_state=None,

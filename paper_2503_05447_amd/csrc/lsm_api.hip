@@ -58,11 +58,7 @@ int check_params(const lsm_params* p, lsm::Dims* d) {
     d->N = int(n); d->kind = p->decay_kind; d->bf16 = p->dtype == LSM_DTYPE_BF16;
     d->layout = p->layout; d->nseq = p->n_seq; d->cu = p->cu_seqlens; d->cstart = nullptr;
     // Only the matrix-core kernels keep states between the two calls; elsewhere the flag changes nothing.
-    // Scalar kinds with few recurrences: a lone scan leaves most of the chip idle, and the recomputing
-    // backward pass, which runs its two scans side by side, is the faster one (measured: it wins at 32
-    // recurrences, loses at 48).
-    d->save = (p->flags & LSM_FLAG_SAVE_STATES) != 0 && lsm::mfma_supported(*d) &&
-              (d->kind == LSM_DECAY_VECTOR || d->seqs() >= 40 || (p->flags & LSM_FLAG_SAVE_ALWAYS) != 0);
+    d->save = (p->flags & LSM_FLAG_SAVE_STATES) != 0 && lsm::mfma_supported(*d);
     return LSM_OK;
 }
 
@@ -80,7 +76,7 @@ hipError_t prepare_tables(lsm::Dims& d, void*& workspace, hipStream_t stream) {
 
 extern "C" {
 
-int lsm_version(void) { return 3; }
+int lsm_version(void) { return 4; }
 
 const char* lsm_status_string(int status) {
     switch (status) {
@@ -126,7 +122,8 @@ const char* lsm_kernel_name(int kernel_id) {
     static const char* names[lsm::KID_COUNT] = {
         "generic_cumsum", "generic_chunk_state", "generic_scan", "generic_output", "generic_chunk_dstate",
         "generic_reverse_scan", "generic_grad", "head_reduce", "mfma_state_scan_fwd", "mfma_output",
-        "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep", "mfma_vector_decay_dv", "recurrent_step"};
+        "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep", "mfma_vector_decay_dv", "recurrent_step",
+        "walk_segment_summary", "walk_segment_scan", "walk_fwd", "walk_bwd_dq_dk_dv", "walk_decay_grad"};
     return kernel_id >= 0 && kernel_id < lsm::KID_COUNT ? names[kernel_id] : "unknown";
 }
 
@@ -187,6 +184,12 @@ int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void*
     return e == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
 }
 
+size_t lsm_bench_intra_chunk_workspace_bytes(const lsm_params* p) {
+    lsm::Dims d{};
+    if (check_params(p, &d) != LSM_OK || !lsm::mfma_supported(d) || d.kind == LSM_DECAY_VECTOR || d.nseq) return 0;
+    return lsm::mfma_intra_bench_workspace(d);
+}
+
 int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
                           void* o, void* workspace, size_t workspace_bytes, int repeats, void* stream) {
     lsm::Dims d{};
@@ -197,7 +200,7 @@ int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, con
     if (!lsm::mfma_supported(d) || d.kind == LSM_DECAY_VECTOR || repeats < 1 || d.nseq) return LSM_ERR_UNSUPPORTED;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_decay) || misaligned(workspace))
         return LSM_ERR_ALIGN;
-    if (!workspace || workspace_bytes < lsm_chunk_fwd_workspace_bytes(p)) return LSM_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < lsm_bench_intra_chunk_workspace_bytes(p)) return LSM_ERR_WORKSPACE;
     lsm::FwdArgs a{q, k, v, log_decay, nullptr, o, nullptr, workspace, static_cast<hipStream_t>(stream)};
     return lsm::mfma_intra_bench(d, a, repeats) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
 }

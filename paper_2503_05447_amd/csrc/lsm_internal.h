@@ -97,7 +97,8 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 // Kernel identifiers reported by the optional per-kernel timing (lsm_profile_start / _stop).
 enum KernelId {
     KID_GEN_CUMSUM = 0, KID_GEN_STATE, KID_GEN_SCAN, KID_GEN_OUTPUT, KID_GEN_DSTATE, KID_GEN_RSCAN, KID_GEN_GRAD,
-    KID_HEAD_REDUCE, KID_MFMA_STATE, KID_MFMA_OUTPUT, KID_MFMA_STATE_BWD, KID_MFMA_DSTATE, KID_MFMA_GRAD, KID_MFMA_PREP, KID_MFMA_VEC_PREP, KID_MFMA_VEC_DV, KID_STEP, KID_COUNT
+    KID_HEAD_REDUCE, KID_MFMA_STATE, KID_MFMA_OUTPUT, KID_MFMA_STATE_BWD, KID_MFMA_DSTATE, KID_MFMA_GRAD, KID_MFMA_PREP, KID_MFMA_VEC_PREP, KID_MFMA_VEC_DV, KID_STEP,
+    KID_WALK_SUMMARY, KID_WALK_SCAN, KID_WALK_FWD, KID_WALK_BWD, KID_WALK_DG, KID_COUNT
 };
 // Bracket a kernel launch with events when timing is switched on (no-ops otherwise).
 void prof_begin(int kernel_id, hipStream_t stream);
@@ -122,7 +123,8 @@ size_t mfma_bwd_workspace(const Dims& d);
 hipError_t mfma_fwd(const Dims& d, const FwdArgs& a);
 hipError_t mfma_bwd(const Dims& d, const BwdArgs& a);
 // benchmark aid: the output kernel alone with its compute phase repeated `reps` times (scalar decay kinds);
-// the workspace must hold the chunk states of a preceding mfma_fwd call on the same inputs
+// it runs the chunk-state scan itself and needs mfma_intra_bench_workspace() bytes
+size_t mfma_intra_bench_workspace(const Dims& d);
 hipError_t mfma_intra_bench(const Dims& d, const FwdArgs& a, int reps);
 
 // Recurrent single-token step (decoding): state updated in place, T of the Dims ignored.

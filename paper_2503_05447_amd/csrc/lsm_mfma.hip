@@ -21,6 +21,8 @@
 // cost two MFMAs.
 #include "lsm_mfma_dev.h"
 
+#include <atomic>
+
 namespace lsm {
 namespace {
 
@@ -808,6 +810,7 @@ __global__ __launch_bounds__(kThreads) void mk_state_pair_vec(Dims d, StateArgs 
 }
 
 #include "lsm_mfma_vec.h"
+#include "lsm_mfma_walk.h"
 
 struct Ws {
     uint16_t *states, *dstates, *states_rem, *dstates_t, *dstates_rem;
@@ -864,9 +867,67 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
     return w;
 }
 
+
+// ---- fused walkers (scalar decay kinds): segment plan and workspace
+// Segments per sequence: enough workgroups to give every compute unit one, no more (each extra segment
+// adds a share of the summary pass).  m = chunks per segment.
+constexpr int kWalkTargetWgs = 256;
+struct SegPlan { int m, nseg; };
+SegPlan seg_plan(const Dims& d) {
+    const int nmax = (d.T + C - 1) / C;  // chunks of the longest possible sequence
+    int nseg = (kWalkTargetWgs + d.seqs() - 1) / d.seqs();
+    nseg = nseg < 1 ? 1 : (nseg > nmax ? nmax : nseg);
+    const int m = (nmax + nseg - 1) / nseg;
+    return SegPlan{m, (nmax + m - 1) / m};
+}
+struct WalkWs {
+    float *bound_f, *gseg_f;                  // forward-in-time entry states (o, dq walkers) and segment decays
+    float *bound_r, *gseg_r;                  // backward-in-time entry states (dk, dv walkers)
+    float *pf, *pr, *asum, *bsum, *ych, *y0;  // decay gradient: per-token and per-chunk dot products
+    float* dgc;                               // per-head kind: per-chunk sums of dg
+    size_t bytes;
+};
+// The forward part comes first, at the same offsets in both carvings: with saved states the backward
+// call finds the entry states of the forward-in-time walkers where the forward call left them.
+WalkWs carve_walk(const Dims& d, void* ws, bool bwd) {
+    char* p = static_cast<char*>(ws);
+    size_t off = 0;
+    WalkWs w{};
+    const SegPlan sp = seg_plan(d);
+    auto take = [&](size_t bytes) { float* r = reinterpret_cast<float*>(p + off); off += align256(bytes); return r; };
+    const size_t nb = sp.nseg > 1 ? size_t(d.seqs()) * sp.nseg * D * D * 4 : 0, ng = sp.nseg > 1 ? size_t(d.seqs()) * sp.nseg * 4 : 0;
+    w.bound_f = take(nb);
+    w.gseg_f = take(ng);
+    if (bwd) {
+        w.bound_r = take(nb);
+        w.gseg_r = take(ng);
+        if (d.kind != 0) {
+            w.pf = take(size_t(d.BH()) * d.T * 4);
+            w.pr = take(size_t(d.BH()) * d.T * 4);
+            w.asum = take(size_t(d.BH()) * d.N * 4);
+            w.bsum = take(size_t(d.BH()) * d.N * 4);
+            w.ych = take(size_t(d.BH()) * d.N * 4);
+            w.y0 = take(size_t(d.seqs()) * 4);
+            if (d.kind == 1) w.dgc = take(size_t(d.BH()) * d.N * 4);
+        }
+    }
+    w.bytes = off;
+    return w;
+}
+
+// Raise a kernel's dynamic LDS limit, once per kernel and device (every kernel is always launched with the
+// same size, so the first call settles it).
 template <typename K>
 hipError_t allow_lds(K kernel, int bytes) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    static std::atomic<uint64_t> done{0};  // one flag per device and template instantiation
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = uint64_t(1) << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
 }
 
 }  // namespace
@@ -877,8 +938,14 @@ bool mfma_supported(const Dims& d) {
 }
 bool mfma_bwd_supported(const Dims& d) { return mfma_supported(d); }
 
-size_t mfma_fwd_workspace(const Dims& d) { return carve(d, nullptr, false).bytes; }
-size_t mfma_bwd_workspace(const Dims& d) { return carve(d, nullptr, true).bytes; }
+size_t mfma_fwd_workspace(const Dims& d) { return d.kind == 3 ? carve(d, nullptr, false).bytes : carve_walk(d, nullptr, d.save).bytes; }
+// chunk states and decay tables of the intra-chunk benchmark aid
+size_t mfma_intra_bench_workspace(const Dims& d0) {
+    Dims d = d0;
+    d.save = false;
+    return carve(d, nullptr, false).bytes;
+}
+size_t mfma_bwd_workspace(const Dims& d) { return d.kind == 3 ? carve(d, nullptr, true).bytes : carve_walk(d, nullptr, true).bytes; }
 
 namespace {
 template <int MODE>
@@ -967,29 +1034,108 @@ hipError_t vec_fwd(const Dims& d, const FwdArgs& a) {
 }
 }  // namespace
 
-hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
-    if (d.kind == 3) return vec_fwd(d, a);
-    Ws w = carve(d, a.ws, false);
-    const dim3 grid(d.N, d.BH()), block(kThreads);
-    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+namespace {
+// ---- fused walkers: host side
+// entry states of the segments of one direction: summary pass, then the scan over segments
+template <bool REV>
+hipError_t walk_bounds(const Dims& d, hipStream_t st, const SegPlan& sp, const uint16_t* xk, const uint16_t* xv, const float* g,
+                       const float* edge_in, float* bound, float* gseg) {
+    if (sp.nseg <= 1) return hipSuccess;
+    WalkArgs a{};
+    a.xk = xk; a.xv = xv; a.g = g; a.bound = bound; a.gseg = gseg; a.m = sp.m; a.nseg = sp.nseg;
     hipError_t e;
-    if ((e = allow_lds(mk_output<false>, kOutLds)) != hipSuccess) return e;
-    launch_prep(d, a.stream, a.g, w);
+    const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
     {
-        ProfScope ps(KID_MFMA_STATE, a.stream);
-        if (d.save) {
-            const StateArgs sa{v, k, w.wdec, w.lam, w.states_t, d.kind ? w.states_rem : nullptr, a.m0, a.mT, nullptr, 0, 0, w.states};
-            if ((e = launch_state_save(d, a.stream, sa)) != hipSuccess) return e;
-        } else if ((e = launch_state<0>(d, a.stream, StateArgs{k, v, w.wdec, w.lam, w.states, nullptr, a.m0, a.mT})) != hipSuccess) {
-            return e;
+        ProfScope ps(KID_WALK_SUMMARY, st);
+        constexpr int lds = walk_lds(false, true);
+        if (d.kind == 0) {
+            if ((e = allow_lds(mk_walk<REV, false, true>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk<REV, false, true>), grid, block, lds, st, d, a);
+        } else {
+            if ((e = allow_lds(mk_walk<REV, true, true>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk<REV, true, true>), grid, block, lds, st, d, a);
         }
     }
-    {
-        ProfScope ps(KID_MFMA_OUTPUT, a.stream);
-        hipLaunchKernelGGL(mk_output<false>, grid, block, kOutLds, a.stream, d, q, k, v, a.g, w.states_t,
-                           static_cast<uint16_t*>(a.o), 1);
+    ProfScope ps(KID_WALK_SCAN, st);
+    hipLaunchKernelGGL(mk_bound_scan<REV>, dim3(D * D / kThreads, d.seqs()), block, 0, st, d, edge_in, bound, gseg, sp.m, sp.nseg);
+    return hipSuccess;
+}
+
+hipError_t walk_fwd(const Dims& d, const FwdArgs& a) {
+    const WalkWs w = carve_walk(d, a.ws, false);
+    const SegPlan sp = seg_plan(d);
+    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    hipError_t e;
+    if ((e = walk_bounds<false>(d, a.stream, sp, k, v, a.g, a.m0, w.bound_f, w.gseg_f)) != hipSuccess) return e;
+    WalkArgs wa{};
+    wa.xq = q; wa.xk = k; wa.xv = v; wa.g = a.g; wa.out = static_cast<uint16_t*>(a.o);
+    wa.edge_in = a.m0; wa.edge_out = a.mT; wa.bound = w.bound_f; wa.m = sp.m; wa.nseg = sp.nseg;
+    const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
+    constexpr int lds = walk_lds(false, false);
+    ProfScope ps(KID_WALK_FWD, a.stream);
+    if (d.kind == 0) {
+        if ((e = allow_lds(mk_walk<false, false, false>, lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk<false, false, false>), grid, block, lds, a.stream, d, wa);
+    } else {
+        if ((e = allow_lds(mk_walk<false, true, false>, lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk<false, true, false>), grid, block, lds, a.stream, d, wa);
     }
     return hipGetLastError();
+}
+
+hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
+    const WalkWs w = carve_walk(d, a.ws, true);
+    const SegPlan sp = seg_plan(d);
+    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    auto d_o = static_cast<const uint16_t*>(a.d_o);
+    hipError_t e;
+    // entry states: forward in time from (k, v) unless the forward call left them; backward in time from (q, d_o)
+    if (!d.save && (e = walk_bounds<false>(d, a.stream, sp, k, v, a.g, a.m0, w.bound_f, w.gseg_f)) != hipSuccess) return e;
+    if ((e = walk_bounds<true>(d, a.stream, sp, q, d_o, a.g, a.d_mT, w.bound_r, w.gseg_r)) != hipSuccess) return e;
+    const bool dg = a.dg != nullptr;
+    WalkTriple t{};
+    WalkArgs& f = t.w[0];   // dq: roles (d_o, v, k), state M^T
+    f.xq = d_o; f.xk = v; f.xv = k; f.xx = q; f.g = a.g; f.out = static_cast<uint16_t*>(a.dq);
+    f.edge_in = a.m0; f.bound = w.bound_f; f.pdot = w.pf; f.isum = w.asum; f.transposed = 1; f.m = sp.m; f.nseg = sp.nseg;
+    WalkArgs& rk = t.w[1];  // dk: roles (v, d_o, q), state dM^T
+    rk.xq = v; rk.xk = d_o; rk.xv = q; rk.xx = k; rk.g = a.g; rk.out = static_cast<uint16_t*>(a.dk);
+    rk.edge_in = a.d_mT; rk.bound = w.bound_r; rk.pdot = w.pr; rk.isum = w.bsum; rk.transposed = 1; rk.m = sp.m; rk.nseg = sp.nseg;
+    WalkArgs& rv = t.w[2];  // dv: roles (k, q, d_o), state dM
+    rv.xq = k; rv.xk = q; rv.xv = d_o; rv.g = a.g; rv.out = static_cast<uint16_t*>(a.dv);
+    rv.edge_in = a.d_mT; rv.edge_out = a.d_m0; rv.bound = w.bound_r; rv.m = sp.m; rv.nseg = sp.nseg;
+    if (dg) { rv.y0 = w.y0; rv.dot_with = a.m0; }
+    const int units = d.seqs() * sp.nseg;
+    const dim3 grid(3 * units), block(kThreads);
+    {
+        ProfScope ps(KID_WALK_BWD, a.stream);
+        if (d.kind == 0) {
+            constexpr int lds = walk_lds(false, false);
+            if ((e = allow_lds(mk_walk_bwd<false, false>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_bwd<false, false>), grid, block, lds, a.stream, d, t, units);
+        } else if (!dg) {
+            constexpr int lds = walk_lds(false, false);
+            if ((e = allow_lds(mk_walk_bwd<true, false>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_bwd<true, false>), grid, block, lds, a.stream, d, t, units);
+        } else {
+            constexpr int lds = walk_lds(true, false);
+            if ((e = allow_lds(mk_walk_bwd<true, true>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_bwd<true, true>), grid, block, lds, a.stream, d, t, units);
+        }
+    }
+    if (dg) {
+        ProfScope ps(KID_WALK_DG, a.stream);
+        hipLaunchKernelGGL(mk_dg_chunks, dim3(d.seqs()), block, 0, a.stream, d, w.asum, w.bsum, w.y0, w.ych);
+        hipLaunchKernelGGL(mk_dg_tokens, dim3(d.N, d.BH()), dim3(64), 0, a.stream, d, w.pf, w.pr, w.ych,
+                           d.kind == 1 ? w.dgc : a.dg);
+        if (d.kind == 1) hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dgc, a.dg);
+    }
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t mfma_fwd(const Dims& d, const FwdArgs& a) {
+    if (d.kind == 3) return vec_fwd(d, a);
+    return walk_fwd(d, a);
 }
 
 namespace {
@@ -1038,11 +1184,17 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
 }
 }  // namespace
 
-hipError_t mfma_intra_bench(const Dims& d, const FwdArgs& a, int reps) {
-    if (d.kind == 3 || !mfma_supported(d)) return hipErrorInvalidValue;
+hipError_t mfma_intra_bench(const Dims& d0, const FwdArgs& a, int reps) {
+    if (d0.kind == 3 || !mfma_supported(d0)) return hipErrorInvalidValue;
+    Dims d = d0;
+    d.save = false;
     Ws w = carve(d, a.ws, false);
     hipError_t e;
     if ((e = allow_lds(mk_output<true>, kOutLdsRepeat)) != hipSuccess) return e;
+    // the per-chunk kernel reads materialised chunk states: decay tables and the chunk-state scan first
+    launch_prep(d, a.stream, a.g, w);
+    const StateArgs sa{static_cast<const uint16_t*>(a.k), static_cast<const uint16_t*>(a.v), w.wdec, w.lam, w.states, nullptr, a.m0, nullptr};
+    if ((e = launch_state<0>(d, a.stream, sa)) != hipSuccess) return e;
     ProfScope ps(KID_MFMA_OUTPUT, a.stream);
     hipLaunchKernelGGL(mk_output<true>, dim3(d.N, d.BH()), dim3(kThreads), kOutLdsRepeat, a.stream, d,
                        static_cast<const uint16_t*>(a.q), static_cast<const uint16_t*>(a.k),
@@ -1052,42 +1204,7 @@ hipError_t mfma_intra_bench(const Dims& d, const FwdArgs& a, int reps) {
 
 hipError_t mfma_bwd(const Dims& d, const BwdArgs& a) {
     if (d.kind == 3) return vec_bwd(d, a);
-    Ws w = carve(d, a.ws, true);
-    const dim3 grid(d.N, d.BH()), block(kThreads);
-    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
-    auto d_o = static_cast<const uint16_t*>(a.d_o);
-    hipError_t e;
-    if ((e = allow_lds(mk_grad<true>, kGradLds)) != hipSuccess) return e;
-    if ((e = allow_lds(mk_grad<false>, kGradLds)) != hipSuccess) return e;
-    if (d.save) {  // decay tables and states are the forward call's: only the reverse scan runs
-        ProfScope ps(KID_MFMA_DSTATE, a.stream);
-        if ((e = launch_state<2>(d, a.stream, StateArgs{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0})) != hipSuccess)
-            return e;
-    } else {
-        launch_prep(d, a.stream, a.g, w);
-        ProfScope ps(KID_MFMA_STATE_BWD, a.stream);
-        const StateArgs s1{v, k, w.wdec, w.lam, w.states, a.dg ? w.states_rem : nullptr, a.m0, nullptr};
-        const StateArgs s2{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0};
-        if ((e = launch_state_pair(d, a.stream, s1, s2)) != hipSuccess) return e;
-    }
-    float* dg_tok = nullptr;
-    if (a.dg) dg_tok = d.kind == 1 ? w.dg_tok : a.dg;  // per-token scalar decay: written in place
-    {
-        ProfScope ps(KID_MFMA_GRAD, a.stream);
-        if (dg_tok)
-            hipLaunchKernelGGL(mk_grad<true>, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem,
-                               w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
-                               static_cast<uint16_t*>(a.dv), dg_tok);
-        else
-            hipLaunchKernelGGL(mk_grad<false>, grid, block, kGradLds, a.stream, d, q, k, v, d_o, a.g, w.states, w.states_rem,
-                               w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
-                               static_cast<uint16_t*>(a.dv), dg_tok);
-    }
-    if (a.dg && d.kind == 1) {
-        ProfScope ps(KID_HEAD_REDUCE, a.stream);
-        hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dg_tok, a.dg);
-    }
-    return hipGetLastError();
+    return walk_bwd(d, a);
 }
 
 }  // namespace lsm

@@ -119,19 +119,23 @@ def test_binding_rejects_host_tensors():
 
 
 def test_saved_state_flags_and_workspace_sizes():
-    """One buffer serves both calls when states are kept; the size rule and the flag checks are host logic."""
+    """One buffer serves both calls when states are kept; the flag checks are host logic."""
     fwdb, bwdb = pkg.lsm_chunk_fwd_workspace_bytes, pkg.lsm_chunk_bwd_workspace_bytes
     big = dict(B=4, H=16, T=8192, d_k=128, d_v=128)
     plain, keep = P(**big), P(**big, flags=pkg.FLAG_SAVE_STATES)
-    assert fwdb(keep) == bwdb(keep) > bwdb(plain) > fwdb(plain)       # the transposed plane comes on top
-    # scalar kind with few recurrences: the library declines unless told otherwise
-    few = dict(B=1, H=16, T=8192, d_k=128, d_v=128)
-    assert fwdb(P(**few, flags=1)) == bwdb(P(**few, flags=1)) == bwdb(P(**few))
-    assert fwdb(P(**few, flags=3)) == bwdb(P(**few, flags=3)) > bwdb(P(**few))
-    assert fwdb(P(**few, decay_kind=3, flags=1)) > bwdb(P(**few, decay_kind=3))   # vector kind: always kept
+    assert fwdb(keep) == bwdb(keep) == bwdb(plain) > fwdb(plain) > 0   # the backward carving starts with the forward's
+    assert pkg.keeps_states(keep) == 1 and pkg.keeps_states(plain) == 0
+    # scalar kinds keep one state per segment of chunks, not one per chunk: a fraction of the inputs' size
+    assert fwdb(plain) < 4 * 16 * 8192 * 128 * 2 // 4
+    assert pkg.keeps_states(P(**big, decay_kind=3, flags=1)) == 1
+    assert fwdb(P(**big, decay_kind=3, flags=1)) > bwdb(P(**big, decay_kind=3))   # vector kind: chunk states in both orders
     # kernels that keep nothing: the one buffer is the larger of the two
     gen = dict(B=2, H=2, T=300, d_k=64, d_v=64, dtype=0)
+    assert pkg.keeps_states(P(**gen, flags=1)) == 0
     assert fwdb(P(**gen, flags=3)) == bwdb(P(**gen, flags=3)) == max(fwdb(P(**gen)), bwdb(P(**gen)))
+    # benchmark aid: its own workspace figure, zero where it does not apply
+    aid = pkg.library().lsm_bench_intra_chunk_workspace_bytes
+    assert aid(ctypes.byref(plain)) >= 4 * 16 * 128 * 128 * 128 * 2 and aid(ctypes.byref(P(**gen))) == 0
     ERR_UNSUP = -3
     assert fwd(P(flags=2)) == ERR_UNSUP          # "always" without the flag it qualifies
     assert fwd(P(flags=4)) == ERR_UNSUP
