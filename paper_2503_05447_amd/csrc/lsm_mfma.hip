@@ -869,9 +869,9 @@ Ws carve(const Dims& d, void* ws, bool bwd) {
 
 
 // ---- fused walkers (scalar decay kinds): segment plan and workspace
-// Segments per sequence: enough workgroups to give every compute unit one, no more (each extra segment
-// adds a share of the summary pass).  m = chunks per segment.
-constexpr int kWalkTargetWgs = 256;
+// Segments per sequence: enough workgroups to give every compute unit two (the walkers fit two to a
+// unit, and one hides the other's waits), no more (each extra segment adds a share of the summary pass).  m = chunks per segment.
+constexpr int kWalkTargetWgs = 512;
 struct SegPlan { int m, nseg; };
 SegPlan seg_plan(const Dims& d) {
     const int nmax = (d.T + C - 1) / C;  // chunks of the longest possible sequence
@@ -881,14 +881,14 @@ SegPlan seg_plan(const Dims& d) {
     return SegPlan{m, (nmax + m - 1) / m};
 }
 struct WalkWs {
-    float *bound_f, *gseg_f;                  // forward-in-time entry states (o, dq walkers) and segment decays
-    float *bound_r, *gseg_r;                  // backward-in-time entry states (dk, dv walkers)
-    float *pf, *pr, *asum, *bsum, *ych, *y0;  // decay gradient: per-token and per-chunk dot products
-    float* dgc;                               // per-head kind: per-chunk sums of dg
+    float *bound_f, *gseg_f;     // entry states of the segments (forward in time) and the segments' total log-decays
+    uint16_t* dstates;           // backward: one state gradient per chunk (fragment-major bf16)
+    float *wdec, *winc, *lam;    // backward: decay tables of the reverse scan
+    float* dgc;                  // per-head kind: per-chunk sums of dg
     size_t bytes;
 };
 // The forward part comes first, at the same offsets in both carvings: with saved states the backward
-// call finds the entry states of the forward-in-time walkers where the forward call left them.
+// call finds the entry states where the forward call left them.
 WalkWs carve_walk(const Dims& d, void* ws, bool bwd) {
     char* p = static_cast<char*>(ws);
     size_t off = 0;
@@ -899,17 +899,13 @@ WalkWs carve_walk(const Dims& d, void* ws, bool bwd) {
     w.bound_f = take(nb);
     w.gseg_f = take(ng);
     if (bwd) {
-        w.bound_r = take(nb);
-        w.gseg_r = take(ng);
+        w.dstates = reinterpret_cast<uint16_t*>(take(size_t(d.BH()) * d.N * D * D * 2));
         if (d.kind != 0) {
-            w.pf = take(size_t(d.BH()) * d.T * 4);
-            w.pr = take(size_t(d.BH()) * d.T * 4);
-            w.asum = take(size_t(d.BH()) * d.N * 4);
-            w.bsum = take(size_t(d.BH()) * d.N * 4);
-            w.ych = take(size_t(d.BH()) * d.N * 4);
-            w.y0 = take(size_t(d.seqs()) * 4);
-            if (d.kind == 1) w.dgc = take(size_t(d.BH()) * d.N * 4);
+            w.wdec = take(size_t(d.BH()) * d.N * C * 4);
+            w.winc = take(size_t(d.BH()) * d.N * C * 4);
+            w.lam = take(size_t(d.BH()) * d.N * 4);
         }
+        if (d.kind == 1) w.dgc = take(size_t(d.BH()) * d.N * 4);
     }
     w.bytes = off;
     return w;
@@ -1089,45 +1085,37 @@ hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     auto d_o = static_cast<const uint16_t*>(a.d_o);
     hipError_t e;
-    // entry states: forward in time from (k, v) unless the forward call left them; backward in time from (q, d_o)
+    // state gradients: the reverse scan leaves one per chunk (and d_init_state)
+    if (d.kind != 0) {
+        ProfScope ps(KID_MFMA_PREP, a.stream);
+        hipLaunchKernelGGL(mk_decay_prep, dim3(d.N, d.BH()), dim3(64), 0, a.stream, d, a.g, w.wdec, w.winc, w.lam);
+    }
+    {
+        ProfScope ps(KID_MFMA_DSTATE, a.stream);
+        if ((e = launch_state<2>(d, a.stream, StateArgs{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0})) != hipSuccess)
+            return e;
+    }
+    // entry states of the segments, unless the forward call left them
     if (!d.save && (e = walk_bounds<false>(d, a.stream, sp, k, v, a.g, a.m0, w.bound_f, w.gseg_f)) != hipSuccess) return e;
-    if ((e = walk_bounds<true>(d, a.stream, sp, q, d_o, a.g, a.d_mT, w.bound_r, w.gseg_r)) != hipSuccess) return e;
-    const bool dg = a.dg != nullptr;
-    WalkTriple t{};
-    WalkArgs& f = t.w[0];   // dq: roles (d_o, v, k), state M^T
-    f.xq = d_o; f.xk = v; f.xv = k; f.xx = q; f.g = a.g; f.out = static_cast<uint16_t*>(a.dq);
-    f.edge_in = a.m0; f.bound = w.bound_f; f.pdot = w.pf; f.isum = w.asum; f.transposed = 1; f.m = sp.m; f.nseg = sp.nseg;
-    WalkArgs& rk = t.w[1];  // dk: roles (v, d_o, q), state dM^T
-    rk.xq = v; rk.xk = d_o; rk.xv = q; rk.xx = k; rk.g = a.g; rk.out = static_cast<uint16_t*>(a.dk);
-    rk.edge_in = a.d_mT; rk.bound = w.bound_r; rk.pdot = w.pr; rk.isum = w.bsum; rk.transposed = 1; rk.m = sp.m; rk.nseg = sp.nseg;
-    WalkArgs& rv = t.w[2];  // dv: roles (k, q, d_o), state dM
-    rv.xq = k; rv.xk = q; rv.xv = d_o; rv.g = a.g; rv.out = static_cast<uint16_t*>(a.dv);
-    rv.edge_in = a.d_mT; rv.edge_out = a.d_m0; rv.bound = w.bound_r; rv.m = sp.m; rv.nseg = sp.nseg;
-    if (dg) { rv.y0 = w.y0; rv.dot_with = a.m0; }
-    const int units = d.seqs() * sp.nseg;
-    const dim3 grid(3 * units), block(kThreads);
+    GradArgs ga{q, k, v, d_o, a.g, w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv),
+                a.dg ? (d.kind == 1 ? w.dgc : a.dg) : nullptr, a.m0, w.bound_f, sp.m, sp.nseg};
+    const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
     {
         ProfScope ps(KID_WALK_BWD, a.stream);
         if (d.kind == 0) {
-            constexpr int lds = walk_lds(false, false);
-            if ((e = allow_lds(mk_walk_bwd<false, false>, lds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((mk_walk_bwd<false, false>), grid, block, lds, a.stream, d, t, units);
-        } else if (!dg) {
-            constexpr int lds = walk_lds(false, false);
-            if ((e = allow_lds(mk_walk_bwd<true, false>, lds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((mk_walk_bwd<true, false>), grid, block, lds, a.stream, d, t, units);
+            if ((e = allow_lds(mk_walk_grad<false, false>, kWalkGradLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_grad<false, false>), grid, block, kWalkGradLds, a.stream, d, ga);
+        } else if (!a.dg) {
+            if ((e = allow_lds(mk_walk_grad<true, false>, kWalkGradLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_grad<true, false>), grid, block, kWalkGradLds, a.stream, d, ga);
         } else {
-            constexpr int lds = walk_lds(true, false);
-            if ((e = allow_lds(mk_walk_bwd<true, true>, lds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((mk_walk_bwd<true, true>), grid, block, lds, a.stream, d, t, units);
+            if ((e = allow_lds(mk_walk_grad<true, true>, kWalkGradLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_grad<true, true>), grid, block, kWalkGradLds, a.stream, d, ga);
         }
     }
-    if (dg) {
-        ProfScope ps(KID_WALK_DG, a.stream);
-        hipLaunchKernelGGL(mk_dg_chunks, dim3(d.seqs()), block, 0, a.stream, d, w.asum, w.bsum, w.y0, w.ych);
-        hipLaunchKernelGGL(mk_dg_tokens, dim3(d.N, d.BH()), dim3(64), 0, a.stream, d, w.pf, w.pr, w.ych,
-                           d.kind == 1 ? w.dgc : a.dg);
-        if (d.kind == 1) hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dgc, a.dg);
+    if (a.dg && d.kind == 1) {
+        ProfScope ps(KID_HEAD_REDUCE, a.stream);
+        hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dgc, a.dg);
     }
     return hipGetLastError();
 }

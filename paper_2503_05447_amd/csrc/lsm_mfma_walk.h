@@ -48,15 +48,25 @@ struct WalkArgs {
     int m, nseg;           // chunks per segment, segments per sequence (upper bound for packed input)
 };
 
-// tile rows in walk order: row r holds token r (forward) or token L-1-r (backward); rows >= L are zero
-template <bool REV>
+// tile rows in walk order: row r holds token r (forward) or token L-1-r (backward); rows >= L are zero.
+// NT threads share a tile: 1024 / NT pieces of 16 bytes each.
+template <bool REV, int NT>
 __device__ __forceinline__ void walk_gload(TileRegs& r, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
-    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-        const int p = tid + kThreads * it, row = min(p >> 4, L - 1), cp = p & 15;
+    _Pragma("unroll") for (int it = 0; it < 1024 / NT; ++it) {
+        const int p = tid + NT * it, row = min(p >> 4, L - 1), cp = p & 15;
         const int tok = REV ? L - 1 - row : row;
         r.v[it] = *reinterpret_cast<const u32x4*>(src + (tok0 + size_t(tok) * ts) * D + cp * 8);
     }
 }
+template <int NT>
+__device__ __forceinline__ void walk_commit(uint16_t* dst, const TileRegs& r, int L, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 1024 / NT; ++it) {
+        const int p = tid + NT * it, row = p >> 4, cp = p & 15;
+        const uint32_t keep = row < L ? 0xffffffffu : 0u;
+        *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{r.v[it].x & keep, r.v[it].y & keep, r.v[it].z & keep, r.v[it].w & keep};
+    }
+}
+// 256 threads store an output stage
 template <bool REV>
 __device__ __forceinline__ void walk_store(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
@@ -93,22 +103,184 @@ __device__ __forceinline__ void walk_mask(f32x16& acc, int m0, int ncol, const f
     }
 }
 
-constexpr int kWalkTiles = 3;  // Q (later the output stage), K, V; DG adds X
 __host__ __device__ constexpr int walk_lds(bool dg, bool summary) {
     return summary ? 2 * C * LD * 2 + (2 * C + 8) * 4
-                   : ((dg ? 4 : 3) * C * LD + 2 * C * LDP) * 2 + (2 * C + 8) * 4 + (dg ? 4 * 2 * C * 4 : 0);
+                   : (3 * C * LD + 2 * C * LDP) * 2 + (2 * C + 8) * 4 + (dg ? 4 * 2 * C * 4 : 0);
+}
+
+// Rows of the tensor dotted with the output (decay gradient), straight from global memory in the
+// layout of an output block: for token 32 jb + n the features 32 wave + 8 gg + 4 half + 0..3.  Rows
+// beyond the ragged end repeat the last valid row (their output rows are zero).
+struct DotRegs { u32x2 v[2][4]; };
+template <bool REV>
+__device__ __forceinline__ void dot_gload(DotRegs& r, const uint16_t* src, size_t tok0, int ts, int L, int wave, int n, int half) {
+    _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+        const int row = min(32 * jb + n, L - 1), tok = REV ? L - 1 - row : row;
+        const uint16_t* p = src + (tok0 + size_t(tok) * ts) * D + 32 * wave + 4 * half;
+        _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) r.v[jb][gg] = *reinterpret_cast<const u32x2*>(p + 8 * gg);
+    }
+}
+__device__ __forceinline__ float dot_rows(const DotRegs& r, int jb, const f32x16& a) {
+    float s = 0.f;
+    _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
+        const u32x2 x = r.v[jb][gg];
+        s += bf16_lo(x.x) * a[4 * gg] + bf16_hi(x.x) * a[4 * gg + 1] + bf16_lo(x.y) * a[4 * gg + 2] + bf16_hi(x.y) * a[4 * gg + 3];
+    }
+    return s;
+}
+
+// D[m][n] = sum_f Am[m0 + m][f] * Bm[n0 + n][f] over the 128 features of two row-major LDS tiles, the
+// fragments requested four k-steps at a time (a lower register peak than all sixteen at once)
+__device__ __forceinline__ f32x16 score_block2(const uint16_t* Am, int m0, const uint16_t* Bm, int n0, int n, int half) {
+    f32x16 acc = {0};
+    _Pragma("unroll") for (int h4 = 0; h4 < 2; ++h4) {
+        bf16x8 fa[4], fb[4];
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+            fa[ks] = frag(Am, LD, m0 + n, 16 * (4 * h4 + ks) + 8 * half);
+            fb[ks] = frag(Bm, LD, n0 + n, 16 * (4 * h4 + ks) + 8 * half);
+        }
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) acc = mfma(fa[ks], fb[ks], acc);
+    }
+    return acc;
+}
+
+// ---- the four contractions of one chunk for the wave that owns value features [32 w4, 32 w4 + 32)
+// state block ib: S[ib][4g+j] = state[key feature 32 ib + 8g + 4 half + j][value feature 32 w4 + n]
+
+// inter: O^T[v][j] = e^{beta_j} sum_i S[i][v] q_j[i], the state blocks as A operands straight from the
+// accumulators (bf16 head + remainder), the query rows read in the matching k order
+template <bool DEC>
+__device__ __forceinline__ void walk_inter(f32x16 (&O)[2], const f32x16 (&S)[4], const uint16_t* Q, const float* bs, int n, int half) {
+    O[0] = f32x16{0};
+    O[1] = f32x16{0};
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+        _Pragma("unroll") for (int p = 0; p < 2; ++p) {
+            u32x4 hi, lo;
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {
+                const float x0 = S[ib][8 * p + 2 * e], x1 = S[ib][8 * p + 2 * e + 1];
+                hi[e] = pack2(x0, x1);
+                lo[e] = pack2(x0 - bf16_lo(hi[e]), x1 - bf16_hi(hi[e]));
+            }
+            const bf16x8 sh = __builtin_bit_cast(bf16x8, hi), sl = __builtin_bit_cast(bf16x8, lo);
+            const bf16x8 qf0 = frag_perm(Q, LD, n, 32 * ib + 16 * p, half);
+            const bf16x8 qf1 = frag_perm(Q, LD, 32 + n, 32 * ib + 16 * p, half);
+            O[0] = mfma(sh, qf0, O[0]);
+            O[1] = mfma(sh, qf1, O[1]);
+            O[0] = mfma(sl, qf0, O[0]);
+            O[1] = mfma(sl, qf1, O[1]);
+        }
+    if (DEC) {
+        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+            const float w = __expf(bs[32 * jb + n]);
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) O[jb][x] *= w;
+        }
+    }
+}
+// scores: each of the three 32 x 32 blocks on or below the diagonal by one wave (w4 = 0: (0,0), 1: (1,0),
+// 2: (1,1)), mask and decay on its accumulators, handed to the others through LDS as head + remainder
+template <bool DEC>
+__device__ __forceinline__ void walk_scores(const uint16_t* K, const uint16_t* Q, uint16_t* Ph, uint16_t* Pl, const float* bs,
+                                            int w4, int n, int half) {
+    if (w4 >= 3) return;
+    const int pjb = w4 ? 1 : 0, prb = w4 == 2 ? 1 : 0;
+    f32x16 P = score_block2(K, 32 * prb, Q, 32 * pjb, n, half);  // D[m = r][n = j] = k_r . q_j
+    walk_mask<DEC>(P, 32 * prb, 32 * pjb + n, bs, half);
+    store_block_t_split(Ph, Pl, LDP, 32 * pjb + n, 32 * prb, half, P);
+}
+// intra: O^T[v][j] += sum_{r <= j} V^T[v][r] P[j][r] for the query block jb
+__device__ __forceinline__ void walk_intra(f32x16& O, int jb, const uint16_t* V, const uint16_t* Ph, const uint16_t* Pl, int w4,
+                                           int lane, int n, int half) {
+    const int j = 32 * jb + n;
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+        if (ks >= 2 * (jb + 1)) break;  // keys r >= 32 never reach queries j < 32
+        const bf16x8 vt = frag_tr(V, LD, 16 * ks, 32 * w4, lane);
+        O = mfma(vt, frag(Ph, LDP, j, 16 * ks + 8 * half), O);
+        O = mfma(vt, frag(Pl, LDP, j, 16 * ks + 8 * half), O);
+    }
+}
+// state: S[i][v] = e^{b_C} S[i][v] + sum_t K^T[i][t] (wo_t V[t][v]); the weighted value slice of this wave is
+// split into head + remainder in registers.  SCALE = false: the weights already carry every decay.
+template <bool DEC, bool SCALE>
+__device__ __forceinline__ void walk_update(f32x16 (&S)[4], const uint16_t* K, const uint16_t* V, const float* wo, float bC, int w4,
+                                            int lane, int half) {
+    if (DEC && SCALE) {
+        const float lam = __expf(bC);
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) S[ib][x] *= lam;
+    }
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+        const u32x4 raw = __builtin_bit_cast(u32x4, frag_tr(V, LD, 16 * ks, 32 * w4, lane));
+        u32x4 hi = raw, lo = {0, 0, 0, 0};
+        if (DEC) {
+            const float4 w0 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half);
+            const float4 w1 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half + 4);
+            const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            _Pragma("unroll") for (int p = 0; p < 4; ++p) {
+                const float x0 = bf16_lo(raw[p]) * w[2 * p], x1 = bf16_hi(raw[p]) * w[2 * p + 1];
+                hi[p] = pack2(x0, x1);
+                lo[p] = pack2(x0 - bf16_lo(hi[p]), x1 - bf16_hi(hi[p]));
+            }
+        }
+        const bf16x8 vh = __builtin_bit_cast(bf16x8, hi), vl = __builtin_bit_cast(bf16x8, lo);
+        bf16x8 ka[4];
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) ka[ib] = frag_tr(K, LD, 16 * ks, 32 * ib, lane);
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(ka[ib], vh, S[ib]);
+        if (DEC) {
+            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(ka[ib], vl, S[ib]);
+        }
+    }
+}
+// chunk-local decay tables by one wave: beta (inclusive running sum of the log-decays in walk order, exclusive
+// when walking backward), b_C, and the weights wo = e^{b_C - beta + extra} of the state update
+template <bool REV>
+__device__ __forceinline__ float walk_decay_tables(float gval, int L, float extra, float* bs, float* wo, int lane) {
+    const float x = lane < L ? gval : 0.f;
+    float inc = x;
+    for (int off = 1; off < 64; off <<= 1) {
+        const float y = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += y;
+    }
+    const float bC = __shfl(inc, 63, 64), beta = REV ? inc - x : inc;
+    bs[lane] = beta;
+    wo[lane] = __expf(bC - beta + extra);
+    if (lane == 0) bs[C] = bC;
+    return bC;
+}
+// state block layout <-> the [i][v] fp32 arrays (transposed: the walker's state is the transpose of the array)
+__device__ __forceinline__ void walk_state_load(f32x16 (&S)[4], const float* e, bool transposed, int w4, int n, int half) {
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+            const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * w4 + n;
+            S[ib][x] = transposed ? e[nn * D + mm] : e[mm * D + nn];
+        }
+}
+__device__ __forceinline__ void walk_state_store(const f32x16 (&S)[4], float* e, bool transposed, int w4, int n, int half) {
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+            const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * w4 + n;
+            e[transposed ? nn * D + mm : mm * D + nn] = S[ib][x];
+        }
+}
+__device__ __forceinline__ float walk_state_dot(const f32x16 (&S)[4], const float* e, bool transposed, int w4, int n, int half) {
+    float z = 0.f;
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+            const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * w4 + n;
+            z += S[ib][x] * e[transposed ? nn * D + mm : mm * D + nn];
+        }
+    for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
+    return z;
 }
 
 // REV: walk backward in time.  DEC: a decay is present.  DG: emit the dot products of the decay
 // gradient (needs a.xx).  SUMMARY: the state update alone, from a zero state, result to a.bound / a.gseg.
 template <bool REV, bool DEC, bool DG, bool SUMMARY>
 __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int seq, int seg, unsigned char* smem) {
-    // LDS: SUMMARY: K | V | bs | wo;   else: Q | K | V | (X) | P head | P remainder | bs | wo | (red)
+    // LDS: SUMMARY: K | V | bs | wo;   else: Q | K | V | P head | P remainder | bs | wo | (red)
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = SUMMARY ? Q : Q + C * LD;
     uint16_t* V = K + C * LD;
-    uint16_t* X = V + C * LD;
-    uint16_t* Ph = (DG ? X : V) + C * LD;
+    uint16_t* Ph = V + C * LD;
     uint16_t* Pl = Ph + C * LDP;
     float* bs = reinterpret_cast<float*>(SUMMARY ? V + C * LD : Pl + C * LDP);  // beta[64], then b_C
     float* wo = bs + C + 4;                                                      // e^{b_C - beta}[64]
@@ -128,113 +300,58 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
     }
     const bool last = empty_seq || (REV ? seg == 0 : seg == nsq - 1);  // this walk ends the sequence
 
-    // state block ib of this wave: S[ib][4g+j] = state[key feature 32 ib + 8g + 4 half + j][value feature 32 wave + n]
     f32x16 S[4];
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
     if (!SUMMARY) {
         const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
                                       : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-        if (ein) {
-            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-                    const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * wave + n;
-                    S[ib][x] = a.transposed ? ein[nn * D + mm] : ein[mm * D + nn];
-                }
-        }
+        if (ein) walk_state_load(S, ein, a.transposed, wave, n, half);
     }
 
-    TileRegs rq, rk, rv, rx;
+    TileRegs rq, rk, rv;
+    DotRegs rx;
     float gval = 0.f, gtot = 0.f;
-    ChunkPos cp{};
-    auto chunk_of = [&](int kk) { return REV ? kend - 1 - kk : kbeg + kk; };
+    // The summary pass visits the chunks of its segment in the order opposite to the walk (a sum: each
+    // chunk's weights carry the decay of the chunks that follow it in walk order), so that the walker,
+    // which runs next, starts with the rows read last.
+    auto chunk_of = [&](int kk) { return (REV != SUMMARY) ? kend - 1 - kk : kbeg + kk; };
     auto gload = [&](int kk) {
         const ChunkPos p = walk_pos(d, walk, chunk_of(min(kk, cnt - 1)));
         if (DEC) {
             const int row = min(lane, p.L - 1), tok = REV ? p.L - 1 - row : row;
             gval = a.g[d.kind == 1 ? size_t(walk.bh % d.H) : p.tok0 + size_t(tok) * p.ts];
         }
-        if (!SUMMARY) walk_gload<REV>(rq, a.xq, p.tok0, p.ts, p.L, tid);
-        walk_gload<REV>(rk, a.xk, p.tok0, p.ts, p.L, tid);
-        walk_gload<REV>(rv, a.xv, p.tok0, p.ts, p.L, tid);
-        if (DG) walk_gload<REV>(rx, a.xx, p.tok0, p.ts, p.L, tid);
+        if (!SUMMARY) walk_gload<REV, kThreads>(rq, a.xq, p.tok0, p.ts, p.L, tid);
+        walk_gload<REV, kThreads>(rk, a.xk, p.tok0, p.ts, p.L, tid);
+        walk_gload<REV, kThreads>(rv, a.xv, p.tok0, p.ts, p.L, tid);
     };
     if (cnt > 0) gload(0);
 
     for (int kk = 0; kk < cnt; ++kk) {
-        cp = walk_pos(d, walk, chunk_of(kk));
+        const ChunkPos cp = walk_pos(d, walk, chunk_of(kk));
         const int L = cp.L;
         // ---- registers of this chunk -> LDS; decay tables; loads of the next chunk
-        if (!SUMMARY) tile_commit(Q, rq, L, tid);
-        tile_commit(K, rk, L, tid);
-        tile_commit(V, rv, L, tid);
-        if (DG) tile_commit(X, rx, L, tid);
-        if (DEC) {
-            if (wave == 0) {
-                const float x = lane < L ? gval : 0.f;
-                float inc = x;
-                for (int off = 1; off < 64; off <<= 1) {
-                    const float y = __shfl_up(inc, off, 64);
-                    if (lane >= off) inc += y;
-                }
-                const float bC = __shfl(inc, 63, 64), beta = REV ? inc - x : inc;
-                bs[lane] = beta;
-                wo[lane] = __expf(bC - beta);
-                if (lane == 0) bs[C] = bC;
-                gtot += bC;
-            }
-        }
+        if (!SUMMARY) walk_commit<kThreads>(Q, rq, L, tid);
+        walk_commit<kThreads>(K, rk, L, tid);
+        walk_commit<kThreads>(V, rv, L, tid);
+        if (DEC && wave == 0) gtot += walk_decay_tables<REV>(gval, L, SUMMARY ? gtot : 0.f, bs, wo, lane);
         gload(kk + 1);
+        // needed only after the scores: no copy in LDS, no prefetch registers
+        if (DG) dot_gload<REV>(rx, a.xx, cp.tok0, cp.ts, L, wave, n, half);
         __syncthreads();  // (A) tiles and decay tables of this chunk are in LDS
         const float bC = DEC ? bs[C] : 0.f;
 
-        f32x16 O[2];
-        float isp[2] = {0.f, 0.f};
         if (!SUMMARY) {
-            // ---- inter: O^T[v][j] = e^{beta_j} sum_i S[i][v] q_j[i], the state blocks as A operands straight
-            // from the accumulators (head + remainder), the query rows read in the matching k order
-            O[0] = f32x16{0};
-            O[1] = f32x16{0};
-            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-                _Pragma("unroll") for (int p = 0; p < 2; ++p) {
-                    u32x4 hi, lo;
-                    _Pragma("unroll") for (int e = 0; e < 4; ++e) {
-                        const float x0 = S[ib][8 * p + 2 * e], x1 = S[ib][8 * p + 2 * e + 1];
-                        hi[e] = pack2(x0, x1);
-                        lo[e] = pack2(x0 - bf16_lo(hi[e]), x1 - bf16_hi(hi[e]));
-                    }
-                    const bf16x8 sh = __builtin_bit_cast(bf16x8, hi), sl = __builtin_bit_cast(bf16x8, lo);
-                    _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                        const bf16x8 qf = frag_perm(Q, LD, 32 * jb + n, 32 * ib + 16 * p, half);
-                        O[jb] = mfma(sh, qf, O[jb]);
-                        O[jb] = mfma(sl, qf, O[jb]);
-                    }
-                }
-            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                if (DEC) {
-                    const float w = __expf(bs[32 * jb + n]);
-                    _Pragma("unroll") for (int x = 0; x < 16; ++x) O[jb][x] *= w;
-                }
-                if (DG) isp[jb] = row_dot(X, 32 * jb + n, wave, half, O[jb]);
-            }
-            // ---- scores: each of the three 32 x 32 blocks on or below the diagonal by one wave
-            const int pjb = wave ? 1 : 0, prb = wave == 2 ? 1 : 0;  // wave 0: (0,0), wave 1: (1,0), wave 2: (1,1)
-            if (wave < 3) {
-                f32x16 P = score_block(K, 32 * prb, Q, 32 * pjb, n, half);  // D[m = r][n = j] = k_r . q_j
-                walk_mask<DEC>(P, 32 * prb, 32 * pjb + n, bs, half);
-                store_block_t_split(Ph, Pl, LDP, 32 * pjb + n, 32 * prb, half, P);
-            }
+            f32x16 O[2];
+            walk_inter<DEC>(O, S, Q, bs, n, half);
+            walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
             __syncthreads();  // (C) scores are in LDS; nobody reads Q any more
-            // ---- intra: O^T[v][j] += sum_{r <= j} V^T[v][r] P[j][r]
-            float pdp[2] = {0.f, 0.f};
+            float pdp[2] = {0.f, 0.f}, isp[2] = {0.f, 0.f};
             _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                const int j = 32 * jb + n;
-                _Pragma("unroll") for (int ks = 0; ks < 2 * (jb + 1); ++ks) {  // keys r >= 32 never reach queries j < 32
-                    const bf16x8 vt = frag_tr(V, LD, 16 * ks, 32 * wave, lane);
-                    O[jb] = mfma(vt, frag(Ph, LDP, j, 16 * ks + 8 * half), O[jb]);
-                    O[jb] = mfma(vt, frag(Pl, LDP, j, 16 * ks + 8 * half), O[jb]);
-                }
-                if (DG) pdp[jb] = row_dot(X, j, wave, half, O[jb]);
-                store_packed(stage, LD, j, 32 * wave, half, pack_block(O[jb]));
+                if (DG) isp[jb] = dot_rows(rx, jb, O[jb]);
+                walk_intra(O[jb], jb, V, Ph, Pl, wave, lane, n, half);
+                if (DG) pdp[jb] = dot_rows(rx, jb, O[jb]);
+                store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
             }
             if (DG) {
                 _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
@@ -246,36 +363,10 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
                 }
             }
         }
-        // ---- state: S[i][v] = e^{b_C} S[i][v] + sum_t K^T[i][t] (e^{b_C - beta_t} V[t][v]); the weighted value
-        // slice of this wave is split into head + remainder in registers
-        if (DEC) {
-            const float lam = __expf(bC);
-            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) S[ib][x] *= lam;
-        }
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
-            const u32x4 raw = __builtin_bit_cast(u32x4, frag_tr(V, LD, 16 * ks, 32 * wave, lane));
-            u32x4 hi = raw, lo = {0, 0, 0, 0};
-            if (DEC) {
-                const float4 w0 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half);
-                const float4 w1 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half + 4);
-                const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-                _Pragma("unroll") for (int p = 0; p < 4; ++p) {
-                    const float x0 = bf16_lo(raw[p]) * w[2 * p], x1 = bf16_hi(raw[p]) * w[2 * p + 1];
-                    hi[p] = pack2(x0, x1);
-                    lo[p] = pack2(x0 - bf16_lo(hi[p]), x1 - bf16_hi(hi[p]));
-                }
-            }
-            const bf16x8 vh = __builtin_bit_cast(bf16x8, hi), vl = __builtin_bit_cast(bf16x8, lo);
-            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) {
-                const bf16x8 ka = frag_tr(K, LD, 16 * ks, 32 * ib, lane);
-                S[ib] = mfma(ka, vh, S[ib]);
-                if (DEC) S[ib] = mfma(ka, vl, S[ib]);
-            }
-        }
+        walk_update<DEC, !SUMMARY>(S, K, V, wo, bC, wave, lane, half);
         __syncthreads();  // (D) the output stage is complete and every read of this chunk's tiles is done
         if (!SUMMARY) {
-            // every thread reads back exactly the stage pieces that its own next tile_commit overwrites: no barrier
+            // every thread reads back exactly the stage pieces that its own next walk_commit overwrites: no barrier
             walk_store<REV>(a.out, stage, cp.tok0, cp.ts, L, tid);
             if (DG && tid < 64) {
                 float pd = 0.f, is = 0.f;
@@ -292,36 +383,138 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
 
     // ---- the state this walk ends with
     if (SUMMARY) {
-        float* e = a.bound + (size_t(seq) * a.nseg + (REV ? seg - 1 : seg + 1)) * D * D;
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-            _Pragma("unroll") for (int x = 0; x < 16; ++x)
-                e[(32 * ib + 8 * (x >> 2) + 4 * half + (x & 3)) * D + 32 * wave + n] = S[ib][x];
+        walk_state_store(S, a.bound + (size_t(seq) * a.nseg + (REV ? seg - 1 : seg + 1)) * D * D, false, wave, n, half);
         if (tid == 0) a.gseg[size_t(seq) * a.nseg + seg] = gtot;
         return;
     }
-    if (last && a.edge_out) {
-        float* e = a.edge_out + size_t(seq) * D * D;
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-                const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * wave + n;
-                e[a.transposed ? nn * D + mm : mm * D + nn] = S[ib][x];
-            }
-    }
+    if (last && a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, a.transposed, wave, n, half);
     if (last && a.y0) {
-        float z = 0.f;
-        if (a.dot_with) {
-            const float* w = a.dot_with + size_t(seq) * D * D;
-            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-                    const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * wave + n;
-                    z += S[ib][x] * w[a.transposed ? nn * D + mm : mm * D + nn];
-                }
-        }
-        for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
+        const float z = a.dot_with ? walk_state_dot(S, a.dot_with + size_t(seq) * D * D, a.transposed, wave, n, half) : 0.f;
         __syncthreads();  // the decay tables of the last chunk have been read by everyone
         if (lane == 0) wo[wave] = z;
         __syncthreads();
         if (tid == 0) a.y0[seq] = (wo[0] + wo[1]) + (wo[2] + wo[3]);
+    }
+}
+
+// The two backward-in-time walkers of the backward pass as one workgroup of eight waves: waves 0-3
+// compute dv (roles k, q, d_o; state dM), waves 4-7 compute dk (roles v, d_o, q; state dM^T; with DG
+// also k_t . dk_t and b_c).  They need the same four tiles, which are loaded once; each half keeps its
+// own copy of the state.
+constexpr int kPairThreads = 2 * kThreads;
+__host__ __device__ constexpr int walk_pair_lds() {
+    return (4 * C * LD + 4 * C * LDP + 2 * C * LD) * 2 + (2 * C + 8) * 4 + 4 * 2 * C * 4;
+}
+template <bool DEC, bool DG>
+__device__ __forceinline__ void walk_pair_body(const Dims& d, const WalkArgs& av, const WalkArgs& ak, int seq, int seg,
+                                               unsigned char* smem) {
+    constexpr bool REV = true;
+    // LDS: q | k | v | d_o | P of dv (head, remainder) | P of dk | stage of dv | stage of dk | bs | wo | red
+    uint16_t* Tq = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Tk = Tq + C * LD;
+    uint16_t* Tv = Tk + C * LD;
+    uint16_t* To = Tv + C * LD;
+    uint16_t* Pbase = To + C * LD;
+    uint16_t* Sbase = Pbase + 4 * C * LDP;
+    float* bs = reinterpret_cast<float*>(Sbase + 2 * C * LD);
+    float* wo = bs + C + 4;
+    float* red = wo + C + 4;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int role = wave >> 2, w4 = wave & 3, rtid = tid & (kThreads - 1);  // role 0: dv, role 1: dk
+    const WalkArgs& a = role ? ak : av;
+    const uint16_t* Q = role ? Tv : Tk;   // query role
+    const uint16_t* K = role ? To : Tq;   // key role
+    const uint16_t* V = role ? Tq : To;   // value role
+    uint16_t* Ph = Pbase + role * 2 * C * LDP;
+    uint16_t* Pl = Ph + C * LDP;
+    uint16_t* stage = Sbase + role * C * LD;
+
+    const SeqWalk walk = seq_walk(d, seq);
+    const int nsq = (walk.n + av.m - 1) / av.m;
+    const int kbeg = seg * av.m, kend = min(walk.n, kbeg + av.m), cnt = kend - kbeg;
+    const bool empty_seq = walk.n == 0 && seg == 0;
+    if (cnt <= 0 && !empty_seq) return;
+    const bool last = empty_seq || seg == 0;
+
+    f32x16 S[4];
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
+    {
+        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
+                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
+        if (ein) walk_state_load(S, ein, a.transposed, w4, n, half);
+    }
+
+    TileRegs rq, rk, rv, ro;
+    float gval = 0.f;
+    auto gload = [&](int kk) {
+        const ChunkPos p = walk_pos(d, walk, kend - 1 - min(kk, cnt - 1));
+        if (DEC) {
+            const int row = min(lane, p.L - 1), tok = p.L - 1 - row;
+            gval = av.g[d.kind == 1 ? size_t(walk.bh % d.H) : p.tok0 + size_t(tok) * p.ts];
+        }
+        walk_gload<REV, kPairThreads>(rq, av.xk, p.tok0, p.ts, p.L, tid);  // dv's key role = q
+        walk_gload<REV, kPairThreads>(rk, av.xq, p.tok0, p.ts, p.L, tid);  // dv's query role = k
+        walk_gload<REV, kPairThreads>(rv, ak.xq, p.tok0, p.ts, p.L, tid);  // dk's query role = v
+        walk_gload<REV, kPairThreads>(ro, av.xv, p.tok0, p.ts, p.L, tid);  // dv's value role = d_o
+    };
+    if (cnt > 0) gload(0);
+
+    for (int kk = 0; kk < cnt; ++kk) {
+        const ChunkPos cp = walk_pos(d, walk, kend - 1 - kk);
+        const int L = cp.L;
+        walk_commit<kPairThreads>(Tq, rq, L, tid);
+        walk_commit<kPairThreads>(Tk, rk, L, tid);
+        walk_commit<kPairThreads>(Tv, rv, L, tid);
+        walk_commit<kPairThreads>(To, ro, L, tid);
+        if (DEC && wave == 0) walk_decay_tables<REV>(gval, L, 0.f, bs, wo, lane);
+        gload(kk + 1);
+        __syncthreads();  // (A)
+        const float bC = DEC ? bs[C] : 0.f;
+
+        f32x16 O[2];
+        walk_inter<DEC>(O, S, Q, bs, n, half);
+        walk_scores<DEC>(K, Q, Ph, Pl, bs, w4, n, half);
+        __syncthreads();  // (C)
+        float pdp[2] = {0.f, 0.f}, isp[2] = {0.f, 0.f};
+        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+            if (DG && role) isp[jb] = row_dot(Tk, 32 * jb + n, w4, half, O[jb]);
+            walk_intra(O[jb], jb, V, Ph, Pl, w4, lane, n, half);
+            if (DG && role) pdp[jb] = row_dot(Tk, 32 * jb + n, w4, half, O[jb]);
+            store_packed(stage, LD, 32 * jb + n, 32 * w4, half, pack_block(O[jb]));
+        }
+        if (DG && role) {
+            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+                const float pd = pdp[jb] + __shfl_xor(pdp[jb], 32, 64), is = isp[jb] + __shfl_xor(isp[jb], 32, 64);
+                if (half == 0) {
+                    red[(w4 * 2 + 0) * C + 32 * jb + n] = pd;
+                    red[(w4 * 2 + 1) * C + 32 * jb + n] = is;
+                }
+            }
+        }
+        walk_update<DEC, true>(S, K, V, wo, bC, w4, lane, half);
+        __syncthreads();  // (D) both stages are complete; every read of this chunk's tiles is done
+        walk_store<REV>(a.out, stage, cp.tok0, cp.ts, L, rtid);
+        if (DG && role && rtid < 64) {
+            float pd = 0.f, is = 0.f;
+            _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
+                pd += red[(wv * 2 + 0) * C + rtid];
+                is += red[(wv * 2 + 1) * C + rtid];
+            }
+            if (rtid < L) ak.pdot[cp.wtok0 + (L - 1 - rtid)] = pd;
+            for (int off = 32; off > 0; off >>= 1) is += __shfl_xor(is, off, 64);
+            if (rtid == 0) ak.isum[cp.slot] = is;
+        }
+        // the stages are read above and written again only after the next (A) and (C)
+    }
+
+    if (last && role == 0 && av.edge_out) walk_state_store(S, av.edge_out + size_t(seq) * D * D, false, w4, n, half);
+    if (last && av.y0) {
+        const float z = (role == 0 && av.dot_with) ? walk_state_dot(S, av.dot_with + size_t(seq) * D * D, false, w4, n, half) : 0.f;
+        __syncthreads();
+        if (role == 0 && lane == 0) wo[w4] = z;
+        __syncthreads();
+        if (tid == 0) av.y0[seq] = (wo[0] + wo[1]) + (wo[2] + wo[3]);
     }
 }
 
@@ -332,28 +525,258 @@ __global__ __launch_bounds__(kThreads, 2) void mk_walk(Dims d, WalkArgs a) {
     walk_body<REV, DEC, false, SUMMARY>(d, a, blockIdx.y, blockIdx.x, smem);
 }
 
-// The three walkers of the backward pass in one grid: role 0 = dq (forward in time), 1 = dk, 2 = dv
-// (backward in time).  Workgroups are dealt to the 8 XCDs round-robin by linear id; the id is decoded
-// so that the three roles of one segment run on one XCD at about the same time (dk and dv read the
-// same tiles in the same order and share them in that XCD's L2).
-struct WalkTriple { WalkArgs w[3]; };
-template <bool DEC, bool DG>
-__global__ __launch_bounds__(kThreads, DG ? 1 : 2) void mk_walk_bwd(Dims d, WalkTriple t, int units) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int id = blockIdx.x, full = (units / 8) * 8;
-    int role, unit;
-    if (id < 3 * full) {
-        const int xcd = id & 7, slot = id >> 3;
-        role = slot % 3;
-        unit = xcd + 8 * (slot / 3);
-    } else {  // tail when the number of segments is not a multiple of 8
-        role = (id - 3 * full) % 3;
-        unit = full + (id - 3 * full) / 3;
+// ---------------------------------------------------------------------------------------------
+// Gradient walker: dq, dk, dv and the decay gradient of a segment of chunks in one pass, forward in
+// time, with the state S (as S^T: rows v, columns i) in accumulators and the state gradients dS read
+// from memory, one per chunk (written by the reverse scan, fragment-major bf16).  Per chunk, with
+// S = state at the chunk start, dS = gradient of the state at the chunk end, D_jr = e^{b_j-b_r} (r <= j):
+//   G = (dO V^T) * D ,  As = (Q K^T) * D
+//   dq^T[i][j] = e^{b_j}     sum_v S[i][v]  d_o_j[v] + sum_r K^T[i][r] G[j][r]
+//   dk^T[i][r] = e^{b_C-b_r} sum_v dS[i][v] v_r[v]   + sum_j Q^T[i][j] G[j][r]
+//   dv^T[v][r] = e^{b_C-b_r} sum_i dS^T[v][i] k_r[i] + sum_j dO^T[v][j] As[j][r]
+//   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + sum_r k_r.dk_r^{inter} + e^{b_C} <S, dS>
+//   S   <- e^{b_C} S + sum_r e^{b_C-b_r} k_r^T v_r
+// Wave w owns i (and v) in [32w, 32w+32).  S enters its product as bf16 head + remainder taken from the
+// fp32 accumulators, so the q.dq term of the decay gradient sees no state rounding.  G and As are each
+// computed once per workgroup, one wave per 32 x 32 block, and parked as head + remainder in a tile that
+// is dead at that point (G in the V tile, As in the Q tile); dS rows are handed between waves through
+// the V tile for the dv inter part.
+// One workgroup per compute unit (the kernel needs the whole register file: state, three output
+// accumulators, the dS rows, the tiles of the next chunk in flight), so LDS is plentiful and G, As and the
+// dS rows each get an area of their own: four barriers per chunk.
+// LDS: Q | K | V | dO (64 x LD; at the end the stages of dq, dk, dv) | G head | G remainder | As head |
+//      As remainder (64 x LDP each) | dS rows (128 x LD) | bs | wo | red (4 x 3 x 64) | zred
+constexpr int kWalkGradLds = (4 * C * LD + 4 * C * LDP + D * LD) * 2 + (2 * C + 8) * 4 + 4 * 64 * 3 * 4 + 64;
+
+struct GradArgs {
+    const uint16_t *q, *k, *v, *d_o;
+    const float* g;
+    const uint16_t* dstates;  // [BH*N] fragment-major bf16: slot c = gradient of the state at the end of chunk c
+    uint16_t *dq, *dk, *dv;
+    float* dg_tok;            // per-token scalar kind: d_log_decay itself; per-head kind: [BH*N] per-chunk sums
+    const float* edge_in;     // M_0 [i][v] per sequence or NULL
+    const float* bound;       // entry states of the segments ([i][v]) when nseg > 1
+    int m, nseg;
+};
+
+template <bool DEC, bool WANT_DG>
+__device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a, int seq, int seg, unsigned char* smem) {
+    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* K = Q + C * LD;
+    uint16_t* V = K + C * LD;
+    uint16_t* dO = V + C * LD;
+    uint16_t* Gh = dO + C * LD;
+    uint16_t* Gl = Gh + C * LDP;
+    uint16_t* Ah = Gl + C * LDP;
+    uint16_t* Al = Ah + C * LDP;
+    uint16_t* dSt = Al + C * LDP;    // [i][v] rows of dS, all 128
+    float* bs = reinterpret_cast<float*>(dSt + D * LD);
+    float* wo = bs + C + 4;
+    float* red = wo + C + 4;         // [wave][3][64]: q.dq, k.dk, k.dk_inter partial sums over this wave's i
+    float* zred = red + 4 * 3 * 64;  // [wave]: partial <S, dS>
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const SeqWalk walk = seq_walk(d, seq);
+    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
+    if (cnt <= 0) return;
+
+    // S block vb of this wave: S[vb][4g+j] = M[i = 32 wave + n][v = 32 vb + 8g + 4 half + j]
+    f32x16 S[4];
+    _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) S[vb] = f32x16{0};
+    {
+        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
+                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
+        if (ein) walk_state_load(S, ein, true, wave, n, half);
     }
-    const int nseg = t.w[0].nseg, seq = unit / nseg, seg = unit % nseg;
-    if (role == 0) walk_body<false, DEC, DG, false>(d, t.w[0], seq, seg, smem);
-    else if (role == 1) walk_body<true, DEC, DG, false>(d, t.w[1], seq, seg, smem);
-    else walk_body<true, DEC, false, false>(d, t.w[2], seq, seg, smem);
+
+    TileRegs tq, tk, tv, to;
+    bf16x8 dsfrag[8];
+    float gval = 0.f;
+    auto gload = [&](int kk) {
+        const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
+        if (DEC) gval = a.g[d.kind == 1 ? size_t(walk.bh % d.H) : p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
+        walk_gload<false, kThreads>(tq, a.q, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(tk, a.k, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(tv, a.v, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(to, a.d_o, p.tok0, p.ts, p.L, tid);
+        // rows i in [32w, 32w+32) of dS: A operands [m = i][k = v]
+        const uint16_t* dS = a.dstates + p.slot * D * D;
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+            dsfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane)));
+    };
+    gload(0);
+
+    for (int kk = 0; kk < cnt; ++kk) {
+        const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
+        const int L = cp.L;
+        walk_commit<kThreads>(Q, tq, L, tid);
+        walk_commit<kThreads>(K, tk, L, tid);
+        walk_commit<kThreads>(V, tv, L, tid);
+        walk_commit<kThreads>(dO, to, L, tid);
+        // the dS rows of this wave, for the waves that contract over i (dv)
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+            *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
+        if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
+        __syncthreads();  // (1) tiles, dS rows and decay tables of this chunk are in LDS
+        const float bC = DEC ? bs[C] : 0.f;
+
+        PackedBlock resq[2], resk[2], resv[2];
+        f32x16 aq[2], ak[2] = {{0}, {0}};
+        float pk_inter[2] = {0.f, 0.f};
+        // ---- score blocks: G = (dO V^T) * D by waves 0, 1, 2 and As = (Q K^T) * D by waves 3, 0, 1 (blocks (0,0),
+        // (1,0), (1,1) in that order), mask and decay on the accumulators, to areas of their own
+        {
+            const int gi = wave, ai = (wave + 1) & 3;  // block index of this wave in either set; 3 = none
+            if (gi < 3) {
+                const int pjb = gi ? 1 : 0, prb = gi == 2 ? 1 : 0;
+                f32x16 G = score_block2(V, 32 * prb, dO, 32 * pjb, n, half);  // D[m = r][n = j] = v_r . d_o_j
+                walk_mask<DEC>(G, 32 * prb, 32 * pjb + n, bs, half);
+                store_block_t_split(Gh, Gl, LDP, 32 * pjb + n, 32 * prb, half, G);
+            }
+            if (ai < 3) {
+                const int pjb = ai ? 1 : 0, prb = ai == 2 ? 1 : 0;
+                f32x16 As = score_block2(K, 32 * prb, Q, 32 * pjb, n, half);  // D[m = r][n = j] = k_r . q_j
+                walk_mask<DEC>(As, 32 * prb, 32 * pjb + n, bs, half);
+                store_block_t_split(Ah, Al, LDP, 32 * pjb + n, 32 * prb, half, As);
+            }
+        }
+        // ---- inter parts: dq^T[i][j] from the state in registers, dk^T[i][r] from the dS rows
+        walk_inter<DEC>(aq, S, dO, bs, n, half);
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+            const int tok = 32 * nb + n;
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
+            if (DEC) {
+                const float wk = wo[tok];
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) ak[nb][x] *= wk;
+            }
+            if (WANT_DG) pk_inter[nb] = row_dot(K, tok, wave, half, ak[nb]);
+        }
+        // ---- <S, dS> over this wave's rows i: lanes l and l + 32 exchange halves of the dS fragments so that
+        // each lane holds dS at exactly the (i, v) of its state registers
+        if (WANT_DG) {
+            float z = 0.f;
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                const u32x4 f = __builtin_bit_cast(u32x4, dsfrag[ks]);
+                const auto s0 = __builtin_amdgcn_permlane32_swap(f[0], f[2], false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(f[1], f[3], false, false);
+                const f32x16& sv = S[ks >> 1];
+                const int b = 8 * (ks & 1);
+                z += sv[b + 0] * bf16_lo(s0[0]) + sv[b + 1] * bf16_hi(s0[0]) + sv[b + 2] * bf16_lo(s1[0]) + sv[b + 3] * bf16_hi(s1[0]) +
+                     sv[b + 4] * bf16_lo(s0[1]) + sv[b + 5] * bf16_hi(s0[1]) + sv[b + 6] * bf16_lo(s1[1]) + sv[b + 7] * bf16_hi(s1[1]);
+            }
+            for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
+            if (lane == 0) zred[wave] = z;
+        }
+        // ---- the state moves on to the end of the chunk (roles: key = v, value = k)
+        walk_update<DEC, true>(S, V, K, wo, bC, wave, lane, half);
+        // the next chunk's rows are requested now: the dS registers are free, the tile registers have been since (1)
+        if (kk + 1 < cnt) gload(kk + 1);
+        __syncthreads();  // (2) G and As are in LDS
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+            const int tok = 32 * nb + n;
+            // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r]: keys r >= 32 never reach queries j < 32
+            _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {
+                const bf16x8 kt = frag_tr(K, LD, 16 * ks, 32 * wave, lane);
+                aq[nb] = mfma(kt, frag(Gh, LDP, tok, 16 * ks + 8 * half), aq[nb]);
+                aq[nb] = mfma(kt, frag(Gl, LDP, tok, 16 * ks + 8 * half), aq[nb]);
+            }
+            // dk^T[i][r] += sum_{j>=r} Q^T[i][j] G[j][r]: queries j < 32 never see keys r >= 32
+            _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+                const bf16x8 qt = frag_tr(Q, LD, 16 * ks, 32 * wave, lane);
+                ak[nb] = mfma(qt, frag_tr(Gh, LDP, 16 * ks, 32 * nb, lane), ak[nb]);  // B[k = j][n = r] = G[j][r]
+                ak[nb] = mfma(qt, frag_tr(Gl, LDP, 16 * ks, 32 * nb, lane), ak[nb]);
+            }
+            if (WANT_DG) {
+                float pq = row_dot(Q, tok, wave, half, aq[nb]), pk = row_dot(K, tok, wave, half, ak[nb]);
+                pq += __shfl_xor(pq, 32, 64);
+                pk += __shfl_xor(pk, 32, 64);
+                const float pi = pk_inter[nb] + __shfl_xor(pk_inter[nb], 32, 64);
+                if (half == 0) {
+                    red[(wave * 3 + 0) * 64 + tok] = pq;
+                    red[(wave * 3 + 1) * 64 + tok] = pk;
+                    red[(wave * 3 + 2) * 64 + tok] = pi;
+                }
+            }
+            resq[nb] = pack_block(aq[nb]);
+            resk[nb] = pack_block(ak[nb]);
+        }
+        // ---- dv^T[v][r], v in this wave's slice: the inter part contracts over the rows i of dS (token-major read of
+        // the dS area), the intra part over the queries
+        {
+            f32x16 av[2] = {{0}, {0}};
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 dst = frag_tr(dSt, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 16 ks + ..
+                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                    av[nb] = mfma(dst, frag(K, LD, 32 * nb + n, 16 * ks + 8 * half), av[nb]);
+            }
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                const int r = 32 * nb + n;
+                if (DEC) {
+                    const float wk = wo[r];
+                    _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
+                }
+                // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]: queries j < 32 never see keys r >= 32
+                _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+                    const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
+                    av[nb] = mfma(dot, frag_tr(Ah, LDP, 16 * ks, 32 * nb, lane), av[nb]);  // B[k = j][n = r] = As[j][r]
+                    av[nb] = mfma(dot, frag_tr(Al, LDP, 16 * ks, 32 * nb, lane), av[nb]);
+                }
+                resv[nb] = pack_block(av[nb]);
+            }
+        }
+        __syncthreads();  // (3) every wave is done with the tiles
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+            store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
+            store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
+            store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
+        }
+        __syncthreads();  // (4)
+        // every thread reads back exactly the stage pieces that its own next walk_commit overwrites
+        walk_store<false>(a.dq, Q, cp.tok0, cp.ts, L, tid);
+        walk_store<false>(a.dk, K, cp.tok0, cp.ts, L, tid);
+        walk_store<false>(a.dv, V, cp.tok0, cp.ts, L, tid);
+        if (WANT_DG && tid < 64) {
+            // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
+            float w = 0.f, tail = 0.f, z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
+            _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
+                w += red[(wv * 3 + 0) * 64 + tid] - red[(wv * 3 + 1) * 64 + tid];
+                tail += red[(wv * 3 + 2) * 64 + tid];
+            }
+            for (int off = 32; off > 0; off >>= 1) tail += __shfl_xor(tail, off, 64);
+            float sfx = w;  // suffix sum of w over tokens >= tid
+            for (int off = 1; off < 64; off <<= 1) {
+                const float y = __shfl_down(sfx, off, 64);
+                if (tid + off < 64) sfx += y;
+            }
+            float dgv = tid < L ? sfx + tail + __expf(bC) * z : 0.f;
+            if (d.kind == 1) {
+                // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
+                for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
+                if (tid == 0) a.dg_tok[cp.slot] = dgv;
+            } else if (tid < L) {
+                a.dg_tok[cp.tok0 + size_t(tid) * cp.ts] = dgv;
+            }
+        }
+    }
+}
+
+template <bool DEC, bool WANT_DG>
+__global__ __launch_bounds__(kThreads, 1) void mk_walk_grad(Dims d, GradArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    walk_grad_body<DEC, WANT_DG>(d, a, blockIdx.y, blockIdx.x, smem);
+}
+
+// the dq walker of the backward pass (forward in time)
+template <bool DEC, bool DG>
+__global__ __launch_bounds__(kThreads, 2) void mk_walk_dq(Dims d, WalkArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    walk_body<false, DEC, DG, false>(d, a, blockIdx.y, blockIdx.x, smem);
+}
+// the dk and dv walkers of the backward pass (backward in time), one workgroup of eight waves per segment
+template <bool DEC, bool DG>
+__global__ __launch_bounds__(kPairThreads, 1) void mk_walk_dkdv(Dims d, WalkArgs av, WalkArgs ak) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    walk_pair_body<DEC, DG>(d, av, ak, blockIdx.y, blockIdx.x, smem);
 }
 
 // Entry state of every segment from the segments' own contributions (left by the summary pass in the
