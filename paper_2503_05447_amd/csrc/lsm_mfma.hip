@@ -1,7 +1,9 @@
 // MFMA kernel family of the chunkwise LSM path for gfx950: bf16 operands, fp32 accumulation,
-// chunk = 64 tokens, d_k = 128.  This file: the state scans (all decay kinds) and the per-chunk
-// kernels of the decay kinds none / per-head / per-token scalar (d_v = 128); the per-chunk kernels
-// of the per-key-feature (vector) kind are in lsm_mfma_vec.h (d_v = 128 or 256).
+// chunk = 64 tokens, d_k = 128.  This file: the chunk-state scans (the vector kind's forward and backward
+// scans, the scalar kinds' reverse scan of state gradients), the per-chunk output kernel kept as the
+// intra-chunk benchmark aid, and the host side; the fused chunk walkers of the scalar decay kinds
+// (none / per-head / per-token scalar, d_v = 128) are in lsm_mfma_walk.h, the per-chunk kernels of the
+// per-key-feature (vector) kind in lsm_mfma_vec.h (d_v = 128 or 256).
 //
 // Algorithm 2 of the paper generalised to a decay, per (b,h) and chunk c with chunk-local
 // cumulative log-decay b_j:
@@ -394,16 +396,6 @@ __global__ __launch_bounds__(kThreads) void mk_state_seq(Dims d, StateArgs sa) {
     state_scan_body<MODE, DEC, false, false, SAVE>(d, sa, blockIdx.x, gridDim.x, smem);
 }
 
-// The two scans of the backward pass (states forward in time, state gradients backward in time) are
-// independent sequential chains; launched as one grid they share the CUs two workgroups at a time,
-// which hides most of each other's latency.  blockIdx.y selects the scan.
-template <bool DEC, bool REM>
-__global__ __launch_bounds__(kThreads) void mk_state_pair(Dims d, StateArgs s1, StateArgs s2) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    if (blockIdx.y == 0) state_scan_body<1, DEC, REM, false>(d, s1, blockIdx.x, gridDim.x, smem);
-    else state_scan_body<2, DEC, false, false>(d, s2, blockIdx.x, gridDim.x, smem);
-}
-
 
 // D[m][n] = sum_f Am[m0 + m][f] * Bm[n0 + n][f] over the 128 features of two row-major LDS tiles
 __device__ __forceinline__ f32x16 score_block(const uint16_t* Am, int m0, const uint16_t* Bm, int n0, int n, int half) {
@@ -541,234 +533,6 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) store_packed(stage, LD, 32 * jb + n, 32 * wave, half, res[jb]);
     __syncthreads();
     store_tile(o, stage, tok0, ts, L, tid);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Gradients of one chunk (scalar decay kinds).  S = state at the chunk start [i][v], dS = gradient
-// of the state at the chunk end [i][v].  D_jr = e^{b_j-b_r} for r <= j, else 0.
-//   dA = d_o V^T ,  G = dA * D ,  As = (Q K^T) * D
-//   dq^T[i][j] = e^{b_j}     sum_v S[i][v]  d_o_j[v] + sum_r K^T[i][r] G[j][r]
-//   dk^T[i][r] = e^{b_C-b_r} sum_v dS[i][v] v_r[v]   + sum_j Q^T[i][j] G[j][r]
-//   dv^T[v][r] = e^{b_C-b_r} sum_i dS^T[v][i] k_r[i] + sum_j dO^T[v][j] As[j][r]
-//   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + sum_r k_r.dk_r^{inter} + e^{b_C} <S, dS>
-// Wave w owns i (and v) in [32w, 32w+32).  The inter parts come first (state rows as A operands from
-// global memory, scaled on the accumulators).  G and As are each computed once per workgroup, one
-// wave per 32 x 32 block (mask and decay on its accumulators), and parked as bf16 head + remainder in
-// a tile that is dead at that point: G in the V tile (dq reads it by rows, dk through the LDS
-// transpose read, so G^T is never formed), As in the Q tile for dv.  K^T, Q^T and dO^T come from
-// transpose reads of the row-major tiles.
-// LDS: Q | K | V | dO (64 x LD; later stages of dq, dk, dv) | bs (64) | red (4 x 3 x 64 floats:
-//      per-wave partial row dots) | zred
-constexpr int kGradLds = 4 * C * LD * 2 + C * 4 + 4 * 64 * 3 * 4 + 64;
-
-template <bool WANT_DG>  // decay gradient asked for: then states_rem and dg_tok are present
-__global__ __launch_bounds__(kThreads, 2) void mk_grad(Dims d, const uint16_t* __restrict__ q,
-                                                       const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                       const uint16_t* __restrict__ d_o, const float* __restrict__ g,
-                                                       const uint16_t* __restrict__ states,
-                                                       const uint16_t* __restrict__ states_rem,
-                                                       const uint16_t* __restrict__ dstates,
-                                                       uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
-                                                       uint16_t* __restrict__ dv, float* __restrict__ dg_tok) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* K = Q + C * LD;
-    uint16_t* V = K + C * LD;
-    uint16_t* dO = V + C * LD;
-    float* bs = reinterpret_cast<float*>(dO + C * LD);
-    float* red = bs + C;             // [wave][3][64]: q.dq, k.dk, k.dk_inter partial sums over this wave's i
-    float* zred = red + 4 * 3 * 64;  // [wave]: partial <S, dS>
-
-    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const ChunkPos cp = chunk_pos(d, c, bh);
-    const int L = cp.L;
-    if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
-    const size_t tok0 = cp.tok0;
-    const int ts = cp.ts;
-    const int n = lane & 31, half = lane >> 5;
-    const uint16_t* S = states + cp.slot * D * D;
-    const uint16_t* dS = dstates + cp.slot * D * D;
-    constexpr bool want_dg = WANT_DG;
-
-    // The tiles are requested first and the state rows after them: loads return in order, so the tiles
-    // can go to LDS (and the barrier be reached) while the state rows, needed only by the first MFMAs,
-    // are still on their way.
-    const float gval = decay_gload(d, g, bh, cp, lane);
-    TileRegs tq, tk, tv, to;
-    tile_gload(tq, q, tok0, ts, L, tid);
-    tile_gload(tk, k, tok0, ts, L, tid);
-    tile_gload(tv, v, tok0, ts, L, tid);
-    tile_gload(to, d_o, tok0, ts, L, tid);
-    // rows i in [32w, 32w+32) of S (and its remainder): A operands [m = i][k = v]
-    bf16x8 sfrag[8], srfrag[8], dsfrag[8];
-    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-        sfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(S + state_frag_off(wave, ks, lane)));
-        dsfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane)));
-        if (want_dg)
-            srfrag[ks] = rem8_to_bf16(__builtin_nontemporal_load(reinterpret_cast<const u32x2*>(
-                reinterpret_cast<const uint8_t*>(states_rem) + (S - states) + state_frag_off(wave, ks, lane))));
-    }
-    tile_commit(Q, tq, L, tid);
-    tile_commit(K, tk, L, tid);
-    tile_commit(V, tv, L, tid);
-    tile_commit(dO, to, L, tid);
-    cumulative_decay(gval, L, bs, tid);
-    __syncthreads();
-    const float bC = bs[C - 1];
-
-    PackedBlock resq[2], resk[2], resv[2];
-    // ---- inter parts of dq^T[i][j] and dk^T[i][r], i in this wave's slice
-    f32x16 aq[2] = {{0}, {0}}, aqr[2] = {{0}, {0}}, ak[2] = {{0}, {0}};  // aqr: remainder of S, enters the decay gradient only
-    float pk_inter[2] = {0.f, 0.f};
-    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        const int tok = 32 * nb + n;
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 dof = frag(dO, LD, tok, 16 * ks + 8 * half);
-            aq[nb] = mfma(sfrag[ks], dof, aq[nb]);
-            if (want_dg) aqr[nb] = mfma(srfrag[ks], dof, aqr[nb]);
-            ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
-        }
-        const float wq = __expf(bs[tok]), wk = __expf(bC - bs[tok]), wqr = wq * kRem8Unscale;
-        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-            aq[nb][x] *= wq;
-            aqr[nb][x] *= wqr;
-            ak[nb][x] *= wk;
-        }
-        if (want_dg) pk_inter[nb] = row_dot(K, tok, wave, half, ak[nb]);
-    }
-    // ---- <S, dS> over this wave's rows
-    if (want_dg) {
-        float z = 0.f;
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-            u32x4 a = __builtin_bit_cast(u32x4, sfrag[ks]), b = __builtin_bit_cast(u32x4, dsfrag[ks]);
-            u32x4 ar = __builtin_bit_cast(u32x4, srfrag[ks]);
-            _Pragma("unroll") for (int p = 0; p < 4; ++p)
-                z += (bf16_lo(a[p]) + kRem8Unscale * bf16_lo(ar[p])) * bf16_lo(b[p]) +
-                     (bf16_hi(a[p]) + kRem8Unscale * bf16_hi(ar[p])) * bf16_hi(b[p]);
-        }
-        for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
-        if (lane == 0) zred[wave] = z;
-    }
-    // ---- G = (dO V^T) * D: each of its three 32 x 32 blocks is computed by one wave (wave 0: (0,0),
-    // wave 1: (1,0), wave 2: (1,1)) and handed to the others as head + remainder through the V tile,
-    // which nothing reads between here and the dS hand-over of the dv phase.  Rows j; columns r of the
-    // head in 0..63, of the remainder in 64..127 (one 64 x 128 tile).
-    constexpr int LDG = LD;
-    uint16_t* Gh = V;
-    uint16_t* Gl = V + C;
-    {
-        f32x16 G = {0};
-        const int pjb = wave ? 1 : 0, prb = wave == 2 ? 1 : 0;
-        if (wave < 3) {
-            G = score_block(V, 32 * prb, dO, 32 * pjb, n, half);  // D[m = r][n = j] = v_r . d_o_j
-            decay_mask<true>(G, 32 * prb, 32 * pjb + n, bs, half);
-        }
-        __syncthreads();  // every wave is done with V
-        if (wave < 3) store_block_t_split(Gh, Gl, LDG, 32 * pjb + n, 32 * prb, half, G);
-        __syncthreads();
-    }
-    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        const int tok = 32 * nb + n;
-        // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r]: keys r >= 32 never reach queries j < 32
-        _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {
-            const bf16x8 kt = frag_tr(K, LD, 16 * ks, 32 * wave, lane);
-            aq[nb] = mfma(kt, frag(Gh, LDG, tok, 16 * ks + 8 * half), aq[nb]);
-            aq[nb] = mfma(kt, frag(Gl, LDG, tok, 16 * ks + 8 * half), aq[nb]);
-        }
-        // dk^T[i][r] += sum_{j>=r} Q^T[i][j] G[j][r]: queries j < 32 never see keys r >= 32
-        _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
-            const bf16x8 qt = frag_tr(Q, LD, 16 * ks, 32 * wave, lane);
-            ak[nb] = mfma(qt, frag_tr(Gh, LDG, 16 * ks, 32 * nb, lane), ak[nb]);  // B[k = j][n = r] = G[j][r]
-            ak[nb] = mfma(qt, frag_tr(Gl, LDG, 16 * ks, 32 * nb, lane), ak[nb]);
-        }
-        if (want_dg) {
-            f32x16 full = aq[nb];
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) full[x] += aqr[nb][x];
-            float pq = row_dot(Q, tok, wave, half, full), pk = row_dot(K, tok, wave, half, ak[nb]);
-            pq += __shfl_xor(pq, 32, 64);
-            pk += __shfl_xor(pk, 32, 64);
-            const float pi = pk_inter[nb] + __shfl_xor(pk_inter[nb], 32, 64);
-            if (half == 0) {
-                red[(wave * 3 + 0) * 64 + tok] = pq;
-                red[(wave * 3 + 1) * 64 + tok] = pk;
-                red[(wave * 3 + 2) * 64 + tok] = pi;
-            }
-        }
-        resq[nb] = pack_block(aq[nb]);
-        resk[nb] = pack_block(ak[nb]);
-    }
-    // ---- dv^T[v][r], v in this wave's slice.  The inter part contracts over the rows i of dS, which
-    // the four waves hold as their A fragments: they are handed over through the V tile (dead by now),
-    // 64 rows at a time, and read back token-major with the LDS transpose read.
-    // The intra part needs As = (Q K^T) * D: like G, one wave per block, handed over through the Q tile
-    // (dead once the dk products are done) at the barriers of the dS hand-over.
-    {
-        f32x16 av[2] = {{0}, {0}};
-        f32x16 As = {0};
-        const int pjb = wave ? 1 : 0, prb = wave == 2 ? 1 : 0;
-        if (wave < 3) {
-            As = score_block(K, 32 * prb, Q, 32 * pjb, n, half);  // D[m = r][n = j] = k_r . q_j
-            decay_mask<true>(As, 32 * prb, 32 * pjb + n, bs, half);
-        }
-        _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {
-            __syncthreads();  // hf = 0: every wave is done with V (G) and Q; hf = 1: done with the first 64 rows
-            if (hf == 0 && wave < 3) store_block_t_split(Q, Q + C, LD, 32 * pjb + n, 32 * prb, half, As);
-            if ((wave >> 1) == hf) {
-                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                    *reinterpret_cast<bf16x8*>(V + (32 * (wave & 1) + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
-            }
-            __syncthreads();
-            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
-                const bf16x8 dst = frag_tr(V, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 64 hf + 16 ks + ..
-                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-                    av[nb] = mfma(dst, frag(K, LD, 32 * nb + n, 64 * hf + 16 * ks + 8 * half), av[nb]);
-            }
-        }
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            const int r = 32 * nb + n;
-            const float wk = __expf(bC - bs[r]);
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
-            // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]: queries j < 32 never see keys r >= 32
-            _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
-                const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
-                av[nb] = mfma(dot, frag_tr(Q, LD, 16 * ks, 32 * nb, lane), av[nb]);      // B[k = j][n = r] = As[j][r]
-                av[nb] = mfma(dot, frag_tr(Q, LD, 16 * ks, C + 32 * nb, lane), av[nb]);  // remainder
-            }
-            resv[nb] = pack_block(av[nb]);
-        }
-    }
-    __syncthreads();  // every wave is done with Q, K, V, dO
-    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-        store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
-        store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
-        store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
-    }
-    __syncthreads();
-    store_tile(dq, Q, tok0, ts, L, tid);
-    store_tile(dk, K, tok0, ts, L, tid);
-    store_tile(dv, V, tok0, ts, L, tid);
-    if (want_dg && tid < 64) {
-        // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
-        float w = 0.f, tail = 0.f, z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
-        _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
-            w += red[(wv * 3 + 0) * 64 + tid] - red[(wv * 3 + 1) * 64 + tid];
-            tail += red[(wv * 3 + 2) * 64 + tid];
-        }
-        for (int off = 32; off > 0; off >>= 1) tail += __shfl_xor(tail, off, 64);
-        float sfx = w;  // suffix sum of w over tokens >= tid
-        for (int off = 1; off < 64; off <<= 1) {
-            const float y = __shfl_down(sfx, off, 64);
-            if (tid + off < 64) sfx += y;
-        }
-        float dgv = tid < L ? sfx + tail + __expf(bC) * z : 0.f;
-        if (d.kind == 1) {
-            // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
-            for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
-            if (tid == 0) dg_tok[cp.slot] = dgv;
-        } else if (tid < L) {
-            dg_tok[tok0 + size_t(tid) * ts] = dgv;
-        }
-    }
 }
 
 // dg[h] = sum over batch elements and chunks of the per-chunk sums dg_chunk[b,h,c], in a fixed order (grid: H)
@@ -958,32 +722,6 @@ hipError_t launch_state(const Dims& d, hipStream_t st, const StateArgs& sa) {
     }
     return hipSuccess;
 }
-// forward scan that also leaves the states (and, with a decay, their remainder plane) for the backward pass
-hipError_t launch_state_save(const Dims& d, hipStream_t st, const StateArgs& sa) {
-    const dim3 sgrid(D / 32 * d.seqs()), block(kThreads);
-    hipError_t e;
-    if (d.kind == 0) {
-        if ((e = allow_lds(mk_state_seq<3, false, true>, kStateLdsPlain)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_state_seq<3, false, true>), sgrid, block, kStateLdsPlain, st, d, sa);
-    } else {
-        if ((e = allow_lds(mk_state_seq<3, true, true>, kStateLdsPlain)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_state_seq<3, true, true>), sgrid, block, kStateLdsPlain, st, d, sa);
-    }
-    return hipSuccess;
-}
-template <bool DEC, bool REM>
-hipError_t launch_state_pair_t(const Dims& d, hipStream_t st, const StateArgs& s1, const StateArgs& s2) {
-    const dim3 sgrid(D / 32 * d.seqs(), 2), block(kThreads);
-    const int lds = kStateLdsNone;
-    const hipError_t e = allow_lds(mk_state_pair<DEC, REM>, lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((mk_state_pair<DEC, REM>), sgrid, block, lds, st, d, s1, s2);
-    return hipSuccess;
-}
-hipError_t launch_state_pair(const Dims& d, hipStream_t st, const StateArgs& s1, const StateArgs& s2) {
-    if (d.kind == 0) return launch_state_pair_t<false, false>(d, st, s1, s2);  // no decay gradient, no remainder
-    return s1.states_rem ? launch_state_pair_t<true, true>(d, st, s1, s2) : launch_state_pair_t<true, false>(d, st, s1, s2);
-}
 void launch_prep(const Dims& d, hipStream_t st, const float* g, const Ws& w) {
     if (d.kind == 0) return;
     ProfScope ps(KID_MFMA_PREP, st);
@@ -1043,7 +781,7 @@ hipError_t walk_bounds(const Dims& d, hipStream_t st, const SegPlan& sp, const u
     const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
     {
         ProfScope ps(KID_WALK_SUMMARY, st);
-        constexpr int lds = walk_lds(false, true);
+        constexpr int lds = walk_lds(true);
         if (d.kind == 0) {
             if ((e = allow_lds(mk_walk<REV, false, true>, lds)) != hipSuccess) return e;
             hipLaunchKernelGGL((mk_walk<REV, false, true>), grid, block, lds, st, d, a);
@@ -1067,7 +805,7 @@ hipError_t walk_fwd(const Dims& d, const FwdArgs& a) {
     wa.xq = q; wa.xk = k; wa.xv = v; wa.g = a.g; wa.out = static_cast<uint16_t*>(a.o);
     wa.edge_in = a.m0; wa.edge_out = a.mT; wa.bound = w.bound_f; wa.m = sp.m; wa.nseg = sp.nseg;
     const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
-    constexpr int lds = walk_lds(false, false);
+    constexpr int lds = walk_lds(false);
     ProfScope ps(KID_WALK_FWD, a.stream);
     if (d.kind == 0) {
         if ((e = allow_lds(mk_walk<false, false, false>, lds)) != hipSuccess) return e;
@@ -1101,7 +839,7 @@ hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
                 a.dg ? (d.kind == 1 ? w.dgc : a.dg) : nullptr, a.m0, w.bound_f, sp.m, sp.nseg};
     const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
     {
-        ProfScope ps(KID_WALK_BWD, a.stream);
+        ProfScope ps(KID_WALK_GRAD, a.stream);
         if (d.kind == 0) {
             if ((e = allow_lds(mk_walk_grad<false, false>, kWalkGradLds)) != hipSuccess) return e;
             hipLaunchKernelGGL((mk_walk_grad<false, false>), grid, block, kWalkGradLds, a.stream, d, ga);

@@ -2,49 +2,30 @@
 // accumulation, chunk = 64, d_k = d_v = 128.  Included by lsm_mfma.hip.
 //
 // One workgroup walks a run of consecutive chunks (a "segment") of one (b,h) recurrence with the
-// 128 x 128 state in MFMA accumulators, so no per-chunk state ever goes to memory.  Per chunk it
-// evaluates Algorithm 2 of the paper with the decay folded in,
-//     out_t = e^{beta_t} x^q_t S + sum_{r <= t} (x^q_t . x^k_r) e^{beta_t - beta_r} x^v_r      (O_inter + O_intra)
-//     S    <- e^{b_C} S + sum_r e^{b_C - beta_r} x^k_r^T x^v_r                                (chunk state, prefix)
-// for three row tensors in the roles "query", "key", "value".  The same body serves all four outputs:
-//     o   : forward in time,  roles (q, k, v),    S = M
-//     dq  : forward in time,  roles (d_o, v, k),  S = M^T
-//     dv  : backward in time, roles (k, q, d_o),  S = dM
-//     dk  : backward in time, roles (v, d_o, q),  S = dM^T
-// since each gradient of the recurrence is again a causal (or anti-causal) linear-attention read-out.
-// Walking backward, a chunk's rows are loaded in reverse token order, and beta is the exclusive instead
-// of the inclusive running sum of the log-decays in walk order; everything else is identical.
+// 128 x 128 state in MFMA accumulators, so the forward pass writes no per-chunk state at all and the
+// backward pass only the state gradients.  Per chunk the forward walker evaluates Algorithm 2 of the
+// paper with the decay folded in,
+//     o_t = e^{b_t} q_t S + sum_{r <= t} (q_t . k_r) e^{b_t - b_r} v_r        (O_inter + O_intra)
+//     S  <- e^{b_C} S + sum_r e^{b_C - b_r} k_r^T v_r                         (chunk state, prefix)
+// and the gradient walker (further down) the adjoint of the same chunk with S carried the same way.
 //
-// Segments: with fewer recurrences than the chip has compute units a sequence is cut into segments of
-// m chunks.  A first pass (SUMMARY: the state update alone, from a zero state) leaves each segment's
-// own contribution and total log-decay, a small scan turns them into the state every segment starts
-// from, and the walkers then run all segments in parallel.  Only those entry states (one per m chunks)
-// ever reach memory.
-//
-// Decay gradient (DG).  With F_t = sum_{u >= t, u in chunk} q_u . dq_u,  R_t likewise with k_u . dk_u,
-//     dg_t = F_t - R_t + y_{c+1} ,    y_{c+1} = <S_{c+1}, dS_{c+1}> = y_c - a_c + b_c ,
-//     a_c = sum_{t in c} q_t . dq_t^{inter} ,   b_c = sum_{t in c} k_t . dk_t^{inter} ,   y_0 = <M_0, dM_0>
-// (the adjoint identity dg_t = a_t <dM_t, M_{t-1}> split at the chunk boundaries).  The dq walker emits
-// q_t . dq_t and a_c, the dk walker k_t . dk_t and b_c, the dv walker y_0; a small kernel combines them.
-// All of them are formed from the fp32 accumulators, and the state enters its products as a bf16 head
-// plus a bf16 remainder, so that the running sum over chunks does not collect the 2^-9 rounding of a
-// single bf16 operand.
+// Segments: with fewer recurrences than the chip can keep busy a sequence is cut into segments of m
+// chunks.  A first pass (SUMMARY: the state update alone, from a zero state) leaves each segment's own
+// contribution and total log-decay, a small scan turns them into the state every segment starts from,
+// and the walkers then run all segments in parallel.  Only those entry states (one per m chunks) ever
+// reach memory.  REV walks backward in time (a chunk's rows are loaded in reverse token order and beta
+// is the exclusive instead of the inclusive running sum of the log-decays in walk order); it serves
+// the summary pass of the reverse direction.
 #pragma once
 
 struct WalkArgs {
-    const uint16_t *xq, *xk, *xv;  // rows in the query, key and value role
-    const uint16_t* xx;            // DG: rows dotted with the output rows
+    const uint16_t *xq, *xk, *xv;  // rows in the query, key and value role (forward pass: q, k, v)
     const float* g;                // log-decay (per kind)
     uint16_t* out;
     const float* edge_in;  // state a whole sequence starts from, [i][v] fp32 per sequence; NULL = zero
     float* edge_out;       // state it ends with; NULL = not wanted
     float* bound;          // [seqs][nseg][128 x 128] fp32, [i][v]: entry state of every segment (nseg > 1)
     float* gseg;           // [seqs][nseg]: total log-decay of each segment (SUMMARY writes)
-    float* pdot;           // DG: [BH*T] x_t . out_t
-    float* isum;           // DG: [BH*N] sum over the chunk of x_t . out_t^{inter}
-    const float* dot_with; // if y0: [i][v] fp32 per sequence, its inner product with the final state goes to y0 (NULL: 0)
-    float* y0;             // [seqs] or NULL
-    int transposed;        // the walker's state [key feature][value feature] is the transpose of the [i][v] arrays
     int m, nseg;           // chunks per segment, segments per sequence (upper bound for packed input)
 };
 
@@ -103,30 +84,8 @@ __device__ __forceinline__ void walk_mask(f32x16& acc, int m0, int ncol, const f
     }
 }
 
-__host__ __device__ constexpr int walk_lds(bool dg, bool summary) {
-    return summary ? 2 * C * LD * 2 + (2 * C + 8) * 4
-                   : (3 * C * LD + 2 * C * LDP) * 2 + (2 * C + 8) * 4 + (dg ? 4 * 2 * C * 4 : 0);
-}
-
-// Rows of the tensor dotted with the output (decay gradient), straight from global memory in the
-// layout of an output block: for token 32 jb + n the features 32 wave + 8 gg + 4 half + 0..3.  Rows
-// beyond the ragged end repeat the last valid row (their output rows are zero).
-struct DotRegs { u32x2 v[2][4]; };
-template <bool REV>
-__device__ __forceinline__ void dot_gload(DotRegs& r, const uint16_t* src, size_t tok0, int ts, int L, int wave, int n, int half) {
-    _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-        const int row = min(32 * jb + n, L - 1), tok = REV ? L - 1 - row : row;
-        const uint16_t* p = src + (tok0 + size_t(tok) * ts) * D + 32 * wave + 4 * half;
-        _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) r.v[jb][gg] = *reinterpret_cast<const u32x2*>(p + 8 * gg);
-    }
-}
-__device__ __forceinline__ float dot_rows(const DotRegs& r, int jb, const f32x16& a) {
-    float s = 0.f;
-    _Pragma("unroll") for (int gg = 0; gg < 4; ++gg) {
-        const u32x2 x = r.v[jb][gg];
-        s += bf16_lo(x.x) * a[4 * gg] + bf16_hi(x.x) * a[4 * gg + 1] + bf16_lo(x.y) * a[4 * gg + 2] + bf16_hi(x.y) * a[4 * gg + 3];
-    }
-    return s;
+__host__ __device__ constexpr int walk_lds(bool summary) {
+    return summary ? 2 * C * LD * 2 + (2 * C + 8) * 4 : (3 * C * LD + 2 * C * LDP) * 2 + (2 * C + 8) * 4;
 }
 
 // D[m][n] = sum_f Am[m0 + m][f] * Bm[n0 + n][f] over the 128 features of two row-major LDS tiles, the
@@ -261,22 +220,11 @@ __device__ __forceinline__ void walk_state_store(const f32x16 (&S)[4], float* e,
             e[transposed ? nn * D + mm : mm * D + nn] = S[ib][x];
         }
 }
-__device__ __forceinline__ float walk_state_dot(const f32x16 (&S)[4], const float* e, bool transposed, int w4, int n, int half) {
-    float z = 0.f;
-    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
-            const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * w4 + n;
-            z += S[ib][x] * e[transposed ? nn * D + mm : mm * D + nn];
-        }
-    for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
-    return z;
-}
-
-// REV: walk backward in time.  DEC: a decay is present.  DG: emit the dot products of the decay
-// gradient (needs a.xx).  SUMMARY: the state update alone, from a zero state, result to a.bound / a.gseg.
-template <bool REV, bool DEC, bool DG, bool SUMMARY>
+// REV: walk backward in time.  DEC: a decay is present.  SUMMARY: the state update alone, from a zero
+// state, result to a.bound / a.gseg.
+template <bool REV, bool DEC, bool SUMMARY>
 __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int seq, int seg, unsigned char* smem) {
-    // LDS: SUMMARY: K | V | bs | wo;   else: Q | K | V | P head | P remainder | bs | wo | (red)
+    // LDS: SUMMARY: K | V | bs | wo;   else: Q | K | V | P head | P remainder | bs | wo
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = SUMMARY ? Q : Q + C * LD;
     uint16_t* V = K + C * LD;
@@ -284,7 +232,6 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
     uint16_t* Pl = Ph + C * LDP;
     float* bs = reinterpret_cast<float*>(SUMMARY ? V + C * LD : Pl + C * LDP);  // beta[64], then b_C
     float* wo = bs + C + 4;                                                      // e^{b_C - beta}[64]
-    float* red = wo + C + 4;                                                     // DG: [4 waves][2][64]
     uint16_t* stage = Q;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
@@ -305,11 +252,10 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
     if (!SUMMARY) {
         const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
                                       : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-        if (ein) walk_state_load(S, ein, a.transposed, wave, n, half);
+        if (ein) walk_state_load(S, ein, false, wave, n, half);
     }
 
     TileRegs rq, rk, rv;
-    DotRegs rx;
     float gval = 0.f, gtot = 0.f;
     // The summary pass visits the chunks of its segment in the order opposite to the walk (a sum: each
     // chunk's weights carry the decay of the chunks that follow it in walk order), so that the walker,
@@ -336,8 +282,6 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         walk_commit<kThreads>(V, rv, L, tid);
         if (DEC && wave == 0) gtot += walk_decay_tables<REV>(gval, L, SUMMARY ? gtot : 0.f, bs, wo, lane);
         gload(kk + 1);
-        // needed only after the scores: no copy in LDS, no prefetch registers
-        if (DG) dot_gload<REV>(rx, a.xx, cp.tok0, cp.ts, L, wave, n, half);
         __syncthreads();  // (A) tiles and decay tables of this chunk are in LDS
         const float bC = DEC ? bs[C] : 0.f;
 
@@ -346,39 +290,15 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
             walk_inter<DEC>(O, S, Q, bs, n, half);
             walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
             __syncthreads();  // (C) scores are in LDS; nobody reads Q any more
-            float pdp[2] = {0.f, 0.f}, isp[2] = {0.f, 0.f};
             _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                if (DG) isp[jb] = dot_rows(rx, jb, O[jb]);
                 walk_intra(O[jb], jb, V, Ph, Pl, wave, lane, n, half);
-                if (DG) pdp[jb] = dot_rows(rx, jb, O[jb]);
                 store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
-            }
-            if (DG) {
-                _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                    const float pd = pdp[jb] + __shfl_xor(pdp[jb], 32, 64), is = isp[jb] + __shfl_xor(isp[jb], 32, 64);
-                    if (half == 0) {
-                        red[(wave * 2 + 0) * C + 32 * jb + n] = pd;
-                        red[(wave * 2 + 1) * C + 32 * jb + n] = is;
-                    }
-                }
             }
         }
         walk_update<DEC, !SUMMARY>(S, K, V, wo, bC, wave, lane, half);
         __syncthreads();  // (D) the output stage is complete and every read of this chunk's tiles is done
-        if (!SUMMARY) {
-            // every thread reads back exactly the stage pieces that its own next walk_commit overwrites: no barrier
-            walk_store<REV>(a.out, stage, cp.tok0, cp.ts, L, tid);
-            if (DG && tid < 64) {
-                float pd = 0.f, is = 0.f;
-                _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
-                    pd += red[(wv * 2 + 0) * C + tid];
-                    is += red[(wv * 2 + 1) * C + tid];
-                }
-                if (tid < L) a.pdot[cp.wtok0 + (REV ? L - 1 - tid : tid)] = pd;
-                for (int off = 32; off > 0; off >>= 1) is += __shfl_xor(is, off, 64);
-                if (tid == 0) a.isum[cp.slot] = is;
-            }
-        }
+        // every thread reads back exactly the stage pieces that its own next walk_commit overwrites: no barrier
+        if (!SUMMARY) walk_store<REV>(a.out, stage, cp.tok0, cp.ts, L, tid);
     }
 
     // ---- the state this walk ends with
@@ -387,142 +307,14 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         if (tid == 0) a.gseg[size_t(seq) * a.nseg + seg] = gtot;
         return;
     }
-    if (last && a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, a.transposed, wave, n, half);
-    if (last && a.y0) {
-        const float z = a.dot_with ? walk_state_dot(S, a.dot_with + size_t(seq) * D * D, a.transposed, wave, n, half) : 0.f;
-        __syncthreads();  // the decay tables of the last chunk have been read by everyone
-        if (lane == 0) wo[wave] = z;
-        __syncthreads();
-        if (tid == 0) a.y0[seq] = (wo[0] + wo[1]) + (wo[2] + wo[3]);
-    }
+    if (last && a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
 }
 
-// The two backward-in-time walkers of the backward pass as one workgroup of eight waves: waves 0-3
-// compute dv (roles k, q, d_o; state dM), waves 4-7 compute dk (roles v, d_o, q; state dM^T; with DG
-// also k_t . dk_t and b_c).  They need the same four tiles, which are loaded once; each half keeps its
-// own copy of the state.
-constexpr int kPairThreads = 2 * kThreads;
-__host__ __device__ constexpr int walk_pair_lds() {
-    return (4 * C * LD + 4 * C * LDP + 2 * C * LD) * 2 + (2 * C + 8) * 4 + 4 * 2 * C * 4;
-}
-template <bool DEC, bool DG>
-__device__ __forceinline__ void walk_pair_body(const Dims& d, const WalkArgs& av, const WalkArgs& ak, int seq, int seg,
-                                               unsigned char* smem) {
-    constexpr bool REV = true;
-    // LDS: q | k | v | d_o | P of dv (head, remainder) | P of dk | stage of dv | stage of dk | bs | wo | red
-    uint16_t* Tq = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* Tk = Tq + C * LD;
-    uint16_t* Tv = Tk + C * LD;
-    uint16_t* To = Tv + C * LD;
-    uint16_t* Pbase = To + C * LD;
-    uint16_t* Sbase = Pbase + 4 * C * LDP;
-    float* bs = reinterpret_cast<float*>(Sbase + 2 * C * LD);
-    float* wo = bs + C + 4;
-    float* red = wo + C + 4;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
-    const int role = wave >> 2, w4 = wave & 3, rtid = tid & (kThreads - 1);  // role 0: dv, role 1: dk
-    const WalkArgs& a = role ? ak : av;
-    const uint16_t* Q = role ? Tv : Tk;   // query role
-    const uint16_t* K = role ? To : Tq;   // key role
-    const uint16_t* V = role ? Tq : To;   // value role
-    uint16_t* Ph = Pbase + role * 2 * C * LDP;
-    uint16_t* Pl = Ph + C * LDP;
-    uint16_t* stage = Sbase + role * C * LD;
-
-    const SeqWalk walk = seq_walk(d, seq);
-    const int nsq = (walk.n + av.m - 1) / av.m;
-    const int kbeg = seg * av.m, kend = min(walk.n, kbeg + av.m), cnt = kend - kbeg;
-    const bool empty_seq = walk.n == 0 && seg == 0;
-    if (cnt <= 0 && !empty_seq) return;
-    const bool last = empty_seq || seg == 0;
-
-    f32x16 S[4];
-    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
-    {
-        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
-                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-        if (ein) walk_state_load(S, ein, a.transposed, w4, n, half);
-    }
-
-    TileRegs rq, rk, rv, ro;
-    float gval = 0.f;
-    auto gload = [&](int kk) {
-        const ChunkPos p = walk_pos(d, walk, kend - 1 - min(kk, cnt - 1));
-        if (DEC) {
-            const int row = min(lane, p.L - 1), tok = p.L - 1 - row;
-            gval = av.g[d.kind == 1 ? size_t(walk.bh % d.H) : p.tok0 + size_t(tok) * p.ts];
-        }
-        walk_gload<REV, kPairThreads>(rq, av.xk, p.tok0, p.ts, p.L, tid);  // dv's key role = q
-        walk_gload<REV, kPairThreads>(rk, av.xq, p.tok0, p.ts, p.L, tid);  // dv's query role = k
-        walk_gload<REV, kPairThreads>(rv, ak.xq, p.tok0, p.ts, p.L, tid);  // dk's query role = v
-        walk_gload<REV, kPairThreads>(ro, av.xv, p.tok0, p.ts, p.L, tid);  // dv's value role = d_o
-    };
-    if (cnt > 0) gload(0);
-
-    for (int kk = 0; kk < cnt; ++kk) {
-        const ChunkPos cp = walk_pos(d, walk, kend - 1 - kk);
-        const int L = cp.L;
-        walk_commit<kPairThreads>(Tq, rq, L, tid);
-        walk_commit<kPairThreads>(Tk, rk, L, tid);
-        walk_commit<kPairThreads>(Tv, rv, L, tid);
-        walk_commit<kPairThreads>(To, ro, L, tid);
-        if (DEC && wave == 0) walk_decay_tables<REV>(gval, L, 0.f, bs, wo, lane);
-        gload(kk + 1);
-        __syncthreads();  // (A)
-        const float bC = DEC ? bs[C] : 0.f;
-
-        f32x16 O[2];
-        walk_inter<DEC>(O, S, Q, bs, n, half);
-        walk_scores<DEC>(K, Q, Ph, Pl, bs, w4, n, half);
-        __syncthreads();  // (C)
-        float pdp[2] = {0.f, 0.f}, isp[2] = {0.f, 0.f};
-        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-            if (DG && role) isp[jb] = row_dot(Tk, 32 * jb + n, w4, half, O[jb]);
-            walk_intra(O[jb], jb, V, Ph, Pl, w4, lane, n, half);
-            if (DG && role) pdp[jb] = row_dot(Tk, 32 * jb + n, w4, half, O[jb]);
-            store_packed(stage, LD, 32 * jb + n, 32 * w4, half, pack_block(O[jb]));
-        }
-        if (DG && role) {
-            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                const float pd = pdp[jb] + __shfl_xor(pdp[jb], 32, 64), is = isp[jb] + __shfl_xor(isp[jb], 32, 64);
-                if (half == 0) {
-                    red[(w4 * 2 + 0) * C + 32 * jb + n] = pd;
-                    red[(w4 * 2 + 1) * C + 32 * jb + n] = is;
-                }
-            }
-        }
-        walk_update<DEC, true>(S, K, V, wo, bC, w4, lane, half);
-        __syncthreads();  // (D) both stages are complete; every read of this chunk's tiles is done
-        walk_store<REV>(a.out, stage, cp.tok0, cp.ts, L, rtid);
-        if (DG && role && rtid < 64) {
-            float pd = 0.f, is = 0.f;
-            _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
-                pd += red[(wv * 2 + 0) * C + rtid];
-                is += red[(wv * 2 + 1) * C + rtid];
-            }
-            if (rtid < L) ak.pdot[cp.wtok0 + (L - 1 - rtid)] = pd;
-            for (int off = 32; off > 0; off >>= 1) is += __shfl_xor(is, off, 64);
-            if (rtid == 0) ak.isum[cp.slot] = is;
-        }
-        // the stages are read above and written again only after the next (A) and (C)
-    }
-
-    if (last && role == 0 && av.edge_out) walk_state_store(S, av.edge_out + size_t(seq) * D * D, false, w4, n, half);
-    if (last && av.y0) {
-        const float z = (role == 0 && av.dot_with) ? walk_state_dot(S, av.dot_with + size_t(seq) * D * D, false, w4, n, half) : 0.f;
-        __syncthreads();
-        if (role == 0 && lane == 0) wo[w4] = z;
-        __syncthreads();
-        if (tid == 0) av.y0[seq] = (wo[0] + wo[1]) + (wo[2] + wo[3]);
-    }
-}
-
-// forward walker, or the summary pass of either direction
+// forward walker, or the summary pass of either direction (grid: segments x sequences)
 template <bool REV, bool DEC, bool SUMMARY>
 __global__ __launch_bounds__(kThreads, 2) void mk_walk(Dims d, WalkArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    walk_body<REV, DEC, false, SUMMARY>(d, a, blockIdx.y, blockIdx.x, smem);
+    walk_body<REV, DEC, SUMMARY>(d, a, blockIdx.y, blockIdx.x, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -766,19 +558,6 @@ __global__ __launch_bounds__(kThreads, 1) void mk_walk_grad(Dims d, GradArgs a) 
     walk_grad_body<DEC, WANT_DG>(d, a, blockIdx.y, blockIdx.x, smem);
 }
 
-// the dq walker of the backward pass (forward in time)
-template <bool DEC, bool DG>
-__global__ __launch_bounds__(kThreads, 2) void mk_walk_dq(Dims d, WalkArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    walk_body<false, DEC, DG, false>(d, a, blockIdx.y, blockIdx.x, smem);
-}
-// the dk and dv walkers of the backward pass (backward in time), one workgroup of eight waves per segment
-template <bool DEC, bool DG>
-__global__ __launch_bounds__(kPairThreads, 1) void mk_walk_dkdv(Dims d, WalkArgs av, WalkArgs ak) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    walk_pair_body<DEC, DG>(d, av, ak, blockIdx.y, blockIdx.x, smem);
-}
-
 // Entry state of every segment from the segments' own contributions (left by the summary pass in the
 // slot of the segment that follows in walk order) and total log-decays: E' = e^{G} E + U, in walk order.
 // grid: (128 * 128 / 256, seqs)
@@ -806,50 +585,3 @@ __global__ __launch_bounds__(kThreads) void mk_bound_scan(Dims d, const float* _
     }
 }
 
-// y_{c+1} = y_0 + sum_{c' <= c} (b_c' - a_c') for the chunks of one sequence, in a fixed order (grid: seqs)
-__global__ __launch_bounds__(kThreads) void mk_dg_chunks(Dims d, const float* __restrict__ asum, const float* __restrict__ bsum,
-                                                         const float* __restrict__ y0, float* __restrict__ ych) {
-    __shared__ float part[kThreads];
-    const int seq = blockIdx.x, tid = threadIdx.x;
-    const SeqWalk walk = seq_walk(d, seq);
-    const size_t base = size_t(walk.bh) * d.N + walk.c0;
-    float carry = y0[seq];
-    for (int c0 = 0; c0 < walk.n; c0 += kThreads) {
-        const int c = c0 + tid;
-        float x = c < walk.n ? bsum[base + c] - asum[base + c] : 0.f;
-        // inclusive scan over the block: within waves by shuffles, across waves through LDS
-        for (int off = 1; off < 64; off <<= 1) {
-            const float y = __shfl_up(x, off, 64);
-            if ((tid & 63) >= off) x += y;
-        }
-        if ((tid & 63) == 63) part[tid >> 6] = x;
-        __syncthreads();
-        float pre = carry;
-        for (int w = 0; w < (tid >> 6); ++w) pre += part[w];
-        const float tot = ((part[0] + part[1]) + part[2]) + part[3];
-        if (c < walk.n) ych[base + c] = pre + x;
-        carry += tot;
-        __syncthreads();
-    }
-}
-
-// dg_t = sum_{u >= t, u in chunk} (q_u . dq_u - k_u . dk_u) + y_{c+1}   (grid: N x BH, one wave)
-__global__ __launch_bounds__(64) void mk_dg_tokens(Dims d, const float* __restrict__ pf, const float* __restrict__ pr,
-                                                   const float* __restrict__ ych, float* __restrict__ dg) {
-    const int c = blockIdx.x, bh = blockIdx.y, lane = threadIdx.x;
-    const ChunkPos cp = chunk_pos(d, c, bh);
-    const int L = cp.L;
-    if (L <= 0) return;
-    float sfx = lane < L ? pf[cp.wtok0 + lane] - pr[cp.wtok0 + lane] : 0.f;
-    for (int off = 1; off < 64; off <<= 1) {
-        const float y = __shfl_down(sfx, off, 64);
-        if (lane + off < 64) sfx += y;
-    }
-    float v = lane < L ? sfx + ych[cp.slot] : 0.f;
-    if (d.kind == 1) {  // one decay per head: this chunk's share of the sum over tokens
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-        if (lane == 0) dg[cp.slot] = v;
-    } else if (lane < L) {
-        dg[cp.tok0 + size_t(lane) * cp.ts] = v;
-    }
-}
