@@ -127,6 +127,24 @@ int lsm_chunk_fwd(const lsm_params* p,
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lsm_chunk_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels and
+ * results as lsm_chunk_fwd, minus the workspace: the scratch (segment entry states, decay tables, the
+ * chunk table of a packed input) lives in a device array built into the library, LSM_NOALLOC_SCRATCH_BYTES
+ * per GPU, held from the first call on that GPU until the process ends.  Parameter sets whose
+ * lsm_chunk_fwd_workspace_bytes(p) exceeds that size are rejected with LSM_ERR_WORKSPACE before anything
+ * is enqueued.  The call allocates and frees nothing.  All calls on one GPU share the one array, which
+ * keeps the previous call's contents (nothing in it has to start at zero): calls that overlap on one GPU,
+ * on different streams or from different threads, race - serialise them.  LSM_FLAG_SAVE_STATES has no
+ * meaning here (there is no workspace to hand to lsm_chunk_bwd); leave flags at 0.
+ */
+#define LSM_NOALLOC_SCRATCH_BYTES (8u << 20)
+int lsm_chunk_fwd_noalloc(const lsm_params* p,
+                          const void* q, const void* k, const void* v,
+                          const float* log_decay, const float* init_state,
+                          void* o, float* final_state, void* stream);
+
+/*
  * Backward of  L = <o, d_o> + <M_T, d_final_state>  (the paper states no
  * backward; it is the adjoint of the forward above, evaluated chunkwise with a
  * reverse scan over chunk-state gradients).  Chunk states are recomputed from
@@ -209,7 +227,7 @@ int lsm_keeps_states(const lsm_params* p);
 /* Static, NUL-terminated description of a status code. */
 const char* lsm_status_string(int status);
 
-/* ABI version, bumped when a signature or struct changes (2: layout and packed input in lsm_params; 3: flags; 4: workspace query of the benchmark aid). */
+/* ABI version, bumped when a signature or struct changes (2: layout and packed input in lsm_params; 3: flags; 4: workspace query of the benchmark aid; 5: lsm_chunk_fwd_noalloc). */
 int lsm_version(void);
 
 #ifdef __cplusplus

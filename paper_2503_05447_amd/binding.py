@@ -45,6 +45,8 @@ def library():
     vp, sz, pp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(_Params)
     lib.lsm_chunk_fwd.restype = ctypes.c_int
     lib.lsm_chunk_fwd.argtypes = [pp] + [vp] * 8 + [sz, vp]
+    lib.lsm_chunk_fwd_noalloc.restype = ctypes.c_int
+    lib.lsm_chunk_fwd_noalloc.argtypes = [pp] + [vp] * 8
     lib.lsm_chunk_bwd.restype = ctypes.c_int
     lib.lsm_chunk_bwd.argtypes = [pp] + [vp] * 13 + [sz, vp]
     lib.lsm_chunk_fwd_workspace_bytes.restype = sz
@@ -215,6 +217,28 @@ def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None
     if rc != 0:
         raise LsmError(rc, "lsm_chunk_fwd")
     return o, final
+
+
+NOALLOC_SCRATCH_BYTES = 8 << 20
+
+
+def lsm_chunk_fwd_noalloc(q, k, v, log_decay, decay_kind, o, final_state=None, chunk_size=64, init_state=None, stream=None,
+                          layout=LAYOUT_BHTD, cu_seqlens=None):
+    """lsm_chunk_fwd without a workspace: the library's built-in scratch is used, nothing is allocated
+    (the caller passes the outputs ``o`` and, if wanted, ``final_state``).  Raises LsmError (workspace) for
+    shapes whose scratch need exceeds NOALLOC_SCRATCH_BYTES."""
+    import torch
+    p, (B, H, T, dk, dv), _ = _setup(q, k, v, log_decay, decay_kind, chunk_size, layout, cu_seqlens, 0)
+    _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
+    _check(final_state, (B, H, dk, dv), torch.float32, "final_state")
+    _check(o, tuple(v.shape), q.dtype, "o")
+    if o is None:
+        raise ValueError("o is required")
+    rc = library().lsm_chunk_fwd_noalloc(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(init_state),
+                                         _ptr(o), _ptr(final_state), _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_chunk_fwd_noalloc")
+    return o, final_state
 
 
 def lsm_step(q, k, v, log_decay, decay_kind, state, o=None, stream=None):

@@ -74,9 +74,38 @@ hipError_t prepare_tables(lsm::Dims& d, void*& workspace, hipStream_t stream) {
 
 }  // namespace
 
+// ---- scratch of the entry point that allocates nothing -------------------------------------------------
+// A file-scope device array: every GPU the library runs on holds its own copy, at its own address, until
+// the process ends.  Its name is a host-side stand-in; the device address comes from hipGetSymbolAddress,
+// once per device, and only that pointer is ever handed to a kernel.
+namespace {
+constexpr size_t kScratchBytes = LSM_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[64] = {};  // per device, filled on the first call on that device (a once-initialised cache)
+
+hipError_t scratch_of_current_device(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
 extern "C" {
 
-int lsm_version(void) { return 4; }
+int lsm_version(void) { return 5; }
 
 const char* lsm_status_string(int status) {
     switch (status) {
@@ -85,7 +114,7 @@ const char* lsm_status_string(int status) {
         case LSM_ERR_SHAPE: return "bad dimension or struct_size";
         case LSM_ERR_UNSUPPORTED: return "unsupported d_k/d_v/chunk_size/decay_kind/dtype";
         case LSM_ERR_ALIGN: return "pointer not 16-byte aligned";
-        case LSM_ERR_WORKSPACE: return "workspace missing or too small";
+        case LSM_ERR_WORKSPACE: return "workspace missing or too small (or, without a workspace argument, larger than the built-in scratch)";
         case LSM_ERR_LAUNCH: return "HIP error while enqueuing kernels";
         default: return "unknown status";
     }
@@ -182,6 +211,23 @@ int lsm_chunk_fwd(const lsm_params* p, const void* q, const void* k, const void*
     lsm::FwdArgs a{q, k, v, log_decay, init_state, o, final_state, workspace, static_cast<hipStream_t>(stream)};
     const hipError_t e = lsm::mfma_supported(d) ? lsm::mfma_fwd(d, a) : lsm::generic_fwd(d, a);
     return e == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
+}
+
+int lsm_chunk_fwd_noalloc(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,
+                          const float* init_state, void* o, float* final_state, void* stream) {
+    // every check of lsm_chunk_fwd, and the size limit, before the first HIP call
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !o) return LSM_ERR_NULL;
+    if ((d.kind == LSM_DECAY_NONE) != (log_decay == nullptr)) return LSM_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_decay) ||
+        misaligned(init_state) || misaligned(final_state))
+        return LSM_ERR_ALIGN;
+    if (lsm_chunk_fwd_workspace_bytes(p) > kScratchBytes) return LSM_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (scratch_of_current_device(&ws) != hipSuccess) return LSM_ERR_LAUNCH;
+    return lsm_chunk_fwd(p, q, k, v, log_decay, init_state, o, final_state, ws, kScratchBytes, stream);
 }
 
 size_t lsm_bench_intra_chunk_workspace_bytes(const lsm_params* p) {

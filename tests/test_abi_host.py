@@ -90,6 +90,14 @@ def test_error_codes_are_reached_before_any_launch():
     assert lib.lsm_bench_intra_chunk(ctypes.byref(P()), vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000), vp(0x5000),
                                      vp(0x10000), 1 << 40, 4, vp(None)) == ERR_UNSUP   # d = 64 is not on the MFMA path
     assert pkg.library().lsm_chunk_fwd(None, *([ctypes.c_void_p(None)] * 8), 0, ctypes.c_void_p(None)) == ERR_NULL
+    # the entry point without a workspace: the same checks, and the size limit of its built-in scratch
+    na = lambda p, q=0x1000, o=0x5000: lib.lsm_chunk_fwd_noalloc(ctypes.byref(p), vp(q), vp(0x2000), vp(0x3000), vp(0x4000),
+                                                                   vp(None), vp(o), vp(None), vp(None))
+    assert na(P(), q=None) == ERR_NULL
+    assert na(P(), o=0x5004) == ERR_ALIGN
+    assert na(P(d_k=96)) == ERR_UNSUP
+    big = P(B=4, H=16, T=8192, d_k=128, d_v=128)
+    assert pkg.lsm_chunk_fwd_workspace_bytes(big) > pkg.NOALLOC_SCRATCH_BYTES and na(big) == ERR_WS
 
 
 def test_workspace_queries_and_status_strings():
