@@ -24,7 +24,10 @@
  * enqueued on `stream` and outputs are valid once the stream reaches that
  * point.  Outputs are overwritten, never accumulated; inputs are not
  * modified; outputs must not alias inputs or each other.  Results are
- * bitwise reproducible from run to run (no atomics).
+ * bitwise reproducible from run to run (no atomics).  Calls may be made from
+ * several threads at once (the only state kept is a per-device cache that is
+ * written once); the benchmark aids of lsm_bench.h are the exception and say
+ * so there.
  *
  * Every argument check happens before the first HIP call, so the error
  * returns below can be exercised on a host without a GPU.
@@ -192,33 +195,6 @@ size_t lsm_chunk_bwd_workspace_bytes(const lsm_params* p);
  * Host-only.  (Both families run on the GPU; there is no CPU fallback.)
  */
 int lsm_kernel_path(const lsm_params* p);
-
-/*
- * Optional per-kernel timing for benchmarks (not part of the method).  After lsm_profile_start()
- * every kernel the library enqueues is bracketed by a pair of HIP events on the call's stream;
- * lsm_profile_stop() waits for them, writes up to `capacity` (kernel id, elapsed ms) pairs in launch
- * order, returns how many it wrote, and switches timing off again.  Process-wide state: do not use
- * from concurrent threads while other calls are in flight.  lsm_kernel_name() names an id.
- */
-int lsm_profile_start(void);
-int lsm_profile_stop(int* kernel_ids, float* milliseconds, int capacity);
-const char* lsm_kernel_name(int kernel_id);
-
-/*
- * Benchmark aid (not part of the method): the intra-chunk phase of the forward (masked decayed scores
- * times V plus Q times the chunk state; Algorithm 2, O_intra + O_inter) as a kernel of its own, one
- * chunk per workgroup, with its compute phase repeated `repeats` times on the tiles resident in LDS,
- * so that the arithmetic rate of that phase can be measured apart from the HBM traffic that bounds
- * the streamed path.  Only for parameter sets with lsm_kernel_path() == 1, a decay kind other than
- * LSM_DECAY_VECTOR and no packed input (else LSM_ERR_UNSUPPORTED).  The call first materialises one
- * chunk state per chunk in `workspace` (at least lsm_bench_intra_chunk_workspace_bytes(p), 0 if
- * unsupported), from a zero initial state; `o` receives lsm_chunk_fwd's output for init_state = NULL
- * (to rounding).
- */
-size_t lsm_bench_intra_chunk_workspace_bytes(const lsm_params* p);
-int lsm_bench_intra_chunk(const lsm_params* p, const void* q, const void* k, const void* v,
-                          const float* log_decay, void* o, void* workspace, size_t workspace_bytes,
-                          int repeats, void* stream);
 
 /* 1 if, for these params, lsm_chunk_fwd keeps its chunk states for lsm_chunk_bwd (see lsm_flags), 0 if the
  * backward call recomputes them, a negative lsm_status for invalid params. */

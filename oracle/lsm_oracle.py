@@ -31,8 +31,13 @@ def build_oracle(force=False):
 def _load():
     global _lib
     if _lib is None:
-        build_oracle()
-        lib = ctypes.CDLL(_LIB)
+        # LSM_ORACLE_LIB: test hook of the mutation test (tests/test_oracle_meta.py), which points the pins at a
+        # deliberately broken copy of the oracle to show that they notice
+        path = os.environ.get("LSM_ORACLE_LIB")
+        if not path:
+            build_oracle()
+            path = _LIB
+        lib = ctypes.CDLL(path)
         dp = ctypes.POINTER(ctypes.c_double)
         lib.lsm_oracle_fwd.restype = ctypes.c_int
         lib.lsm_oracle_fwd.argtypes = [ctypes.c_int] * 6 + [dp] * 7

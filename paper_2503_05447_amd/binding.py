@@ -34,13 +34,18 @@ _lib = None
 
 
 def library():
-    """Load liblsm_hip.so (building it only if no built library exists)."""
+    """Load liblsm_hip.so (building it only if no built library exists; a library older than its sources is
+    loaded as it is, with a warning: rebuild with paper_2503_05447_amd.build.build_library())."""
     global _lib
     if _lib is not None:
         return _lib
     path = _build.LIB_PATH
     if not os.path.exists(path):
         _build.build_library()
+    elif _build._stale():
+        import warnings
+        warnings.warn("liblsm_hip.so is older than its sources; run paper_2503_05447_amd.build.build_library()",
+                      RuntimeWarning, stacklevel=2)
     lib = ctypes.CDLL(path)
     vp, sz, pp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(_Params)
     lib.lsm_chunk_fwd.restype = ctypes.c_int
@@ -67,6 +72,12 @@ def library():
     lib.lsm_keeps_states.argtypes = [pp]
     lib.lsm_step.restype = ctypes.c_int
     lib.lsm_step.argtypes = [pp] + [vp] * 7
+    lib.lsm_calib_copy.restype = ctypes.c_int
+    lib.lsm_calib_copy.argtypes = [vp, vp, sz, vp]
+    lib.lsm_calib_mfma.restype = ctypes.c_int
+    lib.lsm_calib_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
+    lib.lsm_calib_mfma_flops.restype = ctypes.c_double
+    lib.lsm_calib_mfma_flops.argtypes = [ctypes.c_int, ctypes.c_int]
     lib.lsm_bench_intra_chunk_workspace_bytes.restype = sz
     lib.lsm_bench_intra_chunk_workspace_bytes.argtypes = [pp]
     lib.lsm_bench_intra_chunk.restype = ctypes.c_int
@@ -172,6 +183,14 @@ def _setup(q, k, v, log_decay, decay_kind, chunk_size, layout=LAYOUT_BHTD, cu_se
     return p, (n_seq or B, H, T, dk, dv), gshape
 
 
+def _alloc_on(stream):
+    """Context in which torch allocates for `stream` (its caching allocator ties a block to the stream that is
+    current at allocation time; a temporary used on another stream could be handed out again too early)."""
+    import contextlib
+    import torch
+    return torch.cuda.stream(stream) if stream is not None else contextlib.nullcontext()
+
+
 def _stream_handle(stream):
     import torch
     s = stream if stream is not None else torch.cuda.current_stream()
@@ -208,10 +227,11 @@ def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None
                                      _save_flags(save_states))
     _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
     need = lsm_chunk_fwd_workspace_bytes(p)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    o = torch.empty_like(v)
-    final = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
+    with _alloc_on(stream):   # what is allocated here is used on `stream`: allocate it there
+        if workspace is None:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        o = torch.empty_like(v)
+        final = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
     rc = library().lsm_chunk_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(init_state),
                                  _ptr(o), _ptr(final), _ptr(workspace), workspace.numel(), _stream_handle(stream))
     if rc != 0:
@@ -284,6 +304,21 @@ def lsm_bench_intra_chunk(q, k, v, log_decay, decay_kind, o, workspace, repeats,
         raise LsmError(rc, "lsm_bench_intra_chunk")
 
 
+def lsm_calib_copy(dst, src, stream=None):
+    """Benchmark aid: dst <- src with the library's plain streaming-copy kernel (uint8 tensors, equal sizes)."""
+    rc = library().lsm_calib_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_calib_copy")
+
+
+def lsm_calib_mfma(out, workgroups, iters, stream=None):
+    """Benchmark aid: a loop of nothing but bf16 MFMAs; returns the flop count of the launch."""
+    rc = library().lsm_calib_mfma(_ptr(out), int(workgroups), int(iters), _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_calib_mfma")
+    return float(library().lsm_calib_mfma_flops(int(workgroups), int(iters)))
+
+
 def lsm_bench_intra_chunk_workspace(q, k, v, log_decay, decay_kind, chunk_size=64):
     import torch
     p, _, _ = _setup(q, k, v, log_decay, decay_kind, chunk_size)
@@ -307,13 +342,14 @@ def lsm_chunk_bwd(q, k, v, log_decay, decay_kind, d_o, chunk_size=64, init_state
     _check(d_final_state, (B, H, dk, dv), torch.float32, "d_final_state")
     _check(d_o, tuple(v.shape), q.dtype, "d_o")
     need = lsm_chunk_bwd_workspace_bytes(p)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    dq = torch.empty_like(q)
-    dk_ = torch.empty_like(k)
-    dv_ = torch.empty_like(v)
-    dg = torch.empty(gshape, dtype=torch.float32, device=q.device) if (gshape and want_d_log_decay) else None
-    d_init = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_d_init_state else None
+    with _alloc_on(stream):
+        if workspace is None:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        dq = torch.empty_like(q)
+        dk_ = torch.empty_like(k)
+        dv_ = torch.empty_like(v)
+        dg = torch.empty(gshape, dtype=torch.float32, device=q.device) if (gshape and want_d_log_decay) else None
+        d_init = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_d_init_state else None
     rc = library().lsm_chunk_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_decay), _ptr(init_state),
                                  _ptr(d_o), _ptr(d_final_state), _ptr(dq), _ptr(dk_), _ptr(dv_), _ptr(dg),
                                  _ptr(d_init), _ptr(workspace), workspace.numel(), _stream_handle(stream))

@@ -1,6 +1,7 @@
 // C-ABI front end: argument validation, routing to a kernel family, status strings.
 // All checks run before the first HIP call so they can be exercised without a GPU.
 #include "../../include/lsm.h"
+#include "../../include/lsm_bench.h"
 #include "lsm_internal.h"
 
 #include <mutex>
@@ -10,7 +11,9 @@ namespace lsm {
 namespace {
 struct ProfRec { int id; hipEvent_t t0, t1; };
 std::mutex g_prof_mu;
-bool g_prof_on = false;
+// Benchmark-only, process-wide state (declared in lsm_bench.h, outside the thread-safety contract of lsm.h):
+// off unless lsm_profile_start() was called.
+bool g_prof_on = false, g_prof_open = false;
 std::vector<ProfRec> g_prof;
 }  // namespace
 
@@ -18,14 +21,22 @@ void prof_begin(int kernel_id, hipStream_t stream) {
     if (!g_prof_on) return;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     ProfRec r{kernel_id, nullptr, nullptr};
-    if (hipEventCreate(&r.t0) != hipSuccess || hipEventCreate(&r.t1) != hipSuccess) return;
+    g_prof_open = false;
+    if (hipEventCreate(&r.t0) != hipSuccess) return;
+    if (hipEventCreate(&r.t1) != hipSuccess) {
+        (void)hipEventDestroy(r.t0);
+        return;
+    }
     (void)hipEventRecord(r.t0, stream);
     g_prof.push_back(r);
+    g_prof_open = true;
 }
 void prof_end(hipStream_t stream) {
     if (!g_prof_on) return;
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    if (!g_prof.empty()) (void)hipEventRecord(g_prof.back().t1, stream);
+    // only the record that the matching prof_begin opened (none if its events could not be created)
+    if (g_prof_open && !g_prof.empty()) (void)hipEventRecord(g_prof.back().t1, stream);
+    g_prof_open = false;
 }
 }  // namespace lsm
 
