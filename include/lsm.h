@@ -150,9 +150,13 @@ int lsm_chunk_fwd_noalloc(const lsm_params* p,
 /*
  * Backward of  L = <o, d_o> + <M_T, d_final_state>  (the paper states no
  * backward; it is the adjoint of the forward above, evaluated chunkwise with a
- * reverse scan over chunk-state gradients).  Chunk states are recomputed from
- * the inputs; nothing saved by the forward call is needed (unless
- * LSM_FLAG_SAVE_STATES is set, see lsm_flags).
+ * reverse scan over chunk-state gradients).  The forward's states that the
+ * gradients need are recomputed from the inputs; nothing saved by the forward
+ * call is needed (unless LSM_FLAG_SAVE_STATES is set, see lsm_flags).
+ * Shapes outside the matrix-core family (lsm_kernel_path(p) == 0: fp32
+ * elements, d_k other than 128, chunk other than 64) run on plain fp32 kernels
+ * that are correct to the fp32 tolerance and far slower; they are meant for
+ * checks and odd shapes.
  *   q,k,v,log_decay,init_state   as in the forward                         in
  *   d_o            [B,H,T,d_v] dtype                                       in
  *   d_final_state  NULL (= zeros) or [B,H,d_k,d_v] fp32                    in
