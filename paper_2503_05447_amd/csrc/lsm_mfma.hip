@@ -116,6 +116,11 @@ struct StateArgs {
     int a_stride;           // row stride (elements) of the A-side operand = d_v
     int vh_count;           // 128-wide value slices per (b,h); each is scanned as a sequence of its own
     uint16_t* states_twin;  // MODE 2 only: second copy of the head, untransposed (dS^T [v][i]), or NULL
+    // scan cut into segments (seg_n > 1; grid = seg_n times the plain one): segment s walks chunks
+    // [s seg_m, (s+1) seg_m) from the state in seg_bound, which holds fp32 [i][v] entry states at a finer grain
+    // (one per fine_m chunks, fine_n slots per sequence, slot f = the state the walk enters fine segment f with)
+    const float* seg_bound;
+    int seg_m, seg_n, fine_m, fine_n;
 };
 
 // coalesced: the A side as whole 256-byte rows (16 lanes per row), the B side as 64-byte row slices.
@@ -271,8 +276,9 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     // XCDs round-robin by linear id, so the id is decoded such that those four share an XCD (and
     // its L2): id = xcd + 8 * (4 * (seq / 8) + nb), seq = xcd + 8 * (seq / 8).
     int nb, seq;
+    const int nsegs = sa.seg_n > 1 ? sa.seg_n : 1, seg = wg_id / (wg_count / nsegs);
     {
-        const int id = wg_id, nwg = wg_count, full = (nwg / 32) * 32;  // 32 = 8 XCDs x 4 blocks
+        const int nwg = wg_count / nsegs, id = wg_id % nwg, full = (nwg / 32) * 32;  // 32 = 8 XCDs x 4 blocks
         if (id < full) {
             const int xcd = id & 7, slot = id >> 3;
             nb = slot & 3;
@@ -284,7 +290,9 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     }
     const int vh = VEC ? seq % sa.vh_count : 0, nvh = VEC ? sa.vh_count : 1;
     const SeqWalk walk = seq_walk(d, VEC ? seq / sa.vh_count : seq);
-    const int cnt = walk.n;  // chunks to walk
+    const int kbeg = nsegs > 1 ? seg * sa.seg_m : 0, kend = nsegs > 1 ? min(walk.n, kbeg + sa.seg_m) : walk.n;
+    if (seg > 0 && kend <= kbeg) return;  // a sequence shorter than this segment's start
+    const int cnt = kend - kbeg;  // chunks to walk
     const int tid = threadIdx.x, lane = tid & 63, mb = tid >> 6;
     const int n = lane & 31, half = lane >> 5;
     constexpr int sz = D * D;
@@ -292,14 +300,25 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
 
     // acc[4g+j] = state element (m = 32mb + 8g + 4half + j, n = 32nb + lane%32); MODE 0: m = i, else m = v
     f32x16 acc = {0};
-    if (edge_in) {
+    if (nsegs > 1) {
+        // MODE 2 walks backward: it enters with the state of the last fine segment it covers
+        const int nfine = max(1, (walk.n + sa.fine_m - 1) / sa.fine_m), per = sa.seg_m / sa.fine_m;
+        const int f = MODE == 2 ? min(nfine, (seg + 1) * per) - 1 : seg * per;
+        const float* e = sa.seg_bound + (size_t(seq) * sa.fine_n + f) * D * D;
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {
+            const int mm = 32 * mb + 8 * (r >> 2) + 4 * half + (r & 3), nn = 32 * nb + n;
+            acc[r] = MODE == 0 ? e[mm * D + nn] : e[nn * D + mm];
+        }
+    } else if (edge_in) {
         const float* e = edge_in + size_t(walk.edge) * D * erow + D * vh;
         _Pragma("unroll") for (int r = 0; r < 16; ++r) {
             const int mm = 32 * mb + 8 * (r >> 2) + 4 * half + (r & 3), nn = 32 * nb + n;
             acc[r] = MODE == 0 ? e[mm * erow + nn] : e[nn * erow + mm];
         }
     }
-    const int first = MODE == 2 ? cnt - 1 : 0, step = MODE == 2 ? -1 : 1;
+    const int first = MODE == 2 ? kend - 1 : kbeg, step = MODE == 2 ? -1 : 1;
+    // the state this walk ends with leaves through edge_out only where the walk ends the sequence
+    if (nsegs > 1 && (MODE == 2 ? seg != 0 : kend < walk.n)) edge_out = nullptr;
     auto bufA = [&](int k) { return tiles + (k & 1) * kStateTile; };
     auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
     auto slot = [&](int k) { return ((size_t(walk.bh) * d.N + walk.c0 + (first + step * k)) * nvh + vh) * sz; };
@@ -644,8 +663,20 @@ SegPlan seg_plan(const Dims& d) {
     const int m = (nmax + nseg - 1) / nseg;
     return SegPlan{m, (nmax + m - 1) / m};
 }
+// The reverse scan of the state gradients has four workgroups per sequence.  With fewer than one per compute
+// unit it is cut into segments as well: `per` of the walkers' segments to each of its own, entry gradients from a
+// summary pass of the reverse direction.
+struct RevPlan { int per, nseg; };
+RevPlan rev_plan(const Dims& d, const SegPlan& sp) {
+    const int wgs = D / 32 * d.seqs();
+    if (wgs >= 256 || sp.nseg <= 1) return RevPlan{sp.nseg, 1};
+    const int want = (kWalkTargetWgs + wgs - 1) / wgs;
+    const int per = sp.nseg / want > 1 ? sp.nseg / want : 1;
+    return RevPlan{per, (sp.nseg + per - 1) / per};
+}
 struct WalkWs {
     float *bound_f, *gseg_f;     // entry states of the segments (forward in time) and the segments' total log-decays
+    float *bound_r, *gseg_r;     // backward, segmented reverse scan only: the same for the state gradients, backward in time
     uint16_t* dstates;           // backward: one state gradient per chunk (fragment-major bf16)
     float *wdec, *winc, *lam;    // backward: decay tables of the reverse scan
     float* dgc;                  // per-head kind: per-chunk sums of dg
@@ -670,6 +701,10 @@ WalkWs carve_walk(const Dims& d, void* ws, bool bwd) {
             w.lam = take(size_t(d.BH()) * d.N * 4);
         }
         if (d.kind == 1) w.dgc = take(size_t(d.BH()) * d.N * 4);
+        if (rev_plan(d, sp).nseg > 1) {
+            w.bound_r = take(nb);
+            w.gseg_r = take(ng);
+        }
     }
     w.bytes = off;
     return w;
@@ -710,7 +745,7 @@ size_t mfma_bwd_workspace(const Dims& d) { return d.kind == 3 ? carve(d, nullptr
 namespace {
 template <int MODE>
 hipError_t launch_state(const Dims& d, hipStream_t st, const StateArgs& sa) {
-    const dim3 sgrid(D / 32 * d.seqs()), block(kThreads);
+    const dim3 sgrid(D / 32 * d.seqs() * (sa.seg_n > 1 ? sa.seg_n : 1)), block(kThreads);
     const int lds = kStateLdsNone;
     hipError_t e;
     if (d.kind == 0) {
@@ -773,10 +808,10 @@ namespace {
 // entry states of the segments of one direction: summary pass, then the scan over segments
 template <bool REV>
 hipError_t walk_bounds(const Dims& d, hipStream_t st, const SegPlan& sp, const uint16_t* xk, const uint16_t* xv, const float* g,
-                       const float* edge_in, float* bound, float* gseg) {
+                       const float* edge_in, float* bound, float* gseg, int skip = 1) {
     if (sp.nseg <= 1) return hipSuccess;
     WalkArgs a{};
-    a.xk = xk; a.xv = xv; a.g = g; a.bound = bound; a.gseg = gseg; a.m = sp.m; a.nseg = sp.nseg;
+    a.xk = xk; a.xv = xv; a.g = g; a.bound = bound; a.gseg = gseg; a.m = sp.m; a.nseg = sp.nseg; a.skip = skip;
     hipError_t e;
     const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
     {
@@ -791,7 +826,7 @@ hipError_t walk_bounds(const Dims& d, hipStream_t st, const SegPlan& sp, const u
         }
     }
     ProfScope ps(KID_WALK_SCAN, st);
-    hipLaunchKernelGGL(mk_bound_scan<REV>, dim3(D * D / kThreads, d.seqs()), block, 0, st, d, edge_in, bound, gseg, sp.m, sp.nseg);
+    hipLaunchKernelGGL(mk_bound_scan<REV>, dim3(D * D / kThreads, d.seqs()), block, 0, st, d, edge_in, bound, gseg, sp.m, sp.nseg, skip);
     return hipSuccess;
 }
 
@@ -829,9 +864,17 @@ hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
         hipLaunchKernelGGL(mk_decay_prep, dim3(d.N, d.BH()), dim3(64), 0, a.stream, d, a.g, w.wdec, w.winc, w.lam);
     }
     {
+        StateArgs sa{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0};
+        const RevPlan rp = rev_plan(d, sp);
+        if (rp.nseg > 1) {
+            // entry gradients of the segments: the summary pass and the segment scan, backward in time (roles: key = q,
+            // value = d_o)
+            if ((e = walk_bounds<true>(d, a.stream, sp, q, d_o, a.g, a.d_mT, w.bound_r, w.gseg_r, rp.per)) != hipSuccess) return e;
+            sa.seg_bound = w.bound_r;
+            sa.seg_m = rp.per * sp.m; sa.seg_n = rp.nseg; sa.fine_m = sp.m; sa.fine_n = sp.nseg;
+        }
         ProfScope ps(KID_MFMA_DSTATE, a.stream);
-        if ((e = launch_state<2>(d, a.stream, StateArgs{d_o, q, w.winc, w.lam, w.dstates, nullptr, a.d_mT, a.d_m0})) != hipSuccess)
-            return e;
+        if ((e = launch_state<2>(d, a.stream, sa)) != hipSuccess) return e;
     }
     // entry states of the segments, unless the forward call left them
     if (!d.save && (e = walk_bounds<false>(d, a.stream, sp, k, v, a.g, a.m0, w.bound_f, w.gseg_f)) != hipSuccess) return e;

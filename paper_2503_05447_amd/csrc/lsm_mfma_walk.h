@@ -27,6 +27,7 @@ struct WalkArgs {
     float* bound;          // [seqs][nseg][128 x 128] fp32, [i][v]: entry state of every segment (nseg > 1)
     float* gseg;           // [seqs][nseg]: total log-decay of each segment (SUMMARY writes)
     int m, nseg;           // chunks per segment, segments per sequence (upper bound for packed input)
+    int skip;              // SUMMARY, REV: segments [0, skip) feed no other walk and are left out (at least 1)
 };
 
 // tile rows in walk order: row r holds token r (forward) or token L-1-r (backward); rows >= L are zero.
@@ -241,7 +242,7 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
     const bool empty_seq = walk.n == 0 && seg == 0;  // packed input: the state passes through
     if (SUMMARY) {
         // only segments whose end state another segment starts from
-        if (cnt <= 0 || (REV ? seg == 0 : seg >= nsq - 1)) return;
+        if (cnt <= 0 || (REV ? seg < a.skip : seg >= nsq - 1)) return;
     } else if (cnt <= 0 && !empty_seq) {
         return;
     }
@@ -563,7 +564,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_walk_grad(Dims d, GradArgs a) 
 // grid: (128 * 128 / 256, seqs)
 template <bool REV>
 __global__ __launch_bounds__(kThreads) void mk_bound_scan(Dims d, const float* __restrict__ edge_in, float* __restrict__ bound,
-                                                          const float* __restrict__ gseg, int m, int nseg) {
+                                                          const float* __restrict__ gseg, int m, int nseg, int skip) {
     const int seq = blockIdx.y, e = blockIdx.x * kThreads + threadIdx.x;
     const SeqWalk walk = seq_walk(d, seq);
     const int nsq = max(1, (walk.n + m - 1) / m);
@@ -578,7 +579,7 @@ __global__ __launch_bounds__(kThreads) void mk_bound_scan(Dims d, const float* _
         }
     } else {
         b[size_t(nsq - 1) * D * D] = E;
-        for (int s = nsq - 1; s > 0; --s) {
+        for (int s = nsq - 1; s >= skip; --s) {  // slots below skip - 1 are entered by no walk
             E = __expf(gs[s]) * E + b[size_t(s - 1) * D * D];
             b[size_t(s - 1) * D * D] = E;
         }

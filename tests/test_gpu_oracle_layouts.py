@@ -146,8 +146,9 @@ def test_strong_decay_with_carried_states(kind, decay, saved):
 
 
 # (B, H, T): 512 sequences -> one segment each; 6 sequences -> many segments; T chosen so that the last segment and
-# the last chunk are both ragged; one chunk only; two sequences with 21 chunks
-SEGMENT_SHAPES = [(32, 16, 130), (2, 3, 1500), (1, 5, 1111), (1, 1, 64), (1, 2, 1300)]
+# the last chunk are both ragged; one chunk only; two sequences with 21 chunks; 40 sequences of 24 chunks -> walker
+# segments of two chunks, and a reverse scan in four segments of three walker segments each
+SEGMENT_SHAPES = [(32, 16, 130), (2, 3, 1500), (1, 5, 1111), (1, 1, 64), (1, 2, 1300), (5, 8, 1500)]
 
 
 @pytest.mark.parametrize("saved", [False, True])
