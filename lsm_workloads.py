@@ -96,6 +96,43 @@ def make_inputs(B, H, T, dk, dv, kind, dtype="bf16", seed=0, decay="default",
                 B=B, H=H, T=T, dk=dk, dv=dv)
 
 
+def make_delta_inputs(B, H, T, dk, dv, gated, dtype="bf16", seed=0, decay="default", init_state=False, d_final=False,
+                      init_std=0.1, tie_b=True):
+    """Inputs of the delta-rule rows (DeltaNet: gated False; Gated DeltaNet: gated True), from one seeded stream.
+
+    q ~ N(0,1)/sqrt(dk); k drawn N(0,1) and scaled to unit length (as the delta-rule models normalise their keys);
+    v ~ N(0,1); the row's write strength b_s = sigmoid(N(0,1)); DeltaNet's erase strength a_s = b_s (``tie_b``, the
+    usual parametrisation) or an independent draw of the same law; Gated DeltaNet's decay log a_s by the scalar-decay
+    law named by ``decay`` (see make_inputs).  Values are float32; with dtype "bf16" q, k, v, d_o are rounded to bf16
+    (so a key's length is 1 up to that rounding).
+    """
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((B, H, T, dk), dtype=np.float32) * np.float32(1.0 / np.sqrt(dk))
+    k = rng.standard_normal((B, H, T, dk), dtype=np.float32)
+    k /= np.maximum(np.sqrt((k * k).sum(-1, keepdims=True)), np.float32(1e-6))
+    v = rng.standard_normal((B, H, T, dv), dtype=np.float32)
+    sig = lambda n: (1.0 / (1.0 + np.exp(-n))).astype(np.float32)
+    b = sig(rng.standard_normal((B, H, T), dtype=np.float32))
+    n2 = rng.standard_normal((B, H, T), dtype=np.float32)
+    n3 = rng.standard_normal((B, H, T), dtype=np.float32)
+    beta = None if gated else (b.copy() if tie_b else sig(n2))
+    log_alpha = None
+    if gated:
+        shift = {"default": 3.0, "strong4": 4.0, "weak": -4.0}.get(decay)
+        if shift is None:
+            raise ValueError(decay)
+        log_alpha = np.ascontiguousarray(-_softplus(n3 + shift), dtype=np.float32)
+    m0 = (rng.standard_normal((B, H, dk, dv), dtype=np.float32) * np.float32(init_std)) if init_state else None
+    d_o = rng.standard_normal((B, H, T, dv), dtype=np.float32)
+    d_mT = rng.standard_normal((B, H, dk, dv), dtype=np.float32) * np.float32(init_std) if d_final else None
+    if dtype == "bf16":
+        q, k, v, d_o = bf16_round(q), bf16_round(k), bf16_round(v), bf16_round(d_o)
+    elif dtype != "f32":
+        raise ValueError(dtype)
+    return dict(q=q, k=k, v=v, log_alpha=log_alpha, beta=beta, b=b, m0=m0, d_o=d_o, d_mT=d_mT, gated=gated, dtype=dtype,
+                B=B, H=H, T=T, dk=dk, dv=dv)
+
+
 # The five benchmark configurations (index 0..4 = configs 1..5 of the task statement).
 CONFIGS = [
     dict(name="config1_bla_f32", B=1, H=2, T=256, dk=64, dv=64, kind=KIND_NONE, dtype="f32",

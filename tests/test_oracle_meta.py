@@ -1,6 +1,6 @@
 """CPU-only checks around the oracle and the test metric themselves:
-  * the pins of tests/test_oracle_pins.py notice planted mistakes (each mutation of a copy of the oracle's C
-    source must make at least one pin fail);
+  * the pins of tests/test_oracle_pins.py and tests/test_delta_oracle_pins.py notice planted mistakes (each
+    mutation of a copy of an oracle's C source must make at least one pin fail);
   * the harness's bf16 round-to-nearest-even helper, which fixes the inputs of BOTH sides, agrees with torch;
   * the reading of the bf16 tolerance: storing an exact result in a bf16 container alone exceeds 2e-2 of the
     RMS at the largest elements of these heavy-tailed outputs, and the discount of 2^-8 |ref| used by the
@@ -36,9 +36,29 @@ MUTATIONS = [
 ]
 
 
-def _run_pins(lib):
-    env = dict(os.environ, LSM_ORACLE_LIB=lib)
-    return subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+# the same for the delta-rule oracle and tests/test_delta_oracle_pins.py
+DELTA_SRC = os.path.join(ROOT, "oracle", "delta_oracle.c")
+DELTA_MUTATIONS = [
+    ("the erase term reads the new state instead of M_{s-1}: update applied row by row while w is being formed",
+     r"M\[\(size_t\)i \* dv \+ j\] = alpha \* \(M\[\(size_t\)i \* dv \+ j\] - beta \* k\[i\] \* w\[j\]\) \+ bw \* k\[i\] \* v\[j\];",
+     "M[(size_t)i * dv + j] = alpha * (M[(size_t)i * dv + j] - beta * k[i] * w[j]) + bw * k[i] * v[j], w[j] += 0.01 * M[(size_t)i * dv + j];"),
+    ("erase term with the wrong sign", r"- beta \* k\[i\] \* w\[j\]\) \+ bw", "+ beta * k[i] * w[j]) + bw"),
+    ("alpha also applied to the written value", r"\+ bw \* k\[i\] \* v\[j\];", "+ alpha * bw * k[i] * v[j];"),
+    ("beta left out of the erase term", r"alpha \* \(M\[\(size_t\)i \* dv \+ j\] - beta \* k\[i\]", "alpha * (M[(size_t)i * dv + j] - k[i]"),
+    ("w = M k^T taken with the state transposed", r"w\[j\] \+= k\[i\] \* M\[\(size_t\)i \* dv \+ j\];   /\* w = k M_\{s-1\} \*/",
+     "w[j] += k[i] * M[(size_t)(j % dk) * dv + (i % dv)];"),
+    ("alpha dropped from the gradient of beta", r"d_beta\[tok\] = -al \* zw;", "d_beta[tok] = -zw;"),
+    ("second key term of dk dropped", r"\+ Mp\[\(size_t\)i \* dv \+ j\] \* z\[j\]\);", ");"),
+    ("state gradient passed on without the erase term", r"dM\[\(size_t\)i \* dv \+ j\] = al \* \(dM\[\(size_t\)i \* dv \+ j\] - be \* kt\[i\] \* z\[j\]\);",
+     "dM[(size_t)i * dv + j] = al * dM[(size_t)i * dv + j];"),
+    ("read-out gradient uses the state before the token", r"s \+= Mt\[\(size_t\)i \* dv \+ j\] \* dot\[j\];", "s += Mp[(size_t)i * dv + j] * dot[j];"),
+    ("gradient of the final state ignored", r"if \(d_mT\) memcpy\(dM, d_mT", "if (0) memcpy(dM, d_mT"),
+]
+
+
+def _run_pins(lib, pins="test_oracle_pins.py", var="LSM_ORACLE_LIB"):
+    env = dict(os.environ, **{var: lib})
+    return subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", pins), "-x", "-q",
                            "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
                           text=True)
 
@@ -64,6 +84,25 @@ def test_a_planted_mistake_fails_a_pin(tmp_path, what, pattern, repl):
     lib = str(tmp_path / "mut.so")
     _compile(mutated, lib)
     res = _run_pins(lib)
+    assert res.returncode != 0, "no pin noticed: " + what
+    assert "failed" in res.stdout
+
+
+def test_delta_pins_pass_on_an_unmodified_copy(tmp_path):
+    lib = str(tmp_path / "copy.so")
+    _compile(open(DELTA_SRC).read(), lib)
+    res = _run_pins(lib, "test_delta_oracle_pins.py", "DELTA_ORACLE_LIB")
+    assert res.returncode == 0, res.stdout[-2000:]
+
+
+@pytest.mark.parametrize("what,pattern,repl", DELTA_MUTATIONS, ids=[m[0][:60] for m in DELTA_MUTATIONS])
+def test_a_planted_mistake_fails_a_delta_pin(tmp_path, what, pattern, repl):
+    text = open(DELTA_SRC).read()
+    mutated, n = re.subn(pattern, repl, text)
+    assert n >= 1, "the mutation no longer matches the oracle source: " + what
+    lib = str(tmp_path / "mut.so")
+    _compile(mutated, lib)
+    res = _run_pins(lib, "test_delta_oracle_pins.py", "DELTA_ORACLE_LIB")
     assert res.returncode != 0, "no pin noticed: " + what
     assert "failed" in res.stdout
 
