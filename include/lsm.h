@@ -148,6 +148,28 @@ int lsm_chunk_fwd_noalloc(const lsm_params* p,
                           void* o, float* final_state, void* stream);
 
 /*
+ * Forward of the two delta-rule rows of Table 1 under Eq. 5, chunkwise:
+ *     M_t = alpha_t (I - beta_t k_t^T k_t) M_{t-1} + b_t k_t^T v_t ,    o_t = q_t M_t
+ * DeltaNet:        alpha = 1 (log_alpha NULL, decay_kind LSM_DECAY_NONE), beta = the row's a_t, b = the row's b_t;
+ * Gated DeltaNet:  alpha = the row's a_t (log_alpha = log a_t <= 0, decay_kind LSM_DECAY_SCALAR), beta NULL (= 1).
+ *   q, k, v, init_state, o, final_state   as in lsm_chunk_fwd (both layouts)
+ *   log_alpha, beta, b   fp32 per token, [B,H,T] ([B,T,H] with LSM_LAYOUT_BTHD); NULL = the constant 1        in
+ *   workspace            at least lsm_delta_fwd_workspace_bytes(p); contents undefined after the call
+ * Served for bf16 elements, d_k = d_v = 128, chunk_size 64, unpacked input (n_seq = 0); everything else returns
+ * LSM_ERR_UNSUPPORTED (the workspace query then returns 0).  flags are ignored.  Keys are expected to have
+ * at most unit length times sqrt(2 / beta) (the erase factor is then a contraction); nothing is checked.
+ * One workgroup walks a sequence from end to end, so the chip is full from B*H >= 256 sequences on.
+ * The backward of these rows is not part of the library.
+ */
+size_t lsm_delta_fwd_workspace_bytes(const lsm_params* p);
+int lsm_delta_fwd(const lsm_params* p,
+                  const void* q, const void* k, const void* v,
+                  const float* log_alpha, const float* beta, const float* b,
+                  const float* init_state,
+                  void* o, float* final_state,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Backward of  L = <o, d_o> + <M_T, d_final_state>  (the paper states no
  * backward; it is the adjoint of the forward above, evaluated chunkwise with a
  * reverse scan over chunk-state gradients).  The forward's states that the

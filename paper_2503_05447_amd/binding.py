@@ -79,6 +79,10 @@ def library():
     lib.lsm_calib_mfma_flops.restype = ctypes.c_double
     lib.lsm_calib_mfma_flops.argtypes = [ctypes.c_int, ctypes.c_int]
     lib.lsm_bench_intra_chunk_workspace_bytes.restype = sz
+    lib.lsm_delta_fwd.restype = ctypes.c_int
+    lib.lsm_delta_fwd.argtypes = [pp] + [vp] * 10 + [sz, vp]
+    lib.lsm_delta_fwd_workspace_bytes.restype = sz
+    lib.lsm_delta_fwd_workspace_bytes.argtypes = [pp]
     lib.lsm_bench_intra_chunk_workspace_bytes.argtypes = [pp]
     lib.lsm_bench_intra_chunk.restype = ctypes.c_int
     lib.lsm_bench_intra_chunk.argtypes = [pp] + [vp] * 6 + [sz, ctypes.c_int, vp]
@@ -236,6 +240,37 @@ def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None
                                  _ptr(o), _ptr(final), _ptr(workspace), workspace.numel(), _stream_handle(stream))
     if rc != 0:
         raise LsmError(rc, "lsm_chunk_fwd")
+    return o, final
+
+
+def lsm_delta_fwd(q, k, v, log_alpha=None, beta=None, b=None, init_state=None, want_final_state=True, workspace=None,
+                  stream=None, layout=LAYOUT_BHTD):
+    """o, final_state = chunkwise forward of the delta-rule rows of Table 1,
+    M_t = alpha_t (I - beta_t k_t^T k_t) M_{t-1} + b_t k_t^T v_t, o_t = q_t M_t.
+
+    DeltaNet: log_alpha None, beta = the row's a_t, b = the row's b_t.  Gated DeltaNet: log_alpha = log a_t, beta None.
+    log_alpha, beta, b: float32 per token ([B,H,T], or [B,T,H] for LAYOUT_BTHD), None = the constant 1.
+    bf16, d_k = d_v = 128 only.  Enqueues on ``stream`` (default: torch's current stream) without synchronising."""
+    import torch
+    kind = DECAY_NONE if log_alpha is None else DECAY_SCALAR
+    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_alpha, kind, 64, layout, None, 0)
+    pshape = (B, T, H) if layout == LAYOUT_BTHD else (B, H, T)
+    _check(beta, pshape, torch.float32, "beta")
+    _check(b, pshape, torch.float32, "b")
+    _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
+    need = library().lsm_delta_fwd_workspace_bytes(ctypes.byref(p))
+    if need == 0:
+        raise LsmError(-3, "lsm_delta_fwd")
+    with _alloc_on(stream):
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        o = torch.empty_like(v)
+        final = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_final_state else None
+    rc = library().lsm_delta_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(b),
+                                 _ptr(init_state), _ptr(o), _ptr(final), _ptr(workspace), workspace.numel(),
+                                 _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_delta_fwd")
     return o, final
 
 

@@ -116,7 +116,7 @@ hipError_t scratch_of_current_device(void** out) {
 
 extern "C" {
 
-int lsm_version(void) { return 5; }
+int lsm_version(void) { return 6; }
 
 const char* lsm_status_string(int status) {
     switch (status) {
@@ -163,7 +163,7 @@ const char* lsm_kernel_name(int kernel_id) {
         "generic_cumsum", "generic_chunk_state", "generic_scan", "generic_output", "generic_chunk_dstate",
         "generic_reverse_scan", "generic_grad", "head_reduce", "mfma_state_scan_fwd", "mfma_output",
         "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep", "mfma_vector_decay_dv", "recurrent_step",
-        "walk_segment_summary", "walk_segment_scan", "walk_fwd", "walk_grad"};
+        "walk_segment_summary", "walk_segment_scan", "walk_fwd", "walk_grad", "delta_prep", "delta_walk"};
     return kernel_id >= 0 && kernel_id < lsm::KID_COUNT ? names[kernel_id] : "unknown";
 }
 
@@ -274,6 +274,30 @@ int lsm_step(const lsm_params* p, const void* q, const void* k, const void* v, c
         return LSM_ERR_ALIGN;
     return lsm::step(d, q, k, v, log_decay, state, o, static_cast<hipStream_t>(stream)) == hipSuccess ? LSM_OK
                                                                                                     : LSM_ERR_LAUNCH;
+}
+
+size_t lsm_delta_fwd_workspace_bytes(const lsm_params* p) {
+    lsm::Dims d{};
+    if (check_params(p, &d) != LSM_OK || !lsm::delta_supported(d)) return 0;
+    return lsm::delta_fwd_workspace(d);
+}
+
+int lsm_delta_fwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_alpha,
+                  const float* beta, const float* b, const float* init_state, void* o, float* final_state,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !o) return LSM_ERR_NULL;
+    if (d.kind != LSM_DECAY_NONE && d.kind != LSM_DECAY_SCALAR) return LSM_ERR_UNSUPPORTED;
+    if ((d.kind == LSM_DECAY_NONE) != (log_alpha == nullptr)) return LSM_ERR_NULL;
+    if (!lsm::delta_supported(d)) return LSM_ERR_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_alpha) || misaligned(beta) ||
+        misaligned(b) || misaligned(init_state) || misaligned(final_state) || misaligned(workspace))
+        return LSM_ERR_ALIGN;
+    if (!workspace || workspace_bytes < lsm::delta_fwd_workspace(d)) return LSM_ERR_WORKSPACE;
+    const lsm::DeltaArgs a{q, k, v, log_alpha, beta, b, init_state, o, final_state, workspace, static_cast<hipStream_t>(stream)};
+    return lsm::delta_fwd(d, a) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
 }
 
 int lsm_chunk_bwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,

@@ -594,6 +594,7 @@ __global__ __launch_bounds__(kThreads) void mk_state_pair_vec(Dims d, StateArgs 
 
 #include "lsm_mfma_vec.h"
 #include "lsm_mfma_walk.h"
+#include "lsm_mfma_delta.h"
 
 struct Ws {
     uint16_t *states, *dstates, *states_rem, *dstates_t, *dstates_rem;
@@ -968,6 +969,42 @@ hipError_t mfma_intra_bench(const Dims& d0, const FwdArgs& a, int reps) {
     hipLaunchKernelGGL(mk_output<true>, dim3(d.N, d.BH()), dim3(kThreads), kOutLdsRepeat, a.stream, d,
                        static_cast<const uint16_t*>(a.q), static_cast<const uint16_t*>(a.k),
                        static_cast<const uint16_t*>(a.v), a.g, w.states, static_cast<uint16_t*>(a.o), reps);
+    return hipGetLastError();
+}
+
+// ---- delta-rule rows: host side
+bool delta_supported(const Dims& d) { return d.bf16 && d.C == C && d.dk == D && d.dv == D && (d.kind == 0 || d.kind == 2) && !d.nseq; }
+size_t delta_fwd_workspace(const Dims& d) {
+    return align256(size_t(d.BH()) * d.T * D * 2) + align256(size_t(d.BH()) * d.T * D * 4);
+}
+hipError_t delta_fwd(const Dims& d, const DeltaArgs& a) {
+    char* p = static_cast<char*>(a.ws);
+    uint16_t* what = reinterpret_cast<uint16_t*>(p);
+    float* uhat = reinterpret_cast<float*>(p + align256(size_t(d.BH()) * d.T * D * 2));
+    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    hipError_t e;
+    const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, what, uhat};
+    const DeltaWalkArgs wa{q, k, what, uhat, a.log_alpha, static_cast<uint16_t*>(a.o), a.m0, a.mT};
+    const dim3 pgrid(d.N, d.BH()), wgrid(d.seqs()), block(kThreads);
+    if (d.kind == 0) {
+        if ((e = allow_lds(mk_delta_prep<false>, kDeltaPrepLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_walk<false>, kDeltaWalkLds)) != hipSuccess) return e;
+        {
+            ProfScope ps(KID_DELTA_PREP, a.stream);
+            hipLaunchKernelGGL(mk_delta_prep<false>, pgrid, block, kDeltaPrepLds, a.stream, d, pa);
+        }
+        ProfScope ps(KID_DELTA_WALK, a.stream);
+        hipLaunchKernelGGL(mk_delta_walk<false>, wgrid, block, kDeltaWalkLds, a.stream, d, wa);
+    } else {
+        if ((e = allow_lds(mk_delta_prep<true>, kDeltaPrepLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_walk<true>, kDeltaWalkLds)) != hipSuccess) return e;
+        {
+            ProfScope ps(KID_DELTA_PREP, a.stream);
+            hipLaunchKernelGGL(mk_delta_prep<true>, pgrid, block, kDeltaPrepLds, a.stream, d, pa);
+        }
+        ProfScope ps(KID_DELTA_WALK, a.stream);
+        hipLaunchKernelGGL(mk_delta_walk<true>, wgrid, block, kDeltaWalkLds, a.stream, d, wa);
+    }
     return hipGetLastError();
 }
 

@@ -1,0 +1,120 @@
+"""GPU parity of the delta-rule forward (DeltaNet and Gated DeltaNet rows of Table 1) against the fp64 token-by-token
+oracle, element by element, through the C ABI.  Tolerance: max|x - ref| / RMS(ref) <= 2e-2 for the bf16 output (its
+own container rounding discounted, as for the other kinds), 2e-2 for the fp32 final state too: the pseudo-values
+u_t pass through one bf16 rounding inside the path, so the state carries rounding of the size of a bf16 input."""
+import numpy as np
+import pytest
+
+import lsm_workloads as wl
+from lsm_testlib import BF16_HALF_ULP, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+
+
+def dev(x, layout=0):
+    import torch
+    d = torch.device("cuda:0")
+    def mv(a, dt, per_token):
+        if a is None:
+            return None
+        t = torch.from_numpy(np.ascontiguousarray(a)).to(d).to(dt)
+        if layout == 1 and per_token:
+            t = t.transpose(1, 2)
+        return t.contiguous()
+    t = {n: mv(x[n], torch.bfloat16, True) for n in ("q", "k", "v")}
+    t.update({n: mv(x[n], torch.float32, True) for n in ("log_alpha", "beta", "b")})
+    t["m0"] = mv(x["m0"], torch.float32, False)
+    return t
+
+
+def run_and_check(x, layout=0, report=None):
+    import torch
+    import paper_2503_05447_amd as pkg
+    from oracle import delta_oracle_fwd
+    t = dev(x, layout)
+    o, mT = pkg.lsm_delta_fwd(t["q"], t["k"], t["v"], t["log_alpha"], t["beta"], t["b"], t["m0"], layout=layout)
+    torch.cuda.synchronize()
+    if layout == 1:
+        o = o.transpose(1, 2)
+    o_ref, mT_ref = delta_oracle_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], x["b"], x["m0"])
+    eo, eraw, em = rel_err(host(o), o_ref, BF16_HALF_ULP), rel_err(host(o), o_ref), rel_err(host(mT), mT_ref)
+    if report is not None:
+        report.update(o=eo, o_raw=eraw, final_state=em)
+    print("delta fwd B=%d H=%d T=%d gated=%s layout=%d: o %.3e (raw %.3e) final_state %.3e"
+          % (x["B"], x["H"], x["T"], x["gated"], layout, eo, eraw, em), flush=True)
+    assert eo <= TOL and em <= TOL, (eo, em)
+    return o, mT
+
+
+# (B, H, T): one chunk; a ragged chunk; several chunks and a ragged tail; many chunks
+SHAPES = [(1, 2, 64), (2, 2, 37), (2, 3, 200), (1, 4, 1300)]
+
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_delta_forward_matches_oracle(shape, gated):
+    B, H, T = shape
+    x = wl.make_delta_inputs(B, H, T, 128, 128, gated, seed=4100 + T + int(gated), init_state=True)
+    run_and_check(x)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_delta_forward_separate_strengths_and_no_initial_state(gated):
+    x = wl.make_delta_inputs(2, 2, 330, 128, 128, gated, seed=4200 + int(gated), init_state=False, tie_b=False)
+    if gated:   # all three per-token parameters at once (the general form both rows are instances of)
+        rng = np.random.default_rng(7)
+        x["beta"] = (0.2 + 0.7 * rng.random((2, 2, 330))).astype(np.float32)
+    run_and_check(x)
+
+
+@pytest.mark.parametrize("decay", ["weak", "strong4"])
+def test_gated_delta_decay_strengths(decay):
+    x = wl.make_delta_inputs(1, 3, 700, 128, 128, True, seed=4300, decay=decay, init_state=True)
+    run_and_check(x)
+
+
+def test_delta_token_major_layout():
+    x = wl.make_delta_inputs(2, 3, 150, 128, 128, True, seed=4400, init_state=True)
+    run_and_check(x, layout=1)
+
+
+def test_delta_correlated_keys():
+    """Keys drawn from a handful of directions (plus noise), as trained models produce them: the triangular system of
+    a chunk is then far from the identity."""
+    x = wl.make_delta_inputs(1, 2, 512, 128, 128, False, seed=4500, init_state=True)
+    rng = np.random.default_rng(4501)
+    base = rng.standard_normal((6, 128)).astype(np.float32)
+    pick = rng.integers(0, 6, size=(1, 2, 512))
+    k = base[pick] + 0.3 * rng.standard_normal((1, 2, 512, 128)).astype(np.float32)
+    k /= np.sqrt((k * k).sum(-1, keepdims=True))
+    x["k"] = wl.bf16_round(k)
+    run_and_check(x)
+
+
+def test_delta_zero_erase_equals_the_scalar_kind_bitwise_inputs():
+    """beta = 0: the path must agree with the per-token scalar-decay forward on values b v (same oracle pin, on the GPU)."""
+    import torch
+    import paper_2503_05447_amd as pkg
+    x = wl.make_delta_inputs(1, 2, 300, 128, 128, True, seed=4600, init_state=True)
+    x["beta"] = np.zeros((1, 2, 300), np.float32)
+    x["b"] = np.ones((1, 2, 300), np.float32)
+    o, mT = run_and_check(x)
+    t = dev(x)
+    o2, mT2 = pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"], t["log_alpha"], pkg.DECAY_SCALAR, 64, t["m0"])
+    torch.cuda.synchronize()
+    assert rel_err(host(o), host(o2)) <= 2 ** -7      # two bf16 containers of nearly the same fp32 values
+    assert rel_err(host(mT), host(mT2)) <= 1e-2
+
+
+def test_delta_rejects_what_it_does_not_serve():
+    import torch
+    import paper_2503_05447_amd as pkg
+    d = torch.device("cuda:0")
+    q = torch.zeros(1, 1, 64, 64, device=d, dtype=torch.bfloat16)
+    with pytest.raises(pkg.LsmError):
+        pkg.lsm_delta_fwd(q, q, q)
+    q32 = torch.zeros(1, 1, 64, 128, device=d, dtype=torch.float32)
+    with pytest.raises(pkg.LsmError):
+        pkg.lsm_delta_fwd(q32, q32, q32)
