@@ -11,7 +11,8 @@
 // so U = Uhat - What S with  T = (I + L)^-1 ,  Uhat = T diag(b) V ,  What = T diag(beta Gamma) K  (the chunkwise
 // form published for the delta rule; the paper itself gives no algorithm for these rows).
 //   mk_delta_prep  (one workgroup per chunk, all chunks in parallel): L from K K^T on the matrix cores, T by
-//                  forward substitution in fp32, Uhat (fp32) and What (bf16) to the workspace.
+//                  forward substitution in fp32 inside 32 x 32 diagonal blocks and a block product below them,
+//                  Uhat (fp32) and What (bf16) to the workspace.
 //   mk_delta_walk  (one workgroup per sequence): the forward chunk walker with one more product per chunk,
 //                  U = Uhat - What S from the state in the accumulators; U (as bf16 head + remainder) then plays the
 //                  value tile's part in the intra-chunk product and in the state update.
@@ -21,11 +22,18 @@
 // sum here (it carries the product of the erase factors), so the walkers' segment summaries do not apply.
 #pragma once
 
-constexpr int LDL = C + 4;   // floats per row of L
 constexpr int LDU = D + 4;   // floats per row of an fp32 [64][128] tile in LDS
-constexpr int kDeltaRegion = 4 * C * LDP * 2;  // L (fp32), then the four planes of T (bf16), then the Uhat stage (fp32)
-static_assert(kDeltaRegion >= C * LDL * 4 && kDeltaRegion >= C * LDU * 4, "region holds each of its three tenants");
-constexpr int kDeltaPrepLds = 2 * C * LD * 2 + kDeltaRegion + 3 * C * 4;
+constexpr int LDD = 36;      // floats per row of a 32 x 32 diagonal block of L
+constexpr int LDT = 40;      // elements per row of a 32 x 32 bf16 tile
+// LDS of mk_delta_prep (two workgroups per compute unit):
+//   K tile | R1: the four planes of T^T scaled by columns (64 x LDP bf16 each), later the Uhat stage (fp32)
+//          | R2: diagonal blocks of L (fp32; later R^T head, remainder), L_10 head, remainder, T_00^T and T_11^T head,
+//                remainder (32 x LDT bf16 each); later the V tile
+//          | log Gamma, beta, b
+constexpr int kDeltaR1 = 4 * C * LDP * 2;
+constexpr int kDeltaR2 = 2 * 32 * LDD * 4 + 6 * 32 * LDT * 2;
+static_assert(kDeltaR1 >= C * LDU * 4 && kDeltaR2 >= C * LD * 2 && 2 * 32 * LDD * 4 >= 2 * 32 * LDT * 2, "tenants fit");
+constexpr int kDeltaPrepLds = C * LD * 2 + kDeltaR1 + kDeltaR2 + 3 * C * 4;
 
 struct DeltaPrepArgs {
     const uint16_t *k, *v;
@@ -34,20 +42,43 @@ struct DeltaPrepArgs {
     float* uhat;                         // [BH*T][128] fp32
 };
 
-// grid: (N, BH)
+// 32 consecutive fp32 values -> one 32-element bf16 row, head and remainder
+__device__ __forceinline__ void delta_row_split(uint16_t* hi, uint16_t* lo, const float (&x)[32], float scale) {
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {
+        u32x4 h, l;
+        _Pragma("unroll") for (int p = 0; p < 4; ++p) {
+            const float x0 = x[8 * i + 2 * p] * scale, x1 = x[8 * i + 2 * p + 1] * scale;
+            h[p] = pack2(x0, x1);
+            l[p] = pack2(x0 - bf16_lo(h[p]), x1 - bf16_hi(h[p]));
+        }
+        *reinterpret_cast<u32x4*>(hi + 8 * i) = h;
+        *reinterpret_cast<u32x4*>(lo + 8 * i) = l;
+    }
+}
+
+// grid: (N, BH).  T = (I + L)^-1 in two levels: the two 32 x 32 diagonal blocks by forward substitution in fp32
+// (one wave, lane = block and column), the block below the diagonal as T_10 = -T_11 L_10 T_00 on the matrix cores
+// with every factor as bf16 head + remainder.  T is kept transposed and already scaled by columns (b_r for Uhat,
+// beta_r Gamma_r for What), so every lane writes whole 16-byte row pieces.
 template <bool DEC>
 __global__ __launch_bounds__(kThreads, 2) void mk_delta_prep(Dims d, DeltaPrepArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* Vt = Kt + C * LD;
-    unsigned char* region = reinterpret_cast<unsigned char*>(Vt + C * LD);
-    float* Lm = reinterpret_cast<float*>(region);
-    uint16_t* Tbh = reinterpret_cast<uint16_t*>(region);  // T diag(b), head and remainder
-    uint16_t* Tbl = Tbh + C * LDP;
-    uint16_t* Twh = Tbl + C * LDP;                        // T diag(beta Gamma)
-    uint16_t* Twl = Twh + C * LDP;
-    float* Ust = reinterpret_cast<float*>(region);
-    float* lg = reinterpret_cast<float*>(region + kDeltaRegion);  // log Gamma_t
+    unsigned char* r1 = reinterpret_cast<unsigned char*>(Kt + C * LD);
+    uint16_t* TbTh = reinterpret_cast<uint16_t*>(r1);  // (T diag(b))^T [r][t], head and remainder
+    uint16_t* TbTl = TbTh + C * LDP;
+    uint16_t* TwTh = TbTl + C * LDP;                   // (T diag(beta Gamma))^T
+    uint16_t* TwTl = TwTh + C * LDP;
+    float* Ust = reinterpret_cast<float*>(r1);
+    unsigned char* r2 = r1 + kDeltaR1;
+    float* Ld = reinterpret_cast<float*>(r2);                              // [2][32][LDD]: L_00, L_11
+    uint16_t* RTh = reinterpret_cast<uint16_t*>(r2);                       // over L_00, L_11 once they are spent
+    uint16_t* RTl = RTh + 32 * LDT;
+    uint16_t* L10h = reinterpret_cast<uint16_t*>(r2 + 2 * 32 * LDD * 4);   // L_10 [t'][r]
+    uint16_t* L10l = L10h + 32 * LDT;
+    uint16_t* TTh = L10l + 32 * LDT;                                       // [2] x (head, remainder): T_00^T, T_11^T, [c][t']
+    uint16_t* Vt = reinterpret_cast<uint16_t*>(r2);
+    float* lg = reinterpret_cast<float*>(r2 + kDeltaR2);  // log Gamma_t
     float* be = lg + C;
     float* bb = be + C;
 
@@ -67,36 +98,43 @@ __global__ __launch_bounds__(kThreads, 2) void mk_delta_prep(Dims d, DeltaPrepAr
         be[lane] = lane < L ? bet : 0.f;  // rows beyond the ragged end: no erase, no write
         bb[lane] = lane < L ? bwt : 0.f;
     }
+    TileRegs rv;
+    tile_gload(rv, a.v, cp.tok0, cp.ts, L, tid);  // held in registers until the solve has freed its LDS
     load_tile(Kt, a.k, cp.tok0, cp.ts, L, tid);
-    load_tile(Vt, a.v, cp.tok0, cp.ts, L, tid);
     __syncthreads();
     // ---- L[t][r] = beta_t e^{lg_t - lg_r} (k_t . k_r) for r < t, else 0: blocks (r, t) = (0,0), (0,1), (1,1)
     if (wave < 3) {
         const int rb = wave == 2 ? 1 : 0, tb = wave ? 1 : 0;
-        const f32x16 G = score_block2(Kt, 32 * rb, Kt, 32 * tb, n, half);  // D[m = r][n = t]
+        f32x16 G = score_block2(Kt, 32 * rb, Kt, 32 * tb, n, half);  // D[m = r][n = t]
         const int t = 32 * tb + n;
         const float bt = be[t], lt = lg[t];
         _Pragma("unroll") for (int g = 0; g < 4; ++g) {
             const float4 lr = *reinterpret_cast<const float4*>(lg + 32 * rb + 8 * g + 4 * half);
             const float lrv[4] = {lr.x, lr.y, lr.z, lr.w};
-            float o4[4];
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {
                 const int r = 32 * rb + 8 * g + 4 * half + j;
-                o4[j] = r < t ? bt * (DEC ? __expf(lt - lrv[j]) : 1.f) * G[4 * g + j] : 0.f;
+                G[4 * g + j] = r < t ? bt * (DEC ? __expf(lt - lrv[j]) : 1.f) * G[4 * g + j] : 0.f;
             }
-            *reinterpret_cast<float4*>(Lm + t * LDL + 32 * rb + 8 * g + 4 * half) = float4{o4[0], o4[1], o4[2], o4[3]};
+        }
+        if (rb == tb) {  // diagonal block, fp32 [t'][r']
+            float* dst = Ld + rb * 32 * LDD + n * LDD;
+            _Pragma("unroll") for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4*>(dst + 8 * g + 4 * half) = float4{G[4 * g], G[4 * g + 1], G[4 * g + 2], G[4 * g + 3]};
+        } else {         // L_10 [t'][r], bf16 head + remainder
+            store_block_t_split(L10h, L10l, LDT, n, 0, half, G);
         }
     }
     __syncthreads();
-    // ---- T = (I + L)^-1 by forward substitution, one column per lane: X[t] = [t == c] - sum_{r<t} L[t][r] X[r].
-    // Row t of L is the same address for every lane (a broadcast read).  Entries L[t][r >= t] are zero.
     if (wave == 0) {
-        float X[C];
-        _Pragma("unroll") for (int t = 0; t < C; ++t) X[t] = 0.f;
-        _Pragma("unroll") for (int t = 0; t < C; ++t) {
-            float acc[4] = {lane == t ? 1.f : 0.f, 0.f, 0.f, 0.f};
+        // ---- diagonal blocks: X[t'] = [t' == c] - sum_{r' < t'} L_bb[t'][r'] X[r'], lane = (block, column c)
+        const int blk = half, cc = n;
+        const float* Lb = Ld + blk * 32 * LDD;
+        float X[32];
+        _Pragma("unroll") for (int t = 0; t < 32; ++t) X[t] = 0.f;
+        _Pragma("unroll") for (int t = 0; t < 32; ++t) {
+            float acc[4] = {cc == t ? 1.f : 0.f, 0.f, 0.f, 0.f};
             _Pragma("unroll") for (int q4 = 0; q4 < (t + 3) / 4; ++q4) {
-                const float4 l = *reinterpret_cast<const float4*>(Lm + t * LDL + 4 * q4);
+                const float4 l = *reinterpret_cast<const float4*>(Lb + t * LDD + 4 * q4);
                 acc[0] -= l.x * X[4 * q4];
                 acc[1] -= l.y * X[4 * q4 + 1];
                 acc[2] -= l.z * X[4 * q4 + 2];
@@ -104,28 +142,55 @@ __global__ __launch_bounds__(kThreads, 2) void mk_delta_prep(Dims d, DeltaPrepAr
             }
             X[t] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
         }
-        // column scalings b_c and beta_c Gamma_c, each plane as bf16 head + remainder (over L, which is spent)
-        const float bcol = bb[lane], wcol = be[lane] * (DEC ? __expf(lg[lane]) : 1.f);
-        _Pragma("unroll") for (int t = 0; t < C; ++t) {
-            const float xb = X[t] * bcol, xw = X[t] * wcol;
-            const uint32_t hb = pack2(xb, xw);
-            const uint32_t lb = pack2(xb - bf16_lo(hb), xw - bf16_hi(hb));
-            Tbh[t * LDP + lane] = uint16_t(hb & 0xffffu);
-            Twh[t * LDP + lane] = uint16_t(hb >> 16);
-            Tbl[t * LDP + lane] = uint16_t(lb & 0xffffu);
-            Twl[t * LDP + lane] = uint16_t(lb >> 16);
+        const float bcol = bb[lane], wcol = be[lane] * (DEC ? __expf(lg[lane]) : 1.f);  // lane = this column's token
+        uint16_t* tt = TTh + blk * 2 * 32 * LDT;
+        delta_row_split(tt + cc * LDT, tt + 32 * LDT + cc * LDT, X, 1.f);
+        delta_row_split(TbTh + lane * LDP + 32 * blk, TbTl + lane * LDP + 32 * blk, X, bcol);
+        delta_row_split(TwTh + lane * LDP + 32 * blk, TwTl + lane * LDP + 32 * blk, X, wcol);
+        __builtin_amdgcn_wave_barrier();  // LDS serves one wave's accesses in order: what follows reads what was just written
+        // ---- R[r][t] = sum_t' L_10[t'][r] T_11[t][t'], kept as R^T [t][r]
+        const uint16_t *T00h = TTh, *T00l = TTh + 32 * LDT, *T11h = TTh + 2 * 32 * LDT, *T11l = TTh + 3 * 32 * LDT;
+        f32x16 R = {0};
+        _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 ah = frag_tr(L10h, LDT, 16 * ks, 0, lane), al = frag_tr(L10l, LDT, 16 * ks, 0, lane);
+            const bf16x8 bh_ = frag_tr(T11h, LDT, 16 * ks, 0, lane), bl = frag_tr(T11l, LDT, 16 * ks, 0, lane);
+            R = mfma(ah, bh_, R);
+            R = mfma(ah, bl, R);
+            R = mfma(al, bh_, R);
         }
+        __builtin_amdgcn_wave_barrier();
+        store_block_t_split(RTh, RTl, LDT, n, 0, half, R);  // over the diagonal blocks of L, which are spent
+        __builtin_amdgcn_wave_barrier();
+        // ---- T_10[t][c] = -sum_r R^T[t][r] T_00[r][c], scaled by this lane's column and stored transposed
+        f32x16 T10 = {0};
+        _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 ah = frag(RTh, LDT, n, 16 * ks + 8 * half), al = frag(RTl, LDT, n, 16 * ks + 8 * half);
+            const bf16x8 bh_ = frag(T00h, LDT, n, 16 * ks + 8 * half), bl = frag(T00l, LDT, n, 16 * ks + 8 * half);
+            T10 = mfma(ah, bh_, T10);
+            T10 = mfma(ah, bl, T10);
+            T10 = mfma(al, bh_, T10);
+        }
+        const float b0 = bb[n], w0 = be[n] * (DEC ? __expf(lg[n]) : 1.f);  // column c = n of the first block
+        f32x16 Tb, Tw;
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+            Tb[x] = -T10[x] * b0;
+            Tw[x] = -T10[x] * w0;
+        }
+        store_block_t_split(TbTh, TbTl, LDP, n, 32, half, Tb);  // rows c, columns 32 + t
+        store_block_t_split(TwTh, TwTl, LDP, n, 32, half, Tw);
     }
+    __syncthreads();  // T is complete; the small tiles are spent
+    tile_commit(Vt, rv, L, tid);
     __syncthreads();
     // ---- What^T[c][t] = sum_r K[r][c] Tw[t][r],  Uhat^T[c][t] = sum_r V[r][c] Tb[t][r]; this wave: features 32 w ..
     f32x16 Wt[2] = {{0}, {0}}, Ut[2] = {{0}, {0}};
     _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
         _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {  // T is lower triangular
             const bf16x8 ka = frag_tr(Kt, LD, 16 * ks, 32 * wave, lane), va = frag_tr(Vt, LD, 16 * ks, 32 * wave, lane);
-            Wt[nb] = mfma(ka, frag(Twh, LDP, 32 * nb + n, 16 * ks + 8 * half), Wt[nb]);
-            Wt[nb] = mfma(ka, frag(Twl, LDP, 32 * nb + n, 16 * ks + 8 * half), Wt[nb]);
-            Ut[nb] = mfma(va, frag(Tbh, LDP, 32 * nb + n, 16 * ks + 8 * half), Ut[nb]);
-            Ut[nb] = mfma(va, frag(Tbl, LDP, 32 * nb + n, 16 * ks + 8 * half), Ut[nb]);
+            Wt[nb] = mfma(ka, frag_tr(TwTh, LDP, 16 * ks, 32 * nb, lane), Wt[nb]);
+            Wt[nb] = mfma(ka, frag_tr(TwTl, LDP, 16 * ks, 32 * nb, lane), Wt[nb]);
+            Ut[nb] = mfma(va, frag_tr(TbTh, LDP, 16 * ks, 32 * nb, lane), Ut[nb]);
+            Ut[nb] = mfma(va, frag_tr(TbTl, LDP, 16 * ks, 32 * nb, lane), Ut[nb]);
         }
     __syncthreads();  // every read of the tiles and of the planes is done
     _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
