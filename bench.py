@@ -199,6 +199,77 @@ def calibrate(pkg, torch, dev):
                     "8192 independent 32x32x16 bf16 MFMAs on register operands), same process, same clocks"}
 
 
+def delta_bench(steps, warmup, check):
+    """Forward of the delta-rule rows (DeltaNet, Gated DeltaNet): 256 sequences of 2048 tokens, the shape of a training
+    batch at the paper's 2K context (one workgroup walks a sequence, so 256 sequences fill the chip), and the
+    metric's own shape (64 sequences of 8192 tokens) for what few sequences cost.  Per row: host-clock time per
+    step, HIP-event kernel averages, compulsory bytes over time, and sampled (b,h) pairs against the fp64 oracle."""
+    import ctypes
+    import numpy as np
+    import torch
+    import lsm_workloads as wl
+    import paper_2503_05447_amd as pkg
+    dev = torch.device("cuda:0")
+    out = {"what": "lsm_delta_fwd, bf16, d_k = d_v = 128, chunk 64, forward only; keys of unit length, b = sigmoid(N(0,1)), "
+                   "DeltaNet a = b, Gated DeltaNet log a = -softplus(N(0,1) + 3)"}
+    for (B, H, T) in ((16, 16, 2048), (4, 16, 8192)):
+        for gated in (False, True):
+            x = wl.make_delta_inputs(B, H, T, 128, 128, gated, seed=wl.BASE_SEED + 20 + int(gated) + T)
+            mv = lambda a, dt: None if a is None else torch.from_numpy(a).to(dev).to(dt).contiguous()
+            q, k, v = (mv(x[n_], torch.bfloat16) for n_ in ("q", "k", "v"))
+            la, be, bw = (mv(x[n_], torch.float32) for n_ in ("log_alpha", "beta", "b"))
+            p = pkg.make_params(B, H, T, 128, 128, 64, pkg.DECAY_SCALAR if gated else pkg.DECAY_NONE, 1)
+            ws = torch.empty(pkg.library().lsm_delta_fwd_workspace_bytes(ctypes.byref(p)), dtype=torch.uint8, device=dev)
+            step = lambda: pkg.lsm_delta_fwd(q, k, v, la, be, bw, workspace=ws)
+            t0 = time.perf_counter()
+            while time.perf_counter() - t0 < 0.25:   # settle the clocks, as for the headline
+                for _ in range(5):
+                    step()
+                torch.cuda.synchronize()
+            for _ in range(warmup):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                o, mT = step()
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / steps
+            pkg.lsm_profile_start()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            per = {}
+            for name, ms in pkg.lsm_profile_stop():
+                per.setdefault(name, []).append(ms)
+            th = B * H * T
+            ab = th * (4 * 256 + 4 * (2 if not gated else 2))   # q, k, v, o in bf16; two per-token parameters
+            # chunk-dense flops per token-head: scores, A U, Q S, state update (as the diagonal kinds) + K K^T,
+            # T [V | K], What S
+            fl = th * (2 * 64 * 256 + 2 * 2 * 128 * 128 + 2 * 64 * 128 + 2 * 64 * 256 + 2 * 128 * 128)
+            e = {"B": B, "H": H, "T": T, "ms_per_step": sec * 1e3, "tokens_per_s": B * T / sec, "steps": steps,
+                 "kernel_ms": {n_: float(np.mean(v_)) for n_, v_ in per.items()},
+                 "algorithmic_bytes_per_step": ab, "hbm_frac_whole_step": ab / sec / 1e9 / HBM_PEAK_GBS,
+                 "tflops_chunk_dense": fl / sec / 1e12, "mfma_peak_frac": fl / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+            if check:
+                from oracle import delta_oracle_fwd
+                pairs = [(0, 0), (B - 1, H - 1)]
+                ib, ih = [p_[0] for p_ in pairs], [p_[1] for p_ in pairs]
+                take = lambda a: None if a is None else np.ascontiguousarray(a[ib, ih][None])
+                c0 = time.perf_counter()
+                o_ref, mT_ref = delta_oracle_fwd(take(x["q"]), take(x["k"]), take(x["v"]), take(x["log_alpha"]), take(x["beta"]),
+                                                 take(x["b"]), None)
+                osec = time.perf_counter() - c0
+                pick = lambda t_: t_[ib, ih].float().cpu().numpy().astype(np.float64)[None]
+                e["parity_err_over_rms"] = {"o": rel_err(pick(o), o_ref, BF16_HALF_ULP), "final_state": rel_err(pick(mT), mT_ref, 0.0)}
+                e["parity_err_over_rms_raw"] = {"o": rel_err(pick(o), o_ref, 0.0)}
+                e["parity_pairs"] = pairs
+                e["cpu_oracle_tokens_per_s"] = len(pairs) * T / osec
+            out["%s_B%d_T%d" % ("gated_deltanet" if gated else "deltanet", B, T)] = e
+            del q, k, v, la, be, bw, ws, o, mT
+            torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -216,6 +287,8 @@ def main():
                     help="skip the LDS-resident intra-chunk micro-benchmark, the decode step and the calibration kernels "
                          "(profiling runs: they launch other kernels)")
     ap.add_argument("--no-all-configs", action="store_true", help="skip the other four configurations")
+    ap.add_argument("--no-delta", action="store_true", help="skip the delta-rule rows (lsm_delta_fwd)")
+    ap.add_argument("--delta-only", action="store_true", help="run only the delta-rule rows and print their block (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -231,6 +304,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.delta_only:
+        print(json.dumps({"delta_rule_fwd": delta_bench(max(5, min(args.steps, 50)), min(args.warmup, 10), not args.no_check)}))
+        return
     saved = args.states == "saved"
     w = Workload(args.config, args.layout, saved)
     cfg, kind, C = w.cfg, w.kind, w.C
@@ -439,6 +515,12 @@ def main():
             # are never discounted); a bf16 container alone costs up to 2^-8 |x| / RMS at the largest elements
             result["parity_err_over_rms_raw"] = raw if ulp else {}
             result["parity_tolerance"] = {"f32": 1e-4, "bf16": 2e-2}[cfg["dtype"]]
+
+    if not args.no_delta and not args.no_microbench:
+        del w
+        torch.cuda.empty_cache()
+        result["delta_rule_fwd"] = delta_bench(max(5, min(args.steps, 50)), min(args.warmup, 10), not args.no_check)
+        w = None
 
     if not args.no_all_configs:
         # The other configurations, each on its full shape: a shorter timed run, and every output element of two
