@@ -159,7 +159,6 @@ int lsm_chunk_fwd_noalloc(const lsm_params* p,
  * LSM_ERR_UNSUPPORTED (the workspace query then returns 0).  flags are ignored.  Keys are expected to have
  * at most unit length times sqrt(2 / beta) (the erase factor is then a contraction); nothing is checked.
  * One workgroup walks a sequence from end to end, so the chip is full from B*H >= 256 sequences on.
- * The backward of these rows is not part of the library.
  */
 size_t lsm_delta_fwd_workspace_bytes(const lsm_params* p);
 int lsm_delta_fwd(const lsm_params* p,
@@ -167,6 +166,28 @@ int lsm_delta_fwd(const lsm_params* p,
                   const float* log_alpha, const float* beta, const float* b,
                   const float* init_state,
                   void* o, float* final_state,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of lsm_delta_fwd for  L = <o, d_o> + <M_T, d_final_state>  (the adjoint of the recurrence above,
+ * evaluated chunkwise; nothing saved by the forward call is needed).
+ *   q, k, v, log_alpha, beta, b, init_state   as in lsm_delta_fwd                                   in
+ *   d_o            like o;  d_final_state NULL (= zeros) or [B,H,d_k,d_v] fp32                       in
+ *   dq, dk, dv     like q, k, v                                                                     out
+ *   d_log_alpha, d_beta, d_b   fp32 per token like the parameter; required exactly where the parameter was given,
+ *                  NULL where it was NULL                                                            out
+ *   d_init_state   NULL (not wanted) or [B,H,d_k,d_v] fp32                                           out
+ *   workspace      at least lsm_delta_bwd_workspace_bytes(p)
+ * Same shapes served and same error behaviour as lsm_delta_fwd.
+ */
+size_t lsm_delta_bwd_workspace_bytes(const lsm_params* p);
+int lsm_delta_bwd(const lsm_params* p,
+                  const void* q, const void* k, const void* v,
+                  const float* log_alpha, const float* beta, const float* b,
+                  const float* init_state,
+                  const void* d_o, const float* d_final_state,
+                  void* dq, void* dk, void* dv,
+                  float* d_log_alpha, float* d_beta, float* d_b, float* d_init_state,
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*

@@ -83,6 +83,10 @@ def library():
     lib.lsm_delta_fwd.argtypes = [pp] + [vp] * 10 + [sz, vp]
     lib.lsm_delta_fwd_workspace_bytes.restype = sz
     lib.lsm_delta_fwd_workspace_bytes.argtypes = [pp]
+    lib.lsm_delta_bwd.restype = ctypes.c_int
+    lib.lsm_delta_bwd.argtypes = [pp] + [vp] * 17 + [sz, vp]
+    lib.lsm_delta_bwd_workspace_bytes.restype = sz
+    lib.lsm_delta_bwd_workspace_bytes.argtypes = [pp]
     lib.lsm_bench_intra_chunk_workspace_bytes.argtypes = [pp]
     lib.lsm_bench_intra_chunk.restype = ctypes.c_int
     lib.lsm_bench_intra_chunk.argtypes = [pp] + [vp] * 6 + [sz, ctypes.c_int, vp]
@@ -272,6 +276,39 @@ def lsm_delta_fwd(q, k, v, log_alpha=None, beta=None, b=None, init_state=None, w
     if rc != 0:
         raise LsmError(rc, "lsm_delta_fwd")
     return o, final
+
+
+def lsm_delta_bwd(q, k, v, d_o, log_alpha=None, beta=None, b=None, init_state=None, d_final_state=None, workspace=None,
+                  stream=None, layout=LAYOUT_BHTD, want_d_init_state=True):
+    """Gradients of L = <o, d_o> + <M_T, d_final_state> for the delta-rule rows (see lsm_delta_fwd): a dict with dq, dk,
+    dv (like q, k, v), d_log_alpha, d_beta, d_b (float32 per token, None where the parameter was None) and
+    d_init_state."""
+    import torch
+    kind = DECAY_NONE if log_alpha is None else DECAY_SCALAR
+    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_alpha, kind, 64, layout, None, 0)
+    pshape = (B, T, H) if layout == LAYOUT_BTHD else (B, H, T)
+    _check(beta, pshape, torch.float32, "beta")
+    _check(b, pshape, torch.float32, "b")
+    _check(d_o, tuple(v.shape), q.dtype, "d_o")
+    _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
+    _check(d_final_state, (B, H, dk, dv), torch.float32, "d_final_state")
+    need = library().lsm_delta_bwd_workspace_bytes(ctypes.byref(p))
+    if need == 0:
+        raise LsmError(-3, "lsm_delta_bwd")
+    with _alloc_on(stream):
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        dq, dk_, dv_ = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        par = lambda x: None if x is None else torch.empty(pshape, dtype=torch.float32, device=q.device)
+        dla, dbe, dbw = par(log_alpha), par(beta), par(b)
+        d_m0 = torch.empty((B, H, dk, dv), dtype=torch.float32, device=q.device) if want_d_init_state else None
+    rc = library().lsm_delta_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(b),
+                                 _ptr(init_state), _ptr(d_o), _ptr(d_final_state), _ptr(dq), _ptr(dk_), _ptr(dv_),
+                                 _ptr(dla), _ptr(dbe), _ptr(dbw), _ptr(d_m0), _ptr(workspace), workspace.numel(),
+                                 _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_delta_bwd")
+    return dict(dq=dq, dk=dk_, dv=dv_, d_log_alpha=dla, d_beta=dbe, d_b=dbw, d_init_state=d_m0)
 
 
 NOALLOC_SCRATCH_BYTES = 8 << 20

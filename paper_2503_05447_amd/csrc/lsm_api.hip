@@ -163,7 +163,7 @@ const char* lsm_kernel_name(int kernel_id) {
         "generic_cumsum", "generic_chunk_state", "generic_scan", "generic_output", "generic_chunk_dstate",
         "generic_reverse_scan", "generic_grad", "head_reduce", "mfma_state_scan_fwd", "mfma_output",
         "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep", "mfma_vector_decay_dv", "recurrent_step",
-        "walk_segment_summary", "walk_segment_scan", "walk_fwd", "walk_grad", "delta_prep", "delta_walk"};
+        "walk_segment_summary", "walk_segment_scan", "walk_fwd", "walk_grad", "delta_prep", "delta_walk", "delta_reverse_walk", "delta_dw_walk", "delta_grad"};
     return kernel_id >= 0 && kernel_id < lsm::KID_COUNT ? names[kernel_id] : "unknown";
 }
 
@@ -298,6 +298,38 @@ int lsm_delta_fwd(const lsm_params* p, const void* q, const void* k, const void*
     if (!workspace || workspace_bytes < lsm::delta_fwd_workspace(d)) return LSM_ERR_WORKSPACE;
     const lsm::DeltaArgs a{q, k, v, log_alpha, beta, b, init_state, o, final_state, workspace, static_cast<hipStream_t>(stream)};
     return lsm::delta_fwd(d, a) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
+}
+
+size_t lsm_delta_bwd_workspace_bytes(const lsm_params* p) {
+    lsm::Dims d{};
+    if (check_params(p, &d) != LSM_OK || !lsm::delta_supported(d)) return 0;
+    return lsm::delta_bwd_workspace(d);
+}
+
+int lsm_delta_bwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_alpha,
+                  const float* beta, const float* b, const float* init_state, const void* d_o,
+                  const float* d_final_state, void* dq, void* dk, void* dv, float* d_log_alpha, float* d_beta, float* d_b,
+                  float* d_init_state, void* workspace, size_t workspace_bytes, void* stream) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !d_o || !dq || !dk || !dv) return LSM_ERR_NULL;
+    if (d.kind != LSM_DECAY_NONE && d.kind != LSM_DECAY_SCALAR) return LSM_ERR_UNSUPPORTED;
+    if ((d.kind == LSM_DECAY_NONE) != (log_alpha == nullptr)) return LSM_ERR_NULL;
+    // a gradient is wanted exactly for the parameters that were given
+    if ((log_alpha == nullptr) != (d_log_alpha == nullptr) || (beta == nullptr) != (d_beta == nullptr) ||
+        (b == nullptr) != (d_b == nullptr))
+        return LSM_ERR_NULL;
+    if (!lsm::delta_supported(d)) return LSM_ERR_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(d_o) || misaligned(dq) || misaligned(dk) ||
+        misaligned(dv) || misaligned(log_alpha) || misaligned(beta) || misaligned(b) || misaligned(init_state) ||
+        misaligned(d_final_state) || misaligned(d_log_alpha) || misaligned(d_beta) || misaligned(d_b) ||
+        misaligned(d_init_state) || misaligned(workspace))
+        return LSM_ERR_ALIGN;
+    if (!workspace || workspace_bytes < lsm::delta_bwd_workspace(d)) return LSM_ERR_WORKSPACE;
+    const lsm::DeltaBwdArgs a{q, k, v, log_alpha, beta, b, init_state, d_o, d_final_state, dq, dk, dv, d_log_alpha, d_beta, d_b,
+                              d_init_state, workspace, static_cast<hipStream_t>(stream)};
+    return lsm::delta_bwd(d, a) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
 }
 
 int lsm_chunk_bwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_decay,

@@ -809,16 +809,25 @@ namespace {
 // entry states of the segments of one direction: summary pass, then the scan over segments
 template <bool REV>
 hipError_t walk_bounds(const Dims& d, hipStream_t st, const SegPlan& sp, const uint16_t* xk, const uint16_t* xv, const float* g,
-                       const float* edge_in, float* bound, float* gseg, int skip = 1) {
+                       const float* edge_in, float* bound, float* gseg, int skip = 1, const uint16_t* xv_lo = nullptr) {
     if (sp.nseg <= 1) return hipSuccess;
     WalkArgs a{};
-    a.xk = xk; a.xv = xv; a.g = g; a.bound = bound; a.gseg = gseg; a.m = sp.m; a.nseg = sp.nseg; a.skip = skip;
+    a.xk = xk; a.xv = xv; a.g = g; a.bound = bound; a.gseg = gseg; a.m = sp.m; a.nseg = sp.nseg; a.skip = skip; a.xv_lo = xv_lo;
     hipError_t e;
     const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
     {
         ProfScope ps(KID_WALK_SUMMARY, st);
         constexpr int lds = walk_lds(true);
-        if (d.kind == 0) {
+        if (xv_lo) {  // values in two planes (delta-rule backward; forward direction only)
+            constexpr int lds2 = lds + C * LD * 2;
+            if (d.kind == 0) {
+                if ((e = allow_lds(mk_walk<REV, false, true, true>, lds2)) != hipSuccess) return e;
+                hipLaunchKernelGGL((mk_walk<REV, false, true, true>), grid, block, lds2, st, d, a);
+            } else {
+                if ((e = allow_lds(mk_walk<REV, true, true, true>, lds2)) != hipSuccess) return e;
+                hipLaunchKernelGGL((mk_walk<REV, true, true, true>), grid, block, lds2, st, d, a);
+            }
+        } else if (d.kind == 0) {
             if ((e = allow_lds(mk_walk<REV, false, true>, lds)) != hipSuccess) return e;
             hipLaunchKernelGGL((mk_walk<REV, false, true>), grid, block, lds, st, d, a);
         } else {
@@ -853,6 +862,34 @@ hipError_t walk_fwd(const Dims& d, const FwdArgs& a) {
     return hipGetLastError();
 }
 
+hipError_t launch_walk_grad(const Dims& d, const SegPlan& sp, const GradArgs& ga, hipStream_t st) {
+    const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
+    hipError_t e;
+    ProfScope ps(KID_WALK_GRAD, st);
+    if (ga.v_lo) {  // values in two planes (delta-rule backward)
+        constexpr int lds = walk_grad_lds(true);
+        if (d.kind == 0) {
+            if ((e = allow_lds(mk_walk_grad<false, false, true>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_grad<false, false, true>), grid, block, lds, st, d, ga);
+        } else {
+            if ((e = allow_lds(mk_walk_grad<true, true, true>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((mk_walk_grad<true, true, true>), grid, block, lds, st, d, ga);
+        }
+        return hipSuccess;
+    }
+    if (d.kind == 0) {
+        if ((e = allow_lds(mk_walk_grad<false, false>, kWalkGradLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk_grad<false, false>), grid, block, kWalkGradLds, st, d, ga);
+    } else if (!ga.dg_tok) {
+        if ((e = allow_lds(mk_walk_grad<true, false>, kWalkGradLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk_grad<true, false>), grid, block, kWalkGradLds, st, d, ga);
+    } else {
+        if ((e = allow_lds(mk_walk_grad<true, true>, kWalkGradLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk_grad<true, true>), grid, block, kWalkGradLds, st, d, ga);
+    }
+    return hipSuccess;
+}
+
 hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
     const WalkWs w = carve_walk(d, a.ws, true);
     const SegPlan sp = seg_plan(d);
@@ -881,20 +918,8 @@ hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
     if (!d.save && (e = walk_bounds<false>(d, a.stream, sp, k, v, a.g, a.m0, w.bound_f, w.gseg_f)) != hipSuccess) return e;
     GradArgs ga{q, k, v, d_o, a.g, w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv),
                 a.dg ? (d.kind == 1 ? w.dgc : a.dg) : nullptr, a.m0, w.bound_f, sp.m, sp.nseg};
-    const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
-    {
-        ProfScope ps(KID_WALK_GRAD, a.stream);
-        if (d.kind == 0) {
-            if ((e = allow_lds(mk_walk_grad<false, false>, kWalkGradLds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((mk_walk_grad<false, false>), grid, block, kWalkGradLds, a.stream, d, ga);
-        } else if (!a.dg) {
-            if ((e = allow_lds(mk_walk_grad<true, false>, kWalkGradLds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((mk_walk_grad<true, false>), grid, block, kWalkGradLds, a.stream, d, ga);
-        } else {
-            if ((e = allow_lds(mk_walk_grad<true, true>, kWalkGradLds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((mk_walk_grad<true, true>), grid, block, kWalkGradLds, a.stream, d, ga);
-        }
-    }
+    const dim3 block(kThreads);
+    if ((e = launch_walk_grad(d, sp, ga, a.stream)) != hipSuccess) return e;
     if (a.dg && d.kind == 1) {
         ProfScope ps(KID_HEAD_REDUCE, a.stream);
         hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dgc, a.dg);
@@ -977,14 +1002,22 @@ bool delta_supported(const Dims& d) { return d.bf16 && d.C == C && d.dk == D && 
 size_t delta_fwd_workspace(const Dims& d) {
     return align256(size_t(d.BH()) * d.T * D * 2) + align256(size_t(d.BH()) * d.T * D * 4);
 }
+namespace {
+hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, const DeltaWalkArgs& wa, hipStream_t stream);
+}
 hipError_t delta_fwd(const Dims& d, const DeltaArgs& a) {
     char* p = static_cast<char*>(a.ws);
     uint16_t* what = reinterpret_cast<uint16_t*>(p);
     float* uhat = reinterpret_cast<float*>(p + align256(size_t(d.BH()) * d.T * D * 2));
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, what, uhat, nullptr};
+    const DeltaWalkArgs wa{q, k, what, uhat, a.log_alpha, static_cast<uint16_t*>(a.o), a.m0, a.mT, nullptr, nullptr};
+    return launch_delta_fwd(d, pa, wa, a.stream);
+}
+namespace {
+hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, const DeltaWalkArgs& wa, hipStream_t stream) {
+    struct { hipStream_t stream; } a{stream};
     hipError_t e;
-    const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, what, uhat};
-    const DeltaWalkArgs wa{q, k, what, uhat, a.log_alpha, static_cast<uint16_t*>(a.o), a.m0, a.mT};
     const dim3 pgrid(d.N, d.BH()), wgrid(d.seqs()), block(kThreads);
     if (d.kind == 0) {
         if ((e = allow_lds(mk_delta_prep<false>, kDeltaPrepLds)) != hipSuccess) return e;
@@ -1004,6 +1037,96 @@ hipError_t delta_fwd(const Dims& d, const DeltaArgs& a) {
         }
         ProfScope ps(KID_DELTA_WALK, a.stream);
         hipLaunchKernelGGL(mk_delta_walk<true>, wgrid, block, kDeltaWalkLds, a.stream, d, wa);
+    }
+    return hipGetLastError();
+}
+
+struct DeltaWs {
+    uint16_t *what, *tt, *usave, *usave_l, *dstates, *du_h, *du_l, *dw_h, *dw_l;
+    float* uhat;
+    void* walk;   // bound_f, gseg_f of the gradient walker
+    size_t bytes;
+};
+DeltaWs carve_delta(const Dims& d, void* ws) {
+    char* p = static_cast<char*>(ws);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* r = p + off; off += align256(bytes); return r; };
+    const size_t rows = size_t(d.BH()) * d.T;
+    DeltaWs w{};
+    w.what = reinterpret_cast<uint16_t*>(take(rows * D * 2));
+    w.uhat = reinterpret_cast<float*>(take(rows * D * 4));
+    w.tt = reinterpret_cast<uint16_t*>(take(size_t(d.BH()) * d.N * 2 * C * C * 2));
+    w.usave = reinterpret_cast<uint16_t*>(take(rows * D * 2));
+    w.usave_l = reinterpret_cast<uint16_t*>(take(rows * D * 2));
+    w.dstates = reinterpret_cast<uint16_t*>(take(size_t(d.BH()) * d.N * D * D * 2));
+    w.du_h = reinterpret_cast<uint16_t*>(take(rows * D * 2));
+    w.du_l = reinterpret_cast<uint16_t*>(take(rows * D * 2));
+    w.dw_h = reinterpret_cast<uint16_t*>(take(rows * D * 2));
+    w.dw_l = reinterpret_cast<uint16_t*>(take(rows * D * 2));
+    w.walk = p + off;
+    off += carve_walk(d, nullptr, false).bytes;
+    w.bytes = off;
+    return w;
+}
+}  // namespace
+size_t delta_bwd_workspace(const Dims& d) { return carve_delta(d, nullptr).bytes; }
+
+hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a) {
+    const DeltaWs w = carve_delta(d, a.ws);
+    const WalkWs ww = carve_walk(d, w.walk, false);
+    const SegPlan sp = seg_plan(d);
+    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    auto d_o = static_cast<const uint16_t*>(a.d_o);
+    hipError_t e;
+    // forward again: What, Uhat, T, and the pseudo-values U in the layout of v
+    const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, w.what, w.uhat, w.tt};
+    const DeltaWalkArgs wa{q, k, w.what, w.uhat, a.log_alpha, nullptr, a.m0, nullptr, w.usave, w.usave_l};
+    if ((e = launch_delta_fwd(d, pa, wa, a.stream)) != hipSuccess) return e;
+    // state gradients and dU, backward in time
+    {
+        const DeltaRevArgs ra{q, k, d_o, w.what, a.log_alpha, w.dstates, w.du_h, w.du_l, a.d_mT, a.d_m0};
+        ProfScope ps(KID_DELTA_RWALK, a.stream);
+        if (d.kind == 0) {
+            if ((e = allow_lds(mk_delta_rwalk<false>, kDeltaRevLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_delta_rwalk<false>, dim3(d.seqs()), dim3(kThreads), kDeltaRevLds, a.stream, d, ra);
+        } else {
+            if ((e = allow_lds(mk_delta_rwalk<true>, kDeltaRevLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_delta_rwalk<true>, dim3(d.seqs()), dim3(kThreads), kDeltaRevLds, a.stream, d, ra);
+        }
+    }
+    // with U as the values the recurrence is the scalar-decay one: dq, the key gradient through scores and state update
+    // and the decay gradient of those terms from the gradient walker (its value gradient is dU once more, not wanted)
+    if ((e = walk_bounds<false>(d, a.stream, sp, k, w.usave, a.log_alpha, a.m0, ww.bound_f, ww.gseg_f, 1, w.usave_l)) != hipSuccess) return e;
+    GradArgs ga{q, k, w.usave, d_o, a.log_alpha, w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
+                static_cast<uint16_t*>(a.dv), d.kind == 0 ? nullptr : a.d_log_alpha, a.m0, ww.bound_f, sp.m, sp.nseg, w.usave_l};
+    if ((e = launch_walk_grad(d, sp, ga, a.stream)) != hipSuccess) return e;   // dk <- head, dv <- remainder of its key gradient
+    // gradient of What: one more forward walk over the same segments
+    {
+        const DeltaDwArgs da{k, w.usave, w.usave_l, w.du_h, w.du_l, a.log_alpha, w.dw_h, w.dw_l, a.m0, ww.bound_f, sp.m, sp.nseg};
+        const dim3 grid(sp.nseg, d.seqs());
+        ProfScope ps(KID_DELTA_DW, a.stream);
+        if (d.kind == 0) {
+            if ((e = allow_lds(mk_delta_dw<false>, kDeltaDwLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_delta_dw<false>, grid, dim3(kThreads), kDeltaDwLds, a.stream, d, da);
+        } else {
+            if ((e = allow_lds(mk_delta_dw<true>, kDeltaDwLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_delta_dw<true>, grid, dim3(kThreads), kDeltaDwLds, a.stream, d, da);
+        }
+    }
+    // everything that goes through the triangular solve, chunk by chunk; completes dk, dv and the parameter gradients
+    {
+        const DeltaGradArgs g3{k, v, w.du_h, w.du_l, w.dw_h, w.dw_l, w.tt, a.log_alpha, a.beta, a.bw,
+                               static_cast<const uint16_t*>(a.dk), static_cast<const uint16_t*>(a.dv),
+                               static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv), a.d_log_alpha, a.d_beta, a.d_bw};
+        const dim3 grid(d.N, d.BH());
+        ProfScope ps(KID_DELTA_GRAD, a.stream);
+        if (d.kind == 0) {
+            if ((e = allow_lds(mk_delta_grad<false>, kDeltaGradLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_delta_grad<false>, grid, dim3(kThreads), kDeltaGradLds, a.stream, d, g3);
+        } else {
+            if ((e = allow_lds(mk_delta_grad<true>, kDeltaGradLds)) != hipSuccess) return e;
+            hipLaunchKernelGGL(mk_delta_grad<true>, grid, dim3(kThreads), kDeltaGradLds, a.stream, d, g3);
+        }
     }
     return hipGetLastError();
 }

@@ -40,6 +40,7 @@ struct DeltaPrepArgs {
     const float *log_alpha, *beta, *bw;  // per token ([B,H,T], or [B,T,H] for the token-major layout); NULL = 1
     uint16_t* what;                      // [BH*T][128] bf16
     float* uhat;                         // [BH*T][128] fp32
+    uint16_t* tt;                        // NULL, or [BH*N][2][64][64] bf16: T^T (rows r, columns t), head and remainder planes
 };
 
 // 32 consecutive fp32 values -> one 32-element bf16 row, head and remainder
@@ -147,6 +148,16 @@ __global__ __launch_bounds__(kThreads, 2) void mk_delta_prep(Dims d, DeltaPrepAr
         delta_row_split(tt + cc * LDT, tt + 32 * LDT + cc * LDT, X, 1.f);
         delta_row_split(TbTh + lane * LDP + 32 * blk, TbTl + lane * LDP + 32 * blk, X, bcol);
         delta_row_split(TwTh + lane * LDP + 32 * blk, TwTl + lane * LDP + 32 * blk, X, wcol);
+        uint16_t* gtt = a.tt ? a.tt + cp.slot * 2 * C * C : nullptr;  // the backward pass wants T itself
+        if (gtt) {
+            delta_row_split(gtt + lane * C + 32 * blk, gtt + C * C + lane * C + 32 * blk, X, 1.f);
+            if (blk) {  // T[t][r] = 0 for t < 32 <= r
+                _Pragma("unroll") for (int i = 0; i < 4; ++i) {
+                    *reinterpret_cast<u32x4*>(gtt + lane * C + 8 * i) = u32x4{0, 0, 0, 0};
+                    *reinterpret_cast<u32x4*>(gtt + C * C + lane * C + 8 * i) = u32x4{0, 0, 0, 0};
+                }
+            }
+        }
         __builtin_amdgcn_wave_barrier();  // LDS serves one wave's accesses in order: what follows reads what was just written
         // ---- R[r][t] = sum_t' L_10[t'][r] T_11[t][t'], kept as R^T [t][r]
         const uint16_t *T00h = TTh, *T00l = TTh + 32 * LDT, *T11h = TTh + 2 * 32 * LDT, *T11l = TTh + 3 * 32 * LDT;
@@ -178,6 +189,10 @@ __global__ __launch_bounds__(kThreads, 2) void mk_delta_prep(Dims d, DeltaPrepAr
         }
         store_block_t_split(TbTh, TbTl, LDP, n, 32, half, Tb);  // rows c, columns 32 + t
         store_block_t_split(TwTh, TwTl, LDP, n, 32, half, Tw);
+        if (gtt) {
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) Tb[x] = -T10[x];
+            store_block_t_split(gtt, gtt + C * C, C, n, 32, half, Tb);
+        }
     }
     __syncthreads();  // T is complete; the small tiles are spent
     tile_commit(Vt, rv, L, tid);
@@ -221,6 +236,7 @@ struct DeltaWalkArgs {
     uint16_t* out;
     const float* edge_in;   // M_0 [i][v] per sequence or NULL
     float* edge_out;        // M_T or NULL
+    uint16_t *usave, *usave_l;  // NULL, or the pseudo-values (bf16 head, remainder) in the layout of v, for the backward pass
 };
 // LDS: Q | K | U head (the value tile's place) | U remainder | What (64 x LD bf16 each) | Uhat (64 x LDU fp32) |
 // scores head | scores remainder (64 x LDP) | bs | wo
@@ -242,38 +258,6 @@ __device__ __forceinline__ void delta_intra(f32x16& O, int jb, const uint16_t* V
         O = mfma(vh, frag(Pl, LDP, j, 16 * ks + 8 * half), O);
     }
 }
-// state: S[i][v] = e^{b_C} S[i][v] + sum_t K^T[i][t] (wo_t U[t][v]), U from its two planes, the weighted slice split
-// again into head + remainder in registers
-template <bool DEC>
-__device__ __forceinline__ void delta_update(f32x16 (&S)[4], const uint16_t* K, const uint16_t* Vh, const uint16_t* Vl,
-                                             const float* wo, float bC, int w4, int lane, int half) {
-    if (DEC) {
-        const float lam = __expf(bC);
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) S[ib][x] *= lam;
-    }
-    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
-        const u32x4 rh = __builtin_bit_cast(u32x4, frag_tr(Vh, LD, 16 * ks, 32 * w4, lane));
-        const u32x4 rl = __builtin_bit_cast(u32x4, frag_tr(Vl, LD, 16 * ks, 32 * w4, lane));
-        u32x4 hi = rh, lo = rl;
-        if (DEC) {
-            const float4 w0 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half);
-            const float4 w1 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half + 4);
-            const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-            _Pragma("unroll") for (int p = 0; p < 4; ++p) {
-                const float x0 = (bf16_lo(rh[p]) + bf16_lo(rl[p])) * w[2 * p], x1 = (bf16_hi(rh[p]) + bf16_hi(rl[p])) * w[2 * p + 1];
-                hi[p] = pack2(x0, x1);
-                lo[p] = pack2(x0 - bf16_lo(hi[p]), x1 - bf16_hi(hi[p]));
-            }
-        }
-        const bf16x8 vh = __builtin_bit_cast(bf16x8, hi), vl = __builtin_bit_cast(bf16x8, lo);
-        bf16x8 ka[4];
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) ka[ib] = frag_tr(K, LD, 16 * ks, 32 * ib, lane);
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(ka[ib], vh, S[ib]);
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(ka[ib], vl, S[ib]);
-    }
-}
-
 struct TileRegsF { float4 v[8]; };
 __device__ __forceinline__ void tilef_gload(TileRegsF& r, const float* src, size_t tok0, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 8; ++it) {
@@ -370,9 +354,545 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
             delta_intra(O[jb], jb, V, Vl, Ph, Pl, wave, lane, n, half);
             store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
         }
-        delta_update<DEC>(S, K, V, Vl, wo, bC, wave, lane, half);
+        walk_update_vsplit<DEC, true>(S, K, V, Vl, wo, bC, wave, lane, half);
         __syncthreads();  // (D) the output stage is complete and every read of this chunk's tiles is done
-        walk_store<false>(a.out, stage, cp.tok0, cp.ts, L, tid);
+        if (a.out) walk_store<false>(a.out, stage, cp.tok0, cp.ts, L, tid);
+        // the value tile is not written again before every wave has passed the next barrier (A)
+        if (a.usave) {
+            walk_store<false>(a.usave, V, cp.tok0, cp.ts, L, tid);
+            walk_store<false>(a.usave_l, Vl, cp.tok0, cp.ts, L, tid);
+        }
     }
     if (a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward, sequential part.  With U known, M_t = alpha_t M_{t-1} + k_t^T u_t is the scalar-decay recurrence on values
+// U, so the gradient walker of the diagonal kinds yields dq, the key gradient through the scores and the state
+// update, and the decay gradient of those terms, PROVIDED it is handed the state gradients of the delta rule.  Those
+// differ from the diagonal kinds': u_t depends on the state the chunk starts from (U = Uhat - What S), so per chunk
+//     dU = A^T dO + diag(wo) K dS'          (A = masked decayed scores, dS' = gradient of the state at the chunk end)
+//     dS = Gamma_C dS' + (diag(Gamma) Q)^T dO - What^T dU .
+// mk_delta_rwalk walks a sequence backward with dS in the accumulators (the forward walker's block layout), stores
+// dS' per chunk in the fragment-major bf16 form the gradient walker reads, and dU as bf16 head + remainder for the
+// kernels that take the gradient through the triangular solve.
+struct DeltaRevArgs {
+    const uint16_t *q, *k, *d_o;
+    const uint16_t* what;     // [BH*T][128] bf16 (library order)
+    const float* log_alpha;
+    uint16_t* dstates;        // [BH*N] fragment-major bf16: slot c = gradient of the state at the end of chunk c
+    uint16_t *du_h, *du_l;    // [BH*T][128] bf16 (library order)
+    const float* edge_in;     // d M_T [i][v] per sequence or NULL
+    float* edge_out;          // d M_0 or NULL
+};
+constexpr int LDW = 40;  // row stride of a wave's private 32-column tiles
+// LDS: Q | K | dO | What (64 x LD) | scores head | remainder (64 x LDP) | per wave: 128 x LDW bf16 (its columns of dS',
+// then of dU head and remainder, 64 x LDW each) | bs | wo | Gamma
+constexpr int kDeltaRevLds = (4 * C * LD + 2 * C * LDP) * 2 + 4 * D * LDW * 2 + (3 * C + 8) * 4;
+
+// grid: (seqs)
+template <bool DEC>
+__global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* K = Q + C * LD;
+    uint16_t* dO = K + C * LD;
+    uint16_t* Wh = dO + C * LD;
+    uint16_t* Ph = Wh + C * LD;
+    uint16_t* Pl = Ph + C * LDP;
+    uint16_t* priv = Pl + C * LDP;
+    float* bs = reinterpret_cast<float*>(priv + 4 * D * LDW);
+    float* wo = bs + C + 4;
+    float* gm = wo + C + 4;
+
+    const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const SeqWalk walk = seq_walk(d, seq);
+    const int cnt = walk.n;
+    uint16_t* pw = priv + wave * D * LDW;   // this wave's region
+    uint16_t* duh = pw;
+    uint16_t* dul = pw + C * LDW;
+
+    f32x16 S[4];  // dS[ib][4g+j] = dS[i = 32 ib + 8g + 4 half + j][v = 32 wave + n]
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
+    if (a.edge_in) walk_state_load(S, a.edge_in + size_t(seq) * D * D, false, wave, n, half);
+
+    TileRegs rq, rk, ro, rw;
+    float gval = 0.f;
+    auto gload = [&](int kk) {
+        const ChunkPos p = walk_pos(d, walk, cnt - 1 - min(kk, cnt - 1));
+        if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
+        walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(rk, a.k, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(ro, a.d_o, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(rw, a.what, p.wtok0, 1, p.L, tid);
+    };
+    if (cnt > 0) gload(0);
+
+    for (int kk = 0; kk < cnt; ++kk) {
+        const ChunkPos cp = walk_pos(d, walk, cnt - 1 - kk);
+        const int L = cp.L;
+        walk_commit<kThreads>(Q, rq, L, tid);
+        walk_commit<kThreads>(K, rk, L, tid);
+        walk_commit<kThreads>(dO, ro, L, tid);
+        walk_commit<kThreads>(Wh, rw, L, tid);
+        if (DEC && wave == 0) {
+            walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
+            gm[lane] = __expf(bs[lane]);
+        }
+        gload(kk + 1);
+        __syncthreads();  // (A) tiles and decay tables of this chunk are in LDS
+        const float bC = DEC ? bs[C] : 0.f;
+
+        // ---- dS' of this wave's columns -> global, fragment-major: through the wave's private tile [i][v - 32 wave]
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+            _Pragma("unroll") for (int x = 0; x < 16; ++x)
+                pw[(32 * ib + 8 * (x >> 2) + 4 * half + (x & 3)) * LDW + n] = uint16_t(pack2(S[ib][x], 0.f));
+        __builtin_amdgcn_wave_barrier();
+        {
+            uint16_t* dst = a.dstates + cp.slot * D * D;
+            _Pragma("unroll") for (int blk = 0; blk < 4; ++blk)
+                _Pragma("unroll") for (int q2 = 0; q2 < 2; ++q2) {
+                    const u32x4 val = *reinterpret_cast<const u32x4*>(pw + (32 * blk + n) * LDW + 16 * q2 + 8 * half);
+                    __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(dst + state_frag_off(blk, 2 * wave + q2, lane)));
+                }
+        }
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- dU^T[v][t] = wo_t sum_i dS'[i][v] k_t[i] + sum_{j >= t} dO[j][v] P[j][t]
+        f32x16 dU[2];
+        walk_inter<false>(dU, S, K, bs, n, half);
+        if (DEC) {
+            _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
+                const float w = wo[32 * tb + n];
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) dU[tb][x] *= w;
+            }
+        }
+        walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
+        __syncthreads();  // (C) scores are in LDS
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+            _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {  // queries j < 32 never see keys t >= 32
+                const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
+                dU[nb] = mfma(dot, frag_tr(Ph, LDP, 16 * ks, 32 * nb, lane), dU[nb]);
+                dU[nb] = mfma(dot, frag_tr(Pl, LDP, 16 * ks, 32 * nb, lane), dU[nb]);
+            }
+            const PackedBlock uh = pack_block(dU[nb]);
+            f32x16 r = dU[nb];
+            _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                r[4 * g + 0] -= bf16_lo(uh.v[g].x);
+                r[4 * g + 1] -= bf16_hi(uh.v[g].x);
+                r[4 * g + 2] -= bf16_lo(uh.v[g].y);
+                r[4 * g + 3] -= bf16_hi(uh.v[g].y);
+            }
+            store_packed(duh, LDW, 32 * nb + n, 0, half, uh);
+            store_packed(dul, LDW, 32 * nb + n, 0, half, pack_block(r));
+        }
+        __builtin_amdgcn_wave_barrier();
+        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+            const int row = (lane >> 2) + 16 * it, piece = lane & 3;
+            if (row < L) {
+                const size_t off = (cp.wtok0 + row) * D + 32 * wave + 8 * piece;
+                *reinterpret_cast<u32x4*>(a.du_h + off) = *reinterpret_cast<const u32x4*>(duh + row * LDW + 8 * piece);
+                *reinterpret_cast<u32x4*>(a.du_l + off) = *reinterpret_cast<const u32x4*>(dul + row * LDW + 8 * piece);
+            }
+        }
+        // ---- dS = Gamma_C dS' + sum_t (Gamma_t q_t)^T dO_t - sum_t what_t^T dU_t
+        if (DEC) {
+            const float lam = __expf(bC);
+            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) S[ib][x] *= lam;
+        }
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+            const u32x4 raw = __builtin_bit_cast(u32x4, frag_tr(dO, LD, 16 * ks, 32 * wave, lane));
+            u32x4 hi = raw, lo = {0, 0, 0, 0};
+            if (DEC) {
+                const float4 w0 = *reinterpret_cast<const float4*>(gm + 16 * ks + 8 * half);
+                const float4 w1 = *reinterpret_cast<const float4*>(gm + 16 * ks + 8 * half + 4);
+                const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+                _Pragma("unroll") for (int p = 0; p < 4; ++p) {
+                    const float x0 = bf16_lo(raw[p]) * w[2 * p], x1 = bf16_hi(raw[p]) * w[2 * p + 1];
+                    hi[p] = pack2(x0, x1);
+                    lo[p] = pack2(x0 - bf16_lo(hi[p]), x1 - bf16_hi(hi[p]));
+                }
+            }
+            const bf16x8 oh = __builtin_bit_cast(bf16x8, hi), ol = __builtin_bit_cast(bf16x8, lo);
+            u32x4 nh = __builtin_bit_cast(u32x4, frag_tr(duh, LDW, 16 * ks, 0, lane));
+            u32x4 nl = __builtin_bit_cast(u32x4, frag_tr(dul, LDW, 16 * ks, 0, lane));
+            _Pragma("unroll") for (int p = 0; p < 4; ++p) {  // -dU
+                nh[p] ^= 0x80008000u;
+                nl[p] ^= 0x80008000u;
+            }
+            const bf16x8 uh = __builtin_bit_cast(bf16x8, nh), ul = __builtin_bit_cast(bf16x8, nl);
+            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) {
+                const bf16x8 qa = frag_tr(Q, LD, 16 * ks, 32 * ib, lane), wa = frag_tr(Wh, LD, 16 * ks, 32 * ib, lane);
+                S[ib] = mfma(qa, oh, S[ib]);
+                if (DEC) S[ib] = mfma(qa, ol, S[ib]);
+                S[ib] = mfma(wa, uh, S[ib]);
+                S[ib] = mfma(wa, ul, S[ib]);
+            }
+        }
+        __syncthreads();  // (D) every read of this chunk's tiles is done
+    }
+    if (a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward, the gradient of What: dWhat = -dU S^T per chunk (S = state the chunk starts from).  A forward walk over
+// segments with the state in the gradient walker's layout (lanes = key feature i, registers = value feature v, so
+// that contractions over v are the natural ones) and nothing else in it but the state update.
+struct DeltaDwArgs {
+    const uint16_t* k;              // layout of the caller
+    const uint16_t *u_h, *u_l;      // pseudo-values, layout of v
+    const uint16_t *du_h, *du_l;    // [BH*T][128] (library order)
+    const float* log_alpha;
+    uint16_t *dw_h, *dw_l;          // [BH*T][128] (library order): dWhat, head and remainder
+    const float* edge_in;           // M_0 or NULL
+    const float* bound;             // entry states of the segments when nseg > 1
+    int m, nseg;
+};
+// LDS: K | U head | U remainder | dU head | dU remainder (64 x LD; the last two later the stage of dWhat) | bs | wo
+constexpr int kDeltaDwLds = 5 * C * LD * 2 + (2 * C + 8) * 4;
+
+// grid: (nseg, seqs)
+template <bool DEC>
+__global__ __launch_bounds__(kThreads, 1) void mk_delta_dw(Dims d, DeltaDwArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* K = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Uh = K + C * LD;
+    uint16_t* Ul = Uh + C * LD;
+    uint16_t* dUh = Ul + C * LD;
+    uint16_t* dUl = dUh + C * LD;
+    float* bs = reinterpret_cast<float*>(dUl + C * LD);
+    float* wo = bs + C + 4;
+
+    const int seq = blockIdx.y, seg = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const SeqWalk walk = seq_walk(d, seq);
+    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
+    if (cnt <= 0) return;
+
+    f32x16 S[4];  // S[vb][4g+j] = M[i = 32 wave + n][v = 32 vb + 8g + 4 half + j]
+    _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) S[vb] = f32x16{0};
+    {
+        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
+                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
+        if (ein) walk_state_load(S, ein, true, wave, n, half);
+    }
+    TileRegs tk, tuh, tul, tdh, tdl;
+    float gval = 0.f;
+    auto gload = [&](int kk) {
+        const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
+        if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
+        walk_gload<false, kThreads>(tk, a.k, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(tuh, a.u_h, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(tul, a.u_l, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, kThreads>(tdh, a.du_h, p.wtok0, 1, p.L, tid);
+        walk_gload<false, kThreads>(tdl, a.du_l, p.wtok0, 1, p.L, tid);
+    };
+    gload(0);
+    for (int kk = 0; kk < cnt; ++kk) {
+        const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
+        const int L = cp.L;
+        walk_commit<kThreads>(K, tk, L, tid);
+        walk_commit<kThreads>(Uh, tuh, L, tid);
+        walk_commit<kThreads>(Ul, tul, L, tid);
+        walk_commit<kThreads>(dUh, tdh, L, tid);
+        walk_commit<kThreads>(dUl, tdl, L, tid);
+        if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
+        gload(kk + 1);
+        __syncthreads();  // (1) tiles and decay tables are in LDS
+        const float bC = DEC ? bs[C] : 0.f;
+        // dWhat^T[i][t] = -sum_v S[i][v] dU[t][v], both planes of dU
+        f32x16 a0[2], a1[2];
+        walk_inter<false>(a0, S, dUh, bs, n, half);
+        walk_inter<false>(a1, S, dUl, bs, n, half);
+        // the state moves on to the end of the chunk (roles: key = u, value = k)
+        walk_update<DEC, true, true>(S, Uh, K, wo, bC, wave, lane, half, Ul);
+        __syncthreads();  // (2) nobody reads the dU tiles any more: they become the stage
+        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+            f32x16 w;
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) w[x] = -(a0[nb][x] + a1[nb][x]);
+            const PackedBlock wh = pack_block(w);
+            _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                w[4 * g + 0] -= bf16_lo(wh.v[g].x);
+                w[4 * g + 1] -= bf16_hi(wh.v[g].x);
+                w[4 * g + 2] -= bf16_lo(wh.v[g].y);
+                w[4 * g + 3] -= bf16_hi(wh.v[g].y);
+            }
+            store_packed(dUh, LD, 32 * nb + n, 32 * wave, half, wh);
+            store_packed(dUl, LD, 32 * nb + n, 32 * wave, half, pack_block(w));
+        }
+        __syncthreads();  // (3)
+        // every thread reads back exactly the stage pieces that its own next walk_commit overwrites
+        walk_store<false>(a.dw_h, dUh, cp.wtok0, 1, L, tid);
+        walk_store<false>(a.dw_l, dUl, cp.wtok0, 1, L, tid);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward, the chunk-local part: everything that reaches the inputs through the triangular solve.  Per chunk, with
+// T = (I + L)^-1, Uhat = T diag(b) V, What = T diag(beta Gamma) K and the gradients dU (of Uhat) and dWhat:
+//   dVb = T^T dU          -> dv_r = b_r dVb_r ,            db_r = dVb_r . v_r
+//   dKb = T^T dWhat       -> dk_r += beta_r Gamma_r dKb_r , c_r = dKb_r . k_r  (-> d beta_r += Gamma_r c_r, d lg_r += beta_r Gamma_r c_r)
+//   dT  = dU (diag(b) V)^T + dWhat (diag(beta Gamma) K)^T   (only its strictly lower part matters)
+//   dL  = -T^T dT T^T     (strictly lower part);  L_tr = beta_t e^{lg_t - lg_r} (k_t . k_r):
+//   F_tr = dL_tr e^{lg_t - lg_r} (k_t . k_r):  d beta_t += sum_r F_tr ;  d lg_t += beta_t sum_r F_tr ;  d lg_r -= sum_t beta_t F_tr
+//   dG_tr = beta_t e^{lg_t - lg_r} dL_tr:      dk_t += sum_r dG_tr k_r ,  dk_r += sum_t dG_tr k_t
+// and d log alpha_t = sum_{s >= t} d lg_s inside the chunk (lg is the chunk-local running sum).  The key gradient of
+// the gradient walker (head + remainder) is added before the one rounding to bf16, its decay gradient is added to.
+struct DeltaGradArgs {
+    const uint16_t *k, *v;            // layout of the caller
+    const uint16_t *du_h, *du_l, *dw_h, *dw_l;  // [BH*T][128] (library order)
+    const uint16_t* tt;               // [BH*N][2][64][64]
+    const float *log_alpha, *beta, *bw;
+    const uint16_t *dk1_h, *dk1_l;    // the gradient walker's key gradient, layout of the caller
+    uint16_t *dk, *dv;
+    float *d_log_alpha, *d_beta, *d_bw;   // d_log_alpha is added to
+};
+// LDS: K | V | dU head | remainder | dWhat head | remainder (64 x LD) | T^T head | remainder | dT head | remainder
+// (64 x LDP) | lg, beta, b, e^{lg} | reductions.  After the first phase the five tiles behind K are spent and hold
+// M1 = dT T^T and dG (head, remainder, 64 x LDP each) and the stages of dv and dk.
+constexpr int kDeltaGradRed = (4 * C + 4 * 2 * C + 3 * C + 3 * C) * 4;  // params | db, c per wave | row sums | column sums
+constexpr int kDeltaGradLds = 6 * C * LD * 2 + 4 * C * LDP * 2 + kDeltaGradRed;
+
+// grid: (N, BH)
+template <bool DEC>
+__global__ __launch_bounds__(kThreads, 1) void mk_delta_grad(Dims d, DeltaGradArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* K = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* V = K + C * LD;
+    uint16_t* dUh = V + C * LD;
+    uint16_t* dUl = dUh + C * LD;
+    uint16_t* dWh = dUl + C * LD;
+    uint16_t* dWl = dWh + C * LD;
+    uint16_t* TTh = dWl + C * LD;
+    uint16_t* TTl = TTh + C * LDP;
+    uint16_t* dTh = TTl + C * LDP;
+    uint16_t* dTl = dTh + C * LDP;
+    float* lg = reinterpret_cast<float*>(dTl + C * LDP);
+    float* be = lg + C;
+    float* bb = be + C;
+    float* gm = bb + C;           // e^{lg}
+    float* red_db = gm + C;       // [wave][64]
+    float* red_c = red_db + 4 * C;
+    float* rowF = red_c + 4 * C;  // [3 blocks][32]: sum_r F_tr per t of the block
+    float* colE = rowF + 3 * C;   // [3 blocks][32]: sum_t beta_t F_tr per r of the block   (3 * C floats reserved each)
+    // second phase, over V .. dWl
+    uint16_t* M1h = V;
+    uint16_t* M1l = M1h + C * LDP;
+    uint16_t* dGh = M1l + C * LDP;
+    uint16_t* dGl = dGh + C * LDP;
+    uint16_t* stv = dGl + C * LDP;   // stage of dv (64 x LD)
+    uint16_t* stk = stv + C * LD;    // stage of dk
+    static_assert(4 * C * LDP + 2 * C * LD <= 5 * C * LD, "second phase fits behind K");
+
+    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int L = cp.L;
+    if (L <= 0) return;
+    const size_t ptok = cp.tok0 + size_t(min(lane, L - 1)) * cp.ts;
+    if (wave == 0) {
+        float x = (DEC && lane < L) ? a.log_alpha[ptok] : 0.f;
+        const float bet = a.beta ? a.beta[ptok] : 1.f, bwt = a.bw ? a.bw[ptok] : 1.f;
+        for (int off = 1; off < 64; off <<= 1) {
+            const float y = __shfl_up(x, off, 64);
+            if (lane >= off) x += y;
+        }
+        lg[lane] = x;
+        be[lane] = lane < L ? bet : 0.f;
+        bb[lane] = lane < L ? bwt : 0.f;
+        gm[lane] = DEC ? __expf(x) : 1.f;
+    }
+    load_tile(K, a.k, cp.tok0, cp.ts, L, tid);
+    load_tile(V, a.v, cp.tok0, cp.ts, L, tid);
+    load_tile(dUh, a.du_h, cp.wtok0, 1, L, tid);
+    load_tile(dUl, a.du_l, cp.wtok0, 1, L, tid);
+    load_tile(dWh, a.dw_h, cp.wtok0, 1, L, tid);
+    load_tile(dWl, a.dw_l, cp.wtok0, 1, L, tid);
+    {
+        const uint16_t* gtt = a.tt + cp.slot * 2 * C * C;
+        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+            const int p = tid + kThreads * it, plane = p >> 9, row = (p >> 3) & 63, piece = p & 7;
+            *reinterpret_cast<u32x4*>((plane ? TTl : TTh) + row * LDP + 8 * piece) =
+                *reinterpret_cast<const u32x4*>(gtt + plane * C * C + row * C + 8 * piece);
+        }
+    }
+    __syncthreads();
+
+    // ---- first phase
+    PackedBlock resv[2];
+    f32x16 dk2[2];
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        // dVb^T[v][r] = sum_t dU[t][v] T[t][r],  dKb^T[i][r] = sum_t dWhat[t][i] T[t][r]  (T[t][r] = 0 for t < r)
+        f32x16 av = {0}, ak = {0};
+        _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+            const bf16x8 th = frag(TTh, LDP, 32 * nb + n, 16 * ks + 8 * half), tl = frag(TTl, LDP, 32 * nb + n, 16 * ks + 8 * half);
+            const bf16x8 uh = frag_tr(dUh, LD, 16 * ks, 32 * wave, lane), ul = frag_tr(dUl, LD, 16 * ks, 32 * wave, lane);
+            const bf16x8 wh = frag_tr(dWh, LD, 16 * ks, 32 * wave, lane), wl = frag_tr(dWl, LD, 16 * ks, 32 * wave, lane);
+            av = mfma(uh, th, av);
+            av = mfma(uh, tl, av);
+            av = mfma(ul, th, av);
+            ak = mfma(wh, th, ak);
+            ak = mfma(wh, tl, ak);
+            ak = mfma(wl, th, ak);
+        }
+        const int r = 32 * nb + n;
+        float pdb = row_dot(V, r, wave, half, av), pc = row_dot(K, r, wave, half, ak);
+        pdb += __shfl_xor(pdb, 32, 64);
+        pc += __shfl_xor(pc, 32, 64);
+        if (half == 0) {
+            red_db[wave * C + r] = pdb;
+            red_c[wave * C + r] = pc;
+        }
+        const float br = bb[r], wr = be[r] * gm[r];
+        _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+            av[x] *= br;
+            ak[x] *= wr;
+        }
+        resv[nb] = pack_block(av);
+        dk2[nb] = ak;
+    }
+    // dT[t][r] for r < t, blocks (r, t) = (0,0), (0,1), (1,1) by waves 0, 1, 2; wave 3 clears the block above the diagonal
+    if (wave < 3) {
+        const int rb = wave == 2 ? 1 : 0, tb = wave ? 1 : 0;
+        f32x16 t1 = score_block2(V, 32 * rb, dUh, 32 * tb, n, half);   // D[m = r][n = t] = v_r . dU_t
+        t1 = score_block2(V, 32 * rb, dUl, 32 * tb, n, half, t1);
+        f32x16 t2 = score_block2(K, 32 * rb, dWh, 32 * tb, n, half);
+        t2 = score_block2(K, 32 * rb, dWl, 32 * tb, n, half, t2);
+        const int t = 32 * tb + n;
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            const int r0 = 32 * rb + 8 * g + 4 * half;
+            const float4 b4 = *reinterpret_cast<const float4*>(bb + r0), e4 = *reinterpret_cast<const float4*>(be + r0);
+            const float4 g4 = *reinterpret_cast<const float4*>(gm + r0);
+            const float bv[4] = {b4.x, b4.y, b4.z, b4.w}, wv[4] = {e4.x * g4.x, e4.y * g4.y, e4.z * g4.z, e4.w * g4.w};
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)
+                t1[4 * g + j] = (r0 + j < t) ? t1[4 * g + j] * bv[j] + t2[4 * g + j] * wv[j] : 0.f;
+        }
+        store_block_t_split(dTh, dTl, LDP, t, 32 * rb, half, t1);
+    } else {
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {   // rows t < 32, columns r >= 32
+            const int p = lane + 64 * it, row = p >> 2, piece = p & 3;
+            *reinterpret_cast<u32x4*>(dTh + row * LDP + 32 + 8 * piece) = u32x4{0, 0, 0, 0};
+            *reinterpret_cast<u32x4*>(dTl + row * LDP + 32 + 8 * piece) = u32x4{0, 0, 0, 0};
+        }
+    }
+    __syncthreads();  // first phase done: the tiles behind K are spent, dT is complete
+
+    // ---- M1[t][r] = sum_r' dT[t][r'] T[r][r'], blocks (r, t) = (0,0), (0,1), (1,1); kept as a tile [t][r]
+    if (wave < 3) {
+        const int mb = wave == 2 ? 1 : 0, nb = wave ? 1 : 0;
+        f32x16 m1 = {0};
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+            if (ks >= 2 * (mb + 1)) break;  // r' <= r
+            const bf16x8 ah = frag_tr(TTh, LDP, 16 * ks, 32 * mb, lane), al = frag_tr(TTl, LDP, 16 * ks, 32 * mb, lane);  // T[r][r']
+            const bf16x8 bh_ = frag(dTh, LDP, 32 * nb + n, 16 * ks + 8 * half), bl = frag(dTl, LDP, 32 * nb + n, 16 * ks + 8 * half);
+            m1 = mfma(ah, bh_, m1);
+            m1 = mfma(ah, bl, m1);
+            m1 = mfma(al, bh_, m1);
+        }
+        store_block_t_split(M1h, M1l, LDP, 32 * nb + n, 32 * mb, half, m1);
+    } else {
+        _Pragma("unroll") for (int it = 0; it < 2; ++it) {   // rows t' < 32, columns r >= 32: never contribute
+            const int p = lane + 64 * it, row = p >> 2, piece = p & 3;
+            *reinterpret_cast<u32x4*>(M1h + row * LDP + 32 + 8 * piece) = u32x4{0, 0, 0, 0};
+            *reinterpret_cast<u32x4*>(M1l + row * LDP + 32 + 8 * piece) = u32x4{0, 0, 0, 0};
+            *reinterpret_cast<u32x4*>(dGh + row * LDP + 32 + 8 * piece) = u32x4{0, 0, 0, 0};
+            *reinterpret_cast<u32x4*>(dGl + row * LDP + 32 + 8 * piece) = u32x4{0, 0, 0, 0};
+        }
+    }
+    __syncthreads();
+    // ---- dL[t][r] = -sum_t' T[t'][t] M1[t'][r], then F, the row and column sums, and dG as a tile [t][r]
+    if (wave < 3) {
+        const int mb = wave == 2 ? 1 : 0, nb = wave ? 1 : 0;
+        f32x16 dl = {0};
+        _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {  // t' >= t
+            const bf16x8 ah = frag_tr(M1h, LDP, 16 * ks, 32 * mb, lane), al = frag_tr(M1l, LDP, 16 * ks, 32 * mb, lane);  // M1[t'][r]
+            const bf16x8 bh_ = frag(TTh, LDP, 32 * nb + n, 16 * ks + 8 * half), bl = frag(TTl, LDP, 32 * nb + n, 16 * ks + 8 * half);  // T[t'][t]
+            dl = mfma(ah, bh_, dl);
+            dl = mfma(ah, bl, dl);
+            dl = mfma(al, bh_, dl);
+        }
+        const f32x16 G = score_block2(K, 32 * mb, K, 32 * nb, n, half);  // D[m = r][n = t] = k_r . k_t
+        const int t = 32 * nb + n;
+        const float bt = be[t], lt = lg[t];
+        float rs = 0.f;
+        f32x16 dg;
+        float cs[16];
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            const int r0 = 32 * mb + 8 * g + 4 * half;
+            const float4 l4 = *reinterpret_cast<const float4*>(lg + r0);
+            const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {
+                const float dec = DEC ? __expf(lt - lr[j]) : 1.f;
+                const float dlv = (r0 + j < t) ? -dl[4 * g + j] * dec : 0.f;   // dL_tr e^{lg_t - lg_r}
+                const float f = dlv * G[4 * g + j];
+                rs += f;
+                cs[4 * g + j] = bt * f;
+                dg[4 * g + j] = bt * dlv;
+            }
+        }
+        rs += __shfl_xor(rs, 32, 64);
+        if (half == 0) rowF[wave * 32 + n] = rs;
+        if (DEC) {  // column sums over the 32 tokens t of the block, for each r
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                float v_ = cs[x];
+                for (int off = 16; off > 0; off >>= 1) v_ += __shfl_xor(v_, off, 64);
+                cs[x] = v_;
+            }
+            if (n == 0) {
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) colE[wave * 32 + 8 * (x >> 2) + 4 * half + (x & 3)] = cs[x];
+            }
+        }
+        store_block_t_split(dGh, dGl, LDP, t, 32 * mb, half, dg);
+    }
+    __syncthreads();
+    // ---- dk^T[i][t] = dk2[i][t] + sum_r K^T[i][r] (dG[t][r] + dG[r][t]) + the gradient walker's part
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        f32x16 acc = dk2[nb];
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 kt = frag_tr(K, LD, 16 * ks, 32 * wave, lane);
+            if (ks < 2 * (nb + 1)) {  // r < t
+                acc = mfma(kt, frag(dGh, LDP, 32 * nb + n, 16 * ks + 8 * half), acc);
+                acc = mfma(kt, frag(dGl, LDP, 32 * nb + n, 16 * ks + 8 * half), acc);
+            }
+            if (ks >= 2 * nb) {       // r > t
+                acc = mfma(kt, frag_tr(dGh, LDP, 16 * ks, 32 * nb, lane), acc);
+                acc = mfma(kt, frag_tr(dGl, LDP, 16 * ks, 32 * nb, lane), acc);
+            }
+        }
+        const int t = 32 * nb + n;
+        const size_t row = (cp.tok0 + size_t(min(t, L - 1)) * cp.ts) * D + 32 * wave + 4 * half;
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            const u32x2 h = *reinterpret_cast<const u32x2*>(a.dk1_h + row + 8 * g), l = *reinterpret_cast<const u32x2*>(a.dk1_l + row + 8 * g);
+            acc[4 * g + 0] += bf16_lo(h.x) + bf16_lo(l.x);
+            acc[4 * g + 1] += bf16_hi(h.x) + bf16_hi(l.x);
+            acc[4 * g + 2] += bf16_lo(h.y) + bf16_lo(l.y);
+            acc[4 * g + 3] += bf16_hi(h.y) + bf16_hi(l.y);
+        }
+        store_packed(stk, LD, t, 32 * wave, half, pack_block(acc));
+        store_packed(stv, LD, t, 32 * wave, half, resv[nb]);
+    }
+    __syncthreads();
+    store_tile(a.dk, stk, cp.tok0, cp.ts, L, tid);
+    store_tile(a.dv, stv, cp.tok0, cp.ts, L, tid);
+    // ---- per-token parameters (wave 0, lane = token)
+    if (wave == 0) {
+        const int t = lane;
+        const float cb = (red_c[t] + red_c[C + t]) + (red_c[2 * C + t] + red_c[3 * C + t]);
+        const float db = (red_db[t] + red_db[C + t]) + (red_db[2 * C + t] + red_db[3 * C + t]);
+        // row sums of F: t < 32 from block 0; t >= 32 from blocks 1 and 2.  Column sums: r < 32 from blocks 0 and 1; r >= 32 from block 2.
+        const float rf = t < 32 ? rowF[t] : rowF[32 + (t - 32)] + rowF[64 + (t - 32)];
+        if (a.d_bw && t < L) a.d_bw[ptok] = db;
+        if (a.d_beta && t < L) a.d_beta[ptok] = gm[t] * cb + rf;
+        if (DEC) {
+            const float ce = t < 32 ? colE[t] + colE[32 + t] : colE[64 + (t - 32)];
+            float dlg = be[t] * gm[t] * cb + be[t] * rf - ce;
+            if (t >= L) dlg = 0.f;
+            float sfx = dlg;  // suffix sum over tokens >= t
+            for (int off = 1; off < 64; off <<= 1) {
+                const float y = __shfl_down(sfx, off, 64);
+                if (t + off < 64) sfx += y;
+            }
+            if (t < L) a.d_log_alpha[ptok] += sfx;
+        }
+    }
 }

@@ -28,6 +28,7 @@ struct WalkArgs {
     float* gseg;           // [seqs][nseg]: total log-decay of each segment (SUMMARY writes)
     int m, nseg;           // chunks per segment, segments per sequence (upper bound for packed input)
     int skip;              // SUMMARY, REV: segments [0, skip) feed no other walk and are left out (at least 1)
+    const uint16_t* xv_lo; // VSPLIT (summary pass only): remainder plane of the value-role rows
 };
 
 // tile rows in walk order: row r holds token r (forward) or token L-1-r (backward); rows >= L are zero.
@@ -91,8 +92,8 @@ __host__ __device__ constexpr int walk_lds(bool summary) {
 
 // D[m][n] = sum_f Am[m0 + m][f] * Bm[n0 + n][f] over the 128 features of two row-major LDS tiles, the
 // fragments requested four k-steps at a time (a lower register peak than all sixteen at once)
-__device__ __forceinline__ f32x16 score_block2(const uint16_t* Am, int m0, const uint16_t* Bm, int n0, int n, int half) {
-    f32x16 acc = {0};
+__device__ __forceinline__ f32x16 score_block2(const uint16_t* Am, int m0, const uint16_t* Bm, int n0, int n, int half,
+                                               f32x16 acc = f32x16{0}) {
     _Pragma("unroll") for (int h4 = 0; h4 < 2; ++h4) {
         bf16x8 fa[4], fb[4];
         _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
@@ -160,9 +161,10 @@ __device__ __forceinline__ void walk_intra(f32x16& O, int jb, const uint16_t* V,
 }
 // state: S[i][v] = e^{b_C} S[i][v] + sum_t K^T[i][t] (wo_t V[t][v]); the weighted value slice of this wave is
 // split into head + remainder in registers.  SCALE = false: the weights already carry every decay.
-template <bool DEC, bool SCALE>
+// K2 (KSPLIT): remainder plane of the key-role tile (remainder x remainder is left out).
+template <bool DEC, bool SCALE, bool KSPLIT = false>
 __device__ __forceinline__ void walk_update(f32x16 (&S)[4], const uint16_t* K, const uint16_t* V, const float* wo, float bC, int w4,
-                                            int lane, int half) {
+                                            int lane, int half, const uint16_t* K2 = nullptr) {
     if (DEC && SCALE) {
         const float lam = __expf(bC);
         _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
@@ -188,8 +190,43 @@ __device__ __forceinline__ void walk_update(f32x16 (&S)[4], const uint16_t* K, c
         if (DEC) {
             _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(ka[ib], vl, S[ib]);
         }
+        if (KSPLIT) {
+            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(frag_tr(K2, LD, 16 * ks, 32 * ib, lane), vh, S[ib]);
+        }
     }
 }
+// the same state update with the values in two planes (head + remainder; the pseudo-values of the delta rule), the
+// weighted slice split again into head + remainder in registers
+template <bool DEC, bool SCALE>
+__device__ __forceinline__ void walk_update_vsplit(f32x16 (&S)[4], const uint16_t* K, const uint16_t* Vh, const uint16_t* Vl,
+                                             const float* wo, float bC, int w4, int lane, int half) {
+    if (DEC && SCALE) {
+        const float lam = __expf(bC);
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) S[ib][x] *= lam;
+    }
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {
+        const u32x4 rh = __builtin_bit_cast(u32x4, frag_tr(Vh, LD, 16 * ks, 32 * w4, lane));
+        const u32x4 rl = __builtin_bit_cast(u32x4, frag_tr(Vl, LD, 16 * ks, 32 * w4, lane));
+        u32x4 hi = rh, lo = rl;
+        if (DEC) {
+            const float4 w0 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half);
+            const float4 w1 = *reinterpret_cast<const float4*>(wo + 16 * ks + 8 * half + 4);
+            const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            _Pragma("unroll") for (int p = 0; p < 4; ++p) {
+                const float x0 = (bf16_lo(rh[p]) + bf16_lo(rl[p])) * w[2 * p], x1 = (bf16_hi(rh[p]) + bf16_hi(rl[p])) * w[2 * p + 1];
+                hi[p] = pack2(x0, x1);
+                lo[p] = pack2(x0 - bf16_lo(hi[p]), x1 - bf16_hi(hi[p]));
+            }
+        }
+        const bf16x8 vh = __builtin_bit_cast(bf16x8, hi), vl = __builtin_bit_cast(bf16x8, lo);
+        bf16x8 ka[4];
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) ka[ib] = frag_tr(K, LD, 16 * ks, 32 * ib, lane);
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(ka[ib], vh, S[ib]);
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = mfma(ka[ib], vl, S[ib]);
+    }
+}
+
 // chunk-local decay tables by one wave: beta (inclusive running sum of the log-decays in walk order, exclusive
 // when walking backward), b_C, and the weights wo = e^{b_C - beta + extra} of the state update
 template <bool REV>
@@ -223,7 +260,7 @@ __device__ __forceinline__ void walk_state_store(const f32x16 (&S)[4], float* e,
 }
 // REV: walk backward in time.  DEC: a decay is present.  SUMMARY: the state update alone, from a zero
 // state, result to a.bound / a.gseg.
-template <bool REV, bool DEC, bool SUMMARY>
+template <bool REV, bool DEC, bool SUMMARY, bool VSPLIT = false>
 __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int seq, int seg, unsigned char* smem) {
     // LDS: SUMMARY: K | V | bs | wo;   else: Q | K | V | P head | P remainder | bs | wo
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
@@ -234,6 +271,8 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
     float* bs = reinterpret_cast<float*>(SUMMARY ? V + C * LD : Pl + C * LDP);  // beta[64], then b_C
     float* wo = bs + C + 4;                                                      // e^{b_C - beta}[64]
     uint16_t* stage = Q;
+    uint16_t* V2 = reinterpret_cast<uint16_t*>(smem + walk_lds(SUMMARY));  // VSPLIT only
+    static_assert(!VSPLIT || SUMMARY, "two value planes: summary pass only");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
     const SeqWalk walk = seq_walk(d, seq);
@@ -256,7 +295,7 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         if (ein) walk_state_load(S, ein, false, wave, n, half);
     }
 
-    TileRegs rq, rk, rv;
+    TileRegs rq, rk, rv, rv2;
     float gval = 0.f, gtot = 0.f;
     // The summary pass visits the chunks of its segment in the order opposite to the walk (a sum: each
     // chunk's weights carry the decay of the chunks that follow it in walk order), so that the walker,
@@ -271,6 +310,7 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         if (!SUMMARY) walk_gload<REV, kThreads>(rq, a.xq, p.tok0, p.ts, p.L, tid);
         walk_gload<REV, kThreads>(rk, a.xk, p.tok0, p.ts, p.L, tid);
         walk_gload<REV, kThreads>(rv, a.xv, p.tok0, p.ts, p.L, tid);
+        if (VSPLIT) walk_gload<REV, kThreads>(rv2, a.xv_lo, p.tok0, p.ts, p.L, tid);
     };
     if (cnt > 0) gload(0);
 
@@ -281,6 +321,7 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         if (!SUMMARY) walk_commit<kThreads>(Q, rq, L, tid);
         walk_commit<kThreads>(K, rk, L, tid);
         walk_commit<kThreads>(V, rv, L, tid);
+        if (VSPLIT) walk_commit<kThreads>(V2, rv2, L, tid);
         if (DEC && wave == 0) gtot += walk_decay_tables<REV>(gval, L, SUMMARY ? gtot : 0.f, bs, wo, lane);
         gload(kk + 1);
         __syncthreads();  // (A) tiles and decay tables of this chunk are in LDS
@@ -296,7 +337,8 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
                 store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
             }
         }
-        walk_update<DEC, !SUMMARY>(S, K, V, wo, bC, wave, lane, half);
+        if (VSPLIT) walk_update_vsplit<DEC, !SUMMARY>(S, K, V, V2, wo, bC, wave, lane, half);
+        else walk_update<DEC, !SUMMARY>(S, K, V, wo, bC, wave, lane, half);
         __syncthreads();  // (D) the output stage is complete and every read of this chunk's tiles is done
         // every thread reads back exactly the stage pieces that its own next walk_commit overwrites: no barrier
         if (!SUMMARY) walk_store<REV>(a.out, stage, cp.tok0, cp.ts, L, tid);
@@ -312,10 +354,10 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
 }
 
 // forward walker, or the summary pass of either direction (grid: segments x sequences)
-template <bool REV, bool DEC, bool SUMMARY>
+template <bool REV, bool DEC, bool SUMMARY, bool VSPLIT = false>
 __global__ __launch_bounds__(kThreads, 2) void mk_walk(Dims d, WalkArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    walk_body<REV, DEC, SUMMARY>(d, a, blockIdx.y, blockIdx.x, smem);
+    walk_body<REV, DEC, SUMMARY, VSPLIT>(d, a, blockIdx.y, blockIdx.x, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -350,9 +392,14 @@ struct GradArgs {
     const float* edge_in;     // M_0 [i][v] per sequence or NULL
     const float* bound;       // entry states of the segments ([i][v]) when nseg > 1
     int m, nseg;
+    const uint16_t* v_lo;     // VSPLIT: remainder plane of the values (same layout as v)
 };
+// VSPLIT (the delta-rule backward, whose values are the pseudo-values U = head + remainder): the values enter
+// every product with both planes; the value gradient is not formed (it is the caller's dU once more) and its
+// output receives the remainder of the key gradient instead (dk = head, dv = remainder).
+__host__ __device__ constexpr int walk_grad_lds(bool vsplit) { return kWalkGradLds + (vsplit ? C * LD * 2 : 0); }
 
-template <bool DEC, bool WANT_DG>
+template <bool DEC, bool WANT_DG, bool VSPLIT = false>
 __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a, int seq, int seg, unsigned char* smem) {
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = Q + C * LD;
@@ -367,6 +414,7 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
     float* wo = bs + C + 4;
     float* red = wo + C + 4;         // [wave][3][64]: q.dq, k.dk, k.dk_inter partial sums over this wave's i
     float* zred = red + 4 * 3 * 64;  // [wave]: partial <S, dS>
+    uint16_t* V2 = reinterpret_cast<uint16_t*>(smem + kWalkGradLds);  // VSPLIT only
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
     const SeqWalk walk = seq_walk(d, seq);
@@ -382,7 +430,7 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         if (ein) walk_state_load(S, ein, true, wave, n, half);
     }
 
-    TileRegs tq, tk, tv, to;
+    TileRegs tq, tk, tv, to, tv2;
     bf16x8 dsfrag[8];
     float gval = 0.f;
     auto gload = [&](int kk) {
@@ -392,6 +440,7 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         walk_gload<false, kThreads>(tk, a.k, p.tok0, p.ts, p.L, tid);
         walk_gload<false, kThreads>(tv, a.v, p.tok0, p.ts, p.L, tid);
         walk_gload<false, kThreads>(to, a.d_o, p.tok0, p.ts, p.L, tid);
+        if (VSPLIT) walk_gload<false, kThreads>(tv2, a.v_lo, p.tok0, p.ts, p.L, tid);
         // rows i in [32w, 32w+32) of dS: A operands [m = i][k = v]
         const uint16_t* dS = a.dstates + p.slot * D * D;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
@@ -406,6 +455,7 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         walk_commit<kThreads>(K, tk, L, tid);
         walk_commit<kThreads>(V, tv, L, tid);
         walk_commit<kThreads>(dO, to, L, tid);
+        if (VSPLIT) walk_commit<kThreads>(V2, tv2, L, tid);
         // the dS rows of this wave, for the waves that contract over i (dv)
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
             *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
@@ -423,6 +473,7 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
             if (gi < 3) {
                 const int pjb = gi ? 1 : 0, prb = gi == 2 ? 1 : 0;
                 f32x16 G = score_block2(V, 32 * prb, dO, 32 * pjb, n, half);  // D[m = r][n = j] = v_r . d_o_j
+                if (VSPLIT) G = score_block2(V2, 32 * prb, dO, 32 * pjb, n, half, G);
                 walk_mask<DEC>(G, 32 * prb, 32 * pjb + n, bs, half);
                 store_block_t_split(Gh, Gl, LDP, 32 * pjb + n, 32 * prb, half, G);
             }
@@ -438,6 +489,9 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
             const int tok = 32 * nb + n;
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
+            if (VSPLIT) {
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V2, LD, tok, 16 * ks + 8 * half), ak[nb]);
+            }
             if (DEC) {
                 const float wk = wo[tok];
                 _Pragma("unroll") for (int x = 0; x < 16; ++x) ak[nb][x] *= wk;
@@ -461,7 +515,7 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
             if (lane == 0) zred[wave] = z;
         }
         // ---- the state moves on to the end of the chunk (roles: key = v, value = k)
-        walk_update<DEC, true>(S, V, K, wo, bC, wave, lane, half);
+        walk_update<DEC, true, VSPLIT>(S, V, K, wo, bC, wave, lane, half, V2);
         // the next chunk's rows are requested now: the dS registers are free, the tile registers have been since (1)
         if (kk + 1 < cnt) gload(kk + 1);
         __syncthreads();  // (2) G and As are in LDS
@@ -492,10 +546,19 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
             }
             resq[nb] = pack_block(aq[nb]);
             resk[nb] = pack_block(ak[nb]);
+            if (VSPLIT) {  // the key gradient leaves as head + remainder (the caller adds to it before rounding)
+                _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                    ak[nb][4 * g + 0] -= bf16_lo(resk[nb].v[g].x);
+                    ak[nb][4 * g + 1] -= bf16_hi(resk[nb].v[g].x);
+                    ak[nb][4 * g + 2] -= bf16_lo(resk[nb].v[g].y);
+                    ak[nb][4 * g + 3] -= bf16_hi(resk[nb].v[g].y);
+                }
+                resv[nb] = pack_block(ak[nb]);
+            }
         }
         // ---- dv^T[v][r], v in this wave's slice: the inter part contracts over the rows i of dS (token-major read of
         // the dS area), the intra part over the queries
-        {
+        if (!VSPLIT) {
             f32x16 av[2] = {{0}, {0}};
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
                 const bf16x8 dst = frag_tr(dSt, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 16 ks + ..
@@ -553,10 +616,10 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
     }
 }
 
-template <bool DEC, bool WANT_DG>
+template <bool DEC, bool WANT_DG, bool VSPLIT = false>
 __global__ __launch_bounds__(kThreads, 1) void mk_walk_grad(Dims d, GradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    walk_grad_body<DEC, WANT_DG>(d, a, blockIdx.y, blockIdx.x, smem);
+    walk_grad_body<DEC, WANT_DG, VSPLIT>(d, a, blockIdx.y, blockIdx.x, smem);
 }
 
 // Entry state of every segment from the segments' own contributions (left by the summary pass in the
