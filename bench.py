@@ -200,27 +200,30 @@ def calibrate(pkg, torch, dev):
 
 
 def delta_bench(steps, warmup, check):
-    """Forward of the delta-rule rows (DeltaNet, Gated DeltaNet): 256 sequences of 2048 tokens, the shape of a training
-    batch at the paper's 2K context (one workgroup walks a sequence, so 256 sequences fill the chip), and the
-    metric's own shape (64 sequences of 8192 tokens) for what few sequences cost.  Per row: host-clock time per
-    step, HIP-event kernel averages, compulsory bytes over time, and sampled (b,h) pairs against the fp64 oracle."""
+    """Forward and backward of the delta-rule rows (DeltaNet, Gated DeltaNet): 256 sequences of 2048 tokens, the shape of
+    a training batch at the paper's 2K context (one workgroup walks a sequence, so 256 sequences fill the chip), and
+    the metric's own shape (64 sequences of 8192 tokens) for what few sequences cost.  Per row: host-clock time per
+    forward and per forward + backward step, HIP-event kernel averages, compulsory bytes over time, and sampled (b,h)
+    pairs against the fp64 oracle and its adjoint."""
     import ctypes
     import numpy as np
     import torch
     import lsm_workloads as wl
     import paper_2503_05447_amd as pkg
     dev = torch.device("cuda:0")
-    out = {"what": "lsm_delta_fwd, bf16, d_k = d_v = 128, chunk 64, forward only; keys of unit length, b = sigmoid(N(0,1)), "
-                   "DeltaNet a = b, Gated DeltaNet log a = -softplus(N(0,1) + 3)"}
+    out = {"what": "lsm_delta_fwd / lsm_delta_bwd, bf16, d_k = d_v = 128, chunk 64; keys of unit length, b = sigmoid(N(0,1)), "
+                   "DeltaNet a = b, Gated DeltaNet log a = -softplus(N(0,1) + 3); d_o ~ N(0,1)"}
     for (B, H, T) in ((16, 16, 2048), (4, 16, 8192)):
         for gated in (False, True):
             x = wl.make_delta_inputs(B, H, T, 128, 128, gated, seed=wl.BASE_SEED + 20 + int(gated) + T)
             mv = lambda a, dt: None if a is None else torch.from_numpy(a).to(dev).to(dt).contiguous()
-            q, k, v = (mv(x[n_], torch.bfloat16) for n_ in ("q", "k", "v"))
+            q, k, v, d_o = (mv(x[n_], torch.bfloat16) for n_ in ("q", "k", "v", "d_o"))
             la, be, bw = (mv(x[n_], torch.float32) for n_ in ("log_alpha", "beta", "b"))
             p = pkg.make_params(B, H, T, 128, 128, 64, pkg.DECAY_SCALAR if gated else pkg.DECAY_NONE, 1)
             ws = torch.empty(pkg.library().lsm_delta_fwd_workspace_bytes(ctypes.byref(p)), dtype=torch.uint8, device=dev)
+            wsb = torch.empty(pkg.library().lsm_delta_bwd_workspace_bytes(ctypes.byref(p)), dtype=torch.uint8, device=dev)
             step = lambda: pkg.lsm_delta_fwd(q, k, v, la, be, bw, workspace=ws)
+            bstep = lambda: pkg.lsm_delta_bwd(q, k, v, d_o, la, be, bw, workspace=wsb)
             t0 = time.perf_counter()
             while time.perf_counter() - t0 < 0.25:   # settle the clocks, as for the headline
                 for _ in range(5):
@@ -234,6 +237,16 @@ def delta_bench(steps, warmup, check):
                 o, mT = step()
             torch.cuda.synchronize()
             sec = (time.perf_counter() - t0) / steps
+            for _ in range(min(warmup, 3)):
+                step()
+                grads = bstep()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+                grads = bstep()
+            torch.cuda.synchronize()
+            sec_fb = (time.perf_counter() - t0) / steps
             pkg.lsm_profile_start()
             for _ in range(steps):
                 step()
@@ -241,17 +254,29 @@ def delta_bench(steps, warmup, check):
             per = {}
             for name, ms in pkg.lsm_profile_stop():
                 per.setdefault(name, []).append(ms)
+            pkg.lsm_profile_start()
+            for _ in range(steps):
+                bstep()
+            torch.cuda.synchronize()
+            perb = {}
+            for name, ms in pkg.lsm_profile_stop():
+                perb.setdefault(name, []).append(ms)
             th = B * H * T
-            ab = th * (4 * 256 + 4 * (2 if not gated else 2))   # q, k, v, o in bf16; two per-token parameters
+            ab = th * (4 * 256 + 4 * 2)   # q, k, v, o in bf16; two per-token parameters
+            abb = th * (7 * 256 + 4 * 4)  # backward: q, k, v, d_o read, dq, dk, dv written; parameters and their gradients
             # chunk-dense flops per token-head: scores, A U, Q S, state update (as the diagonal kinds) + K K^T,
             # T [V | K], What S
             fl = th * (2 * 64 * 256 + 2 * 2 * 128 * 128 + 2 * 64 * 128 + 2 * 64 * 256 + 2 * 128 * 128)
             e = {"B": B, "H": H, "T": T, "ms_per_step": sec * 1e3, "tokens_per_s": B * T / sec, "steps": steps,
                  "kernel_ms": {n_: float(np.mean(v_)) for n_, v_ in per.items()},
+                 "ms_per_step_fwd_bwd": sec_fb * 1e3, "tokens_per_s_fwd_bwd": B * T / sec_fb,
+                 "kernel_ms_bwd": {n_: float(np.mean(v_)) * len(v_) / steps for n_, v_ in perb.items()},
+                 "algorithmic_bytes_per_step_fwd_bwd": ab + abb,
+                 "hbm_frac_whole_step_fwd_bwd": (ab + abb) / sec_fb / 1e9 / HBM_PEAK_GBS,
                  "algorithmic_bytes_per_step": ab, "hbm_frac_whole_step": ab / sec / 1e9 / HBM_PEAK_GBS,
                  "tflops_chunk_dense": fl / sec / 1e12, "mfma_peak_frac": fl / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS}
             if check:
-                from oracle import delta_oracle_fwd
+                from oracle import delta_oracle_bwd, delta_oracle_fwd
                 pairs = [(0, 0), (B - 1, H - 1)]
                 ib, ih = [p_[0] for p_ in pairs], [p_[1] for p_ in pairs]
                 take = lambda a: None if a is None else np.ascontiguousarray(a[ib, ih][None])
@@ -264,8 +289,18 @@ def delta_bench(steps, warmup, check):
                 e["parity_err_over_rms_raw"] = {"o": rel_err(pick(o), o_ref, 0.0)}
                 e["parity_pairs"] = pairs
                 e["cpu_oracle_tokens_per_s"] = len(pairs) * T / osec
+                r_ref = delta_oracle_bwd(take(x["q"]), take(x["k"]), take(x["v"]), take(x["d_o"]), take(x["log_alpha"]),
+                                         take(x["beta"]), take(x["b"]))
+                names = dict(dq="dq", dk="dk", dv="dv", d_log_alpha="d_log_alpha", d_beta="d_beta", d_b="d_b", d_init_state="d_m0")
+                for n_, rn in names.items():
+                    if grads[n_] is None:
+                        continue
+                    stored = n_ in ("dq", "dk", "dv")
+                    e["parity_err_over_rms"][n_] = rel_err(pick(grads[n_]), r_ref[rn], BF16_HALF_ULP if stored else 0.0)
+                    if stored:
+                        e["parity_err_over_rms_raw"][n_] = rel_err(pick(grads[n_]), r_ref[rn], 0.0)
             out["%s_B%d_T%d" % ("gated_deltanet" if gated else "deltanet", B, T)] = e
-            del q, k, v, la, be, bw, ws, o, mT
+            del q, k, v, d_o, la, be, bw, ws, wsb, o, mT, grads
             torch.cuda.empty_cache()
     return out
 
@@ -305,7 +340,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     if args.delta_only:
-        print(json.dumps({"delta_rule_fwd": delta_bench(max(5, min(args.steps, 50)), min(args.warmup, 10), not args.no_check)}))
+        print(json.dumps({"delta_rule": delta_bench(max(5, min(args.steps, 50)), min(args.warmup, 10), not args.no_check)}))
         return
     saved = args.states == "saved"
     w = Workload(args.config, args.layout, saved)
@@ -519,7 +554,7 @@ def main():
     if not args.no_delta and not args.no_microbench:
         del w
         torch.cuda.empty_cache()
-        result["delta_rule_fwd"] = delta_bench(max(5, min(args.steps, 50)), min(args.warmup, 10), not args.no_check)
+        result["delta_rule"] = delta_bench(max(5, min(args.steps, 50)), min(args.warmup, 10), not args.no_check)
         w = None
 
     if not args.no_all_configs:
