@@ -156,7 +156,10 @@ int lsm_chunk_fwd_noalloc(const lsm_params* p,
  *   log_alpha, beta, b   fp32 per token, [B,H,T] ([B,T,H] with LSM_LAYOUT_BTHD); NULL = the constant 1        in
  *   workspace            at least lsm_delta_fwd_workspace_bytes(p); contents undefined after the call
  * Served for bf16 elements, d_k = d_v = 128, chunk_size 64, unpacked input (n_seq = 0); everything else returns
- * LSM_ERR_UNSUPPORTED (the workspace query then returns 0).  flags are ignored.  Keys are expected to have
+ * LSM_ERR_UNSUPPORTED (the workspace query then returns 0).  LSM_FLAG_SAVE_STATES (in the params of both calls, same
+ * contract as for lsm_chunk_fwd / lsm_chunk_bwd: same inputs, same workspace of lsm_delta_fwd_workspace_bytes(p) =
+ * lsm_delta_bwd_workspace_bytes(p) bytes, untouched in between): the forward call leaves the chunks' triangular
+ * inverses and pseudo-values in the workspace and lsm_delta_bwd does not compute them again.  Keys are expected to have
  * at most unit length times sqrt(2 / beta) (the erase factor is then a contraction); nothing is checked.
  * One workgroup walks a sequence from end to end, so the chip is full from B*H >= 256 sequences on.
  */

@@ -279,6 +279,7 @@ int lsm_step(const lsm_params* p, const void* q, const void* k, const void* v, c
 size_t lsm_delta_fwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK || !lsm::delta_supported(d)) return 0;
+    d.save = (p->flags & LSM_FLAG_SAVE_STATES) != 0;
     return lsm::delta_fwd_workspace(d);
 }
 
@@ -295,6 +296,7 @@ int lsm_delta_fwd(const lsm_params* p, const void* q, const void* k, const void*
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_alpha) || misaligned(beta) ||
         misaligned(b) || misaligned(init_state) || misaligned(final_state) || misaligned(workspace))
         return LSM_ERR_ALIGN;
+    d.save = (p->flags & LSM_FLAG_SAVE_STATES) != 0;
     if (!workspace || workspace_bytes < lsm::delta_fwd_workspace(d)) return LSM_ERR_WORKSPACE;
     const lsm::DeltaArgs a{q, k, v, log_alpha, beta, b, init_state, o, final_state, workspace, static_cast<hipStream_t>(stream)};
     return lsm::delta_fwd(d, a) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
@@ -326,6 +328,7 @@ int lsm_delta_bwd(const lsm_params* p, const void* q, const void* k, const void*
         misaligned(d_final_state) || misaligned(d_log_alpha) || misaligned(d_beta) || misaligned(d_b) ||
         misaligned(d_init_state) || misaligned(workspace))
         return LSM_ERR_ALIGN;
+    d.save = (p->flags & LSM_FLAG_SAVE_STATES) != 0;
     if (!workspace || workspace_bytes < lsm::delta_bwd_workspace(d)) return LSM_ERR_WORKSPACE;
     const lsm::DeltaBwdArgs a{q, k, v, log_alpha, beta, b, init_state, d_o, d_final_state, dq, dk, dv, d_log_alpha, d_beta, d_b,
                               d_init_state, workspace, static_cast<hipStream_t>(stream)};

@@ -999,13 +999,23 @@ hipError_t mfma_intra_bench(const Dims& d0, const FwdArgs& a, int reps) {
 
 // ---- delta-rule rows: host side
 bool delta_supported(const Dims& d) { return d.bf16 && d.C == C && d.dk == D && d.dv == D && (d.kind == 0 || d.kind == 2) && !d.nseq; }
+namespace {
+struct DeltaWs;
+DeltaWs carve_delta(const Dims& d, void* ws);
+size_t carve_delta_bytes(const Dims& d);
+}  // namespace
+// Dims::save: the forward call also leaves T^T and the pseudo-values in the workspace, laid out as the backward call
+// carves it, and the backward call does not run the prep and the walk again.
 size_t delta_fwd_workspace(const Dims& d) {
+    if (d.save) return carve_delta_bytes(d);
     return align256(size_t(d.BH()) * d.T * D * 2) + align256(size_t(d.BH()) * d.T * D * 4);
 }
 namespace {
 hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, const DeltaWalkArgs& wa, hipStream_t stream);
 }
+hipError_t delta_fwd_saving(const Dims& d, const DeltaArgs& a);
 hipError_t delta_fwd(const Dims& d, const DeltaArgs& a) {
+    if (d.save) return delta_fwd_saving(d, a);
     char* p = static_cast<char*>(a.ws);
     uint16_t* what = reinterpret_cast<uint16_t*>(p);
     float* uhat = reinterpret_cast<float*>(p + align256(size_t(d.BH()) * d.T * D * 2));
@@ -1068,8 +1078,17 @@ DeltaWs carve_delta(const Dims& d, void* ws) {
     w.bytes = off;
     return w;
 }
+size_t carve_delta_bytes(const Dims& d) { return carve_delta(d, nullptr).bytes; }
 }  // namespace
 size_t delta_bwd_workspace(const Dims& d) { return carve_delta(d, nullptr).bytes; }
+
+hipError_t delta_fwd_saving(const Dims& d, const DeltaArgs& a) {
+    const DeltaWs w = carve_delta(d, a.ws);
+    auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
+    const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, w.what, w.uhat, w.tt};
+    const DeltaWalkArgs wa{q, k, w.what, w.uhat, a.log_alpha, static_cast<uint16_t*>(a.o), a.m0, a.mT, w.usave, w.usave_l};
+    return launch_delta_fwd(d, pa, wa, a.stream);
+}
 
 hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a) {
     const DeltaWs w = carve_delta(d, a.ws);
@@ -1079,9 +1098,11 @@ hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a) {
     auto d_o = static_cast<const uint16_t*>(a.d_o);
     hipError_t e;
     // forward again: What, Uhat, T, and the pseudo-values U in the layout of v
-    const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, w.what, w.uhat, w.tt};
-    const DeltaWalkArgs wa{q, k, w.what, w.uhat, a.log_alpha, nullptr, a.m0, nullptr, w.usave, w.usave_l};
-    if ((e = launch_delta_fwd(d, pa, wa, a.stream)) != hipSuccess) return e;
+    if (!d.save) {
+        const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, w.what, w.uhat, w.tt};
+        const DeltaWalkArgs wa{q, k, w.what, w.uhat, a.log_alpha, nullptr, a.m0, nullptr, w.usave, w.usave_l};
+        if ((e = launch_delta_fwd(d, pa, wa, a.stream)) != hipSuccess) return e;
+    }
     // state gradients and dU, backward in time
     {
         const DeltaRevArgs ra{q, k, d_o, w.what, a.log_alpha, w.dstates, w.du_h, w.du_l, a.d_mT, a.d_m0};

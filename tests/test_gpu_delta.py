@@ -183,6 +183,29 @@ def test_delta_backward_correlated_keys():
     run_bwd_and_check(x)
 
 
+@pytest.mark.parametrize("gated", [False, True])
+def test_delta_backward_with_kept_forward_results_is_bitwise_the_same(gated):
+    import torch
+    import paper_2503_05447_amd as pkg
+    x = wl.make_delta_inputs(2, 3, 330, 128, 128, gated, seed=5600 + int(gated), init_state=True, d_final=True)
+    t = dev(x)
+    d = torch.device("cuda:0")
+    d_o = torch.from_numpy(x["d_o"]).to(d).to(torch.bfloat16)
+    d_mT = torch.from_numpy(x["d_mT"]).to(d)
+    args = (t["q"], t["k"], t["v"])
+    o1, m1 = pkg.lsm_delta_fwd(*args, t["log_alpha"], t["beta"], t["b"], t["m0"])
+    r1 = pkg.lsm_delta_bwd(*args, d_o, t["log_alpha"], t["beta"], t["b"], t["m0"], d_mT)
+    ws = pkg.lsm_delta_workspace(*args, t["log_alpha"])
+    o2, m2 = pkg.lsm_delta_fwd(*args, t["log_alpha"], t["beta"], t["b"], t["m0"], workspace=ws, save_states=True)
+    r2 = pkg.lsm_delta_bwd(*args, d_o, t["log_alpha"], t["beta"], t["b"], t["m0"], d_mT, workspace=ws, states_saved=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(m1, m2)
+    for n_ in r1:
+        assert (r1[n_] is None) == (r2[n_] is None)
+        if r1[n_] is not None:
+            assert torch.equal(r1[n_], r2[n_]), n_
+
+
 def test_delta_rejects_what_it_does_not_serve():
     import torch
     import paper_2503_05447_amd as pkg
