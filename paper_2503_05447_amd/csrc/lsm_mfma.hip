@@ -1119,21 +1119,9 @@ hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a) {
     // and the decay gradient of those terms from the gradient walker (its value gradient is dU once more, not wanted)
     if ((e = walk_bounds<false>(d, a.stream, sp, k, w.usave, a.log_alpha, a.m0, ww.bound_f, ww.gseg_f, 1, w.usave_l)) != hipSuccess) return e;
     GradArgs ga{q, k, w.usave, d_o, a.log_alpha, w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk),
-                static_cast<uint16_t*>(a.dv), d.kind == 0 ? nullptr : a.d_log_alpha, a.m0, ww.bound_f, sp.m, sp.nseg, w.usave_l};
-    if ((e = launch_walk_grad(d, sp, ga, a.stream)) != hipSuccess) return e;   // dk <- head, dv <- remainder of its key gradient
-    // gradient of What: one more forward walk over the same segments
-    {
-        const DeltaDwArgs da{k, w.usave, w.usave_l, w.du_h, w.du_l, a.log_alpha, w.dw_h, w.dw_l, a.m0, ww.bound_f, sp.m, sp.nseg};
-        const dim3 grid(sp.nseg, d.seqs());
-        ProfScope ps(KID_DELTA_DW, a.stream);
-        if (d.kind == 0) {
-            if ((e = allow_lds(mk_delta_dw<false>, kDeltaDwLds)) != hipSuccess) return e;
-            hipLaunchKernelGGL(mk_delta_dw<false>, grid, dim3(kThreads), kDeltaDwLds, a.stream, d, da);
-        } else {
-            if ((e = allow_lds(mk_delta_dw<true>, kDeltaDwLds)) != hipSuccess) return e;
-            hipLaunchKernelGGL(mk_delta_dw<true>, grid, dim3(kThreads), kDeltaDwLds, a.stream, d, da);
-        }
-    }
+                static_cast<uint16_t*>(a.dv), d.kind == 0 ? nullptr : a.d_log_alpha, a.m0, ww.bound_f, sp.m, sp.nseg, w.usave_l, w.du_h, w.du_l, w.dw_h, w.dw_l};
+    // dk <- head, dv <- remainder of its key gradient; it also leaves dW = -dU S^T, the gradient of What
+    if ((e = launch_walk_grad(d, sp, ga, a.stream)) != hipSuccess) return e;
     // everything that goes through the triangular solve, chunk by chunk; completes dk, dv and the parameter gradients
     {
         const DeltaGradArgs g3{k, v, w.du_h, w.du_l, w.dw_h, w.dw_l, w.tt, a.log_alpha, a.beta, a.bw,

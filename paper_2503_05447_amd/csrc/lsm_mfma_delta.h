@@ -375,7 +375,8 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
 //     dS = Gamma_C dS' + (diag(Gamma) Q)^T dO - What^T dU .
 // mk_delta_rwalk walks a sequence backward with dS in the accumulators (the forward walker's block layout), stores
 // dS' per chunk in the fragment-major bf16 form the gradient walker reads, and dU as bf16 head + remainder for the
-// kernels that take the gradient through the triangular solve.
+// kernels that take the gradient through the triangular solve.  The gradient walker, which has the state S of
+// every chunk in its accumulators, also forms dWhat = -dU S^T on the way (its VSPLIT variant).
 struct DeltaRevArgs {
     const uint16_t *q, *k, *d_o;
     const uint16_t* what;     // [BH*T][128] bf16 (library order)
@@ -533,99 +534,6 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
         __syncthreads();  // (D) every read of this chunk's tiles is done
     }
     if (a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Backward, the gradient of What: dWhat = -dU S^T per chunk (S = state the chunk starts from).  A forward walk over
-// segments with the state in the gradient walker's layout (lanes = key feature i, registers = value feature v, so
-// that contractions over v are the natural ones) and nothing else in it but the state update.
-struct DeltaDwArgs {
-    const uint16_t* k;              // layout of the caller
-    const uint16_t *u_h, *u_l;      // pseudo-values, layout of v
-    const uint16_t *du_h, *du_l;    // [BH*T][128] (library order)
-    const float* log_alpha;
-    uint16_t *dw_h, *dw_l;          // [BH*T][128] (library order): dWhat, head and remainder
-    const float* edge_in;           // M_0 or NULL
-    const float* bound;             // entry states of the segments when nseg > 1
-    int m, nseg;
-};
-// LDS: K | U head | U remainder | dU head | dU remainder (64 x LD; the last two later the stage of dWhat) | bs | wo
-constexpr int kDeltaDwLds = 5 * C * LD * 2 + (2 * C + 8) * 4;
-
-// grid: (nseg, seqs)
-template <bool DEC>
-__global__ __launch_bounds__(kThreads, 1) void mk_delta_dw(Dims d, DeltaDwArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t* K = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* Uh = K + C * LD;
-    uint16_t* Ul = Uh + C * LD;
-    uint16_t* dUh = Ul + C * LD;
-    uint16_t* dUl = dUh + C * LD;
-    float* bs = reinterpret_cast<float*>(dUl + C * LD);
-    float* wo = bs + C + 4;
-
-    const int seq = blockIdx.y, seg = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
-    const SeqWalk walk = seq_walk(d, seq);
-    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
-    if (cnt <= 0) return;
-
-    f32x16 S[4];  // S[vb][4g+j] = M[i = 32 wave + n][v = 32 vb + 8g + 4 half + j]
-    _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) S[vb] = f32x16{0};
-    {
-        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
-                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-        if (ein) walk_state_load(S, ein, true, wave, n, half);
-    }
-    TileRegs tk, tuh, tul, tdh, tdl;
-    float gval = 0.f;
-    auto gload = [&](int kk) {
-        const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
-        if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
-        walk_gload<false, kThreads>(tk, a.k, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(tuh, a.u_h, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(tul, a.u_l, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(tdh, a.du_h, p.wtok0, 1, p.L, tid);
-        walk_gload<false, kThreads>(tdl, a.du_l, p.wtok0, 1, p.L, tid);
-    };
-    gload(0);
-    for (int kk = 0; kk < cnt; ++kk) {
-        const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
-        const int L = cp.L;
-        walk_commit<kThreads>(K, tk, L, tid);
-        walk_commit<kThreads>(Uh, tuh, L, tid);
-        walk_commit<kThreads>(Ul, tul, L, tid);
-        walk_commit<kThreads>(dUh, tdh, L, tid);
-        walk_commit<kThreads>(dUl, tdl, L, tid);
-        if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
-        gload(kk + 1);
-        __syncthreads();  // (1) tiles and decay tables are in LDS
-        const float bC = DEC ? bs[C] : 0.f;
-        // dWhat^T[i][t] = -sum_v S[i][v] dU[t][v], both planes of dU
-        f32x16 a0[2], a1[2];
-        walk_inter<false>(a0, S, dUh, bs, n, half);
-        walk_inter<false>(a1, S, dUl, bs, n, half);
-        // the state moves on to the end of the chunk (roles: key = u, value = k)
-        walk_update<DEC, true, true>(S, Uh, K, wo, bC, wave, lane, half, Ul);
-        __syncthreads();  // (2) nobody reads the dU tiles any more: they become the stage
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            f32x16 w;
-            _Pragma("unroll") for (int x = 0; x < 16; ++x) w[x] = -(a0[nb][x] + a1[nb][x]);
-            const PackedBlock wh = pack_block(w);
-            _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                w[4 * g + 0] -= bf16_lo(wh.v[g].x);
-                w[4 * g + 1] -= bf16_hi(wh.v[g].x);
-                w[4 * g + 2] -= bf16_lo(wh.v[g].y);
-                w[4 * g + 3] -= bf16_hi(wh.v[g].y);
-            }
-            store_packed(dUh, LD, 32 * nb + n, 32 * wave, half, wh);
-            store_packed(dUl, LD, 32 * nb + n, 32 * wave, half, pack_block(w));
-        }
-        __syncthreads();  // (3)
-        // every thread reads back exactly the stage pieces that its own next walk_commit overwrites
-        walk_store<false>(a.dw_h, dUh, cp.wtok0, 1, L, tid);
-        walk_store<false>(a.dw_l, dUl, cp.wtok0, 1, L, tid);
-    }
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -110,10 +110,12 @@ __device__ __forceinline__ f32x16 score_block2(const uint16_t* Am, int m0, const
 
 // inter: O^T[v][j] = e^{beta_j} sum_i S[i][v] q_j[i], the state blocks as A operands straight from the
 // accumulators (bf16 head + remainder), the query rows read in the matching k order
-template <bool DEC>
+template <bool DEC, bool ACC = false>
 __device__ __forceinline__ void walk_inter(f32x16 (&O)[2], const f32x16 (&S)[4], const uint16_t* Q, const float* bs, int n, int half) {
-    O[0] = f32x16{0};
-    O[1] = f32x16{0};
+    if (!ACC) {
+        O[0] = f32x16{0};
+        O[1] = f32x16{0};
+    }
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
         _Pragma("unroll") for (int p = 0; p < 2; ++p) {
             u32x4 hi, lo;
@@ -393,10 +395,16 @@ struct GradArgs {
     const float* bound;       // entry states of the segments ([i][v]) when nseg > 1
     int m, nseg;
     const uint16_t* v_lo;     // VSPLIT: remainder plane of the values (same layout as v)
+    // VSPLIT: dU (head, remainder; [BH*T][128] in the library's own order) and the product dW = -dU S^T of every chunk with
+    // the state it starts from (head, remainder, same order)
+    const uint16_t *du_h, *du_l;
+    uint16_t *dw_h, *dw_l;
 };
 // VSPLIT (the delta-rule backward, whose values are the pseudo-values U = head + remainder): the values enter
 // every product with both planes; the value gradient is not formed (it is the caller's dU once more) and its
-// output receives the remainder of the key gradient instead (dk = head, dv = remainder).
+// output receives the remainder of the key gradient instead (dk = head, dv = remainder).  The area of the dS rows,
+// which only the value gradient reads, holds the two planes of dU instead, and the walker also leaves
+// dW = -dU S^T (the gradient of the delta rule's What), staged through the d_o tile and the second value tile.
 __host__ __device__ constexpr int walk_grad_lds(bool vsplit) { return kWalkGradLds + (vsplit ? C * LD * 2 : 0); }
 
 template <bool DEC, bool WANT_DG, bool VSPLIT = false>
@@ -430,8 +438,10 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         if (ein) walk_state_load(S, ein, true, wave, n, half);
     }
 
-    TileRegs tq, tk, tv, to, tv2;
+    TileRegs tq, tk, tv, to, tv2, tdh, tdl;
     bf16x8 dsfrag[8];
+    uint16_t* dUh = dSt;             // VSPLIT: 64 x LD each, over the dS rows
+    uint16_t* dUl = dSt + C * LD;
     float gval = 0.f;
     auto gload = [&](int kk) {
         const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
@@ -440,7 +450,11 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         walk_gload<false, kThreads>(tk, a.k, p.tok0, p.ts, p.L, tid);
         walk_gload<false, kThreads>(tv, a.v, p.tok0, p.ts, p.L, tid);
         walk_gload<false, kThreads>(to, a.d_o, p.tok0, p.ts, p.L, tid);
-        if (VSPLIT) walk_gload<false, kThreads>(tv2, a.v_lo, p.tok0, p.ts, p.L, tid);
+        if (VSPLIT) {
+            walk_gload<false, kThreads>(tv2, a.v_lo, p.tok0, p.ts, p.L, tid);
+            walk_gload<false, kThreads>(tdh, a.du_h, p.wtok0, 1, p.L, tid);
+            walk_gload<false, kThreads>(tdl, a.du_l, p.wtok0, 1, p.L, tid);
+        }
         // rows i in [32w, 32w+32) of dS: A operands [m = i][k = v]
         const uint16_t* dS = a.dstates + p.slot * D * D;
         _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
@@ -455,10 +469,15 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         walk_commit<kThreads>(K, tk, L, tid);
         walk_commit<kThreads>(V, tv, L, tid);
         walk_commit<kThreads>(dO, to, L, tid);
-        if (VSPLIT) walk_commit<kThreads>(V2, tv2, L, tid);
-        // the dS rows of this wave, for the waves that contract over i (dv)
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-            *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
+        if (VSPLIT) {
+            walk_commit<kThreads>(V2, tv2, L, tid);
+            walk_commit<kThreads>(dUh, tdh, L, tid);
+            walk_commit<kThreads>(dUl, tdl, L, tid);
+        } else {
+            // the dS rows of this wave, for the waves that contract over i (dv)
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
+        }
         if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
         __syncthreads();  // (1) tiles, dS rows and decay tables of this chunk are in LDS
         const float bC = DEC ? bs[C] : 0.f;
@@ -486,6 +505,23 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
         }
         // ---- inter parts: dq^T[i][j] from the state in registers, dk^T[i][r] from the dS rows
         walk_inter<DEC>(aq, S, dO, bs, n, half);
+        PackedBlock resw[2], reswl[2];
+        if (VSPLIT) {  // dW^T[i][t] = -sum_v S[i][v] dU[t][v]
+            f32x16 dw[2];
+            walk_inter<false>(dw, S, dUh, bs, n, half);
+            walk_inter<false, true>(dw, S, dUl, bs, n, half);
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                _Pragma("unroll") for (int x = 0; x < 16; ++x) dw[nb][x] = -dw[nb][x];
+                resw[nb] = pack_block(dw[nb]);
+                _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                    dw[nb][4 * g + 0] -= bf16_lo(resw[nb].v[g].x);
+                    dw[nb][4 * g + 1] -= bf16_hi(resw[nb].v[g].x);
+                    dw[nb][4 * g + 2] -= bf16_lo(resw[nb].v[g].y);
+                    dw[nb][4 * g + 3] -= bf16_hi(resw[nb].v[g].y);
+                }
+                reswl[nb] = pack_block(dw[nb]);
+            }
+        }
         _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
             const int tok = 32 * nb + n;
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
@@ -585,12 +621,20 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
             store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
             store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
             store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
+            if (VSPLIT) {
+                store_packed(dO, LD, 32 * nb + n, 32 * wave, half, resw[nb]);
+                store_packed(V2, LD, 32 * nb + n, 32 * wave, half, reswl[nb]);
+            }
         }
         __syncthreads();  // (4)
         // every thread reads back exactly the stage pieces that its own next walk_commit overwrites
         walk_store<false>(a.dq, Q, cp.tok0, cp.ts, L, tid);
         walk_store<false>(a.dk, K, cp.tok0, cp.ts, L, tid);
         walk_store<false>(a.dv, V, cp.tok0, cp.ts, L, tid);
+        if (VSPLIT) {
+            walk_store<false>(a.dw_h, dO, cp.wtok0, 1, L, tid);
+            walk_store<false>(a.dw_l, V2, cp.wtok0, 1, L, tid);
+        }
         if (WANT_DG && tid < 64) {
             // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
             float w = 0.f, tail = 0.f, z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
