@@ -1127,7 +1127,8 @@ hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a) {
         const DeltaGradArgs g3{k, v, w.du_h, w.du_l, w.dw_h, w.dw_l, w.tt, a.log_alpha, a.beta, a.bw,
                                static_cast<const uint16_t*>(a.dk), static_cast<const uint16_t*>(a.dv),
                                static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv), a.d_log_alpha, a.d_beta, a.d_bw};
-        const dim3 grid(d.N, d.BH());
+        const int jobs = d.N * d.BH();
+        const dim3 grid(jobs < 256 ? jobs : 256);
         ProfScope ps(KID_DELTA_GRAD, a.stream);
         if (d.kind == 0) {
             if ((e = allow_lds(mk_delta_grad<false>, kDeltaGradLds)) != hipSuccess) return e;

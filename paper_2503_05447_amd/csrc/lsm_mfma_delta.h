@@ -562,7 +562,7 @@ struct DeltaGradArgs {
 constexpr int kDeltaGradRed = (4 * C + 4 * 2 * C + 3 * C + 3 * C) * 4;  // params | db, c per wave | row sums | column sums
 constexpr int kDeltaGradLds = 6 * C * LD * 2 + 4 * C * LDP * 2 + kDeltaGradRed;
 
-// grid: (N, BH)
+// grid: up to one workgroup per compute unit; each takes chunks blockIdx.x, blockIdx.x + gridDim.x, ...
 template <bool DEC>
 __global__ __launch_bounds__(kThreads, 1) void mk_delta_grad(Dims d, DeltaGradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -593,37 +593,66 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_grad(Dims d, DeltaGradAr
     uint16_t* stk = stv + C * LD;    // stage of dk
     static_assert(4 * C * LDP + 2 * C * LD <= 5 * C * LD, "second phase fits behind K");
 
-    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
-    const ChunkPos cp = chunk_pos(d, c, bh);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int jobs = d.N * d.BH();
+    // One workgroup per compute unit walks over chunks; the rows of the next chunk are requested into registers while
+    // this one is worked on (the kernel needs most of the unit's LDS, so no second workgroup hides the loads).
+    struct Pre { TileRegs k, v, uh, ul, wh, wl; u32x4 tt[4]; float la, be, bw; } pre;
+    auto gload = [&](int job) {
+        const ChunkPos p = chunk_pos(d, job % d.N, job / d.N);
+        const int Lp = max(p.L, 1);
+        const size_t pt = p.tok0 + size_t(min(lane, Lp - 1)) * p.ts;
+        pre.la = DEC ? a.log_alpha[pt] : 0.f;
+        pre.be = a.beta ? a.beta[pt] : 1.f;
+        pre.bw = a.bw ? a.bw[pt] : 1.f;
+        tile_gload(pre.k, a.k, p.tok0, p.ts, Lp, tid);
+        tile_gload(pre.v, a.v, p.tok0, p.ts, Lp, tid);
+        tile_gload(pre.uh, a.du_h, p.wtok0, 1, Lp, tid);
+        tile_gload(pre.ul, a.du_l, p.wtok0, 1, Lp, tid);
+        tile_gload(pre.wh, a.dw_h, p.wtok0, 1, Lp, tid);
+        tile_gload(pre.wl, a.dw_l, p.wtok0, 1, Lp, tid);
+        const uint16_t* gtt = a.tt + p.slot * 2 * C * C;
+        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+            const int q = tid + kThreads * it, plane = q >> 9, row = (q >> 3) & 63, piece = q & 7;
+            pre.tt[it] = *reinterpret_cast<const u32x4*>(gtt + plane * C * C + row * C + 8 * piece);
+        }
+    };
+    if (int(blockIdx.x) < jobs) gload(blockIdx.x);
+  for (int job = blockIdx.x; job < jobs; job += gridDim.x) {
+    const ChunkPos cp = chunk_pos(d, job % d.N, job / d.N);
     const int L = cp.L;
-    if (L <= 0) return;
-    const size_t ptok = cp.tok0 + size_t(min(lane, L - 1)) * cp.ts;
+    const size_t ptok = cp.tok0 + size_t(min(lane, max(L, 1) - 1)) * cp.ts;
     if (wave == 0) {
-        float x = (DEC && lane < L) ? a.log_alpha[ptok] : 0.f;
-        const float bet = a.beta ? a.beta[ptok] : 1.f, bwt = a.bw ? a.bw[ptok] : 1.f;
+        float x = (DEC && lane < L) ? pre.la : 0.f;
         for (int off = 1; off < 64; off <<= 1) {
             const float y = __shfl_up(x, off, 64);
             if (lane >= off) x += y;
         }
         lg[lane] = x;
-        be[lane] = lane < L ? bet : 0.f;
-        bb[lane] = lane < L ? bwt : 0.f;
+        be[lane] = lane < L ? pre.be : 0.f;
+        bb[lane] = lane < L ? pre.bw : 0.f;
         gm[lane] = DEC ? __expf(x) : 1.f;
     }
-    load_tile(K, a.k, cp.tok0, cp.ts, L, tid);
-    load_tile(V, a.v, cp.tok0, cp.ts, L, tid);
-    load_tile(dUh, a.du_h, cp.wtok0, 1, L, tid);
-    load_tile(dUl, a.du_l, cp.wtok0, 1, L, tid);
-    load_tile(dWh, a.dw_h, cp.wtok0, 1, L, tid);
-    load_tile(dWl, a.dw_l, cp.wtok0, 1, L, tid);
-    {
-        const uint16_t* gtt = a.tt + cp.slot * 2 * C * C;
-        _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-            const int p = tid + kThreads * it, plane = p >> 9, row = (p >> 3) & 63, piece = p & 7;
-            *reinterpret_cast<u32x4*>((plane ? TTl : TTh) + row * LDP + 8 * piece) =
-                *reinterpret_cast<const u32x4*>(gtt + plane * C * C + row * C + 8 * piece);
+    tile_commit(K, pre.k, L, tid);
+    tile_commit(V, pre.v, L, tid);
+    tile_commit(dUh, pre.uh, L, tid);
+    tile_commit(dUl, pre.ul, L, tid);
+    tile_commit(dWh, pre.wh, L, tid);
+    tile_commit(dWl, pre.wl, L, tid);
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
+        const int q = tid + kThreads * it, plane = q >> 9, row = (q >> 3) & 63, piece = q & 7;
+        *reinterpret_cast<u32x4*>((plane ? TTl : TTh) + row * LDP + 8 * piece) = pre.tt[it];
+    }
+    // the gradient walker's key gradient of this chunk (both planes), wanted at the very end
+    u32x2 k1h[2][4], k1l[2][4];
+    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+        const size_t row = (cp.tok0 + size_t(min(32 * nb + n, max(L, 1) - 1)) * cp.ts) * D + 32 * wave + 4 * half;
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            k1h[nb][g] = *reinterpret_cast<const u32x2*>(a.dk1_h + row + 8 * g);
+            k1l[nb][g] = *reinterpret_cast<const u32x2*>(a.dk1_l + row + 8 * g);
         }
     }
+    if (job + int(gridDim.x) < jobs) gload(job + gridDim.x);
     __syncthreads();
 
     // ---- first phase
@@ -768,9 +797,8 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_grad(Dims d, DeltaGradAr
             }
         }
         const int t = 32 * nb + n;
-        const size_t row = (cp.tok0 + size_t(min(t, L - 1)) * cp.ts) * D + 32 * wave + 4 * half;
         _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-            const u32x2 h = *reinterpret_cast<const u32x2*>(a.dk1_h + row + 8 * g), l = *reinterpret_cast<const u32x2*>(a.dk1_l + row + 8 * g);
+            const u32x2 h = k1h[nb][g], l = k1l[nb][g];
             acc[4 * g + 0] += bf16_lo(h.x) + bf16_lo(l.x);
             acc[4 * g + 1] += bf16_hi(h.x) + bf16_hi(l.x);
             acc[4 * g + 2] += bf16_lo(h.y) + bf16_lo(l.y);
@@ -803,4 +831,6 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_grad(Dims d, DeltaGradAr
             if (t < L) a.d_log_alpha[ptok] += sfx;
         }
     }
+    __syncthreads();  // the stages and the reductions are read; the next chunk may overwrite them
+  }
 }
