@@ -153,3 +153,42 @@ def test_saved_state_flags_and_workspace_sizes():
     assert fwd(P(flags=2)) == ERR_UNSUP          # "always" without the flag it qualifies
     assert fwd(P(flags=4)) == ERR_UNSUP
     assert bwd(P(flags=8)) == ERR_UNSUP
+
+
+def test_delta_rule_entry_points_reject_bad_arguments_before_any_launch():
+    ERR_NULL, ERR_UNSUP, ERR_ALIGN, ERR_WS = -1, -3, -4, -5
+    vp = ctypes.c_void_p
+    lib = pkg.library()
+
+    def dfwd(p, q=0x1000, k=0x2000, v=0x3000, la=None, be=0x4000, b=0x4100, m0=None, o=0x5000, mT=None, ws=0x10000, wsb=1 << 40):
+        return lib.lsm_delta_fwd(ctypes.byref(p), vp(q), vp(k), vp(v), vp(la), vp(be), vp(b), vp(m0), vp(o), vp(mT), vp(ws), wsb,
+                                 vp(None))
+
+    def dbwd(p, la=None, be=0x4000, b=0x4100, dla=None, dbe=0xb000, db=0xc000, d_o=0x6000, dq=0x7000, ws=0x10000, wsb=1 << 40):
+        return lib.lsm_delta_bwd(ctypes.byref(p), vp(0x1000), vp(0x2000), vp(0x3000), vp(la), vp(be), vp(b), vp(None), vp(d_o),
+                                 vp(None), vp(dq), vp(0x8000), vp(0x9000), vp(dla), vp(dbe), vp(db), vp(None), vp(ws), wsb, vp(None))
+
+    ok = P(d_k=128, d_v=128, decay_kind=0)
+    gated = P(d_k=128, d_v=128, decay_kind=2)
+    need_f, need_b = lib.lsm_delta_fwd_workspace_bytes(ctypes.byref(ok)), lib.lsm_delta_bwd_workspace_bytes(ctypes.byref(ok))
+    assert 0 < need_f < need_b
+    keep = P(d_k=128, d_v=128, decay_kind=0, flags=pkg.FLAG_SAVE_STATES)   # one buffer serves both calls
+    assert lib.lsm_delta_fwd_workspace_bytes(ctypes.byref(keep)) == lib.lsm_delta_bwd_workspace_bytes(ctypes.byref(keep)) == need_b
+    # shapes the rows are not served for: the size query says 0 and the calls say unsupported
+    for bad in (P(d_k=64, d_v=64, decay_kind=0), P(d_k=128, d_v=128, decay_kind=0, dtype=0), P(d_k=128, d_v=128, decay_kind=0, chunk_size=32),
+                P(d_k=128, d_v=256, decay_kind=0)):
+        assert lib.lsm_delta_fwd_workspace_bytes(ctypes.byref(bad)) == 0
+        assert dfwd(bad) == ERR_UNSUP and dbwd(bad) == ERR_UNSUP
+    assert dfwd(P(d_k=128, d_v=128, decay_kind=1), la=0x4200) == ERR_UNSUP      # per-head and vector decays: not these rows
+    assert dfwd(P(d_k=128, d_v=128, decay_kind=3), la=0x4200) == ERR_UNSUP
+    assert dfwd(ok, q=None) == ERR_NULL and dfwd(ok, o=None) == ERR_NULL
+    assert dfwd(ok, la=0x4200) == ERR_NULL          # a decay without decay_kind scalar
+    assert dfwd(gated) == ERR_NULL                  # decay_kind scalar without a decay
+    assert dfwd(ok, be=0x4004) == ERR_ALIGN
+    assert dfwd(ok, ws=None) == ERR_WS and dfwd(ok, wsb=need_f - 1) == ERR_WS
+    # backward: a gradient exactly where a parameter was given
+    assert dbwd(ok, dbe=None) == ERR_NULL and dbwd(ok, be=None) == ERR_NULL
+    assert dbwd(ok, dla=0xd000) == ERR_NULL
+    assert dbwd(gated, la=0x4200) == ERR_NULL       # d_log_alpha missing
+    assert dbwd(ok, d_o=None) == ERR_NULL and dbwd(ok, dq=None) == ERR_NULL
+    assert dbwd(ok, wsb=need_b - 1) == ERR_WS

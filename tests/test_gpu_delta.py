@@ -206,6 +206,44 @@ def test_delta_backward_with_kept_forward_results_is_bitwise_the_same(gated):
             assert torch.equal(r1[n_], r2[n_]), n_
 
 
+@pytest.mark.parametrize("T", [1, 63, 65, 128])
+def test_delta_tiny_and_boundary_lengths(T):
+    for gated in (False, True):
+        x = wl.make_delta_inputs(1, 1, T, 128, 128, gated, seed=5700 + T, init_state=True, d_final=True)
+        run_and_check(x)
+        run_bwd_and_check(x)
+
+
+def test_delta_degenerate_strengths():
+    """Erase strength 0 (nothing erased), 1 (full erase, the Gated row's own setting) and a write strength of 0 for
+    half of the tokens (those tokens only erase)."""
+    rng = np.random.default_rng(5800)
+    for beta_val in (0.0, 1.0):
+        x = wl.make_delta_inputs(1, 2, 260, 128, 128, False, seed=5801, init_state=True, d_final=True, tie_b=False)
+        x["beta"] = np.full((1, 2, 260), beta_val, np.float32)
+        x["b"] = (x["b"] * (rng.random((1, 2, 260)) < 0.5)).astype(np.float32)
+        run_and_check(x)
+        run_bwd_and_check(x)
+
+
+def test_delta_unit_key_returns_its_value_on_the_gpu():
+    """The stored-value property through the kernels: a = b = 1, keys of unit length, the query equal to the key:
+    o_t = (k_t . k_t) v_t, i.e. v_t up to the bf16 rounding of the key's length (2^-8) and of o."""
+    import torch
+    import paper_2503_05447_amd as pkg
+    x = wl.make_delta_inputs(1, 2, 200, 128, 128, False, seed=5900, init_state=True)
+    x["beta"] = np.ones((1, 2, 200), np.float32)
+    x["b"] = np.ones((1, 2, 200), np.float32)
+    x["q"] = x["k"].copy()
+    t = dev(x)
+    o, _ = pkg.lsm_delta_fwd(t["q"], t["k"], t["v"], None, t["beta"], t["b"], t["m0"])
+    torch.cuda.synchronize()
+    kk = (x["k"].astype(np.float64) ** 2).sum(-1, keepdims=True)
+    # k M_t = v_t + (1 - k.k) (k M_{t-1} - v_t): exact only for an exactly unit key; allow the first-order term
+    assert rel_err(host(o), x["v"].astype(np.float64), 2.0 ** -8 + 4 * np.abs(1 - kk).max()) <= 1e-2
+    run_and_check(x)
+
+
 def test_delta_rejects_what_it_does_not_serve():
     import torch
     import paper_2503_05447_amd as pkg
