@@ -71,3 +71,41 @@ def test_decode_steps_replayed_from_a_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(o_g, o_e) and torch.equal(st_g, st_e), rep
+
+
+@pytest.mark.parametrize("keep", [False, True])
+@pytest.mark.parametrize("gated", [False, True])
+def test_delta_rule_forward_backward_replayed_from_a_graph(gated, keep):
+    import numpy as np
+    import torch
+    import paper_2503_05447_amd as pkg
+    x = wl.make_delta_inputs(2, 2, 200, 128, 128, gated, seed=995 + int(gated), init_state=True, d_final=True)
+    dev = torch.device("cuda:0")
+    mv = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt).contiguous()
+    q, k, v, d_o = (mv(x[n], torch.bfloat16) for n in ("q", "k", "v", "d_o"))
+    la, be, bw, m0, d_mT = (mv(x[n], torch.float32) for n in ("log_alpha", "beta", "b", "m0", "d_mT"))
+    ws = pkg.lsm_delta_workspace(q, k, v, la)
+    run = lambda: (pkg.lsm_delta_fwd(q, k, v, la, be, bw, m0, workspace=ws, save_states=keep),
+                   pkg.lsm_delta_bwd(q, k, v, d_o, la, be, bw, m0, d_mT, workspace=ws, states_saved=keep))
+    names = [n for n in ("dq", "dk", "dv", "d_log_alpha", "d_beta", "d_b", "d_init_state")]
+    (o_e, m_e), r_e = run()
+    torch.cuda.synchronize()
+    eager = [o_e.clone(), m_e.clone()] + [r_e[n].clone() for n in names if r_e[n] is not None]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()   # warm-up on the capture stream (function attributes are set outside the capture)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        (o_g, m_g), r_g = run()
+    outs = [o_g, m_g] + [r_g[n] for n in names if r_g[n] is not None]
+    for rep in range(3):
+        for buf in outs:
+            buf.fill_(0)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outs, eager):
+            assert torch.equal(got, ref), rep
+        (q.float() @ k.float().transpose(-1, -2)).sum().item()   # unrelated eager work in between
