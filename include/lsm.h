@@ -172,6 +172,19 @@ int lsm_delta_fwd(const lsm_params* p,
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * One recurrent step of the delta-rule rows (decoding), for every (b,h):
+ *     state <- alpha (I - beta k^T k) state + b k^T v ,      o = q state .
+ *   q, k [B,H,d_k], v, o [B,H,d_v] in dtype; log_alpha, beta, b: [B,H] fp32 or NULL (= 1; log_alpha exactly when
+ *   decay_kind is LSM_DECAY_SCALAR); state [B,H,d_k,d_v] fp32, updated in place.
+ * Both element types, d_k and d_v in {64,128,256}; p->T and p->chunk_size are not used (pass T = 1).  No workspace.
+ * T calls from init_state give the o and final_state of lsm_delta_fwd over the same T tokens, up to rounding.
+ */
+int lsm_delta_step(const lsm_params* p,
+                   const void* q, const void* k, const void* v,
+                   const float* log_alpha, const float* beta, const float* b,
+                   float* state, void* o, void* stream);
+
+/*
  * Backward of lsm_delta_fwd for  L = <o, d_o> + <M_T, d_final_state>  (the adjoint of the recurrence above,
  * evaluated chunkwise; nothing saved by the forward call is needed).
  *   q, k, v, log_alpha, beta, b, init_state   as in lsm_delta_fwd                                   in

@@ -83,6 +83,8 @@ def library():
     lib.lsm_delta_fwd.argtypes = [pp] + [vp] * 10 + [sz, vp]
     lib.lsm_delta_fwd_workspace_bytes.restype = sz
     lib.lsm_delta_fwd_workspace_bytes.argtypes = [pp]
+    lib.lsm_delta_step.restype = ctypes.c_int
+    lib.lsm_delta_step.argtypes = [pp] + [vp] * 9
     lib.lsm_delta_bwd.restype = ctypes.c_int
     lib.lsm_delta_bwd.argtypes = [pp] + [vp] * 17 + [sz, vp]
     lib.lsm_delta_bwd_workspace_bytes.restype = sz
@@ -245,6 +247,35 @@ def lsm_chunk_fwd(q, k, v, log_decay, decay_kind, chunk_size=64, init_state=None
     if rc != 0:
         raise LsmError(rc, "lsm_chunk_fwd")
     return o, final
+
+
+def lsm_delta_step(q, k, v, state, log_alpha=None, beta=None, b=None, o=None, stream=None):
+    """One recurrent step of the delta-rule rows: ``state`` [B,H,d_k,d_v] fp32 is updated in place, returns o [B,H,d_v].
+    q, k [B,H,d_k], v [B,H,d_v]; log_alpha, beta, b: [B,H] float32 or None (= 1)."""
+    import torch
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    dt = DTYPE_F32 if q.dtype == torch.float32 else DTYPE_BF16
+    if q.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("q must be float32 or bfloat16")
+    _check(k, (B, H, dk), q.dtype, "k")
+    _check(v, (B, H, dv), q.dtype, "v")
+    for name, t_ in (("log_alpha", log_alpha), ("beta", beta), ("b", b)):
+        _check(t_, (B, H), torch.float32, name)
+    _check(state, (B, H, dk, dv), torch.float32, "state")
+    if state is None:
+        raise ValueError("state is required")
+    if o is None:
+        with _alloc_on(stream):
+            o = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
+    else:
+        _check(o, (B, H, dv), q.dtype, "o")
+    p = make_params(B, H, 1, dk, dv, 64, DECAY_NONE if log_alpha is None else DECAY_SCALAR, dt)
+    rc = library().lsm_delta_step(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(b), _ptr(state),
+                                  _ptr(o), _stream_handle(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_delta_step")
+    return o
 
 
 def lsm_delta_workspace(q, k, v, log_alpha=None, layout=LAYOUT_BHTD):

@@ -276,6 +276,22 @@ int lsm_step(const lsm_params* p, const void* q, const void* k, const void* v, c
                                                                                                     : LSM_ERR_LAUNCH;
 }
 
+int lsm_delta_step(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_alpha, const float* beta,
+                   const float* b, float* state, void* o, void* stream) {
+    lsm::Dims d{};
+    const int rc = check_params(p, &d);
+    if (rc != LSM_OK) return rc;
+    if (!q || !k || !v || !o || !state) return LSM_ERR_NULL;
+    if (d.kind != LSM_DECAY_NONE && d.kind != LSM_DECAY_SCALAR) return LSM_ERR_UNSUPPORTED;
+    if ((d.kind == LSM_DECAY_NONE) != (log_alpha == nullptr)) return LSM_ERR_NULL;
+    if (d.nseq) return LSM_ERR_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(log_alpha) || misaligned(beta) ||
+        misaligned(b) || misaligned(state))
+        return LSM_ERR_ALIGN;
+    return lsm::delta_step(d, q, k, v, log_alpha, beta, b, state, o, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LSM_OK : LSM_ERR_LAUNCH;
+}
+
 size_t lsm_delta_fwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK || !lsm::delta_supported(d)) return 0;

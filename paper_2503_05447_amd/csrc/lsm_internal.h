@@ -156,4 +156,8 @@ hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a);
 hipError_t step(const Dims& d, const void* q, const void* k, const void* v, const float* g, float* state, void* o,
                 hipStream_t stream);
 
+// the same for the delta-rule rows; log_alpha, beta, bw: [B,H] or NULL (= 1)
+hipError_t delta_step(const Dims& d, const void* q, const void* k, const void* v, const float* log_alpha, const float* beta,
+                      const float* bw, float* state, void* o, hipStream_t stream);
+
 }  // namespace lsm

@@ -72,3 +72,54 @@ def test_steps_equal_chunked_forward(kind):
     o_step = torch.stack(outs, 2)
     assert rel_err(host(o_chunk), host(o_step), 2.0 ** -7) <= TOL["bf16"]
     assert rel_err(host(mT), host(state)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 64, 64), (1, 2, 128, 128), (2, 2, 128, 256), (1, 1, 256, 64)])
+def test_delta_rule_steps_match_oracle_token_by_token(shape, dtype, gated):
+    """lsm_delta_step against the delta-rule oracle called with T = 1 from its own running state; all three per-token
+    parameters present in the gated case."""
+    import torch
+    import paper_2503_05447_amd as pkg
+    from oracle import delta_oracle_fwd
+    B, H, dk, dv = shape
+    T = 6
+    x = wl.make_delta_inputs(B, H, T, dk, dv, gated, dtype=dtype, seed=860 + int(gated), init_state=True, tie_b=False)
+    if gated:
+        x["beta"] = (0.2 + 0.7 * np.random.default_rng(3).random((B, H, T))).astype(np.float32)
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    state = torch.from_numpy(x["m0"]).to(dev)
+    ref_state = x["m0"].astype(np.float64)
+    for t in range(T):
+        cut = lambda a: None if a is None else np.ascontiguousarray(a[:, :, t])
+        q, k, v = (torch.from_numpy(cut(x[n])).to(dev).to(tdt) for n in ("q", "k", "v"))
+        par = lambda n: None if x[n] is None else torch.from_numpy(cut(x[n])).to(dev)
+        o = pkg.lsm_delta_step(q, k, v, state, par("log_alpha"), par("beta"), par("b"))
+        torch.cuda.synchronize()
+        sl = lambda a: None if a is None else a[:, :, t:t + 1]
+        o_ref, ref_state = delta_oracle_fwd(sl(x["q"]), sl(x["k"]), sl(x["v"]), sl(x["log_alpha"]), sl(x["beta"]), sl(x["b"]),
+                                            ref_state.astype(np.float32))
+        ulp = BF16_HALF_ULP if dtype == "bf16" else 0.0
+        assert rel_err(host(o), o_ref[:, :, 0], ulp) <= TOL[dtype], ("o", t)
+        assert rel_err(host(state), ref_state) <= 1e-5, ("state", t)
+        ref_state = host(state)   # both sides go on from the same fp32 state
+
+
+def test_delta_rule_steps_equal_the_chunkwise_forward():
+    import torch
+    import paper_2503_05447_amd as pkg
+    x = wl.make_delta_inputs(1, 2, 70, 128, 128, True, seed=870, init_state=True)
+    dev = torch.device("cuda:0")
+    mv = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt).contiguous()
+    q, k, v = (mv(x[n], torch.bfloat16) for n in ("q", "k", "v"))
+    la, bw, m0 = (mv(x[n], torch.float32) for n in ("log_alpha", "b", "m0"))
+    o_c, m_c = pkg.lsm_delta_fwd(q, k, v, la, None, bw, m0)
+    state = m0.clone()
+    outs = [pkg.lsm_delta_step(q[:, :, t].contiguous(), k[:, :, t].contiguous(), v[:, :, t].contiguous(), state,
+                               la[:, :, t].contiguous(), None, bw[:, :, t].contiguous()) for t in range(70)]
+    torch.cuda.synchronize()
+    o_s = torch.stack(outs, dim=2)
+    assert rel_err(host(o_s), host(o_c)) <= 2e-2
+    assert rel_err(host(state), host(m_c)) <= 2e-3
