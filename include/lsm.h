@@ -155,8 +155,8 @@ int lsm_chunk_fwd_noalloc(const lsm_params* p,
  *   q, k, v, init_state, o, final_state   as in lsm_chunk_fwd (both layouts)
  *   log_alpha, beta, b   fp32 per token, [B,H,T] ([B,T,H] with LSM_LAYOUT_BTHD); NULL = the constant 1        in
  *   workspace            at least lsm_delta_fwd_workspace_bytes(p); contents undefined after the call
- * Served for bf16 elements, d_k = d_v = 128, chunk_size 64, unpacked input (n_seq = 0); everything else returns
- * LSM_ERR_UNSUPPORTED (the workspace query then returns 0).  LSM_FLAG_SAVE_STATES (in the params of both calls, same
+ * Served for bf16 elements, d_k = d_v = 128, chunk_size 64 (packed variable-length input included, as for
+ * lsm_chunk_fwd); everything else returns LSM_ERR_UNSUPPORTED (the workspace query then returns 0).  LSM_FLAG_SAVE_STATES (in the params of both calls, same
  * contract as for lsm_chunk_fwd / lsm_chunk_bwd: same inputs, same workspace of lsm_delta_fwd_workspace_bytes(p) =
  * lsm_delta_bwd_workspace_bytes(p) bytes, untouched in between): the forward call leaves the chunks' triangular
  * inverses and pseudo-values in the workspace and lsm_delta_bwd does not compute them again.  Keys are expected to have

@@ -278,12 +278,12 @@ def lsm_delta_step(q, k, v, state, log_alpha=None, beta=None, b=None, o=None, st
     return o
 
 
-def lsm_delta_workspace(q, k, v, log_alpha=None, layout=LAYOUT_BHTD):
+def lsm_delta_workspace(q, k, v, log_alpha=None, layout=LAYOUT_BHTD, cu_seqlens=None):
     """A workspace tensor that serves lsm_delta_fwd(..., save_states=True) and the lsm_delta_bwd(..., states_saved=True)
     that follows it on the same inputs."""
     import torch
     kind = DECAY_NONE if log_alpha is None else DECAY_SCALAR
-    p, _, _ = _setup(q, k, v, log_alpha, kind, 64, layout, None, FLAG_SAVE_STATES)
+    p, _, _ = _setup(q, k, v, log_alpha, kind, 64, layout, cu_seqlens, FLAG_SAVE_STATES)
     need = library().lsm_delta_bwd_workspace_bytes(ctypes.byref(p))
     if need == 0:
         raise LsmError(-3, "lsm_delta_workspace")
@@ -291,21 +291,22 @@ def lsm_delta_workspace(q, k, v, log_alpha=None, layout=LAYOUT_BHTD):
 
 
 def lsm_delta_fwd(q, k, v, log_alpha=None, beta=None, b=None, init_state=None, want_final_state=True, workspace=None,
-                  stream=None, layout=LAYOUT_BHTD, save_states=False):
+                  stream=None, layout=LAYOUT_BHTD, save_states=False, cu_seqlens=None):
     """o, final_state = chunkwise forward of the delta-rule rows of Table 1,
     M_t = alpha_t (I - beta_t k_t^T k_t) M_{t-1} + b_t k_t^T v_t, o_t = q_t M_t.
 
     DeltaNet: log_alpha None, beta = the row's a_t, b = the row's b_t.  Gated DeltaNet: log_alpha = log a_t, beta None.
     log_alpha, beta, b: float32 per token ([B,H,T], or [B,T,H] for LAYOUT_BTHD), None = the constant 1.
-    bf16, d_k = d_v = 128 only.  Enqueues on ``stream`` (default: torch's current stream) without synchronising.
+    bf16, d_k = d_v = 128 only.  cu_seqlens: packed variable-length input as in lsm_chunk_fwd (B == 1, states
+    [n_seq,H,d_k,d_v]).  Enqueues on ``stream`` (default: torch's current stream) without synchronising.
     save_states: leave what the backward call needs of this call in ``workspace`` (required then, see
     lsm_delta_workspace) for lsm_delta_bwd(..., workspace=the same tensor, states_saved=True) on the same inputs."""
     import torch
     if save_states and workspace is None:
         raise ValueError("save_states needs a caller-owned workspace that is passed on to lsm_delta_bwd")
     kind = DECAY_NONE if log_alpha is None else DECAY_SCALAR
-    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_alpha, kind, 64, layout, None, FLAG_SAVE_STATES if save_states else 0)
-    pshape = (B, T, H) if layout == LAYOUT_BTHD else (B, H, T)
+    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_alpha, kind, 64, layout, cu_seqlens, FLAG_SAVE_STATES if save_states else 0)
+    pshape = tuple(q.shape[:3])   # per-token scalars follow q's first three axes (B is the sequence count for packed input)
     _check(beta, pshape, torch.float32, "beta")
     _check(b, pshape, torch.float32, "b")
     _check(init_state, (B, H, dk, dv), torch.float32, "init_state")
@@ -326,7 +327,7 @@ def lsm_delta_fwd(q, k, v, log_alpha=None, beta=None, b=None, init_state=None, w
 
 
 def lsm_delta_bwd(q, k, v, d_o, log_alpha=None, beta=None, b=None, init_state=None, d_final_state=None, workspace=None,
-                  stream=None, layout=LAYOUT_BHTD, want_d_init_state=True, states_saved=False):
+                  stream=None, layout=LAYOUT_BHTD, want_d_init_state=True, states_saved=False, cu_seqlens=None):
     """Gradients of L = <o, d_o> + <M_T, d_final_state> for the delta-rule rows (see lsm_delta_fwd): a dict with dq, dk,
     dv (like q, k, v), d_log_alpha, d_beta, d_b (float32 per token, None where the parameter was None) and
     d_init_state.  states_saved: ``workspace`` is the one a preceding lsm_delta_fwd(..., save_states=True) on the same
@@ -335,8 +336,8 @@ def lsm_delta_bwd(q, k, v, d_o, log_alpha=None, beta=None, b=None, init_state=No
     if states_saved and workspace is None:
         raise ValueError("states_saved needs the workspace of the forward call")
     kind = DECAY_NONE if log_alpha is None else DECAY_SCALAR
-    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_alpha, kind, 64, layout, None, FLAG_SAVE_STATES if states_saved else 0)
-    pshape = (B, T, H) if layout == LAYOUT_BTHD else (B, H, T)
+    p, (B, H, T, dk, dv), gshape = _setup(q, k, v, log_alpha, kind, 64, layout, cu_seqlens, FLAG_SAVE_STATES if states_saved else 0)
+    pshape = tuple(q.shape[:3])
     _check(beta, pshape, torch.float32, "beta")
     _check(b, pshape, torch.float32, "b")
     _check(d_o, tuple(v.shape), q.dtype, "d_o")

@@ -296,7 +296,7 @@ size_t lsm_delta_fwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK || !lsm::delta_supported(d)) return 0;
     d.save = (p->flags & LSM_FLAG_SAVE_STATES) != 0;
-    return lsm::delta_fwd_workspace(d);
+    return table_bytes(d) + lsm::delta_fwd_workspace(d);
 }
 
 int lsm_delta_fwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_alpha,
@@ -313,7 +313,8 @@ int lsm_delta_fwd(const lsm_params* p, const void* q, const void* k, const void*
         misaligned(b) || misaligned(init_state) || misaligned(final_state) || misaligned(workspace))
         return LSM_ERR_ALIGN;
     d.save = (p->flags & LSM_FLAG_SAVE_STATES) != 0;
-    if (!workspace || workspace_bytes < lsm::delta_fwd_workspace(d)) return LSM_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < table_bytes(d) + lsm::delta_fwd_workspace(d)) return LSM_ERR_WORKSPACE;
+    if (prepare_tables(d, workspace, static_cast<hipStream_t>(stream)) != hipSuccess) return LSM_ERR_LAUNCH;
     const lsm::DeltaArgs a{q, k, v, log_alpha, beta, b, init_state, o, final_state, workspace, static_cast<hipStream_t>(stream)};
     return lsm::delta_fwd(d, a) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;
 }
@@ -321,7 +322,7 @@ int lsm_delta_fwd(const lsm_params* p, const void* q, const void* k, const void*
 size_t lsm_delta_bwd_workspace_bytes(const lsm_params* p) {
     lsm::Dims d{};
     if (check_params(p, &d) != LSM_OK || !lsm::delta_supported(d)) return 0;
-    return lsm::delta_bwd_workspace(d);
+    return table_bytes(d) + lsm::delta_bwd_workspace(d);
 }
 
 int lsm_delta_bwd(const lsm_params* p, const void* q, const void* k, const void* v, const float* log_alpha,
@@ -345,7 +346,8 @@ int lsm_delta_bwd(const lsm_params* p, const void* q, const void* k, const void*
         misaligned(d_init_state) || misaligned(workspace))
         return LSM_ERR_ALIGN;
     d.save = (p->flags & LSM_FLAG_SAVE_STATES) != 0;
-    if (!workspace || workspace_bytes < lsm::delta_bwd_workspace(d)) return LSM_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < table_bytes(d) + lsm::delta_bwd_workspace(d)) return LSM_ERR_WORKSPACE;
+    if (prepare_tables(d, workspace, static_cast<hipStream_t>(stream)) != hipSuccess) return LSM_ERR_LAUNCH;
     const lsm::DeltaBwdArgs a{q, k, v, log_alpha, beta, b, init_state, d_o, d_final_state, dq, dk, dv, d_log_alpha, d_beta, d_b,
                               d_init_state, workspace, static_cast<hipStream_t>(stream)};
     return lsm::delta_bwd(d, a) == hipSuccess ? LSM_OK : LSM_ERR_LAUNCH;

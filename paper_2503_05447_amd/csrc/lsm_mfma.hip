@@ -998,7 +998,7 @@ hipError_t mfma_intra_bench(const Dims& d0, const FwdArgs& a, int reps) {
 }
 
 // ---- delta-rule rows: host side
-bool delta_supported(const Dims& d) { return d.bf16 && d.C == C && d.dk == D && d.dv == D && (d.kind == 0 || d.kind == 2) && !d.nseq; }
+bool delta_supported(const Dims& d) { return d.bf16 && d.C == C && d.dk == D && d.dv == D && (d.kind == 0 || d.kind == 2); }
 namespace {
 struct DeltaWs;
 DeltaWs carve_delta(const Dims& d, void* ws);

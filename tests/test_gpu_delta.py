@@ -244,6 +244,49 @@ def test_delta_unit_key_returns_its_value_on_the_gpu():
     run_and_check(x)
 
 
+@pytest.mark.parametrize("keep", [False, True])
+@pytest.mark.parametrize("gated", [False, True])
+def test_delta_packed_sequences_equal_separate_calls(gated, keep):
+    """Packed variable-length input (lengths with ragged chunks, one shorter than a chunk, one empty): every sequence
+    must come out bit for bit as from a call of its own, forward and backward."""
+    import torch
+    import paper_2503_05447_amd as pkg
+    lens = [130, 40, 0, 64, 77]
+    T, H, n = sum(lens), 2, len(lens)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    x = wl.make_delta_inputs(1, H, T, 128, 128, gated, seed=6000 + int(gated), tie_b=False)
+    rng = np.random.default_rng(6001)
+    x["m0"] = (rng.standard_normal((n, H, 128, 128)) * 0.1).astype(np.float32)
+    x["d_mT"] = (rng.standard_normal((n, H, 128, 128)) * 0.1).astype(np.float32)
+    if gated:
+        x["beta"] = (0.2 + 0.7 * rng.random((1, H, T))).astype(np.float32)
+    t = dev(x)
+    d = torch.device("cuda:0")
+    d_o, d_mT = torch.from_numpy(x["d_o"]).to(d).to(torch.bfloat16), torch.from_numpy(x["d_mT"]).to(d)
+    cu_d = torch.from_numpy(cu).to(d)
+    ws = pkg.lsm_delta_workspace(t["q"], t["k"], t["v"], t["log_alpha"], cu_seqlens=cu_d) if keep else None
+    o, mT = pkg.lsm_delta_fwd(t["q"], t["k"], t["v"], t["log_alpha"], t["beta"], t["b"], t["m0"], cu_seqlens=cu_d, workspace=ws,
+                              save_states=keep)
+    r = pkg.lsm_delta_bwd(t["q"], t["k"], t["v"], d_o, t["log_alpha"], t["beta"], t["b"], t["m0"], d_mT, cu_seqlens=cu_d,
+                          workspace=ws, states_saved=keep)
+    torch.cuda.synchronize()
+    piece = lambda a, lo, hi: None if a is None else a[:, :, lo:hi].contiguous()
+    for s_, (lo, hi) in enumerate(zip(cu[:-1], cu[1:])):
+        if hi == lo:   # the empty sequence passes its states through
+            assert torch.equal(mT[s_], t["m0"][s_]) and torch.equal(r["d_init_state"][s_], d_mT[s_])
+            continue
+        args = [piece(t[n_], lo, hi) for n_ in ("q", "k", "v")]
+        pars = [piece(t[n_], lo, hi) for n_ in ("log_alpha", "beta", "b")]
+        o_s, mT_s = pkg.lsm_delta_fwd(*args, *pars, t["m0"][s_:s_ + 1].contiguous())
+        r_s = pkg.lsm_delta_bwd(*args, piece(d_o, lo, hi), *pars, t["m0"][s_:s_ + 1].contiguous(), d_mT[s_:s_ + 1].contiguous())
+        torch.cuda.synchronize()
+        assert torch.equal(o[:, :, lo:hi], o_s) and torch.equal(mT[s_:s_ + 1], mT_s), s_
+        for n_ in ("dq", "dk", "dv", "d_log_alpha", "d_beta", "d_b"):
+            if r_s[n_] is not None:
+                assert torch.equal(r[n_][:, :, lo:hi], r_s[n_]), (n_, s_)
+        assert torch.equal(r["d_init_state"][s_:s_ + 1], r_s["d_init_state"]), s_
+
+
 def test_delta_rejects_what_it_does_not_serve():
     import torch
     import paper_2503_05447_amd as pkg
