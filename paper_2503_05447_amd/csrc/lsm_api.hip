@@ -163,7 +163,7 @@ const char* lsm_kernel_name(int kernel_id) {
         "generic_cumsum", "generic_chunk_state", "generic_scan", "generic_output", "generic_chunk_dstate",
         "generic_reverse_scan", "generic_grad", "head_reduce", "mfma_state_scan_fwd", "mfma_output",
         "mfma_state_and_dstate_scans_bwd", "mfma_dstate_scan", "mfma_grad", "mfma_decay_prep", "mfma_vector_decay_prep", "mfma_vector_decay_dv", "recurrent_step",
-        "walk_segment_summary", "walk_segment_scan", "walk_fwd", "walk_grad", "delta_prep", "delta_walk", "delta_reverse_walk", "delta_grad"};
+        "walk_segment_summary", "walk_segment_scan", "walk_fwd", "walk_grad", "delta_prep", "delta_walk", "delta_reverse_walk", "delta_grad", "delta_segment_summary", "delta_segment_combine"};
     return kernel_id >= 0 && kernel_id < lsm::KID_COUNT ? names[kernel_id] : "unknown";
 }
 

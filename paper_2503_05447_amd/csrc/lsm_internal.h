@@ -98,7 +98,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 enum KernelId {
     KID_GEN_CUMSUM = 0, KID_GEN_STATE, KID_GEN_SCAN, KID_GEN_OUTPUT, KID_GEN_DSTATE, KID_GEN_RSCAN, KID_GEN_GRAD,
     KID_HEAD_REDUCE, KID_MFMA_STATE, KID_MFMA_OUTPUT, KID_MFMA_STATE_BWD, KID_MFMA_DSTATE, KID_MFMA_GRAD, KID_MFMA_PREP, KID_MFMA_VEC_PREP, KID_MFMA_VEC_DV, KID_STEP,
-    KID_WALK_SUMMARY, KID_WALK_SCAN, KID_WALK_FWD, KID_WALK_GRAD, KID_DELTA_PREP, KID_DELTA_WALK, KID_DELTA_RWALK, KID_DELTA_GRAD, KID_COUNT
+    KID_WALK_SUMMARY, KID_WALK_SCAN, KID_WALK_FWD, KID_WALK_GRAD, KID_DELTA_PREP, KID_DELTA_WALK, KID_DELTA_RWALK, KID_DELTA_GRAD, KID_DELTA_SUMMARY, KID_DELTA_COMBINE, KID_COUNT
 };
 // Bracket a kernel launch with events when timing is switched on (no-ops otherwise).
 void prof_begin(int kernel_id, hipStream_t stream);

@@ -1003,15 +1003,29 @@ namespace {
 struct DeltaWs;
 DeltaWs carve_delta(const Dims& d, void* ws);
 size_t carve_delta_bytes(const Dims& d);
+// Segments of the delta walkers: one workgroup per compute unit is the most they can use, so a sequence is cut only
+// when there are clearly fewer sequences than units.
+SegPlan delta_plan(const Dims& d) {
+    const int nmax = (d.T + C - 1) / C;
+    int nseg = d.seqs() >= 192 ? 1 : (256 + d.seqs() - 1) / d.seqs();
+    nseg = nseg > nmax ? nmax : nseg;
+    const int m = (nmax + nseg - 1) / nseg;
+    return SegPlan{m, (nmax + m - 1) / m};
+}
+// sum A | sum B | entry states, [seqs][nseg][128 x 128] fp32 each (nothing for a single segment)
+size_t delta_seg_bytes(const Dims& d) {
+    const SegPlan sp = delta_plan(d);
+    return sp.nseg > 1 ? 3 * align256(size_t(d.seqs()) * sp.nseg * D * D * 4) : 0;
+}
 }  // namespace
 // Dims::save: the forward call also leaves T^T and the pseudo-values in the workspace, laid out as the backward call
 // carves it, and the backward call does not run the prep and the walk again.
 size_t delta_fwd_workspace(const Dims& d) {
     if (d.save) return carve_delta_bytes(d);
-    return align256(size_t(d.BH()) * d.T * D * 2) + align256(size_t(d.BH()) * d.T * D * 4);
+    return align256(size_t(d.BH()) * d.T * D * 2) + align256(size_t(d.BH()) * d.T * D * 4) + delta_seg_bytes(d);
 }
 namespace {
-hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, const DeltaWalkArgs& wa, hipStream_t stream);
+hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, DeltaWalkArgs wa, void* segws, hipStream_t stream);
 }
 hipError_t delta_fwd_saving(const Dims& d, const DeltaArgs& a);
 hipError_t delta_fwd(const Dims& d, const DeltaArgs& a) {
@@ -1022,39 +1036,101 @@ hipError_t delta_fwd(const Dims& d, const DeltaArgs& a) {
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, what, uhat, nullptr};
     const DeltaWalkArgs wa{q, k, what, uhat, a.log_alpha, static_cast<uint16_t*>(a.o), a.m0, a.mT, nullptr, nullptr};
-    return launch_delta_fwd(d, pa, wa, a.stream);
+    return launch_delta_fwd(d, pa, wa, p + align256(size_t(d.BH()) * d.T * D * 2) + align256(size_t(d.BH()) * d.T * D * 4), a.stream);
 }
 namespace {
-hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, const DeltaWalkArgs& wa, hipStream_t stream) {
-    struct { hipStream_t stream; } a{stream};
+template <bool DEC>
+hipError_t launch_delta_fwd_t(const Dims& d, const DeltaPrepArgs& pa, DeltaWalkArgs wa, void* segws, hipStream_t st) {
     hipError_t e;
-    const dim3 pgrid(d.N, d.BH()), wgrid(d.seqs()), block(kThreads);
-    if (d.kind == 0) {
-        if ((e = allow_lds(mk_delta_prep<false>, kDeltaPrepLds)) != hipSuccess) return e;
-        if ((e = allow_lds(mk_delta_walk<false>, kDeltaWalkLds)) != hipSuccess) return e;
-        {
-            ProfScope ps(KID_DELTA_PREP, a.stream);
-            hipLaunchKernelGGL(mk_delta_prep<false>, pgrid, block, kDeltaPrepLds, a.stream, d, pa);
-        }
-        ProfScope ps(KID_DELTA_WALK, a.stream);
-        hipLaunchKernelGGL(mk_delta_walk<false>, wgrid, block, kDeltaWalkLds, a.stream, d, wa);
-    } else {
-        if ((e = allow_lds(mk_delta_prep<true>, kDeltaPrepLds)) != hipSuccess) return e;
-        if ((e = allow_lds(mk_delta_walk<true>, kDeltaWalkLds)) != hipSuccess) return e;
-        {
-            ProfScope ps(KID_DELTA_PREP, a.stream);
-            hipLaunchKernelGGL(mk_delta_prep<true>, pgrid, block, kDeltaPrepLds, a.stream, d, pa);
-        }
-        ProfScope ps(KID_DELTA_WALK, a.stream);
-        hipLaunchKernelGGL(mk_delta_walk<true>, wgrid, block, kDeltaWalkLds, a.stream, d, wa);
+    const SegPlan sp = delta_plan(d);
+    const dim3 pgrid(d.N, d.BH()), wgrid(sp.nseg, d.seqs()), block(kThreads);
+    if ((e = allow_lds(mk_delta_prep<DEC>, kDeltaPrepLds)) != hipSuccess) return e;
+    if ((e = allow_lds(mk_delta_walk<DEC, 0>, kDeltaWalkLds)) != hipSuccess) return e;
+    {
+        ProfScope ps(KID_DELTA_PREP, st);
+        hipLaunchKernelGGL(mk_delta_prep<DEC>, pgrid, block, kDeltaPrepLds, st, d, pa);
     }
+    wa.m = sp.m;
+    wa.nseg = sp.nseg;
+    if (sp.nseg > 1) {
+        const size_t one = align256(size_t(d.seqs()) * sp.nseg * D * D * 4);
+        float* sumA = reinterpret_cast<float*>(segws);
+        float* sumB = reinterpret_cast<float*>(static_cast<char*>(segws) + one);
+        float* bound = reinterpret_cast<float*>(static_cast<char*>(segws) + 2 * one);
+        if ((e = allow_lds(mk_delta_walk<DEC, 1>, kDeltaWalkLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_walk<DEC, 2>, kDeltaWalkLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_combine<false>, kDeltaCombineLds)) != hipSuccess) return e;
+        {
+            ProfScope ps(KID_DELTA_SUMMARY, st);
+            DeltaWalkArgs sa = wa;
+            sa.sum = sumB;
+            hipLaunchKernelGGL((mk_delta_walk<DEC, 1>), wgrid, block, kDeltaWalkLds, st, d, sa);
+        }
+        {
+            ProfScope ps(KID_DELTA_SUMMARY, st);
+            DeltaWalkArgs sa = wa;
+            sa.sum = sumA;
+            hipLaunchKernelGGL((mk_delta_walk<DEC, 2>), wgrid, block, kDeltaWalkLds, st, d, sa);
+        }
+        {
+            ProfScope ps(KID_DELTA_COMBINE, st);
+            hipLaunchKernelGGL(mk_delta_combine<false>, dim3(d.seqs()), block, kDeltaCombineLds, st, d, wa.edge_in, sumA, sumB, bound, sp.m, sp.nseg);
+        }
+        wa.bound = bound;
+    }
+    ProfScope ps(KID_DELTA_WALK, st);
+    hipLaunchKernelGGL((mk_delta_walk<DEC, 0>), wgrid, block, kDeltaWalkLds, st, d, wa);
     return hipGetLastError();
+}
+hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, DeltaWalkArgs wa, void* segws, hipStream_t stream) {
+    return d.kind == 0 ? launch_delta_fwd_t<false>(d, pa, wa, segws, stream) : launch_delta_fwd_t<true>(d, pa, wa, segws, stream);
+}
+
+template <bool DEC>
+hipError_t launch_delta_rwalk(const Dims& d, DeltaRevArgs ra, void* segws, hipStream_t st) {
+    hipError_t e;
+    const SegPlan sp = delta_plan(d);
+    const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
+    if ((e = allow_lds(mk_delta_rwalk<DEC, 0>, kDeltaRevLds)) != hipSuccess) return e;
+    ra.m = sp.m;
+    ra.nseg = sp.nseg;
+    if (sp.nseg > 1) {
+        const size_t one = align256(size_t(d.seqs()) * sp.nseg * D * D * 4);
+        float* sumA = reinterpret_cast<float*>(segws);
+        float* sumB = reinterpret_cast<float*>(static_cast<char*>(segws) + one);
+        float* bound = reinterpret_cast<float*>(static_cast<char*>(segws) + 2 * one);
+        if ((e = allow_lds(mk_delta_rwalk<DEC, 1>, kDeltaRevLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_rwalk<DEC, 2>, kDeltaRevLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_combine<true>, kDeltaCombineLds)) != hipSuccess) return e;
+        {
+            ProfScope ps(KID_DELTA_SUMMARY, st);
+            DeltaRevArgs sa = ra;
+            sa.sum = sumB;
+            hipLaunchKernelGGL((mk_delta_rwalk<DEC, 1>), grid, block, kDeltaRevLds, st, d, sa);
+        }
+        {
+            ProfScope ps(KID_DELTA_SUMMARY, st);
+            DeltaRevArgs sa = ra;
+            sa.sum = sumA;
+            hipLaunchKernelGGL((mk_delta_rwalk<DEC, 2>), grid, block, kDeltaRevLds, st, d, sa);
+        }
+        {
+            ProfScope ps(KID_DELTA_COMBINE, st);
+            hipLaunchKernelGGL(mk_delta_combine<true>, dim3(d.seqs()), block, kDeltaCombineLds, st, d, ra.edge_in, sumA, sumB, bound, sp.m, sp.nseg);
+        }
+        ra.bound = bound;
+    }
+    ProfScope ps(KID_DELTA_RWALK, st);
+    hipLaunchKernelGGL((mk_delta_rwalk<DEC, 0>), grid, block, kDeltaRevLds, st, d, ra);
+    return hipSuccess;
 }
 
 struct DeltaWs {
     uint16_t *what, *tt, *usave, *usave_l, *dstates, *du_h, *du_l, *dw_h, *dw_l;
     float* uhat;
     void* walk;   // bound_f, gseg_f of the gradient walker
+    void* seg;    // segment summaries and entry states of the delta walker
+    void* seg_r;  // the same for the reverse walker
     size_t bytes;
 };
 DeltaWs carve_delta(const Dims& d, void* ws) {
@@ -1075,6 +1151,10 @@ DeltaWs carve_delta(const Dims& d, void* ws) {
     w.dw_l = reinterpret_cast<uint16_t*>(take(rows * D * 2));
     w.walk = p + off;
     off += carve_walk(d, nullptr, false).bytes;
+    w.seg = p + off;
+    off += delta_seg_bytes(d);
+    w.seg_r = p + off;
+    off += delta_seg_bytes(d);
     w.bytes = off;
     return w;
 }
@@ -1087,7 +1167,7 @@ hipError_t delta_fwd_saving(const Dims& d, const DeltaArgs& a) {
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, w.what, w.uhat, w.tt};
     const DeltaWalkArgs wa{q, k, w.what, w.uhat, a.log_alpha, static_cast<uint16_t*>(a.o), a.m0, a.mT, w.usave, w.usave_l};
-    return launch_delta_fwd(d, pa, wa, a.stream);
+    return launch_delta_fwd(d, pa, wa, w.seg, a.stream);
 }
 
 hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a) {
@@ -1101,19 +1181,13 @@ hipError_t delta_bwd(const Dims& d, const DeltaBwdArgs& a) {
     if (!d.save) {
         const DeltaPrepArgs pa{k, v, a.log_alpha, a.beta, a.bw, w.what, w.uhat, w.tt};
         const DeltaWalkArgs wa{q, k, w.what, w.uhat, a.log_alpha, nullptr, a.m0, nullptr, w.usave, w.usave_l};
-        if ((e = launch_delta_fwd(d, pa, wa, a.stream)) != hipSuccess) return e;
+        if ((e = launch_delta_fwd(d, pa, wa, w.seg, a.stream)) != hipSuccess) return e;
     }
     // state gradients and dU, backward in time
     {
         const DeltaRevArgs ra{q, k, d_o, w.what, a.log_alpha, w.dstates, w.du_h, w.du_l, a.d_mT, a.d_m0};
-        ProfScope ps(KID_DELTA_RWALK, a.stream);
-        if (d.kind == 0) {
-            if ((e = allow_lds(mk_delta_rwalk<false>, kDeltaRevLds)) != hipSuccess) return e;
-            hipLaunchKernelGGL(mk_delta_rwalk<false>, dim3(d.seqs()), dim3(kThreads), kDeltaRevLds, a.stream, d, ra);
-        } else {
-            if ((e = allow_lds(mk_delta_rwalk<true>, kDeltaRevLds)) != hipSuccess) return e;
-            hipLaunchKernelGGL(mk_delta_rwalk<true>, dim3(d.seqs()), dim3(kThreads), kDeltaRevLds, a.stream, d, ra);
-        }
+        e = d.kind == 0 ? launch_delta_rwalk<false>(d, ra, w.seg_r, a.stream) : launch_delta_rwalk<true>(d, ra, w.seg_r, a.stream);
+        if (e != hipSuccess) return e;
     }
     // with U as the values the recurrence is the scalar-decay one: dq, the key gradient through scores and state update
     // and the decay gradient of those terms from the gradient walker (its value gradient is dU once more, not wanted)

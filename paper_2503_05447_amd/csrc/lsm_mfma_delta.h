@@ -18,8 +18,12 @@
 //                  value tile's part in the intra-chunk product and in the state update.
 // Every value column of the state evolves on its own (the erase term acts on the key side only), so a wave
 // keeps its 128 x 32 slice of S and its 32 columns of U to itself.
-// A sequence is walked by one workgroup from end to end: the state a segment would start from is not a decayed
-// sum here (it carries the product of the erase factors), so the walkers' segment summaries do not apply.
+// Segments.  The state a segment of chunks ends with is an affine function of the state it starts from, S' = A S + B,
+// with a dense d_k x d_k factor A (the product of the chunks' erase-and-decay factors), not a decayed sum.  Because
+// the value columns evolve independently, A is what the same walk makes of the identity when the values are zero,
+// and B what it makes of a zero state: with fewer sequences than compute units, a summary pass runs the state part
+// of the walker twice per segment (MODE 1: B, MODE 2: A), mk_delta_combine chains E' = A E + B over the segments of
+// each sequence on the matrix cores, and the walker proper then runs all segments in parallel.
 #pragma once
 
 constexpr int LDU = D + 4;   // floats per row of an fp32 [64][128] tile in LDS
@@ -237,6 +241,11 @@ struct DeltaWalkArgs {
     const float* edge_in;   // M_0 [i][v] per sequence or NULL
     float* edge_out;        // M_T or NULL
     uint16_t *usave, *usave_l;  // NULL, or the pseudo-values (bf16 head, remainder) in the layout of v, for the backward pass
+    // segments (nseg > 1): m chunks each; the walker enters segment s with bound[seq][s]; the summary modes leave their
+    // end state in sum[seq][s] ([i][v] fp32, 128 x 128 each)
+    int m, nseg;
+    const float* bound;
+    float* sum;
 };
 // LDS: Q | K | U head (the value tile's place) | U remainder | What (64 x LD bf16 each) | Uhat (64 x LDU fp32) |
 // scores head | scores remainder (64 x LDP) | bs | wo
@@ -273,8 +282,9 @@ __device__ __forceinline__ void tilef_commit(float* dst, const TileRegsF& r, int
     }
 }
 
-// grid: (seqs)
-template <bool DEC>
+// grid: (segments, seqs).  MODE 0: the walk.  MODE 1 / 2: summary of a segment, state part only, from a zero state /
+// from the identity with zero values.
+template <bool DEC, int MODE = 0>
 __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
@@ -289,34 +299,48 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
     float* wo = bs + C + 4;
     uint16_t* stage = Q;
 
-    const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
     const SeqWalk walk = seq_walk(d, seq);
-    const int cnt = walk.n;
+    const int nsq = max(1, (walk.n + a.m - 1) / a.m);  // segments of this sequence
+    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = max(kend - kbeg, 0);
+    if (MODE != 0) {
+        if (cnt <= 0 || seg >= nsq - 1) return;  // only segments whose end state another one starts from
+    } else if (seg >= nsq) {
+        return;
+    }
 
     f32x16 S[4];
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
-    if (a.edge_in) walk_state_load(S, a.edge_in + size_t(seq) * D * D, false, wave, n, half);
+    if (MODE == 0) {
+        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
+                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
+        if (ein) walk_state_load(S, ein, false, wave, n, half);
+    } else if (MODE == 2) {
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+            _Pragma("unroll") for (int x = 0; x < 16; ++x)
+                S[ib][x] = (32 * ib + 8 * (x >> 2) + 4 * half + (x & 3) == 32 * wave + n) ? 1.f : 0.f;
+    }
 
     TileRegs rq, rk, rw;
     TileRegsF ru;
     float gval = 0.f;
     auto gload = [&](int kk) {
-        const ChunkPos p = walk_pos(d, walk, min(kk, cnt - 1));
+        const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
         if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
-        walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, tid);
+        if (MODE == 0) walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, tid);
         walk_gload<false, kThreads>(rk, a.k, p.tok0, p.ts, p.L, tid);
         walk_gload<false, kThreads>(rw, a.what, p.wtok0, 1, p.L, tid);
-        tilef_gload(ru, a.uhat, p.wtok0, p.L, tid);
+        if (MODE != 2) tilef_gload(ru, a.uhat, p.wtok0, p.L, tid);
     };
     if (cnt > 0) gload(0);
 
     for (int kk = 0; kk < cnt; ++kk) {
-        const ChunkPos cp = walk_pos(d, walk, kk);
+        const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
         const int L = cp.L;
-        walk_commit<kThreads>(Q, rq, L, tid);
+        if (MODE == 0) walk_commit<kThreads>(Q, rq, L, tid);
         walk_commit<kThreads>(K, rk, L, tid);
         walk_commit<kThreads>(Wh, rw, L, tid);
-        tilef_commit(Uh, ru, L, tid);
+        if (MODE != 2) tilef_commit(Uh, ru, L, tid);
         if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
         gload(kk + 1);
         __syncthreads();  // (A) tiles and decay tables of this chunk are in LDS
@@ -329,7 +353,8 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
             _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
                 f32x16 u;
                 _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                    const float4 uh = *reinterpret_cast<const float4*>(Uh + (32 * tb + n) * LDU + 32 * wave + 8 * g + 4 * half);
+                    const float4 uh = MODE == 2 ? float4{0.f, 0.f, 0.f, 0.f}
+                                                : *reinterpret_cast<const float4*>(Uh + (32 * tb + n) * LDU + 32 * wave + 8 * g + 4 * half);
                     u[4 * g + 0] = uh.x - Wacc[tb][4 * g + 0];
                     u[4 * g + 1] = uh.y - Wacc[tb][4 * g + 1];
                     u[4 * g + 2] = uh.z - Wacc[tb][4 * g + 2];
@@ -346,24 +371,102 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
                 store_packed(Vl, LD, 32 * tb + n, 32 * wave, half, pack_block(u));
             }
         }
-        f32x16 O[2];
-        walk_inter<DEC>(O, S, Q, bs, n, half);
-        walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
-        __syncthreads();  // (C) scores are in LDS; nobody reads Q any more (this wave's columns of U are its own)
-        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-            delta_intra(O[jb], jb, V, Vl, Ph, Pl, wave, lane, n, half);
-            store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
+        if (MODE == 0) {
+            f32x16 O[2];
+            walk_inter<DEC>(O, S, Q, bs, n, half);
+            walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
+            __syncthreads();  // (C) scores are in LDS; nobody reads Q any more (this wave's columns of U are its own)
+            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+                delta_intra(O[jb], jb, V, Vl, Ph, Pl, wave, lane, n, half);
+                store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
+            }
         }
         walk_update_vsplit<DEC, true>(S, K, V, Vl, wo, bC, wave, lane, half);
         __syncthreads();  // (D) the output stage is complete and every read of this chunk's tiles is done
-        if (a.out) walk_store<false>(a.out, stage, cp.tok0, cp.ts, L, tid);
-        // the value tile is not written again before every wave has passed the next barrier (A)
-        if (a.usave) {
-            walk_store<false>(a.usave, V, cp.tok0, cp.ts, L, tid);
-            walk_store<false>(a.usave_l, Vl, cp.tok0, cp.ts, L, tid);
+        if (MODE == 0) {
+            if (a.out) walk_store<false>(a.out, stage, cp.tok0, cp.ts, L, tid);
+            // the value tile is not written again before every wave has passed the next barrier (A)
+            if (a.usave) {
+                walk_store<false>(a.usave, V, cp.tok0, cp.ts, L, tid);
+                walk_store<false>(a.usave_l, Vl, cp.tok0, cp.ts, L, tid);
+            }
         }
     }
-    if (a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+    if (MODE != 0) {
+        walk_state_store(S, a.sum + (size_t(seq) * a.nseg + seg) * D * D, false, wave, n, half);
+        return;
+    }
+    if (a.edge_out && seg == nsq - 1) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+}
+
+// Entry state of every segment: E_0 = M_0, E_{s+1} = A_s E_s + B_s (REV: from the last segment down, for the state
+// gradients), one workgroup per sequence, the product on the
+// matrix cores with both factors as bf16 head + remainder (three products; about 2^-16 relative).
+// LDS: A head | A remainder | E head | E remainder (128 x LD each).   grid: (seqs)
+constexpr int kDeltaCombineLds = 4 * D * LD * 2;
+__device__ __forceinline__ void delta_split_tile(uint16_t* hi, uint16_t* lo, const float* src, int tid) {
+    _Pragma("unroll") for (int it = 0; it < 16; ++it) {   // 128 x 128 floats by 256 threads, 4 at a time
+        const int p = tid + kThreads * it, row = p >> 5, c4 = p & 31;
+        const float4 x = src ? *reinterpret_cast<const float4*>(src + row * D + 4 * c4) : float4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t h0 = pack2(x.x, x.y), h1 = pack2(x.z, x.w);
+        *reinterpret_cast<u32x2*>(hi + row * LD + 4 * c4) = u32x2{h0, h1};
+        *reinterpret_cast<u32x2*>(lo + row * LD + 4 * c4) =
+            u32x2{pack2(x.x - bf16_lo(h0), x.y - bf16_hi(h0)), pack2(x.z - bf16_lo(h1), x.w - bf16_hi(h1))};
+    }
+}
+template <bool REV>
+__global__ __launch_bounds__(kThreads, 1) void mk_delta_combine(Dims d, const float* __restrict__ edge_in, const float* __restrict__ sumA,
+                                                                const float* __restrict__ sumB, float* __restrict__ bound, int m,
+                                                                int nseg) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* Ah = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Al = Ah + D * LD;
+    uint16_t* Eh = Al + D * LD;
+    uint16_t* El = Eh + D * LD;
+    const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const SeqWalk walk = seq_walk(d, seq);
+    const int nsq = max(1, (walk.n + m - 1) / m);
+    const float* e0 = edge_in ? edge_in + size_t(seq) * D * D : nullptr;
+    float* b = bound + size_t(seq) * nseg * D * D;
+    // the walk's first segment (REV: the last in time) starts from the edge state; the same as tiles
+    float* b0 = b + size_t(REV ? nsq - 1 : 0) * D * D;
+    _Pragma("unroll") for (int it = 0; it < 16; ++it) {
+        const int p = tid + kThreads * it, row = p >> 5, c4 = p & 31;
+        *reinterpret_cast<float4*>(b0 + row * D + 4 * c4) = e0 ? *reinterpret_cast<const float4*>(e0 + row * D + 4 * c4) : float4{0.f, 0.f, 0.f, 0.f};
+    }
+    delta_split_tile(Eh, El, e0, tid);
+    for (int st = 0; st + 1 < nsq; ++st) {
+        const int s = REV ? nsq - 1 - st : st;   // the segment walked in this step; its end state enters segment s -+ 1
+        const size_t slot = (size_t(seq) * nseg + s) * D * D;
+        delta_split_tile(Ah, Al, sumA + slot, tid);
+        __syncthreads();  // A and E tiles are complete
+        // E'[i][v] = sum_j A[i][j] E[j][v] + B[i][v]; this wave: rows i in [32 w, 32 w + 32)
+        f32x16 acc[4];
+        _Pragma("unroll") for (int vb = 0; vb < 4; ++vb)
+            _Pragma("unroll") for (int x = 0; x < 16; ++x)
+                acc[vb][x] = sumB[slot + size_t(32 * wave + 8 * (x >> 2) + 4 * half + (x & 3)) * D + 32 * vb + n];
+        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 ah = frag(Ah, LD, 32 * wave + n, 16 * ks + 8 * half), al = frag(Al, LD, 32 * wave + n, 16 * ks + 8 * half);
+            _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) {
+                const bf16x8 eh = frag_tr(Eh, LD, 16 * ks, 32 * vb, lane), el = frag_tr(El, LD, 16 * ks, 32 * vb, lane);
+                acc[vb] = mfma(ah, eh, acc[vb]);
+                acc[vb] = mfma(ah, el, acc[vb]);
+                acc[vb] = mfma(al, eh, acc[vb]);
+            }
+        }
+        __syncthreads();  // every wave has read E
+        float* out = b + size_t(REV ? s - 1 : s + 1) * D * D;
+        _Pragma("unroll") for (int vb = 0; vb < 4; ++vb)
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) {
+                const int i = 32 * wave + 8 * (x >> 2) + 4 * half + (x & 3), v = 32 * vb + n;
+                const float e = acc[vb][x];
+                out[size_t(i) * D + v] = e;
+                const uint32_t h = pack2(e, 0.f);
+                Eh[i * LD + v] = uint16_t(h & 0xffffu);
+                El[i * LD + v] = uint16_t(pack2(e - bf16_lo(h), 0.f) & 0xffffu);
+            }
+        // the next delta_split_tile writes A only; the barrier at the top of the next step orders the E writes
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -385,14 +488,18 @@ struct DeltaRevArgs {
     uint16_t *du_h, *du_l;    // [BH*T][128] bf16 (library order)
     const float* edge_in;     // d M_T [i][v] per sequence or NULL
     float* edge_out;          // d M_0 or NULL
+    int m, nseg;              // segments as for the forward walker: the walk enters segment s (from above) with bound[seq][s],
+    const float* bound;       // the summary modes leave what the segment makes of a zero / identity state in sum[seq][s]
+    float* sum;
 };
 constexpr int LDW = 40;  // row stride of a wave's private 32-column tiles
 // LDS: Q | K | dO | What (64 x LD) | scores head | remainder (64 x LDP) | per wave: 128 x LDW bf16 (its columns of dS',
 // then of dU head and remainder, 64 x LDW each) | bs | wo | Gamma
 constexpr int kDeltaRevLds = (4 * C * LD + 2 * C * LDP) * 2 + 4 * D * LDW * 2 + (3 * C + 8) * 4;
 
-// grid: (seqs)
-template <bool DEC>
+// grid: (segments, seqs).  MODE 0: the walk.  MODE 1 / 2: summary of a segment (nothing stored but its end state), from a
+// zero state / from the identity with d_o = 0.
+template <bool DEC, int MODE = 0>
 __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
@@ -406,35 +513,53 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
     float* wo = bs + C + 4;
     float* gm = wo + C + 4;
 
-    const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
     const SeqWalk walk = seq_walk(d, seq);
-    const int cnt = walk.n;
+    const int nsq = max(1, (walk.n + a.m - 1) / a.m);
+    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = max(kend - kbeg, 0);
+    if (MODE != 0) {
+        if (cnt <= 0 || seg == 0) return;  // only segments whose end state (backward in time) another one starts from
+    } else if (seg >= nsq) {
+        return;
+    }
     uint16_t* pw = priv + wave * D * LDW;   // this wave's region
     uint16_t* duh = pw;
     uint16_t* dul = pw + C * LDW;
 
     f32x16 S[4];  // dS[ib][4g+j] = dS[i = 32 ib + 8g + 4 half + j][v = 32 wave + n]
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
-    if (a.edge_in) walk_state_load(S, a.edge_in + size_t(seq) * D * D, false, wave, n, half);
+    if (MODE == 0) {
+        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
+                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
+        if (ein) walk_state_load(S, ein, false, wave, n, half);
+    } else if (MODE == 2) {
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+            _Pragma("unroll") for (int x = 0; x < 16; ++x)
+                S[ib][x] = (32 * ib + 8 * (x >> 2) + 4 * half + (x & 3) == 32 * wave + n) ? 1.f : 0.f;
+    }
 
     TileRegs rq, rk, ro, rw;
     float gval = 0.f;
     auto gload = [&](int kk) {
-        const ChunkPos p = walk_pos(d, walk, cnt - 1 - min(kk, cnt - 1));
+        const ChunkPos p = walk_pos(d, walk, kend - 1 - min(kk, cnt - 1));
         if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
-        walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, tid);
+        if (MODE != 2) {
+            walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, tid);
+            walk_gload<false, kThreads>(ro, a.d_o, p.tok0, p.ts, p.L, tid);
+        }
         walk_gload<false, kThreads>(rk, a.k, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(ro, a.d_o, p.tok0, p.ts, p.L, tid);
         walk_gload<false, kThreads>(rw, a.what, p.wtok0, 1, p.L, tid);
     };
     if (cnt > 0) gload(0);
 
     for (int kk = 0; kk < cnt; ++kk) {
-        const ChunkPos cp = walk_pos(d, walk, cnt - 1 - kk);
+        const ChunkPos cp = walk_pos(d, walk, kend - 1 - kk);
         const int L = cp.L;
-        walk_commit<kThreads>(Q, rq, L, tid);
+        if (MODE != 2) {
+            walk_commit<kThreads>(Q, rq, L, tid);
+            walk_commit<kThreads>(dO, ro, L, tid);
+        }
         walk_commit<kThreads>(K, rk, L, tid);
-        walk_commit<kThreads>(dO, ro, L, tid);
         walk_commit<kThreads>(Wh, rw, L, tid);
         if (DEC && wave == 0) {
             walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
@@ -445,6 +570,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
         const float bC = DEC ? bs[C] : 0.f;
 
         // ---- dS' of this wave's columns -> global, fragment-major: through the wave's private tile [i][v - 32 wave]
+        if (MODE == 0) {
         _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
             _Pragma("unroll") for (int x = 0; x < 16; ++x)
                 pw[(32 * ib + 8 * (x >> 2) + 4 * half + (x & 3)) * LDW + n] = uint16_t(pack2(S[ib][x], 0.f));
@@ -458,6 +584,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
                 }
         }
         __builtin_amdgcn_wave_barrier();
+        }
 
         // ---- dU^T[v][t] = wo_t sum_i dS'[i][v] k_t[i] + sum_{j >= t} dO[j][v] P[j][t]
         f32x16 dU[2];
@@ -468,13 +595,17 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
                 _Pragma("unroll") for (int x = 0; x < 16; ++x) dU[tb][x] *= w;
             }
         }
-        walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
-        __syncthreads();  // (C) scores are in LDS
+        if (MODE != 2) {
+            walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
+            __syncthreads();  // (C) scores are in LDS
+        }
         _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {  // queries j < 32 never see keys t >= 32
-                const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
-                dU[nb] = mfma(dot, frag_tr(Ph, LDP, 16 * ks, 32 * nb, lane), dU[nb]);
-                dU[nb] = mfma(dot, frag_tr(Pl, LDP, 16 * ks, 32 * nb, lane), dU[nb]);
+            if (MODE != 2) {
+                _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {  // queries j < 32 never see keys t >= 32
+                    const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
+                    dU[nb] = mfma(dot, frag_tr(Ph, LDP, 16 * ks, 32 * nb, lane), dU[nb]);
+                    dU[nb] = mfma(dot, frag_tr(Pl, LDP, 16 * ks, 32 * nb, lane), dU[nb]);
+                }
             }
             const PackedBlock uh = pack_block(dU[nb]);
             f32x16 r = dU[nb];
@@ -488,6 +619,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
             store_packed(dul, LDW, 32 * nb + n, 0, half, pack_block(r));
         }
         __builtin_amdgcn_wave_barrier();
+        if (MODE == 0) {
         _Pragma("unroll") for (int it = 0; it < 4; ++it) {
             const int row = (lane >> 2) + 16 * it, piece = lane & 3;
             if (row < L) {
@@ -495,6 +627,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
                 *reinterpret_cast<u32x4*>(a.du_h + off) = *reinterpret_cast<const u32x4*>(duh + row * LDW + 8 * piece);
                 *reinterpret_cast<u32x4*>(a.du_l + off) = *reinterpret_cast<const u32x4*>(dul + row * LDW + 8 * piece);
             }
+        }
         }
         // ---- dS = Gamma_C dS' + sum_t (Gamma_t q_t)^T dO_t - sum_t what_t^T dU_t
         if (DEC) {
@@ -524,16 +657,23 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
             }
             const bf16x8 uh = __builtin_bit_cast(bf16x8, nh), ul = __builtin_bit_cast(bf16x8, nl);
             _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) {
-                const bf16x8 qa = frag_tr(Q, LD, 16 * ks, 32 * ib, lane), wa = frag_tr(Wh, LD, 16 * ks, 32 * ib, lane);
-                S[ib] = mfma(qa, oh, S[ib]);
-                if (DEC) S[ib] = mfma(qa, ol, S[ib]);
+                const bf16x8 wa = frag_tr(Wh, LD, 16 * ks, 32 * ib, lane);
+                if (MODE != 2) {
+                    const bf16x8 qa = frag_tr(Q, LD, 16 * ks, 32 * ib, lane);
+                    S[ib] = mfma(qa, oh, S[ib]);
+                    if (DEC) S[ib] = mfma(qa, ol, S[ib]);
+                }
                 S[ib] = mfma(wa, uh, S[ib]);
                 S[ib] = mfma(wa, ul, S[ib]);
             }
         }
         __syncthreads();  // (D) every read of this chunk's tiles is done
     }
-    if (a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+    if (MODE != 0) {
+        walk_state_store(S, a.sum + (size_t(seq) * a.nseg + seg) * D * D, false, wave, n, half);
+        return;
+    }
+    if (a.edge_out && seg == 0) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
 }
 
 // ---------------------------------------------------------------------------------------------
