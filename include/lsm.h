@@ -161,7 +161,7 @@ int lsm_chunk_fwd_noalloc(const lsm_params* p,
  * lsm_delta_bwd_workspace_bytes(p) bytes, untouched in between): the forward call leaves the chunks' triangular
  * inverses and pseudo-values in the workspace and lsm_delta_bwd does not compute them again.  Keys are expected to have
  * at most unit length times sqrt(2 / beta) (the erase factor is then a contraction); nothing is checked.
- * One workgroup walks a sequence from end to end, so the chip is full from B*H >= 256 sequences on.
+ * With fewer than about 200 sequences each is cut into segments that run in parallel (at the price of a summary pass).
  */
 size_t lsm_delta_fwd_workspace_bytes(const lsm_params* p);
 int lsm_delta_fwd(const lsm_params* p,
