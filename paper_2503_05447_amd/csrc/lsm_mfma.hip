@@ -919,7 +919,14 @@ hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
     GradArgs ga{q, k, v, d_o, a.g, w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv),
                 a.dg ? (d.kind == 1 ? w.dgc : a.dg) : nullptr, a.m0, w.bound_f, sp.m, sp.nseg};
     const dim3 block(kThreads);
-    if ((e = launch_walk_grad(d, sp, ga, a.stream)) != hipSuccess) return e;
+    // the gradient walker holds one workgroup per compute unit, the forward walker two: where the plan gives every unit
+    // two workgroups, the gradient walker takes segments of twice the length (half as many state loads and prologues)
+    SegPlan gp = sp;
+    if (sp.nseg % 2 == 0 && sp.nseg * d.seqs() >= 512) {
+        gp = SegPlan{sp.m * 2, sp.nseg / 2};
+        ga.m = gp.m; ga.nseg = gp.nseg; ga.bound_per = 2; ga.bound_n = sp.nseg;
+    }
+    if ((e = launch_walk_grad(d, gp, ga, a.stream)) != hipSuccess) return e;
     if (a.dg && d.kind == 1) {
         ProfScope ps(KID_HEAD_REDUCE, a.stream);
         hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dgc, a.dg);

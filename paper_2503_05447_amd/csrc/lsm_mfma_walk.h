@@ -399,6 +399,9 @@ struct GradArgs {
     // the state it starts from (head, remainder, same order)
     const uint16_t *du_h, *du_l;
     uint16_t *dw_h, *dw_l;
+    // the entry states may be kept at a finer grain than this walk's segments: bound holds bound_n slots per sequence,
+    // one per m / bound_per chunks, and segment s enters with slot s * bound_per (0: same grain, nseg slots)
+    int bound_per, bound_n;
 };
 // VSPLIT (the delta-rule backward, whose values are the pseudo-values U = head + remainder): the values enter
 // every product with both planes; the value gradient is not formed (it is the caller's dU once more) and its
@@ -433,7 +436,7 @@ __device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a,
     f32x16 S[4];
     _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) S[vb] = f32x16{0};
     {
-        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
+        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * (a.bound_per ? a.bound_n : a.nseg) + seg * (a.bound_per ? a.bound_per : 1)) * D * D
                                       : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
         if (ein) walk_state_load(S, ein, true, wave, n, half);
     }
