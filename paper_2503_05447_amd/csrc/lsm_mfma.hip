@@ -671,7 +671,7 @@ struct RevPlan { int per, nseg; };
 RevPlan rev_plan(const Dims& d, const SegPlan& sp) {
     const int wgs = D / 32 * d.seqs();
     if (wgs >= 256 || sp.nseg <= 1) return RevPlan{sp.nseg, 1};
-    const int want = (kWalkTargetWgs + wgs - 1) / wgs;
+    const int want = (256 + wgs - 1) / wgs;  // one workgroup per compute unit: with two, the four strips of a sequence fall out of step and stop sharing their rows in L2
     const int per = sp.nseg / want > 1 ? sp.nseg / want : 1;
     return RevPlan{per, (sp.nseg + per - 1) / per};
 }
