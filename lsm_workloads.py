@@ -103,7 +103,7 @@ def make_delta_inputs(B, H, T, dk, dv, gated, dtype="bf16", seed=0, decay="defau
     q ~ N(0,1)/sqrt(dk); k drawn N(0,1) and scaled to unit length (as the delta-rule models normalise their keys);
     v ~ N(0,1); the row's write strength b_s = sigmoid(N(0,1)); DeltaNet's erase strength a_s = b_s (``tie_b``, the
     usual parametrisation) or an independent draw of the same law; Gated DeltaNet's decay log a_s by the scalar-decay
-    law named by ``decay`` (see make_inputs).  Values are float32; with dtype "bf16" q, k, v, d_o are rounded to bf16
+    law named by ``decay`` (see make_inputs; "harsh" = -20 U(0,1)).  Values are float32; with dtype "bf16" q, k, v, d_o are rounded to bf16
     (so a key's length is 1 up to that rounding).
     """
     rng = np.random.default_rng(seed)
@@ -118,10 +118,13 @@ def make_delta_inputs(B, H, T, dk, dv, gated, dtype="bf16", seed=0, decay="defau
     beta = None if gated else (b.copy() if tie_b else sig(n2))
     log_alpha = None
     if gated:
-        shift = {"default": 3.0, "strong4": 4.0, "weak": -4.0}.get(decay)
-        if shift is None:
-            raise ValueError(decay)
-        log_alpha = np.ascontiguousarray(-_softplus(n3 + shift), dtype=np.float32)
+        if decay == "harsh":    # underflow stress, as for the diagonal kinds
+            log_alpha = (-20.0 * rng.random((B, H, T), dtype=np.float32)).astype(np.float32)
+        else:
+            shift = {"default": 3.0, "strong4": 4.0, "weak": -4.0}.get(decay)
+            if shift is None:
+                raise ValueError(decay)
+            log_alpha = np.ascontiguousarray(-_softplus(n3 + shift), dtype=np.float32)
     m0 = (rng.standard_normal((B, H, dk, dv), dtype=np.float32) * np.float32(init_std)) if init_state else None
     d_o = rng.standard_normal((B, H, T, dv), dtype=np.float32)
     d_mT = rng.standard_normal((B, H, dk, dv), dtype=np.float32) * np.float32(init_std) if d_final else None

@@ -69,7 +69,7 @@ def test_delta_forward_separate_strengths_and_no_initial_state(gated):
     run_and_check(x)
 
 
-@pytest.mark.parametrize("decay", ["weak", "strong4"])
+@pytest.mark.parametrize("decay", ["weak", "strong4", "harsh"])
 def test_gated_delta_decay_strengths(decay):
     x = wl.make_delta_inputs(1, 3, 700, 128, 128, True, seed=4300, decay=decay, init_state=True)
     run_and_check(x)
@@ -161,7 +161,7 @@ def test_delta_backward_separate_strengths_no_edge_states(gated):
     run_bwd_and_check(x)
 
 
-@pytest.mark.parametrize("decay", ["weak", "strong4"])
+@pytest.mark.parametrize("decay", ["weak", "strong4", "harsh"])
 def test_gated_delta_backward_decay_strengths(decay):
     x = wl.make_delta_inputs(1, 3, 500, 128, 128, True, seed=5300, decay=decay, init_state=True, d_final=True)
     run_bwd_and_check(x)
