@@ -24,6 +24,8 @@
 #include "lsm_mfma_dev.h"
 
 #include <atomic>
+#include <mutex>
+#include <vector>
 
 namespace lsm {
 namespace {
@@ -712,18 +714,30 @@ WalkWs carve_walk(const Dims& d, void* ws, bool bwd) {
 }
 
 // Raise a kernel's dynamic LDS limit, once per kernel and device (every kernel is always launched with the
-// same size, so the first call settles it).
+// same size, so the first call settles it).  The record is keyed by the kernel's address: instantiations of one
+// kernel template share a function type, so a flag per type would let the first of them speak for all.
 template <typename K>
 hipError_t allow_lds(K kernel, int bytes) {
-    static std::atomic<uint64_t> done{0};  // one flag per device and template instantiation
+    struct Seen { const void* fn; uint64_t devices; };
+    static std::mutex mu;
+    static std::vector<Seen> seen;
+    const void* fn = reinterpret_cast<const void*>(kernel);
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     const uint64_t bit = uint64_t(1) << (dev & 63);
-    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
-    return e;
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        for (const Seen& x : seen)
+            if (x.fn == fn && (x.devices & bit)) return hipSuccess;
+    }
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lk(mu);
+    for (Seen& x : seen)
+        if (x.fn == fn) { x.devices |= bit; return hipSuccess; }
+    seen.push_back(Seen{fn, bit});
+    return hipSuccess;
 }
 
 }  // namespace
