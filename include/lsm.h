@@ -11,6 +11,9 @@
  * inter-chunk product with the prefix of chunk states), generalised to a
  * decay, and its backward.  q_t, k_t are 1 x d_k rows, v_t, o_t are 1 x d_v
  * rows, M is d_k x d_v.  The decay is passed as log-decay g = log a <= 0.
+ * The two delta-rule rows of the same table (DeltaNet, Gated DeltaNet), whose
+ * transition is not diagonal, have entry points of their own further down
+ * (lsm_delta_fwd, lsm_delta_bwd, lsm_delta_step).
  *
  * Readings of the paper fixed by this ABI: o_t sees token t itself; the mask
  * of Algorithm 2 is the multiplicative 0/1 lower triangle; there is no
