@@ -49,11 +49,11 @@ __device__ __forceinline__ void walk_commit(uint16_t* dst, const TileRegs& r, in
         *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{r.v[it].x & keep, r.v[it].y & keep, r.v[it].z & keep, r.v[it].w & keep};
     }
 }
-// 256 threads store an output stage
-template <bool REV>
+// NT threads store an output stage
+template <bool REV, int NT = kThreads>
 __device__ __forceinline__ void walk_store(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
-    _Pragma("unroll") for (int it = 0; it < 4; ++it) {
-        const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+    _Pragma("unroll") for (int it = 0; it < 1024 / NT; ++it) {
+        const int p = tid + NT * it, row = p >> 4, cp = p & 15;
         if (row < L)
             __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
                                         reinterpret_cast<u32x4*>(dst + (tok0 + size_t(REV ? L - 1 - row : row) * ts) * D + cp * 8));
@@ -667,6 +667,239 @@ template <bool DEC, bool WANT_DG, bool VSPLIT = false>
 __global__ __launch_bounds__(kThreads, 1) void mk_walk_grad(Dims d, GradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     walk_grad_body<DEC, WANT_DG, VSPLIT>(d, a, blockIdx.y, blockIdx.x, smem);
+}
+
+// The same chunk adjoint by eight waves, two per SIMD, for the plain (single value plane) case.  The work of a chunk is
+// split by function, not by data, so that neither group needs the other's registers:
+//   waves 0..3 (wave w: key features i in [32w, 32w+32)) carry the state; they form dq (inter part from the state, intra
+//              part from G), <S, dS> (dS read back from the LDS rows) and move the state on;
+//   waves 4..7 (wave w: the same i slice for dk, value features v in [32w, 32w+32) for dv) hold the dS rows of the chunk;
+//              they compute the six score blocks (G, As), dk and dv.
+// Each group runs a loop of its own with the same four barriers per chunk, so a SIMD always has one wave of either
+// kind to issue from: the matrix, vector and LDS work of the two overlap instead of queueing behind one wave's waits.
+// All 512 threads share the tile traffic (global -> registers -> LDS, stage -> global).  LDS as for mk_walk_grad.
+constexpr int kGrad8Threads = 512;
+
+template <bool DEC, bool WANT_DG>
+__global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* K = Q + C * LD;
+    uint16_t* V = K + C * LD;
+    uint16_t* dO = V + C * LD;
+    uint16_t* Gh = dO + C * LD;
+    uint16_t* Gl = Gh + C * LDP;
+    uint16_t* Ah = Gl + C * LDP;
+    uint16_t* Al = Ah + C * LDP;
+    uint16_t* dSt = Al + C * LDP;    // [i][v] rows of dS, all 128
+    float* bs = reinterpret_cast<float*>(dSt + D * LD);
+    float* wo = bs + C + 4;
+    float* red = wo + C + 4;         // [i slice][3][64]: q.dq, k.dk, k.dk_inter partial sums over the slice
+    float* zred = red + 4 * 3 * 64;  // [i slice]: partial <S, dS>
+    constexpr int NT = kGrad8Threads;
+
+    const int seq = blockIdx.y, seg = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, n = lane & 31, half = lane >> 5;
+    const bool carrier = tid < 256;  // waves 0..3
+    const SeqWalk walk = seq_walk(d, seq);
+    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
+    if (cnt <= 0) return;
+
+    TileRegs tq, tk, tv, to;
+    auto gload_tiles = [&](const ChunkPos& p) {
+        walk_gload<false, NT>(tq, a.q, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, NT>(tk, a.k, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, NT>(tv, a.v, p.tok0, p.ts, p.L, tid);
+        walk_gload<false, NT>(to, a.d_o, p.tok0, p.ts, p.L, tid);
+    };
+    auto commit_tiles = [&](int L) {
+        walk_commit<NT>(Q, tq, L, tid);
+        walk_commit<NT>(K, tk, L, tid);
+        walk_commit<NT>(V, tv, L, tid);
+        walk_commit<NT>(dO, to, L, tid);
+    };
+    auto store_tiles = [&](const ChunkPos& cp) {
+        // every thread reads back exactly the stage pieces that its own next commit overwrites
+        walk_store<false, NT>(a.dq, Q, cp.tok0, cp.ts, cp.L, tid);
+        walk_store<false, NT>(a.dk, K, cp.tok0, cp.ts, cp.L, tid);
+        walk_store<false, NT>(a.dv, V, cp.tok0, cp.ts, cp.L, tid);
+    };
+
+    if (carrier) {
+        // S block vb of this wave: S[vb][4g+j] = M[i = 32 wave + n][v = 32 vb + 8g + 4 half + j]
+        f32x16 S[4];
+        _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) S[vb] = f32x16{0};
+        {
+            const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * (a.bound_per ? a.bound_n : a.nseg) + seg * (a.bound_per ? a.bound_per : 1)) * D * D
+                                          : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
+            if (ein) walk_state_load(S, ein, true, wave, n, half);
+        }
+        float gval = 0.f;
+        auto gload = [&](int kk) {
+            const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
+            if (DEC) gval = a.g[d.kind == 1 ? size_t(walk.bh % d.H) : p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
+            gload_tiles(p);
+        };
+        gload(0);
+        for (int kk = 0; kk < cnt; ++kk) {
+            const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
+            const int L = cp.L;
+            commit_tiles(L);
+            if (DEC && tid < 64) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
+            __syncthreads();  // (1) tiles, dS rows and decay tables of this chunk are in LDS
+            const float bC = DEC ? bs[C] : 0.f;
+            f32x16 aq[2];
+            walk_inter<DEC>(aq, S, dO, bs, n, half);
+            if (WANT_DG) {  // <S, dS> over this wave's rows i, dS at the (i, v) of the state registers from the LDS rows
+                float z = 0.f;
+                _Pragma("unroll") for (int vb = 0; vb < 4; ++vb)
+                    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                        const u32x2 x = *reinterpret_cast<const u32x2*>(dSt + (32 * wave + n) * LD + 32 * vb + 8 * g + 4 * half);
+                        z += S[vb][4 * g] * bf16_lo(x.x) + S[vb][4 * g + 1] * bf16_hi(x.x) + S[vb][4 * g + 2] * bf16_lo(x.y) +
+                             S[vb][4 * g + 3] * bf16_hi(x.y);
+                    }
+                for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
+                if (lane == 0) zred[wave] = z;
+            }
+            // the state moves on to the end of the chunk (roles: key = v, value = k)
+            walk_update<DEC, true>(S, V, K, wo, bC, wave, lane, half);
+            if (kk + 1 < cnt) gload(kk + 1);
+            __syncthreads();  // (2) G and As are in LDS
+            PackedBlock resq[2];
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                const int tok = 32 * nb + n;
+                // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r]: keys r >= 32 never reach queries j < 32
+                _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {
+                    const bf16x8 kt = frag_tr(K, LD, 16 * ks, 32 * wave, lane);
+                    aq[nb] = mfma(kt, frag(Gh, LDP, tok, 16 * ks + 8 * half), aq[nb]);
+                    aq[nb] = mfma(kt, frag(Gl, LDP, tok, 16 * ks + 8 * half), aq[nb]);
+                }
+                if (WANT_DG) {
+                    float pq = row_dot(Q, tok, wave, half, aq[nb]);
+                    pq += __shfl_xor(pq, 32, 64);
+                    if (half == 0) red[(wave * 3 + 0) * 64 + tok] = pq;
+                }
+                resq[nb] = pack_block(aq[nb]);
+            }
+            __syncthreads();  // (3) every wave is done with the tiles
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
+            __syncthreads();  // (4)
+            store_tiles(cp);
+            if (WANT_DG && tid < 64) {
+                // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
+                float w = 0.f, tail = 0.f, z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
+                _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
+                    w += red[(wv * 3 + 0) * 64 + tid] - red[(wv * 3 + 1) * 64 + tid];
+                    tail += red[(wv * 3 + 2) * 64 + tid];
+                }
+                for (int off = 32; off > 0; off >>= 1) tail += __shfl_xor(tail, off, 64);
+                float sfx = w;  // suffix sum of w over tokens >= tid
+                for (int off = 1; off < 64; off <<= 1) {
+                    const float y = __shfl_down(sfx, off, 64);
+                    if (tid + off < 64) sfx += y;
+                }
+                float dgv = tid < L ? sfx + tail + __expf(bC) * z : 0.f;
+                if (d.kind == 1) {
+                    // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
+                    for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
+                    if (tid == 0) a.dg_tok[cp.slot] = dgv;
+                } else if (tid < L) {
+                    a.dg_tok[cp.tok0 + size_t(tid) * cp.ts] = dgv;
+                }
+            }
+        }
+    } else {
+        bf16x8 dsfrag[8];
+        auto gload = [&](int kk) {
+            const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
+            gload_tiles(p);
+            // rows i in [32w, 32w+32) of dS: A operands [m = i][k = v]
+            const uint16_t* dS = a.dstates + p.slot * D * D;
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                dsfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane)));
+        };
+        // one 32 x 32 score block (0: (0,0), 1: (1,0), 2: (1,1)), mask and decay on its accumulators, as head + remainder
+        auto score = [&](bool isG, int bi) {
+            const int pjb = bi ? 1 : 0, prb = bi == 2 ? 1 : 0;
+            // D[m = r][n = j] = v_r . d_o_j  or  k_r . q_j
+            f32x16 P = isG ? score_block2(V, 32 * prb, dO, 32 * pjb, n, half) : score_block2(K, 32 * prb, Q, 32 * pjb, n, half);
+            walk_mask<DEC>(P, 32 * prb, 32 * pjb + n, bs, half);
+            store_block_t_split(isG ? Gh : Ah, isG ? Gl : Al, LDP, 32 * pjb + n, 32 * prb, half, P);
+        };
+        gload(0);
+        for (int kk = 0; kk < cnt; ++kk) {
+            const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
+            const int L = cp.L;
+            commit_tiles(L);
+            // the dS rows of this wave, for the contractions over i (dv, <S, dS>)
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
+            __syncthreads();  // (1)
+            // G = (dO V^T) * D first (the other group waits for it at (2)), then As = (Q K^T) * D
+            if (wave < 3) score(true, wave);
+            else score(false, 0);
+            if (wave < 2) score(false, wave + 1);
+            // inter parts: dk^T[i][r] from the dS rows in registers, dv^T[v][r] from the transposed read of the LDS rows
+            f32x16 ak[2] = {{0}, {0}}, av[2] = {{0}, {0}};
+            float pk_inter[2] = {0.f, 0.f};
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                const int tok = 32 * nb + n;
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
+                if (DEC) {
+                    const float wk = wo[tok];
+                    _Pragma("unroll") for (int x = 0; x < 16; ++x) ak[nb][x] *= wk;
+                }
+                if (WANT_DG) pk_inter[nb] = row_dot(K, tok, wave, half, ak[nb]);
+            }
+            if (kk + 1 < cnt) gload(kk + 1);  // the dS registers are free
+            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 dst = frag_tr(dSt, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 16 ks + ..
+                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                    av[nb] = mfma(dst, frag(K, LD, 32 * nb + n, 16 * ks + 8 * half), av[nb]);
+            }
+            if (DEC) {
+                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                    const float wk = wo[32 * nb + n];
+                    _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
+                }
+            }
+            __syncthreads();  // (2) G and As are in LDS
+            PackedBlock resk[2], resv[2];
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                const int tok = 32 * nb + n;
+                // dk^T[i][r] += sum_{j>=r} Q^T[i][j] G[j][r]: queries j < 32 never see keys r >= 32
+                _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+                    const bf16x8 qt = frag_tr(Q, LD, 16 * ks, 32 * wave, lane);
+                    ak[nb] = mfma(qt, frag_tr(Gh, LDP, 16 * ks, 32 * nb, lane), ak[nb]);  // B[k = j][n = r] = G[j][r]
+                    ak[nb] = mfma(qt, frag_tr(Gl, LDP, 16 * ks, 32 * nb, lane), ak[nb]);
+                }
+                if (WANT_DG) {
+                    float pk = row_dot(K, tok, wave, half, ak[nb]);
+                    pk += __shfl_xor(pk, 32, 64);
+                    const float pi = pk_inter[nb] + __shfl_xor(pk_inter[nb], 32, 64);
+                    if (half == 0) {
+                        red[(wave * 3 + 1) * 64 + tok] = pk;
+                        red[(wave * 3 + 2) * 64 + tok] = pi;
+                    }
+                }
+                resk[nb] = pack_block(ak[nb]);
+                // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]
+                _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+                    const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
+                    av[nb] = mfma(dot, frag_tr(Ah, LDP, 16 * ks, 32 * nb, lane), av[nb]);  // B[k = j][n = r] = As[j][r]
+                    av[nb] = mfma(dot, frag_tr(Al, LDP, 16 * ks, 32 * nb, lane), av[nb]);
+                }
+                resv[nb] = pack_block(av[nb]);
+            }
+            __syncthreads();  // (3)
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
+                store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
+            }
+            __syncthreads();  // (4)
+            store_tiles(cp);
+        }
+    }
 }
 
 // Entry state of every segment from the segments' own contributions (left by the summary pass in the
