@@ -877,7 +877,7 @@ hipError_t walk_fwd(const Dims& d, const FwdArgs& a) {
 }
 
 hipError_t launch_walk_grad(const Dims& d, const SegPlan& sp, const GradArgs& ga, hipStream_t st) {
-    const dim3 grid(sp.nseg, d.seqs()), block(kThreads);
+    const dim3 grid(sp.nseg, d.seqs()), block(kGrad8Threads);
     hipError_t e;
     ProfScope ps(KID_WALK_GRAD, st);
     if (ga.v_lo) {  // values in two planes (delta-rule backward)
@@ -891,16 +891,15 @@ hipError_t launch_walk_grad(const Dims& d, const SegPlan& sp, const GradArgs& ga
         }
         return hipSuccess;
     }
-    const dim3 block8(kGrad8Threads);
     if (d.kind == 0) {
-        if ((e = allow_lds(mk_walk_grad8<false, false>, kWalkGradLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_walk_grad8<false, false>), grid, block8, kWalkGradLds, st, d, ga);
+        if ((e = allow_lds(mk_walk_grad<false, false>, kWalkGradLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk_grad<false, false>), grid, block, kWalkGradLds, st, d, ga);
     } else if (!ga.dg_tok) {
-        if ((e = allow_lds(mk_walk_grad8<true, false>, kWalkGradLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_walk_grad8<true, false>), grid, block8, kWalkGradLds, st, d, ga);
+        if ((e = allow_lds(mk_walk_grad<true, false>, kWalkGradLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk_grad<true, false>), grid, block, kWalkGradLds, st, d, ga);
     } else {
-        if ((e = allow_lds(mk_walk_grad8<true, true>, kWalkGradLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_walk_grad8<true, true>), grid, block8, kWalkGradLds, st, d, ga);
+        if ((e = allow_lds(mk_walk_grad<true, true>, kWalkGradLds)) != hipSuccess) return e;
+        hipLaunchKernelGGL((mk_walk_grad<true, true>), grid, block, kWalkGradLds, st, d, ga);
     }
     return hipSuccess;
 }

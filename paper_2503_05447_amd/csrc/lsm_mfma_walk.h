@@ -35,10 +35,13 @@ struct WalkArgs {
 // NT threads share a tile: 1024 / NT pieces of 16 bytes each.
 template <bool REV, int NT>
 __device__ __forceinline__ void walk_gload(TileRegs& r, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
+    // uniform base (scalar registers) + a 32-bit byte offset per lane, shared by every tile of the chunk
+    const char* base = reinterpret_cast<const char*>(src + tok0 * D);
     _Pragma("unroll") for (int it = 0; it < 1024 / NT; ++it) {
         const int p = tid + NT * it, row = min(p >> 4, L - 1), cp = p & 15;
         const int tok = REV ? L - 1 - row : row;
-        r.v[it] = *reinterpret_cast<const u32x4*>(src + (tok0 + size_t(tok) * ts) * D + cp * 8);
+        const uint32_t off = (uint32_t(tok) * uint32_t(ts) * D + cp * 8) * 2;
+        r.v[it] = *reinterpret_cast<const u32x4*>(base + off);
     }
 }
 template <int NT>
@@ -52,11 +55,12 @@ __device__ __forceinline__ void walk_commit(uint16_t* dst, const TileRegs& r, in
 // NT threads store an output stage
 template <bool REV, int NT = kThreads>
 __device__ __forceinline__ void walk_store(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
+    char* base = reinterpret_cast<char*>(dst + tok0 * D);
     _Pragma("unroll") for (int it = 0; it < 1024 / NT; ++it) {
         const int p = tid + NT * it, row = p >> 4, cp = p & 15;
+        const uint32_t off = (uint32_t(REV ? L - 1 - row : row) * uint32_t(ts) * D + cp * 8) * 2;
         if (row < L)
-            __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
-                                        reinterpret_cast<u32x4*>(dst + (tok0 + size_t(REV ? L - 1 - row : row) * ts) * D + cp * 8));
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8), reinterpret_cast<u32x4*>(base + off));
     }
 }
 
@@ -371,19 +375,15 @@ __global__ __launch_bounds__(kThreads, 2) void mk_walk(Dims d, WalkArgs a) {
 //   dq^T[i][j] = e^{b_j}     sum_v S[i][v]  d_o_j[v] + sum_r K^T[i][r] G[j][r]
 //   dk^T[i][r] = e^{b_C-b_r} sum_v dS[i][v] v_r[v]   + sum_j Q^T[i][j] G[j][r]
 //   dv^T[v][r] = e^{b_C-b_r} sum_i dS^T[v][i] k_r[i] + sum_j dO^T[v][j] As[j][r]
-//   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + sum_r k_r.dk_r^{inter} + e^{b_C} <S, dS>
 //   S   <- e^{b_C} S + sum_r e^{b_C-b_r} k_r^T v_r
-// Wave w owns i (and v) in [32w, 32w+32).  S enters its product as bf16 head + remainder taken from the
-// fp32 accumulators, so the q.dq term of the decay gradient sees no state rounding.  G and As are each
-// computed once per workgroup, one wave per 32 x 32 block, and parked as head + remainder in a tile that
-// is dead at that point (G in the V tile, As in the Q tile); dS rows are handed between waves through
-// the V tile for the dv inter part.
-// One workgroup per compute unit (the kernel needs the whole register file: state, three output
-// accumulators, the dS rows, the tiles of the next chunk in flight), so LDS is plentiful and G, As and the
-// dS rows each get an area of their own: four barriers per chunk.
+//   dg_t = sum_{u>=t} (q_u.dq_u - k_u.dk_u) + <S, dS>      (S after the update: the state at the chunk end)
+// S enters its product as bf16 head + remainder taken from the fp32 accumulators, so the q.dq term of the decay
+// gradient sees no state rounding.  G and As are each computed once per workgroup, one wave per 32 x 32 block, and
+// parked as head + remainder in areas of their own; the dS rows, which arrive as the A operands of the dk inter part,
+// also go to LDS for the contractions over i.  One workgroup per compute unit, four barriers per chunk.
 // LDS: Q | K | V | dO (64 x LD; at the end the stages of dq, dk, dv) | G head | G remainder | As head |
-//      As remainder (64 x LDP each) | dS rows (128 x LD) | bs | wo | red (4 x 3 x 64) | zred
-constexpr int kWalkGradLds = (4 * C * LD + 4 * C * LDP + D * LD) * 2 + (2 * C + 8) * 4 + 4 * 64 * 3 * 4 + 64;
+//      As remainder (64 x LDP each) | dS rows (128 x LD) | bs | wo | red (4 x 2 x 64) | zred
+constexpr int kWalkGradLds = (4 * C * LD + 4 * C * LDP + D * LD) * 2 + (2 * C + 8) * 4 + 4 * 64 * 2 * 4 + 64;
 
 struct GradArgs {
     const uint16_t *q, *k, *v, *d_o;
@@ -405,283 +405,55 @@ struct GradArgs {
 };
 // VSPLIT (the delta-rule backward, whose values are the pseudo-values U = head + remainder): the values enter
 // every product with both planes; the value gradient is not formed (it is the caller's dU once more) and its
-// output receives the remainder of the key gradient instead (dk = head, dv = remainder).  The area of the dS rows,
-// which only the value gradient reads, holds the two planes of dU instead, and the walker also leaves
-// dW = -dU S^T (the gradient of the delta rule's What), staged through the d_o tile and the second value tile.
+// output receives the remainder of the key gradient instead (dk = head, dv = remainder).  The area of the dS rows
+// holds the two planes of dU instead, and the walker also leaves dW = -dU S^T (the gradient of the delta rule's
+// What), staged through the d_o tile and the second value tile.
 __host__ __device__ constexpr int walk_grad_lds(bool vsplit) { return kWalkGradLds + (vsplit ? C * LD * 2 : 0); }
 
-template <bool DEC, bool WANT_DG, bool VSPLIT = false>
-__device__ __forceinline__ void walk_grad_body(const Dims& d, const GradArgs& a, int seq, int seg, unsigned char* smem) {
-    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* K = Q + C * LD;
-    uint16_t* V = K + C * LD;
-    uint16_t* dO = V + C * LD;
-    uint16_t* Gh = dO + C * LD;
-    uint16_t* Gl = Gh + C * LDP;
-    uint16_t* Ah = Gl + C * LDP;
-    uint16_t* Al = Ah + C * LDP;
-    uint16_t* dSt = Al + C * LDP;    // [i][v] rows of dS, all 128
-    float* bs = reinterpret_cast<float*>(dSt + D * LD);
-    float* wo = bs + C + 4;
-    float* red = wo + C + 4;         // [wave][3][64]: q.dq, k.dk, k.dk_inter partial sums over this wave's i
-    float* zred = red + 4 * 3 * 64;  // [wave]: partial <S, dS>
-    uint16_t* V2 = reinterpret_cast<uint16_t*>(smem + kWalkGradLds);  // VSPLIT only
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
-    const SeqWalk walk = seq_walk(d, seq);
-    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
-    if (cnt <= 0) return;
-
-    // S block vb of this wave: S[vb][4g+j] = M[i = 32 wave + n][v = 32 vb + 8g + 4 half + j]
-    f32x16 S[4];
-    _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) S[vb] = f32x16{0};
-    {
-        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * (a.bound_per ? a.bound_n : a.nseg) + seg * (a.bound_per ? a.bound_per : 1)) * D * D
-                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-        if (ein) walk_state_load(S, ein, true, wave, n, half);
-    }
-
-    TileRegs tq, tk, tv, to, tv2, tdh, tdl;
-    bf16x8 dsfrag[8];
-    uint16_t* dUh = dSt;             // VSPLIT: 64 x LD each, over the dS rows
-    uint16_t* dUl = dSt + C * LD;
-    float gval = 0.f;
-    auto gload = [&](int kk) {
-        const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
-        if (DEC) gval = a.g[d.kind == 1 ? size_t(walk.bh % d.H) : p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
-        walk_gload<false, kThreads>(tq, a.q, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(tk, a.k, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(tv, a.v, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(to, a.d_o, p.tok0, p.ts, p.L, tid);
-        if (VSPLIT) {
-            walk_gload<false, kThreads>(tv2, a.v_lo, p.tok0, p.ts, p.L, tid);
-            walk_gload<false, kThreads>(tdh, a.du_h, p.wtok0, 1, p.L, tid);
-            walk_gload<false, kThreads>(tdl, a.du_l, p.wtok0, 1, p.L, tid);
+// inter product of the state with rows kept in two planes (head Qh, remainder Ql), the state blocks converted once:
+// O^T[i][t] = sum_v S[i][v] (Qh + Ql)[t][v], remainder x remainder left out
+__device__ __forceinline__ void walk_inter_split(f32x16 (&O)[2], const f32x16 (&S)[4], const uint16_t* Qh, const uint16_t* Ql, int n,
+                                                 int half) {
+    O[0] = f32x16{0};
+    O[1] = f32x16{0};
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+        _Pragma("unroll") for (int p = 0; p < 2; ++p) {
+            u32x4 hi, lo;
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {
+                const float x0 = S[ib][8 * p + 2 * e], x1 = S[ib][8 * p + 2 * e + 1];
+                hi[e] = pack2(x0, x1);
+                lo[e] = pack2(x0 - bf16_lo(hi[e]), x1 - bf16_hi(hi[e]));
+            }
+            const bf16x8 sh = __builtin_bit_cast(bf16x8, hi), sl = __builtin_bit_cast(bf16x8, lo);
+            const bf16x8 qh0 = frag_perm(Qh, LD, n, 32 * ib + 16 * p, half), qh1 = frag_perm(Qh, LD, 32 + n, 32 * ib + 16 * p, half);
+            const bf16x8 ql0 = frag_perm(Ql, LD, n, 32 * ib + 16 * p, half), ql1 = frag_perm(Ql, LD, 32 + n, 32 * ib + 16 * p, half);
+            O[0] = mfma(sh, qh0, O[0]);
+            O[1] = mfma(sh, qh1, O[1]);
+            O[0] = mfma(sl, qh0, O[0]);
+            O[1] = mfma(sl, qh1, O[1]);
+            O[0] = mfma(sh, ql0, O[0]);
+            O[1] = mfma(sh, ql1, O[1]);
         }
-        // rows i in [32w, 32w+32) of dS: A operands [m = i][k = v]
-        const uint16_t* dS = a.dstates + p.slot * D * D;
-        _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-            dsfrag[ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(dS + state_frag_off(wave, ks, lane)));
-    };
-    gload(0);
-
-    for (int kk = 0; kk < cnt; ++kk) {
-        const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
-        const int L = cp.L;
-        walk_commit<kThreads>(Q, tq, L, tid);
-        walk_commit<kThreads>(K, tk, L, tid);
-        walk_commit<kThreads>(V, tv, L, tid);
-        walk_commit<kThreads>(dO, to, L, tid);
-        if (VSPLIT) {
-            walk_commit<kThreads>(V2, tv2, L, tid);
-            walk_commit<kThreads>(dUh, tdh, L, tid);
-            walk_commit<kThreads>(dUl, tdl, L, tid);
-        } else {
-            // the dS rows of this wave, for the waves that contract over i (dv)
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
-        }
-        if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
-        __syncthreads();  // (1) tiles, dS rows and decay tables of this chunk are in LDS
-        const float bC = DEC ? bs[C] : 0.f;
-
-        PackedBlock resq[2], resk[2], resv[2];
-        f32x16 aq[2], ak[2] = {{0}, {0}};
-        float pk_inter[2] = {0.f, 0.f};
-        // ---- score blocks: G = (dO V^T) * D by waves 0, 1, 2 and As = (Q K^T) * D by waves 3, 0, 1 (blocks (0,0),
-        // (1,0), (1,1) in that order), mask and decay on the accumulators, to areas of their own
-        {
-            const int gi = wave, ai = (wave + 1) & 3;  // block index of this wave in either set; 3 = none
-            if (gi < 3) {
-                const int pjb = gi ? 1 : 0, prb = gi == 2 ? 1 : 0;
-                f32x16 G = score_block2(V, 32 * prb, dO, 32 * pjb, n, half);  // D[m = r][n = j] = v_r . d_o_j
-                if (VSPLIT) G = score_block2(V2, 32 * prb, dO, 32 * pjb, n, half, G);
-                walk_mask<DEC>(G, 32 * prb, 32 * pjb + n, bs, half);
-                store_block_t_split(Gh, Gl, LDP, 32 * pjb + n, 32 * prb, half, G);
-            }
-            if (ai < 3) {
-                const int pjb = ai ? 1 : 0, prb = ai == 2 ? 1 : 0;
-                f32x16 As = score_block2(K, 32 * prb, Q, 32 * pjb, n, half);  // D[m = r][n = j] = k_r . q_j
-                walk_mask<DEC>(As, 32 * prb, 32 * pjb + n, bs, half);
-                store_block_t_split(Ah, Al, LDP, 32 * pjb + n, 32 * prb, half, As);
-            }
-        }
-        // ---- inter parts: dq^T[i][j] from the state in registers, dk^T[i][r] from the dS rows
-        walk_inter<DEC>(aq, S, dO, bs, n, half);
-        PackedBlock resw[2], reswl[2];
-        if (VSPLIT) {  // dW^T[i][t] = -sum_v S[i][v] dU[t][v]
-            f32x16 dw[2];
-            walk_inter<false>(dw, S, dUh, bs, n, half);
-            walk_inter<false, true>(dw, S, dUl, bs, n, half);
-            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) dw[nb][x] = -dw[nb][x];
-                resw[nb] = pack_block(dw[nb]);
-                _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                    dw[nb][4 * g + 0] -= bf16_lo(resw[nb].v[g].x);
-                    dw[nb][4 * g + 1] -= bf16_hi(resw[nb].v[g].x);
-                    dw[nb][4 * g + 2] -= bf16_lo(resw[nb].v[g].y);
-                    dw[nb][4 * g + 3] -= bf16_hi(resw[nb].v[g].y);
-                }
-                reswl[nb] = pack_block(dw[nb]);
-            }
-        }
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            const int tok = 32 * nb + n;
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
-            if (VSPLIT) {
-                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V2, LD, tok, 16 * ks + 8 * half), ak[nb]);
-            }
-            if (DEC) {
-                const float wk = wo[tok];
-                _Pragma("unroll") for (int x = 0; x < 16; ++x) ak[nb][x] *= wk;
-            }
-            if (WANT_DG) pk_inter[nb] = row_dot(K, tok, wave, half, ak[nb]);
-        }
-        // ---- <S, dS> over this wave's rows i: lanes l and l + 32 exchange halves of the dS fragments so that
-        // each lane holds dS at exactly the (i, v) of its state registers
-        if (WANT_DG) {
-            float z = 0.f;
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                const u32x4 f = __builtin_bit_cast(u32x4, dsfrag[ks]);
-                const auto s0 = __builtin_amdgcn_permlane32_swap(f[0], f[2], false, false);
-                const auto s1 = __builtin_amdgcn_permlane32_swap(f[1], f[3], false, false);
-                const f32x16& sv = S[ks >> 1];
-                const int b = 8 * (ks & 1);
-                z += sv[b + 0] * bf16_lo(s0[0]) + sv[b + 1] * bf16_hi(s0[0]) + sv[b + 2] * bf16_lo(s1[0]) + sv[b + 3] * bf16_hi(s1[0]) +
-                     sv[b + 4] * bf16_lo(s0[1]) + sv[b + 5] * bf16_hi(s0[1]) + sv[b + 6] * bf16_lo(s1[1]) + sv[b + 7] * bf16_hi(s1[1]);
-            }
-            for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
-            if (lane == 0) zred[wave] = z;
-        }
-        // ---- the state moves on to the end of the chunk (roles: key = v, value = k)
-        walk_update<DEC, true, VSPLIT>(S, V, K, wo, bC, wave, lane, half, V2);
-        // the next chunk's rows are requested now: the dS registers are free, the tile registers have been since (1)
-        if (kk + 1 < cnt) gload(kk + 1);
-        __syncthreads();  // (2) G and As are in LDS
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            const int tok = 32 * nb + n;
-            // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r]: keys r >= 32 never reach queries j < 32
-            _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {
-                const bf16x8 kt = frag_tr(K, LD, 16 * ks, 32 * wave, lane);
-                aq[nb] = mfma(kt, frag(Gh, LDP, tok, 16 * ks + 8 * half), aq[nb]);
-                aq[nb] = mfma(kt, frag(Gl, LDP, tok, 16 * ks + 8 * half), aq[nb]);
-            }
-            // dk^T[i][r] += sum_{j>=r} Q^T[i][j] G[j][r]: queries j < 32 never see keys r >= 32
-            _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
-                const bf16x8 qt = frag_tr(Q, LD, 16 * ks, 32 * wave, lane);
-                ak[nb] = mfma(qt, frag_tr(Gh, LDP, 16 * ks, 32 * nb, lane), ak[nb]);  // B[k = j][n = r] = G[j][r]
-                ak[nb] = mfma(qt, frag_tr(Gl, LDP, 16 * ks, 32 * nb, lane), ak[nb]);
-            }
-            if (WANT_DG) {
-                float pq = row_dot(Q, tok, wave, half, aq[nb]), pk = row_dot(K, tok, wave, half, ak[nb]);
-                pq += __shfl_xor(pq, 32, 64);
-                pk += __shfl_xor(pk, 32, 64);
-                const float pi = pk_inter[nb] + __shfl_xor(pk_inter[nb], 32, 64);
-                if (half == 0) {
-                    red[(wave * 3 + 0) * 64 + tok] = pq;
-                    red[(wave * 3 + 1) * 64 + tok] = pk;
-                    red[(wave * 3 + 2) * 64 + tok] = pi;
-                }
-            }
-            resq[nb] = pack_block(aq[nb]);
-            resk[nb] = pack_block(ak[nb]);
-            if (VSPLIT) {  // the key gradient leaves as head + remainder (the caller adds to it before rounding)
-                _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                    ak[nb][4 * g + 0] -= bf16_lo(resk[nb].v[g].x);
-                    ak[nb][4 * g + 1] -= bf16_hi(resk[nb].v[g].x);
-                    ak[nb][4 * g + 2] -= bf16_lo(resk[nb].v[g].y);
-                    ak[nb][4 * g + 3] -= bf16_hi(resk[nb].v[g].y);
-                }
-                resv[nb] = pack_block(ak[nb]);
-            }
-        }
-        // ---- dv^T[v][r], v in this wave's slice: the inter part contracts over the rows i of dS (token-major read of
-        // the dS area), the intra part over the queries
-        if (!VSPLIT) {
-            f32x16 av[2] = {{0}, {0}};
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 dst = frag_tr(dSt, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 16 ks + ..
-                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-                    av[nb] = mfma(dst, frag(K, LD, 32 * nb + n, 16 * ks + 8 * half), av[nb]);
-            }
-            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-                const int r = 32 * nb + n;
-                if (DEC) {
-                    const float wk = wo[r];
-                    _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
-                }
-                // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]: queries j < 32 never see keys r >= 32
-                _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
-                    const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
-                    av[nb] = mfma(dot, frag_tr(Ah, LDP, 16 * ks, 32 * nb, lane), av[nb]);  // B[k = j][n = r] = As[j][r]
-                    av[nb] = mfma(dot, frag_tr(Al, LDP, 16 * ks, 32 * nb, lane), av[nb]);
-                }
-                resv[nb] = pack_block(av[nb]);
-            }
-        }
-        __syncthreads();  // (3) every wave is done with the tiles
-        _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-            store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
-            store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
-            store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
-            if (VSPLIT) {
-                store_packed(dO, LD, 32 * nb + n, 32 * wave, half, resw[nb]);
-                store_packed(V2, LD, 32 * nb + n, 32 * wave, half, reswl[nb]);
-            }
-        }
-        __syncthreads();  // (4)
-        // every thread reads back exactly the stage pieces that its own next walk_commit overwrites
-        walk_store<false>(a.dq, Q, cp.tok0, cp.ts, L, tid);
-        walk_store<false>(a.dk, K, cp.tok0, cp.ts, L, tid);
-        walk_store<false>(a.dv, V, cp.tok0, cp.ts, L, tid);
-        if (VSPLIT) {
-            walk_store<false>(a.dw_h, dO, cp.wtok0, 1, L, tid);
-            walk_store<false>(a.dw_l, V2, cp.wtok0, 1, L, tid);
-        }
-        if (WANT_DG && tid < 64) {
-            // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
-            float w = 0.f, tail = 0.f, z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
-            _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
-                w += red[(wv * 3 + 0) * 64 + tid] - red[(wv * 3 + 1) * 64 + tid];
-                tail += red[(wv * 3 + 2) * 64 + tid];
-            }
-            for (int off = 32; off > 0; off >>= 1) tail += __shfl_xor(tail, off, 64);
-            float sfx = w;  // suffix sum of w over tokens >= tid
-            for (int off = 1; off < 64; off <<= 1) {
-                const float y = __shfl_down(sfx, off, 64);
-                if (tid + off < 64) sfx += y;
-            }
-            float dgv = tid < L ? sfx + tail + __expf(bC) * z : 0.f;
-            if (d.kind == 1) {
-                // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
-                for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
-                if (tid == 0) a.dg_tok[cp.slot] = dgv;
-            } else if (tid < L) {
-                a.dg_tok[cp.tok0 + size_t(tid) * cp.ts] = dgv;
-            }
-        }
-    }
 }
 
-template <bool DEC, bool WANT_DG, bool VSPLIT = false>
-__global__ __launch_bounds__(kThreads, 1) void mk_walk_grad(Dims d, GradArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    walk_grad_body<DEC, WANT_DG, VSPLIT>(d, a, blockIdx.y, blockIdx.x, smem);
-}
-
-// The same chunk adjoint by eight waves, two per SIMD, for the plain (single value plane) case.  The work of a chunk is
-// split by function, not by data, so that neither group needs the other's registers:
+// Gradient walker kernel: eight waves, two per SIMD.  The work of a chunk is split by function, not by data, so that
+// neither group needs the other's registers:
 //   waves 0..3 (wave w: key features i in [32w, 32w+32)) carry the state; they form dq (inter part from the state, intra
-//              part from G), <S, dS> (dS read back from the LDS rows) and move the state on;
+//              part from G), <S, dS>, with VSPLIT dW, and move the state on;
 //   waves 4..7 (wave w: the same i slice for dk, value features v in [32w, 32w+32) for dv) hold the dS rows of the chunk;
-//              they compute the six score blocks (G, As), dk and dv.
+//              they compute the score blocks (G, As), dk and dv.
 // Each group runs a loop of its own with the same four barriers per chunk, so a SIMD always has one wave of either
 // kind to issue from: the matrix, vector and LDS work of the two overlap instead of queueing behind one wave's waits.
-// All 512 threads share the tile traffic (global -> registers -> LDS, stage -> global).  LDS as for mk_walk_grad.
+// Plain case: all 512 threads share the tile traffic (global -> registers -> LDS, stage -> global), and the carrier
+// waves read dS for <S, dS> at the (i, v) of their state registers from the LDS rows.
+// VSPLIT: the carrier waves' registers are full (state, dq, dW), so the other group moves most of the tiles; the carrier
+// waves form <S, dS> (dS by loads of their own from the fragment-major array, which the other group has just pulled
+// into L2: the LDS area of the dS rows holds dU) and dW before barrier (2), and dq and the state update after it, so
+// that the accumulators of dW and dq never coexist.
 constexpr int kGrad8Threads = 512;
 
-template <bool DEC, bool WANT_DG>
-__global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradArgs a) {
+template <bool DEC, bool WANT_DG, bool VSPLIT = false>
+__global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = Q + C * LD;
@@ -694,35 +466,88 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradAr
     uint16_t* dSt = Al + C * LDP;    // [i][v] rows of dS, all 128
     float* bs = reinterpret_cast<float*>(dSt + D * LD);
     float* wo = bs + C + 4;
-    float* red = wo + C + 4;         // [i slice][3][64]: q.dq, k.dk, k.dk_inter partial sums over the slice
-    float* zred = red + 4 * 3 * 64;  // [i slice]: partial <S, dS>
-    constexpr int NT = kGrad8Threads;
+    float* red = wo + C + 4;         // [i slice][2][64]: q.dq, k.dk partial sums over the slice
+    float* zred = red + 4 * 2 * 64;  // [i slice]: partial <S, dS>
+    uint16_t* V2 = reinterpret_cast<uint16_t*>(smem + kWalkGradLds);  // VSPLIT only
+    uint16_t* dUh = dSt;             // VSPLIT: 64 x LD each, over the dS rows
+    uint16_t* dUl = dSt + C * LD;
+    uint16_t* Wl = Ah;               // VSPLIT (no As): stage of the remainder plane of dW, 64 x LD
+    static_assert(2 * C * LDP >= C * LD, "the dW stage fits the area of As");
+    constexpr int NT = VSPLIT ? 256 : kGrad8Threads;  // threads that share the tile traffic
 
     const int seq = blockIdx.y, seg = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, n = lane & 31, half = lane >> 5;
-    const bool carrier = tid < 256;  // waves 0..3
+    const int tid = threadIdx.x, wave = (tid >> 6) & 3;
+    int lane = tid & 63, n = lane & 31, half = lane >> 5;
+    int tt = VSPLIT ? tid & 255 : tid;  // index among the threads that move tiles
+    const bool carrier = tid < 256;     // waves 0..3
+    // VSPLIT: every LDS access pattern keeps a lane-dependent base address per 64 KiB window of the 159 KiB
+    // in use, and with the state, two sets of accumulators and the tiles in flight there is no room to keep a hundred of
+    // them alive across the loop.  Hiding the lane id from the optimiser at the phase boundaries makes it recompute the
+    // addresses of a phase inside the phase (a few vector instructions each) instead of spilling them.
+    auto fresh = [&]() {
+        if (VSPLIT) {
+            asm volatile("" : "+v"(lane));
+            n = lane & 31;
+            half = lane >> 5;
+            tt = 64 * wave + lane;
+        }
+    };
     const SeqWalk walk = seq_walk(d, seq);
     const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
     if (cnt <= 0) return;
 
-    TileRegs tq, tk, tv, to;
-    auto gload_tiles = [&](const ChunkPos& p) {
-        walk_gload<false, NT>(tq, a.q, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, NT>(tk, a.k, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, NT>(tv, a.v, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, NT>(to, a.d_o, p.tok0, p.ts, p.L, tid);
+    // VSPLIT: the carrier group moves the head plane of dU in, and d_o when it has no decay tables to keep (its registers
+    // are full otherwise); the other group moves the other tiles in and all five out
+    constexpr bool kCarrierMovesDo = !DEC;
+    TileRegs tq, tk, tv, to, tv2, tdh, tdl;
+    auto gload_tiles = [&](const ChunkPos& p, bool first_group) {
+        if (!VSPLIT || !first_group) {
+            walk_gload<false, NT>(tq, a.q, p.tok0, p.ts, p.L, tt);
+            walk_gload<false, NT>(tk, a.k, p.tok0, p.ts, p.L, tt);
+            walk_gload<false, NT>(tv, a.v, p.tok0, p.ts, p.L, tt);
+        }
+        if (!VSPLIT || first_group == kCarrierMovesDo) walk_gload<false, NT>(to, a.d_o, p.tok0, p.ts, p.L, tt);
+        if (VSPLIT && first_group) walk_gload<false, NT>(tdh, a.du_h, p.wtok0, 1, p.L, tt);
+        if (VSPLIT && !first_group) {
+            walk_gload<false, NT>(tv2, a.v_lo, p.tok0, p.ts, p.L, tt);
+            walk_gload<false, NT>(tdl, a.du_l, p.wtok0, 1, p.L, tt);
+        }
     };
-    auto commit_tiles = [&](int L) {
-        walk_commit<NT>(Q, tq, L, tid);
-        walk_commit<NT>(K, tk, L, tid);
-        walk_commit<NT>(V, tv, L, tid);
-        walk_commit<NT>(dO, to, L, tid);
+    auto commit_tiles = [&](int L, bool first_group) {
+        if (!VSPLIT || !first_group) {
+            walk_commit<NT>(Q, tq, L, tt);
+            walk_commit<NT>(K, tk, L, tt);
+            walk_commit<NT>(V, tv, L, tt);
+        }
+        if (!VSPLIT || first_group == kCarrierMovesDo) walk_commit<NT>(dO, to, L, tt);
+        if (VSPLIT && first_group) walk_commit<NT>(dUh, tdh, L, tt);
+        if (VSPLIT && !first_group) {
+            walk_commit<NT>(V2, tv2, L, tt);
+            walk_commit<NT>(dUl, tdl, L, tt);
+        }
     };
-    auto store_tiles = [&](const ChunkPos& cp) {
-        // every thread reads back exactly the stage pieces that its own next commit overwrites
-        walk_store<false, NT>(a.dq, Q, cp.tok0, cp.ts, cp.L, tid);
-        walk_store<false, NT>(a.dk, K, cp.tok0, cp.ts, cp.L, tid);
-        walk_store<false, NT>(a.dv, V, cp.tok0, cp.ts, cp.L, tid);
+    auto store_tiles = [&](const ChunkPos& cp, bool first_group) {
+        // Every thread reads back exactly the stage pieces that its own next commit overwrites: no barrier between this and
+        // the next chunk's commit.  (VSPLIT: the head of dW is staged over the plane of dU that the carrier group commits,
+        // so that group stores it; the stage of the remainder is next written after barrier (1).)
+        if (!VSPLIT || !first_group) {
+            walk_store<false, NT>(a.dq, Q, cp.tok0, cp.ts, cp.L, tt);
+            walk_store<false, NT>(a.dk, K, cp.tok0, cp.ts, cp.L, tt);
+            walk_store<false, NT>(a.dv, V, cp.tok0, cp.ts, cp.L, tt);
+        }
+        if (VSPLIT && first_group) walk_store<false, NT>(a.dw_h, dUh, cp.wtok0, 1, cp.L, tt);
+        if (VSPLIT && !first_group) walk_store<false, NT>(a.dw_l, Wl, cp.wtok0, 1, cp.L, tt);
+    };
+    // head of a block; the block keeps its remainder
+    auto split_block = [](f32x16& x) {
+        const PackedBlock h = pack_block(x);
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            x[4 * g + 0] -= bf16_lo(h.v[g].x);
+            x[4 * g + 1] -= bf16_hi(h.v[g].x);
+            x[4 * g + 2] -= bf16_lo(h.v[g].y);
+            x[4 * g + 3] -= bf16_hi(h.v[g].y);
+        }
+        return h;
     };
 
     if (carrier) {
@@ -738,37 +563,12 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradAr
         auto gload = [&](int kk) {
             const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
             if (DEC) gval = a.g[d.kind == 1 ? size_t(walk.bh % d.H) : p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
-            gload_tiles(p);
+            gload_tiles(p, true);
         };
-        gload(0);
-        for (int kk = 0; kk < cnt; ++kk) {
-            const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
-            const int L = cp.L;
-            commit_tiles(L);
-            if (DEC && tid < 64) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
-            __syncthreads();  // (1) tiles, dS rows and decay tables of this chunk are in LDS
-            const float bC = DEC ? bs[C] : 0.f;
-            f32x16 aq[2];
-            walk_inter<DEC>(aq, S, dO, bs, n, half);
-            if (WANT_DG) {  // <S, dS> over this wave's rows i, dS at the (i, v) of the state registers from the LDS rows
-                float z = 0.f;
-                _Pragma("unroll") for (int vb = 0; vb < 4; ++vb)
-                    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                        const u32x2 x = *reinterpret_cast<const u32x2*>(dSt + (32 * wave + n) * LD + 32 * vb + 8 * g + 4 * half);
-                        z += S[vb][4 * g] * bf16_lo(x.x) + S[vb][4 * g + 1] * bf16_hi(x.x) + S[vb][4 * g + 2] * bf16_lo(x.y) +
-                             S[vb][4 * g + 3] * bf16_hi(x.y);
-                    }
-                for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
-                if (lane == 0) zred[wave] = z;
-            }
-            // the state moves on to the end of the chunk (roles: key = v, value = k)
-            walk_update<DEC, true>(S, V, K, wo, bC, wave, lane, half);
-            if (kk + 1 < cnt) gload(kk + 1);
-            __syncthreads();  // (2) G and As are in LDS
-            PackedBlock resq[2];
+        // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r] (keys r >= 32 never reach queries j < 32), its share of the decay gradient
+        auto dq_intra = [&](f32x16 (&aq)[2], PackedBlock (&resq)[2]) {
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 const int tok = 32 * nb + n;
-                // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r]: keys r >= 32 never reach queries j < 32
                 _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {
                     const bf16x8 kt = frag_tr(K, LD, 16 * ks, 32 * wave, lane);
                     aq[nb] = mfma(kt, frag(Gh, LDP, tok, 16 * ks + 8 * half), aq[nb]);
@@ -777,28 +577,96 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradAr
                 if (WANT_DG) {
                     float pq = row_dot(Q, tok, wave, half, aq[nb]);
                     pq += __shfl_xor(pq, 32, 64);
-                    if (half == 0) red[(wave * 3 + 0) * 64 + tok] = pq;
+                    if (half == 0) red[(wave * 2 + 0) * 64 + tok] = pq;
                 }
                 resq[nb] = pack_block(aq[nb]);
             }
+        };
+        // <S, dS> with the state at the END of the chunk, over this wave's rows i: together with the running sums of
+        // q.dq - k.dk this is the whole decay gradient (<e^{b_C} S + S_chunk, dS> = e^{b_C} <S, dS> + sum_r k_r.dk_r^{inter}).
+        // dS at the (i, v) of the state registers: from the LDS rows, or (VSPLIT) from the registers dsz
+        auto state_dot = [&](const u32x2 (&dsz)[16]) {
+            float z = 0.f;
+            _Pragma("unroll") for (int vb = 0; vb < 4; ++vb)
+                _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                    const u32x2 x = VSPLIT ? dsz[4 * vb + g]
+                                           : *reinterpret_cast<const u32x2*>(dSt + (32 * wave + n) * LD + 32 * vb + 8 * g + 4 * half);
+                    z += S[vb][4 * g] * bf16_lo(x.x) + S[vb][4 * g + 1] * bf16_hi(x.x) + S[vb][4 * g + 2] * bf16_lo(x.y) +
+                         S[vb][4 * g + 3] * bf16_hi(x.y);
+                }
+            for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off, 64);
+            if (lane == 0) zred[wave] = z;
+        };
+        gload(0);
+        for (int kk = 0; kk < cnt; ++kk) {
+            const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
+            const int L = cp.L;
+            fresh();
+            commit_tiles(L, true);
+            if (DEC && tid < 64) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
+            __syncthreads();  // (1) tiles, dS rows and decay tables of this chunk are in LDS
+            fresh();
+            const float bC = DEC ? bs[C] : 0.f;
+            f32x16 aq[2];
+            PackedBlock resw[2], resq[2];
+            if (VSPLIT) {
+                // dW^T[i][t] = -sum_v S[i][v] dU[t][v]; the remainder plane is staged at once (nobody else uses its area)
+                f32x16 dw[2];
+                walk_inter_split(dw, S, dUh, dUl, n, half);
+                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                    _Pragma("unroll") for (int x = 0; x < 16; ++x) dw[nb][x] = -dw[nb][x];
+                    resw[nb] = split_block(dw[nb]);
+                    store_packed(Wl, LD, 32 * nb + n, 32 * wave, half, pack_block(dw[nb]));
+                }
+            } else {
+                walk_inter<DEC>(aq, S, dO, bs, n, half);
+            }
+            u32x2 dsz[16];  // VSPLIT: dS at the (i, v) of the state registers, four consecutive v per load
+            if (!VSPLIT) {
+                // the state moves on to the end of the chunk (roles: key = v, value = k)
+                walk_update<DEC, true>(S, V, K, wo, bC, wave, lane, half);
+                if (WANT_DG) state_dot(dsz);
+                if (kk + 1 < cnt) gload(kk + 1);
+            }
+            __syncthreads();  // (2) G and As are in LDS
+            fresh();
+            if (VSPLIT) {
+                // the planes of dU are dead: the head of dW is staged over the first
+                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) store_packed(dUh, LD, 32 * nb + n, 32 * wave, half, resw[nb]);
+                walk_inter<DEC>(aq, S, dO, bs, n, half);
+                dq_intra(aq, resq);
+                fresh();
+                if (WANT_DG) {
+                    const uint16_t* dS = a.dstates + cp.slot * D * D;
+                    _Pragma("unroll") for (int vb = 0; vb < 4; ++vb)
+                        _Pragma("unroll") for (int g = 0; g < 4; ++g)
+                            dsz[4 * vb + g] = *reinterpret_cast<const u32x2*>(dS + state_frag_off(wave, 2 * vb + (g >> 1), 32 * (g & 1) + n) + 4 * half);
+                }
+                walk_update<DEC, true, true>(S, V, K, wo, bC, wave, lane, half, V2);
+                if (WANT_DG) state_dot(dsz);
+                if (kk + 1 < cnt) gload(kk + 1);
+            } else {
+                dq_intra(aq, resq);
+            }
             __syncthreads();  // (3) every wave is done with the tiles
-            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
+            fresh();
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
+            }
             __syncthreads();  // (4)
-            store_tiles(cp);
+            fresh();
+            store_tiles(cp, true);
             if (WANT_DG && tid < 64) {
                 // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
-                float w = 0.f, tail = 0.f, z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
-                _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) {
-                    w += red[(wv * 3 + 0) * 64 + tid] - red[(wv * 3 + 1) * 64 + tid];
-                    tail += red[(wv * 3 + 2) * 64 + tid];
-                }
-                for (int off = 32; off > 0; off >>= 1) tail += __shfl_xor(tail, off, 64);
+                float w = 0.f;
+                const float z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
+                _Pragma("unroll") for (int wv = 0; wv < 4; ++wv) w += red[(wv * 2 + 0) * 64 + tid] - red[(wv * 2 + 1) * 64 + tid];
                 float sfx = w;  // suffix sum of w over tokens >= tid
                 for (int off = 1; off < 64; off <<= 1) {
                     const float y = __shfl_down(sfx, off, 64);
                     if (tid + off < 64) sfx += y;
                 }
-                float dgv = tid < L ? sfx + tail + __expf(bC) * z : 0.f;
+                float dgv = tid < L ? sfx + z : 0.f;
                 if (d.kind == 1) {
                     // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
                     for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
@@ -812,7 +680,7 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradAr
         bf16x8 dsfrag[8];
         auto gload = [&](int kk) {
             const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
-            gload_tiles(p);
+            gload_tiles(p, false);
             // rows i in [32w, 32w+32) of dS: A operands [m = i][k = v]
             const uint16_t* dS = a.dstates + p.slot * D * D;
             _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
@@ -823,6 +691,7 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradAr
             const int pjb = bi ? 1 : 0, prb = bi == 2 ? 1 : 0;
             // D[m = r][n = j] = v_r . d_o_j  or  k_r . q_j
             f32x16 P = isG ? score_block2(V, 32 * prb, dO, 32 * pjb, n, half) : score_block2(K, 32 * prb, Q, 32 * pjb, n, half);
+            if (VSPLIT && isG) P = score_block2(V2, 32 * prb, dO, 32 * pjb, n, half, P);
             walk_mask<DEC>(P, 32 * prb, 32 * pjb + n, bs, half);
             store_block_t_split(isG ? Gh : Ah, isG ? Gl : Al, LDP, 32 * pjb + n, 32 * prb, half, P);
         };
@@ -830,40 +699,52 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradAr
         for (int kk = 0; kk < cnt; ++kk) {
             const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
             const int L = cp.L;
-            commit_tiles(L);
-            // the dS rows of this wave, for the contractions over i (dv, <S, dS>)
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
-                *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
+            fresh();
+            commit_tiles(L, false);
+            if (!VSPLIT) {
+                // the dS rows of this wave, for the contractions over i (dv, <S, dS>)
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks)
+                    *reinterpret_cast<bf16x8*>(dSt + (32 * wave + n) * LD + 16 * ks + 8 * half) = dsfrag[ks];
+            }
             __syncthreads();  // (1)
-            // G = (dO V^T) * D first (the other group waits for it at (2)), then As = (Q K^T) * D
-            if (wave < 3) score(true, wave);
-            else score(false, 0);
-            if (wave < 2) score(false, wave + 1);
+            fresh();
+            // G = (dO V^T) * D first (the other group waits for it at (2)), then As = (Q K^T) * D, which only dv needs
+            if (VSPLIT) {
+                if (wave < 3) score(true, wave);
+            } else {
+                if (wave < 3) score(true, wave);
+                else score(false, 0);
+                if (wave < 2) score(false, wave + 1);
+            }
             // inter parts: dk^T[i][r] from the dS rows in registers, dv^T[v][r] from the transposed read of the LDS rows
             f32x16 ak[2] = {{0}, {0}}, av[2] = {{0}, {0}};
-            float pk_inter[2] = {0.f, 0.f};
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 const int tok = 32 * nb + n;
                 _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V, LD, tok, 16 * ks + 8 * half), ak[nb]);
+                if (VSPLIT) {
+                    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) ak[nb] = mfma(dsfrag[ks], frag(V2, LD, tok, 16 * ks + 8 * half), ak[nb]);
+                }
                 if (DEC) {
                     const float wk = wo[tok];
                     _Pragma("unroll") for (int x = 0; x < 16; ++x) ak[nb][x] *= wk;
                 }
-                if (WANT_DG) pk_inter[nb] = row_dot(K, tok, wave, half, ak[nb]);
             }
             if (kk + 1 < cnt) gload(kk + 1);  // the dS registers are free
-            _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 dst = frag_tr(dSt, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 16 ks + ..
-                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
-                    av[nb] = mfma(dst, frag(K, LD, 32 * nb + n, 16 * ks + 8 * half), av[nb]);
-            }
-            if (DEC) {
-                _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
-                    const float wk = wo[32 * nb + n];
-                    _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
+            if (!VSPLIT) {
+                _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) {
+                    const bf16x8 dst = frag_tr(dSt, LD, 16 * ks, 32 * wave, lane);  // dS^T[v][i], i = 16 ks + ..
+                    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)
+                        av[nb] = mfma(dst, frag(K, LD, 32 * nb + n, 16 * ks + 8 * half), av[nb]);
+                }
+                if (DEC) {
+                    _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
+                        const float wk = wo[32 * nb + n];
+                        _Pragma("unroll") for (int x = 0; x < 16; ++x) av[nb][x] *= wk;
+                    }
                 }
             }
             __syncthreads();  // (2) G and As are in LDS
+            fresh();
             PackedBlock resk[2], resv[2];
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 const int tok = 32 * nb + n;
@@ -876,28 +757,31 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad8(Dims d, GradAr
                 if (WANT_DG) {
                     float pk = row_dot(K, tok, wave, half, ak[nb]);
                     pk += __shfl_xor(pk, 32, 64);
-                    const float pi = pk_inter[nb] + __shfl_xor(pk_inter[nb], 32, 64);
-                    if (half == 0) {
-                        red[(wave * 3 + 1) * 64 + tok] = pk;
-                        red[(wave * 3 + 2) * 64 + tok] = pi;
+                    if (half == 0) red[(wave * 2 + 1) * 64 + tok] = pk;
+                }
+                if (VSPLIT) {  // the key gradient leaves as head + remainder (the caller adds to it before rounding)
+                    resk[nb] = split_block(ak[nb]);
+                    resv[nb] = pack_block(ak[nb]);
+                } else {
+                    resk[nb] = pack_block(ak[nb]);
+                    // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]
+                    _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
+                        const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
+                        av[nb] = mfma(dot, frag_tr(Ah, LDP, 16 * ks, 32 * nb, lane), av[nb]);  // B[k = j][n = r] = As[j][r]
+                        av[nb] = mfma(dot, frag_tr(Al, LDP, 16 * ks, 32 * nb, lane), av[nb]);
                     }
+                    resv[nb] = pack_block(av[nb]);
                 }
-                resk[nb] = pack_block(ak[nb]);
-                // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]
-                _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
-                    const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
-                    av[nb] = mfma(dot, frag_tr(Ah, LDP, 16 * ks, 32 * nb, lane), av[nb]);  // B[k = j][n = r] = As[j][r]
-                    av[nb] = mfma(dot, frag_tr(Al, LDP, 16 * ks, 32 * nb, lane), av[nb]);
-                }
-                resv[nb] = pack_block(av[nb]);
             }
             __syncthreads();  // (3)
+            fresh();
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
                 store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
             }
             __syncthreads();  // (4)
-            store_tiles(cp);
+            fresh();
+            store_tiles(cp, false);
         }
     }
 }
