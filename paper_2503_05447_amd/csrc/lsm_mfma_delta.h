@@ -346,10 +346,12 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
         __syncthreads();  // (A) tiles and decay tables of this chunk are in LDS
         const float bC = DEC ? bs[C] : 0.f;
 
-        // pseudo-values of this wave's value columns: U^T[v][t] = Uhat[t][v] - sum_i S[i][v] What[t][i]
+        // pseudo-values of this wave's value columns: U^T[v][t] = Uhat[t][v] - sum_i S[i][v] What[t][i]; the inter part
+        // of the output comes out of the same pass over the state blocks (one conversion to bf16 head + remainder)
+        f32x16 O[2];
         {
             f32x16 Wacc[2];
-            walk_inter<false>(Wacc, S, Wh, bs, n, half);
+            walk_inter_pair<DEC, MODE == 0>(Wacc, O, S, Wh, Q, bs, n, half);
             _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
                 f32x16 u;
                 _Pragma("unroll") for (int g = 0; g < 4; ++g) {
@@ -372,8 +374,6 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
             }
         }
         if (MODE == 0) {
-            f32x16 O[2];
-            walk_inter<DEC>(O, S, Q, bs, n, half);
             walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
             __syncthreads();  // (C) scores are in LDS; nobody reads Q any more (this wave's columns of U are its own)
             _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
@@ -397,6 +397,150 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkAr
         return;
     }
     if (a.edge_out && seg == nsq - 1) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+}
+
+// The walk itself (MODE 0 above) by eight waves, two per SIMD, split by function:
+//   waves 0..3 carry the state (wave w: value columns [32w, 32w+32)): both inter products, the pseudo-values, the intra
+//              part of the output and the state update - the chain that every chunk has to go through in order;
+//   waves 4..7 do everything that does not need the state: all tile traffic (global -> registers -> LDS one chunk ahead,
+//              output stage and pseudo-values -> global), the decay tables, the three score blocks.
+// A chunk has two phases.  In the first the carrier waves read Q, What and Uhat (inter products, pseudo-values) while the
+// others compute the scores and store the previous chunk's output; in the second the carrier waves read only the scores,
+// K and their own pseudo-values (intra part, state update), so the others overwrite Q, What and Uhat with the next
+// chunk's rows and rebuild the decay tables (two sets, used in turn) meanwhile.  Only K, which both phases read, is
+// committed between two chunks.  The output has a stage of its own for the same reason.
+// LDS: Q | K | U head | U remainder | What | output stage (64 x LD bf16 each) | Uhat (64 x LDU fp32) | scores head |
+// scores remainder (64 x LDP) | two sets of (bs, wo)
+constexpr int kDeltaTab = 2 * C + 8;
+constexpr int kDeltaWalk8Lds = (6 * C * LD + 2 * C * LDP) * 2 + C * LDU * 4 + 2 * kDeltaTab * 4;
+static_assert(kDeltaWalk8Lds <= 160 * 1024, "one workgroup's LDS");
+
+template <bool DEC>
+__global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* K = Q + C * LD;
+    uint16_t* V = K + C * LD;    // pseudo-values U of this chunk, bf16 head
+    uint16_t* Vl = V + C * LD;   // and remainder
+    uint16_t* Wh = Vl + C * LD;
+    uint16_t* stage = Wh + C * LD;
+    float* Uh = reinterpret_cast<float*>(stage + C * LD);
+    uint16_t* Ph = reinterpret_cast<uint16_t*>(Uh + C * LDU);
+    uint16_t* Pl = Ph + C * LDP;
+    float* tab = reinterpret_cast<float*>(Pl + C * LDP);  // [2][kDeltaTab]: bs (65), wo (64) of the chunks of either parity
+
+    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, n = lane & 31, half = lane >> 5;
+    const int t256 = tid & 255;
+    const bool carrier = tid < 256;
+    const SeqWalk walk = seq_walk(d, seq);
+    const int nsq = max(1, (walk.n + a.m - 1) / a.m);  // segments of this sequence
+    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = max(kend - kbeg, 0);
+    if (seg >= nsq) return;
+
+    if (carrier) {
+        f32x16 S[4];
+        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
+        {
+            const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
+                                          : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
+            if (ein) walk_state_load(S, ein, false, wave, n, half);
+        }
+        for (int kk = 0; kk < cnt; ++kk) {
+            const float* bs = tab + (kk & 1) * kDeltaTab;
+            const float* wo = bs + C + 4;
+            __syncthreads();  // (A) the tiles and the decay tables of this chunk are in LDS
+            const float bC = DEC ? bs[C] : 0.f;
+            // pseudo-values of this wave's value columns: U^T[v][t] = Uhat[t][v] - sum_i S[i][v] What[t][i]; the inter part
+            // of the output comes out of the same pass over the state blocks (one conversion to bf16 head + remainder)
+            f32x16 O[2];
+            {
+                f32x16 Wacc[2];
+                walk_inter_pair<DEC, true>(Wacc, O, S, Wh, Q, bs, n, half);
+                _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
+                    f32x16 u;
+                    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                        const float4 uh = *reinterpret_cast<const float4*>(Uh + (32 * tb + n) * LDU + 32 * wave + 8 * g + 4 * half);
+                        u[4 * g + 0] = uh.x - Wacc[tb][4 * g + 0];
+                        u[4 * g + 1] = uh.y - Wacc[tb][4 * g + 1];
+                        u[4 * g + 2] = uh.z - Wacc[tb][4 * g + 2];
+                        u[4 * g + 3] = uh.w - Wacc[tb][4 * g + 3];
+                    }
+                    const PackedBlock uh = pack_block(u);
+                    _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+                        u[4 * g + 0] -= bf16_lo(uh.v[g].x);
+                        u[4 * g + 1] -= bf16_hi(uh.v[g].x);
+                        u[4 * g + 2] -= bf16_lo(uh.v[g].y);
+                        u[4 * g + 3] -= bf16_hi(uh.v[g].y);
+                    }
+                    store_packed(V, LD, 32 * tb + n, 32 * wave, half, uh);
+                    store_packed(Vl, LD, 32 * tb + n, 32 * wave, half, pack_block(u));
+                }
+            }
+            __syncthreads();  // (C) scores are in LDS; Q, What and Uhat are spent (this wave's columns of U are its own)
+            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+                delta_intra(O[jb], jb, V, Vl, Ph, Pl, wave, lane, n, half);
+                store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
+            }
+            walk_update_vsplit<DEC, true>(S, K, V, Vl, wo, bC, wave, lane, half);
+            __syncthreads();  // (D) the output stage is complete and every read of K and of the pseudo-values is done
+        }
+        if (a.edge_out && seg == nsq - 1) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+    } else {
+        TileRegs rq, rk, rw;
+        TileRegsF ru;
+        float gval = 0.f;
+        auto pos = [&](int kk) { return walk_pos(d, walk, kbeg + min(kk, cnt - 1)); };
+        auto gload_main = [&](int kk) {  // the rows of the first phase, and the log-decays
+            const ChunkPos p = pos(kk);
+            if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
+            walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, t256);
+            walk_gload<false, kThreads>(rw, a.what, p.wtok0, 1, p.L, t256);
+            tilef_gload(ru, a.uhat, p.wtok0, p.L, t256);
+        };
+        auto commit_main = [&](int kk) {  // ... into LDS, with the decay tables of that chunk
+            const int L = pos(kk).L;
+            walk_commit<kThreads>(Q, rq, L, t256);
+            walk_commit<kThreads>(Wh, rw, L, t256);
+            tilef_commit(Uh, ru, L, t256);
+            float* bs = tab + (kk & 1) * kDeltaTab;
+            if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, bs + C + 4, lane);
+        };
+        auto gload_k = [&](int kk) {
+            const ChunkPos p = pos(kk);
+            walk_gload<false, kThreads>(rk, a.k, p.tok0, p.ts, p.L, t256);
+        };
+        if (cnt > 0) {
+            gload_main(0);
+            gload_k(0);
+            commit_main(0);
+            if (cnt > 1) gload_main(1);
+        }
+        for (int kk = 0; kk < cnt; ++kk) {
+            const ChunkPos cp = pos(kk);
+            walk_commit<kThreads>(K, rk, cp.L, t256);
+            __syncthreads();  // (A)
+            if (kk + 1 < cnt) gload_k(kk + 1);
+            walk_scores<DEC>(K, Q, Ph, Pl, tab + (kk & 1) * kDeltaTab, wave, n, half);
+            if (kk > 0 && a.out) {  // the previous chunk's output
+                const ChunkPos pp = pos(kk - 1);
+                walk_store<false, kThreads>(a.out, stage, pp.tok0, pp.ts, pp.L, t256);
+            }
+            __syncthreads();  // (C)
+            if (kk + 1 < cnt) {
+                commit_main(kk + 1);
+                if (kk + 2 < cnt) gload_main(kk + 2);
+            }
+            if (a.usave) {
+                walk_store<false, kThreads>(a.usave, V, cp.tok0, cp.ts, cp.L, t256);
+                walk_store<false, kThreads>(a.usave_l, Vl, cp.tok0, cp.ts, cp.L, t256);
+            }
+            __syncthreads();  // (D)
+        }
+        if (cnt > 0 && a.out) {
+            const ChunkPos pp = pos(cnt - 1);
+            walk_store<false, kThreads>(a.out, stage, pp.tok0, pp.ts, pp.L, t256);
+        }
+    }
 }
 
 // Entry state of every segment: E_0 = M_0, E_{s+1} = A_s E_s + B_s (REV: from the last segment down, for the state

@@ -143,6 +143,43 @@ __device__ __forceinline__ void walk_inter(f32x16 (&O)[2], const f32x16 (&S)[4],
         }
     }
 }
+// two inter products against the same state with one conversion of its blocks: Oa^T = S^T A^T (unscaled), Ob^T = e^{beta} S^T B^T
+template <bool DEC, bool WANT_B>
+__device__ __forceinline__ void walk_inter_pair(f32x16 (&Oa)[2], f32x16 (&Ob)[2], const f32x16 (&S)[4], const uint16_t* A, const uint16_t* B,
+                                                const float* bs, int n, int half) {
+    _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+        Oa[jb] = f32x16{0};
+        Ob[jb] = f32x16{0};
+    }
+    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+        _Pragma("unroll") for (int p = 0; p < 2; ++p) {
+            u32x4 hi, lo;
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {
+                const float x0 = S[ib][8 * p + 2 * e], x1 = S[ib][8 * p + 2 * e + 1];
+                hi[e] = pack2(x0, x1);
+                lo[e] = pack2(x0 - bf16_lo(hi[e]), x1 - bf16_hi(hi[e]));
+            }
+            const bf16x8 sh = __builtin_bit_cast(bf16x8, hi), sl = __builtin_bit_cast(bf16x8, lo);
+            const bf16x8 a0 = frag_perm(A, LD, n, 32 * ib + 16 * p, half), a1 = frag_perm(A, LD, 32 + n, 32 * ib + 16 * p, half);
+            Oa[0] = mfma(sh, a0, Oa[0]);
+            Oa[1] = mfma(sh, a1, Oa[1]);
+            Oa[0] = mfma(sl, a0, Oa[0]);
+            Oa[1] = mfma(sl, a1, Oa[1]);
+            if (WANT_B) {
+                const bf16x8 b0 = frag_perm(B, LD, n, 32 * ib + 16 * p, half), b1 = frag_perm(B, LD, 32 + n, 32 * ib + 16 * p, half);
+                Ob[0] = mfma(sh, b0, Ob[0]);
+                Ob[1] = mfma(sh, b1, Ob[1]);
+                Ob[0] = mfma(sl, b0, Ob[0]);
+                Ob[1] = mfma(sl, b1, Ob[1]);
+            }
+        }
+    if (DEC && WANT_B) {
+        _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+            const float w = __expf(bs[32 * jb + n]);
+            _Pragma("unroll") for (int x = 0; x < 16; ++x) Ob[jb][x] *= w;
+        }
+    }
+}
 // scores: each of the three 32 x 32 blocks on or below the diagonal by one wave (w4 = 0: (0,0), 1: (1,0),
 // 2: (1,1)), mask and decay on its accumulators, handed to the others through LDS as head + remainder
 template <bool DEC>
