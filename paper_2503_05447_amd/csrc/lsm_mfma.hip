@@ -1066,7 +1066,7 @@ hipError_t launch_delta_fwd_t(const Dims& d, const DeltaPrepArgs& pa, DeltaWalkA
     const SegPlan sp = delta_plan(d);
     const dim3 pgrid(d.N, d.BH()), wgrid(sp.nseg, d.seqs()), block(kThreads);
     if ((e = allow_lds(mk_delta_prep<DEC>, kDeltaPrepLds)) != hipSuccess) return e;
-    if ((e = allow_lds(mk_delta_walk8<DEC>, kDeltaWalk8Lds)) != hipSuccess) return e;
+    if ((e = allow_lds(mk_delta_walk8<DEC, 0>, kDeltaWalk8Lds)) != hipSuccess) return e;
     {
         ProfScope ps(KID_DELTA_PREP, st);
         hipLaunchKernelGGL(mk_delta_prep<DEC>, pgrid, block, kDeltaPrepLds, st, d, pa);
@@ -1078,20 +1078,20 @@ hipError_t launch_delta_fwd_t(const Dims& d, const DeltaPrepArgs& pa, DeltaWalkA
         float* sumA = reinterpret_cast<float*>(segws);
         float* sumB = reinterpret_cast<float*>(static_cast<char*>(segws) + one);
         float* bound = reinterpret_cast<float*>(static_cast<char*>(segws) + 2 * one);
-        if ((e = allow_lds(mk_delta_walk<DEC, 1>, kDeltaWalkLds)) != hipSuccess) return e;
-        if ((e = allow_lds(mk_delta_walk<DEC, 2>, kDeltaWalkLds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_walk8<DEC, 1>, kDeltaWalk8Lds)) != hipSuccess) return e;
+        if ((e = allow_lds(mk_delta_walk8<DEC, 2>, kDeltaWalk8Lds)) != hipSuccess) return e;
         if ((e = allow_lds(mk_delta_combine<false>, kDeltaCombineLds)) != hipSuccess) return e;
         {
             ProfScope ps(KID_DELTA_SUMMARY, st);
             DeltaWalkArgs sa = wa;
             sa.sum = sumB;
-            hipLaunchKernelGGL((mk_delta_walk<DEC, 1>), wgrid, block, kDeltaWalkLds, st, d, sa);
+            hipLaunchKernelGGL((mk_delta_walk8<DEC, 1>), wgrid, dim3(512), kDeltaWalk8Lds, st, d, sa);
         }
         {
             ProfScope ps(KID_DELTA_SUMMARY, st);
             DeltaWalkArgs sa = wa;
             sa.sum = sumA;
-            hipLaunchKernelGGL((mk_delta_walk<DEC, 2>), wgrid, block, kDeltaWalkLds, st, d, sa);
+            hipLaunchKernelGGL((mk_delta_walk8<DEC, 2>), wgrid, dim3(512), kDeltaWalk8Lds, st, d, sa);
         }
         {
             ProfScope ps(KID_DELTA_COMBINE, st);
@@ -1100,7 +1100,7 @@ hipError_t launch_delta_fwd_t(const Dims& d, const DeltaPrepArgs& pa, DeltaWalkA
         wa.bound = bound;
     }
     ProfScope ps(KID_DELTA_WALK, st);
-    hipLaunchKernelGGL(mk_delta_walk8<DEC>, wgrid, dim3(512), kDeltaWalk8Lds, st, d, wa);
+    hipLaunchKernelGGL((mk_delta_walk8<DEC, 0>), wgrid, dim3(512), kDeltaWalk8Lds, st, d, wa);
     return hipGetLastError();
 }
 hipError_t launch_delta_fwd(const Dims& d, const DeltaPrepArgs& pa, DeltaWalkArgs wa, void* segws, hipStream_t stream) {

@@ -13,7 +13,7 @@
 //   mk_delta_prep  (one workgroup per chunk, all chunks in parallel): L from K K^T on the matrix cores, T by
 //                  forward substitution in fp32 inside 32 x 32 diagonal blocks and a block product below them,
 //                  Uhat (fp32) and What (bf16) to the workspace.
-//   mk_delta_walk  (one workgroup per sequence): the forward chunk walker with one more product per chunk,
+//   mk_delta_walk8 (one workgroup per sequence or segment): the forward chunk walker with one more product per chunk,
 //                  U = Uhat - What S from the state in the accumulators; U (as bf16 head + remainder) then plays the
 //                  value tile's part in the intra-chunk product and in the state update.
 // Every value column of the state evolves on its own (the erase term acts on the key side only), so a wave
@@ -247,10 +247,6 @@ struct DeltaWalkArgs {
     const float* bound;
     float* sum;
 };
-// LDS: Q | K | U head (the value tile's place) | U remainder | What (64 x LD bf16 each) | Uhat (64 x LDU fp32) |
-// scores head | scores remainder (64 x LDP) | bs | wo
-constexpr int kDeltaWalkLds = (5 * C * LD + 2 * C * LDP) * 2 + C * LDU * 4 + (2 * C + 8) * 4;
-
 // The pseudo-values are kept as bf16 head + remainder: a single rounding of u_t would show in o_t at the size of
 // an output ulp wherever one token dominates the read-out (strong decay), which the diagonal kinds never pay
 // because their values are inputs.
@@ -282,124 +278,9 @@ __device__ __forceinline__ void tilef_commit(float* dst, const TileRegsF& r, int
     }
 }
 
-// grid: (segments, seqs).  MODE 0: the walk.  MODE 1 / 2: summary of a segment, state part only, from a zero state /
-// from the identity with zero values.
-template <bool DEC, int MODE = 0>
-__global__ __launch_bounds__(kThreads, 1) void mk_delta_walk(Dims d, DeltaWalkArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* K = Q + C * LD;
-    uint16_t* V = K + C * LD;    // pseudo-values U of this chunk, bf16 head
-    uint16_t* Vl = V + C * LD;   // and remainder
-    uint16_t* Wh = Vl + C * LD;
-    float* Uh = reinterpret_cast<float*>(Wh + C * LD);
-    uint16_t* Ph = reinterpret_cast<uint16_t*>(Uh + C * LDU);
-    uint16_t* Pl = Ph + C * LDP;
-    float* bs = reinterpret_cast<float*>(Pl + C * LDP);
-    float* wo = bs + C + 4;
-    uint16_t* stage = Q;
-
-    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
-    const SeqWalk walk = seq_walk(d, seq);
-    const int nsq = max(1, (walk.n + a.m - 1) / a.m);  // segments of this sequence
-    const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = max(kend - kbeg, 0);
-    if (MODE != 0) {
-        if (cnt <= 0 || seg >= nsq - 1) return;  // only segments whose end state another one starts from
-    } else if (seg >= nsq) {
-        return;
-    }
-
-    f32x16 S[4];
-    _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
-    if (MODE == 0) {
-        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
-                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-        if (ein) walk_state_load(S, ein, false, wave, n, half);
-    } else if (MODE == 2) {
-        _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
-            _Pragma("unroll") for (int x = 0; x < 16; ++x)
-                S[ib][x] = (32 * ib + 8 * (x >> 2) + 4 * half + (x & 3) == 32 * wave + n) ? 1.f : 0.f;
-    }
-
-    TileRegs rq, rk, rw;
-    TileRegsF ru;
-    float gval = 0.f;
-    auto gload = [&](int kk) {
-        const ChunkPos p = walk_pos(d, walk, kbeg + min(kk, cnt - 1));
-        if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
-        if (MODE == 0) walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(rk, a.k, p.tok0, p.ts, p.L, tid);
-        walk_gload<false, kThreads>(rw, a.what, p.wtok0, 1, p.L, tid);
-        if (MODE != 2) tilef_gload(ru, a.uhat, p.wtok0, p.L, tid);
-    };
-    if (cnt > 0) gload(0);
-
-    for (int kk = 0; kk < cnt; ++kk) {
-        const ChunkPos cp = walk_pos(d, walk, kbeg + kk);
-        const int L = cp.L;
-        if (MODE == 0) walk_commit<kThreads>(Q, rq, L, tid);
-        walk_commit<kThreads>(K, rk, L, tid);
-        walk_commit<kThreads>(Wh, rw, L, tid);
-        if (MODE != 2) tilef_commit(Uh, ru, L, tid);
-        if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
-        gload(kk + 1);
-        __syncthreads();  // (A) tiles and decay tables of this chunk are in LDS
-        const float bC = DEC ? bs[C] : 0.f;
-
-        // pseudo-values of this wave's value columns: U^T[v][t] = Uhat[t][v] - sum_i S[i][v] What[t][i]; the inter part
-        // of the output comes out of the same pass over the state blocks (one conversion to bf16 head + remainder)
-        f32x16 O[2];
-        {
-            f32x16 Wacc[2];
-            walk_inter_pair<DEC, MODE == 0>(Wacc, O, S, Wh, Q, bs, n, half);
-            _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
-                f32x16 u;
-                _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                    const float4 uh = MODE == 2 ? float4{0.f, 0.f, 0.f, 0.f}
-                                                : *reinterpret_cast<const float4*>(Uh + (32 * tb + n) * LDU + 32 * wave + 8 * g + 4 * half);
-                    u[4 * g + 0] = uh.x - Wacc[tb][4 * g + 0];
-                    u[4 * g + 1] = uh.y - Wacc[tb][4 * g + 1];
-                    u[4 * g + 2] = uh.z - Wacc[tb][4 * g + 2];
-                    u[4 * g + 3] = uh.w - Wacc[tb][4 * g + 3];
-                }
-                const PackedBlock uh = pack_block(u);
-                _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                    u[4 * g + 0] -= bf16_lo(uh.v[g].x);
-                    u[4 * g + 1] -= bf16_hi(uh.v[g].x);
-                    u[4 * g + 2] -= bf16_lo(uh.v[g].y);
-                    u[4 * g + 3] -= bf16_hi(uh.v[g].y);
-                }
-                store_packed(V, LD, 32 * tb + n, 32 * wave, half, uh);
-                store_packed(Vl, LD, 32 * tb + n, 32 * wave, half, pack_block(u));
-            }
-        }
-        if (MODE == 0) {
-            walk_scores<DEC>(K, Q, Ph, Pl, bs, wave, n, half);
-            __syncthreads();  // (C) scores are in LDS; nobody reads Q any more (this wave's columns of U are its own)
-            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                delta_intra(O[jb], jb, V, Vl, Ph, Pl, wave, lane, n, half);
-                store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
-            }
-        }
-        walk_update_vsplit<DEC, true>(S, K, V, Vl, wo, bC, wave, lane, half);
-        __syncthreads();  // (D) the output stage is complete and every read of this chunk's tiles is done
-        if (MODE == 0) {
-            if (a.out) walk_store<false>(a.out, stage, cp.tok0, cp.ts, L, tid);
-            // the value tile is not written again before every wave has passed the next barrier (A)
-            if (a.usave) {
-                walk_store<false>(a.usave, V, cp.tok0, cp.ts, L, tid);
-                walk_store<false>(a.usave_l, Vl, cp.tok0, cp.ts, L, tid);
-            }
-        }
-    }
-    if (MODE != 0) {
-        walk_state_store(S, a.sum + (size_t(seq) * a.nseg + seg) * D * D, false, wave, n, half);
-        return;
-    }
-    if (a.edge_out && seg == nsq - 1) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
-}
-
-// The walk itself (MODE 0 above) by eight waves, two per SIMD, split by function:
+// The walk (MODE 0), and the summaries of a segment for the cut into segments: the state part of the walk alone, from a
+// zero state (MODE 1: the segment's own contribution B) or from the identity with zero values (MODE 2: its transfer
+// matrix A).  grid: (segments, seqs).  Eight waves, two per SIMD, split by function:
 //   waves 0..3 carry the state (wave w: value columns [32w, 32w+32)): both inter products, the pseudo-values, the intra
 //              part of the output and the state update - the chain that every chunk has to go through in order;
 //   waves 4..7 do everything that does not need the state: all tile traffic (global -> registers -> LDS one chunk ahead,
@@ -415,7 +296,7 @@ constexpr int kDeltaTab = 2 * C + 8;
 constexpr int kDeltaWalk8Lds = (6 * C * LD + 2 * C * LDP) * 2 + C * LDU * 4 + 2 * kDeltaTab * 4;
 static_assert(kDeltaWalk8Lds <= 160 * 1024, "one workgroup's LDS");
 
-template <bool DEC>
+template <bool DEC, int MODE>
 __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
@@ -435,15 +316,23 @@ __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a
     const SeqWalk walk = seq_walk(d, seq);
     const int nsq = max(1, (walk.n + a.m - 1) / a.m);  // segments of this sequence
     const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = max(kend - kbeg, 0);
-    if (seg >= nsq) return;
+    if (MODE != 0) {
+        if (cnt <= 0 || seg >= nsq - 1) return;  // only segments whose end state another one starts from
+    } else if (seg >= nsq) {
+        return;
+    }
 
     if (carrier) {
         f32x16 S[4];
         _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
-        {
+        if (MODE == 0) {
             const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
                                           : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
             if (ein) walk_state_load(S, ein, false, wave, n, half);
+        } else if (MODE == 2) {
+            _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
+                _Pragma("unroll") for (int x = 0; x < 16; ++x)
+                    S[ib][x] = (32 * ib + 8 * (x >> 2) + 4 * half + (x & 3) == 32 * wave + n) ? 1.f : 0.f;
         }
         for (int kk = 0; kk < cnt; ++kk) {
             const float* bs = tab + (kk & 1) * kDeltaTab;
@@ -455,11 +344,12 @@ __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a
             f32x16 O[2];
             {
                 f32x16 Wacc[2];
-                walk_inter_pair<DEC, true>(Wacc, O, S, Wh, Q, bs, n, half);
+                walk_inter_pair<DEC, MODE == 0>(Wacc, O, S, Wh, Q, bs, n, half);
                 _Pragma("unroll") for (int tb = 0; tb < 2; ++tb) {
                     f32x16 u;
                     _Pragma("unroll") for (int g = 0; g < 4; ++g) {
-                        const float4 uh = *reinterpret_cast<const float4*>(Uh + (32 * tb + n) * LDU + 32 * wave + 8 * g + 4 * half);
+                        const float4 uh = MODE == 2 ? float4{0.f, 0.f, 0.f, 0.f}
+                                                    : *reinterpret_cast<const float4*>(Uh + (32 * tb + n) * LDU + 32 * wave + 8 * g + 4 * half);
                         u[4 * g + 0] = uh.x - Wacc[tb][4 * g + 0];
                         u[4 * g + 1] = uh.y - Wacc[tb][4 * g + 1];
                         u[4 * g + 2] = uh.z - Wacc[tb][4 * g + 2];
@@ -477,14 +367,17 @@ __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a
                 }
             }
             __syncthreads();  // (C) scores are in LDS; Q, What and Uhat are spent (this wave's columns of U are its own)
-            _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
-                delta_intra(O[jb], jb, V, Vl, Ph, Pl, wave, lane, n, half);
-                store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
+            if (MODE == 0) {
+                _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
+                    delta_intra(O[jb], jb, V, Vl, Ph, Pl, wave, lane, n, half);
+                    store_packed(stage, LD, 32 * jb + n, 32 * wave, half, pack_block(O[jb]));
+                }
             }
             walk_update_vsplit<DEC, true>(S, K, V, Vl, wo, bC, wave, lane, half);
             __syncthreads();  // (D) the output stage is complete and every read of K and of the pseudo-values is done
         }
-        if (a.edge_out && seg == nsq - 1) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+        if (MODE != 0) walk_state_store(S, a.sum + (size_t(seq) * a.nseg + seg) * D * D, false, wave, n, half);
+        else if (a.edge_out && seg == nsq - 1) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
     } else {
         TileRegs rq, rk, rw;
         TileRegsF ru;
@@ -493,15 +386,15 @@ __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a
         auto gload_main = [&](int kk) {  // the rows of the first phase, and the log-decays
             const ChunkPos p = pos(kk);
             if (DEC) gval = a.log_alpha[p.tok0 + size_t(min(lane, p.L - 1)) * p.ts];
-            walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, t256);
+            if (MODE == 0) walk_gload<false, kThreads>(rq, a.q, p.tok0, p.ts, p.L, t256);
             walk_gload<false, kThreads>(rw, a.what, p.wtok0, 1, p.L, t256);
-            tilef_gload(ru, a.uhat, p.wtok0, p.L, t256);
+            if (MODE != 2) tilef_gload(ru, a.uhat, p.wtok0, p.L, t256);
         };
         auto commit_main = [&](int kk) {  // ... into LDS, with the decay tables of that chunk
             const int L = pos(kk).L;
-            walk_commit<kThreads>(Q, rq, L, t256);
+            if (MODE == 0) walk_commit<kThreads>(Q, rq, L, t256);
             walk_commit<kThreads>(Wh, rw, L, t256);
-            tilef_commit(Uh, ru, L, t256);
+            if (MODE != 2) tilef_commit(Uh, ru, L, t256);
             float* bs = tab + (kk & 1) * kDeltaTab;
             if (DEC && wave == 0) walk_decay_tables<false>(gval, L, 0.f, bs, bs + C + 4, lane);
         };
@@ -520,8 +413,8 @@ __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a
             walk_commit<kThreads>(K, rk, cp.L, t256);
             __syncthreads();  // (A)
             if (kk + 1 < cnt) gload_k(kk + 1);
-            walk_scores<DEC>(K, Q, Ph, Pl, tab + (kk & 1) * kDeltaTab, wave, n, half);
-            if (kk > 0 && a.out) {  // the previous chunk's output
+            if (MODE == 0) walk_scores<DEC>(K, Q, Ph, Pl, tab + (kk & 1) * kDeltaTab, wave, n, half);
+            if (MODE == 0 && kk > 0 && a.out) {  // the previous chunk's output
                 const ChunkPos pp = pos(kk - 1);
                 walk_store<false, kThreads>(a.out, stage, pp.tok0, pp.ts, pp.L, t256);
             }
@@ -530,13 +423,13 @@ __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a
                 commit_main(kk + 1);
                 if (kk + 2 < cnt) gload_main(kk + 2);
             }
-            if (a.usave) {
+            if (MODE == 0 && a.usave) {
                 walk_store<false, kThreads>(a.usave, V, cp.tok0, cp.ts, cp.L, t256);
                 walk_store<false, kThreads>(a.usave_l, Vl, cp.tok0, cp.ts, cp.L, t256);
             }
             __syncthreads();  // (D)
         }
-        if (cnt > 0 && a.out) {
+        if (MODE == 0 && cnt > 0 && a.out) {
             const ChunkPos pp = pos(cnt - 1);
             walk_store<false, kThreads>(a.out, stage, pp.tok0, pp.ts, pp.L, t256);
         }
