@@ -80,3 +80,54 @@ def test_config4_vector_decay(keep):
 
 def test_config5_long_sequence_with_carried_state():
     run_config(4, [(0, 0), (0, 31)])
+
+
+def _equal(a, b):
+    import torch
+    if a is None or b is None:
+        return a is None and b is None
+    return torch.equal(a, b)
+
+
+@pytest.mark.parametrize("index", [1, 2, 4])
+def test_repeated_calls_at_full_size_are_bitwise_identical(index):
+    """The walkers split a workgroup into groups of waves that hand tiles to each other through LDS between barriers.
+    Every reduction order is fixed, so a call repeated on the same inputs must reproduce every output bit for bit;
+    a hand-over that was not ordered by a barrier would show as a difference on a chip that is busy throughout."""
+    import torch
+    import paper_2503_05447_amd as pkg
+    x, cfg = wl.make_config(index)
+    t = to_device(x)
+    def once():
+        o, mT = pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"], t["g"], cfg["kind"], cfg["chunk"], t["m0"])
+        r = pkg.lsm_chunk_bwd(t["q"], t["k"], t["v"], t["g"], cfg["kind"], t["d_o"], cfg["chunk"], t["m0"], t["d_mT"])
+        torch.cuda.synchronize()
+        return dict(o=o, mT=mT, **{k: r[k] for k in ("dq", "dk", "dv", "dg", "d_init_state")})
+    first = once()
+    for rep in range(4):
+        again = once()
+        for name, val in first.items():
+            assert _equal(val, again[name]), (cfg["name"], name, rep)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("shape", [(16, 16, 2048), (4, 16, 8192)])
+def test_repeated_delta_rule_calls_at_full_size_are_bitwise_identical(shape, gated):
+    import torch
+    import paper_2503_05447_amd as pkg
+    B, H, T = shape
+    x = wl.make_delta_inputs(B, H, T, 128, 128, gated, seed=77 + int(gated), init_state=True, d_final=True)
+    d = torch.device("cuda:0")
+    mv = lambda a, dt: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(d).to(dt).contiguous()
+    q, k, v, d_o = (mv(x[n], torch.bfloat16) for n in ("q", "k", "v", "d_o"))
+    la, be, bw, m0, d_mT = (mv(x[n], torch.float32) for n in ("log_alpha", "beta", "b", "m0", "d_mT"))
+    def once():
+        o, mT = pkg.lsm_delta_fwd(q, k, v, la, be, bw, m0)
+        r = pkg.lsm_delta_bwd(q, k, v, d_o, la, be, bw, m0, d_mT)
+        torch.cuda.synchronize()
+        return dict(o=o, mT=mT, **{n: r[n] for n in ("dq", "dk", "dv", "d_log_alpha", "d_beta", "d_b", "d_init_state")})
+    first = once()
+    for rep in range(3):
+        again = once()
+        for name, val in first.items():
+            assert _equal(val, again[name]), (shape, gated, name, rep)
