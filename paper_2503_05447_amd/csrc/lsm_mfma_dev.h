@@ -97,7 +97,9 @@ __device__ __forceinline__ bf16x8 rem8_to_bf16(u32x2 raw) {
 __device__ __forceinline__ void load_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + size_t(min(row, L - 1)) * ts) * D + cp * 8));
+        // uniform base (scalar registers) + a 32-bit byte offset per lane
+        const uint32_t off = (uint32_t(min(row, L - 1)) * uint32_t(ts) * D + cp * 8) * 2;
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(src + tok0 * D) + off));
         const uint32_t keep = row < L ? 0xffffffffu : 0u;  // branch-free: a branch around a load drains the load queue
         *reinterpret_cast<u32x4*>(dst + row * LD + cp * 8) = u32x4{v.x & keep, v.y & keep, v.z & keep, v.w & keep};
     }
@@ -107,7 +109,8 @@ struct TileRegs { u32x4 v[4]; };
 __device__ __forceinline__ void tile_gload(TileRegs& r, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
-        r.v[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (tok0 + size_t(min(row, L - 1)) * ts) * D + cp * 8));
+        const uint32_t off = (uint32_t(min(row, L - 1)) * uint32_t(ts) * D + cp * 8) * 2;
+        r.v[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(src + tok0 * D) + off));
     }
 }
 __device__ __forceinline__ void tile_commit(uint16_t* dst, const TileRegs& r, int L, int tid) {
@@ -121,9 +124,10 @@ __device__ __forceinline__ void tile_commit(uint16_t* dst, const TileRegs& r, in
 __device__ __forceinline__ void store_tile(uint16_t* dst, const uint16_t* src, size_t tok0, int ts, int L, int tid) {
     _Pragma("unroll") for (int it = 0; it < 4; ++it) {
         const int p = tid + kThreads * it, row = p >> 4, cp = p & 15;
+        const uint32_t off = (uint32_t(row) * uint32_t(ts) * D + cp * 8) * 2;
         if (row < L)
             __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(src + row * LD + cp * 8),
-                                        reinterpret_cast<u32x4*>(dst + (tok0 + size_t(row) * ts) * D + cp * 8));
+                                        reinterpret_cast<u32x4*>(reinterpret_cast<char*>(dst + tok0 * D) + off));
     }
 }
 

@@ -114,12 +114,10 @@ __device__ __forceinline__ f32x16 score_block2(const uint16_t* Am, int m0, const
 
 // inter: O^T[v][j] = e^{beta_j} sum_i S[i][v] q_j[i], the state blocks as A operands straight from the
 // accumulators (bf16 head + remainder), the query rows read in the matching k order
-template <bool DEC, bool ACC = false>
+template <bool DEC>
 __device__ __forceinline__ void walk_inter(f32x16 (&O)[2], const f32x16 (&S)[4], const uint16_t* Q, const float* bs, int n, int half) {
-    if (!ACC) {
-        O[0] = f32x16{0};
-        O[1] = f32x16{0};
-    }
+    O[0] = f32x16{0};
+    O[1] = f32x16{0};
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
         _Pragma("unroll") for (int p = 0; p < 2; ++p) {
             u32x4 hi, lo;
@@ -835,17 +833,38 @@ __global__ __launch_bounds__(kThreads) void mk_bound_scan(Dims d, const float* _
     float* b = bound + size_t(seq) * nseg * D * D + e;
     const float* gs = gseg + size_t(seq) * nseg;
     float E = edge_in ? edge_in[size_t(seq) * D * D + e] : 0.f;
+    // The contributions are read eight segments at a time before any of them is replaced: the reads of a batch do not
+    // depend on each other, only the recurrence does (read - update - write in turn pays one memory latency per segment).
+    constexpr int G = 8;
     if (!REV) {
         b[0] = E;
-        for (int s = 0; s + 1 < nsq; ++s) {
-            E = __expf(gs[s]) * E + b[size_t(s + 1) * D * D];
-            b[size_t(s + 1) * D * D] = E;
+        for (int s0 = 0; s0 + 1 < nsq; s0 += G) {
+            float u[G], w[G];
+            _Pragma("unroll") for (int i = 0; i < G; ++i) {
+                const int s = min(s0 + i, nsq - 2);
+                u[i] = b[size_t(s + 1) * D * D];
+                w[i] = gs[s];
+            }
+            _Pragma("unroll") for (int i = 0; i < G; ++i)
+                if (s0 + i + 1 < nsq) {
+                    E = __expf(w[i]) * E + u[i];
+                    b[size_t(s0 + i + 1) * D * D] = E;
+                }
         }
     } else {
         b[size_t(nsq - 1) * D * D] = E;
-        for (int s = nsq - 1; s >= skip; --s) {  // slots below skip - 1 are entered by no walk
-            E = __expf(gs[s]) * E + b[size_t(s - 1) * D * D];
-            b[size_t(s - 1) * D * D] = E;
+        for (int s0 = nsq - 1; s0 >= skip; s0 -= G) {  // slots below skip - 1 are entered by no walk
+            float u[G], w[G];
+            _Pragma("unroll") for (int i = 0; i < G; ++i) {
+                const int s = max(s0 - i, skip);
+                u[i] = b[size_t(s - 1) * D * D];
+                w[i] = gs[s];
+            }
+            _Pragma("unroll") for (int i = 0; i < G; ++i)
+                if (s0 - i >= skip) {
+                    E = __expf(w[i]) * E + u[i];
+                    b[size_t(s0 - i - 1) * D * D] = E;
+                }
         }
     }
 }
