@@ -310,9 +310,11 @@ __global__ __launch_bounds__(512, 1) void mk_delta_walk8(Dims d, DeltaWalkArgs a
     uint16_t* Pl = Ph + C * LDP;
     float* tab = reinterpret_cast<float*>(Pl + C * LDP);  // [2][kDeltaTab]: bs (65), wo (64) of the chunks of either parity
 
-    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, n = lane & 31, half = lane >> 5;
+    // the wave index as a scalar: the branch between the two groups is a scalar branch
+    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, wave = wave8 & 3, n = lane & 31, half = lane >> 5;
     const int t256 = tid & 255;
-    const bool carrier = tid < 256;
+    const bool carrier = wave8 < 4;
     const SeqWalk walk = seq_walk(d, seq);
     const int nsq = max(1, (walk.n + a.m - 1) / a.m);  // segments of this sequence
     const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = max(kend - kbeg, 0);

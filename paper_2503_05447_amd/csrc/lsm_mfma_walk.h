@@ -511,10 +511,12 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
     constexpr int NT = VSPLIT ? 256 : kGrad8Threads;  // threads that share the tile traffic
 
     const int seq = blockIdx.y, seg = blockIdx.x;
-    const int tid = threadIdx.x, wave = (tid >> 6) & 3;
+    // the wave index as a scalar: the branch between the two groups is then a scalar branch (each group's barriers are
+    // executed by its own waves only, whatever the compiler makes of the vector condition), and 32 * wave offsets are scalars
+    const int tid = threadIdx.x, wave8 = __builtin_amdgcn_readfirstlane(tid >> 6), wave = wave8 & 3;
     int lane = tid & 63, n = lane & 31, half = lane >> 5;
     int tt = VSPLIT ? tid & 255 : tid;  // index among the threads that move tiles
-    const bool carrier = tid < 256;     // waves 0..3
+    const bool carrier = wave8 < 4;     // waves 0..3
     // VSPLIT: every LDS access pattern keeps a lane-dependent base address per 64 KiB window of the 159 KiB
     // in use, and with the state, two sets of accumulators and the tiles in flight there is no room to keep a hundred of
     // them alive across the loop.  Hiding the lane id from the optimiser at the phase boundaries makes it recompute the
@@ -531,8 +533,8 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
     const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
     if (cnt <= 0) return;
 
-    // VSPLIT: the carrier group moves the head plane of dU in, and d_o when it has no decay tables to keep (its registers
-    // are full otherwise); the other group moves the other tiles in and all five out
+    // VSPLIT: the carrier group moves the head plane of dU in, and d_o when it has no decay tables to keep (measured:
+    // with them it is the slower group already); the other group moves the other tiles in and all but the head of dW out
     constexpr bool kCarrierMovesDo = !DEC;
     TileRegs tq, tk, tv, to, tv2, tdh, tdl;
     auto gload_tiles = [&](const ChunkPos& p, bool first_group) {
@@ -638,7 +640,7 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
             const int L = cp.L;
             fresh();
             commit_tiles(L, true);
-            if (DEC && tid < 64) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
+            if (DEC && wave8 == 0) walk_decay_tables<false>(gval, L, 0.f, bs, wo, lane);
             __syncthreads();  // (1) tiles, dS rows and decay tables of this chunk are in LDS
             fresh();
             const float bC = DEC ? bs[C] : 0.f;
@@ -691,7 +693,7 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
             __syncthreads();  // (4)
             fresh();
             store_tiles(cp, true);
-            if (WANT_DG && tid < 64) {
+            if (WANT_DG && wave8 == 0) {
                 // fixed-order sums over the four feature slices, then the reverse in-chunk running sum
                 float w = 0.f;
                 const float z = (zred[0] + zred[1]) + (zred[2] + zred[3]);
