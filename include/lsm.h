@@ -216,9 +216,11 @@ int lsm_delta_bwd(const lsm_params* p,
  * gradients need are recomputed from the inputs; nothing saved by the forward
  * call is needed (unless LSM_FLAG_SAVE_STATES is set, see lsm_flags).
  * Shapes outside the matrix-core family (lsm_kernel_path(p) == 0: fp32
- * elements, d_k other than 128, chunk other than 64) run on plain fp32 kernels
- * that are correct to the fp32 tolerance and far slower; they are meant for
- * checks and odd shapes.
+ * elements, d_k other than 128, d_v = 64, chunk other than 64) run on plain
+ * fp32 kernels that are correct to the fp32 tolerance and far slower; they are
+ * meant for checks and odd shapes.  (d_v = 256 is in the family: the vector
+ * kind scans each 128-wide value slice, the other kinds run one pass per slice
+ * and keep no states between the two calls, whatever the flags say.)
  *   q,k,v,log_decay,init_state   as in the forward                         in
  *   d_o            [B,H,T,d_v] dtype                                       in
  *   d_final_state  NULL (= zeros) or [B,H,d_k,d_v] fp32                    in

@@ -69,7 +69,8 @@ int check_params(const lsm_params* p, lsm::Dims* d) {
     d->N = int(n); d->kind = p->decay_kind; d->bf16 = p->dtype == LSM_DTYPE_BF16;
     d->layout = p->layout; d->nseq = p->n_seq; d->cu = p->cu_seqlens; d->cstart = nullptr;
     // Only the matrix-core kernels keep states between the two calls; elsewhere the flag changes nothing.
-    d->save = (p->flags & LSM_FLAG_SAVE_STATES) != 0 && lsm::mfma_supported(*d);
+    // (the scalar kinds with d_v = 256 run one pass per 128-wide value slice over a shared workspace and keep nothing)
+    d->save = (p->flags & LSM_FLAG_SAVE_STATES) != 0 && lsm::mfma_supported(*d) && (d->kind == 3 || d->dv == 128);
     return LSM_OK;
 }
 

@@ -18,6 +18,10 @@ struct Dims {
     const int* cu;      // [nseq + 1] first token of each sequence (device memory), cu[nseq] = T
     const int* cstart;  // [nseq + 1] first chunk of each sequence (device memory, written by the library)
     bool save;    // the forward call leaves its chunk states in the workspace and the backward call reads them
+    // Scalar decay kinds with d_v a multiple of 128: the value columns evolve independently, so the walkers take one
+    // 128-wide slice of the value-sized tensors (v, o, d_o, dv, the value side of the states) per pass.  vm = d_v / 128
+    // (value rows are vm rows of 128 elements), vs = the slice of this pass; passes after the first add to dq, dk, dg.
+    int vm = 1, vs = 0;
     __host__ __device__ int BH() const { return B * H; }
     __host__ __device__ int dkd() const { return kind == 3 ? dk : 1; }  // decay values per token
     __host__ __device__ int seqs() const { return nseq ? nseq * H : B * H; }  // independent recurrences
@@ -28,6 +32,8 @@ struct ChunkPos {
     int t0, L;      // first token and number of valid tokens (L <= 0: no such chunk)
     size_t tok0;    // row of the first token in the caller's q/k/v/o arrays (rows of d_k or d_v elements)
     int ts;         // rows between consecutive tokens there
+    size_t vtok0;   // the same for the value-sized arrays in units of 128 elements, at this pass's slice
+    int vts;
     size_t wtok0;   // first token in the library's own per-token arrays ([BH][T] order)
     size_t slot;    // this chunk in the library's per-chunk arrays ([BH][N] order)
 };
@@ -37,6 +43,8 @@ __device__ __forceinline__ ChunkPos chunk_pos_at(const Dims& d, int bh, int t0, 
     p.L = L;
     p.ts = d.layout ? d.H : 1;
     p.tok0 = d.layout ? (size_t(bh / d.H) * d.T + t0) * d.H + bh % d.H : size_t(bh) * d.T + t0;
+    p.vts = p.ts * d.vm;
+    p.vtok0 = p.tok0 * d.vm + d.vs;
     p.wtok0 = size_t(bh) * d.T + t0;
     p.slot = size_t(bh) * d.N + c;
     return p;

@@ -133,7 +133,7 @@ __device__ __forceinline__ void state_gload(const Dims& d, const uint16_t* xa, c
                                             const uint16_t* xb_lo, const float* wts, const float* lam, int a_stride,
                                             const ChunkPos& cp, size_t lamslot, int fb0, int tid, StateRegs& r) {
     const int L = cp.L;
-    const int astride = VEC ? a_stride : D;
+    const int astride = VEC ? a_stride : D * d.vm;  // scalar kinds: the A side is value-sized (d_o), one 128-wide slice per pass
     // The set of this chunk carries e^{b_C} of chunk `lamslot`, the one that is being accumulated when
     // this set goes to LDS: the factor is then read from a set that has arrived, and no loaded value is
     // copied from iteration to iteration (such a copy waits for every load in flight).
@@ -298,7 +298,8 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     const int tid = threadIdx.x, lane = tid & 63, mb = tid >> 6;
     const int n = lane & 31, half = lane >> 5;
     constexpr int sz = D * D;
-    const int erow = VEC ? sa.a_stride : D;  // row stride of the fp32 edge states [i][v]
+    const int erow = VEC ? sa.a_stride : D * d.vm;  // row stride of the fp32 edge states [i][v]
+    const int vcol = VEC ? D * vh : D * d.vs;       // first value column of this scan in the value-sized arrays
 
     // acc[4g+j] = state element (m = 32mb + 8g + 4half + j, n = 32nb + lane%32); MODE 0: m = i, else m = v
     f32x16 acc = {0};
@@ -312,7 +313,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
             acc[r] = MODE == 0 ? e[mm * D + nn] : e[nn * D + mm];
         }
     } else if (edge_in) {
-        const float* e = edge_in + size_t(walk.edge) * D * erow + D * vh;
+        const float* e = edge_in + size_t(walk.edge) * D * erow + vcol;
         _Pragma("unroll") for (int r = 0; r < 16; ++r) {
             const int mm = 32 * mb + 8 * (r >> 2) + 4 * half + (r & 3), nn = 32 * nb + n;
             acc[r] = MODE == 0 ? e[mm * erow + nn] : e[nn * erow + mm];
@@ -324,7 +325,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     auto bufA = [&](int k) { return tiles + (k & 1) * kStateTile; };
     auto bufB = [&](int k) { return tiles + (k & 1) * kStateTile + C * LD; };
     auto slot = [&](int k) { return ((size_t(walk.bh) * d.N + walk.c0 + (first + step * k)) * nvh + vh) * sz; };
-    const uint16_t* xav = xa + (VEC ? D * vh : 0);
+    const uint16_t* xav = xa + vcol;
     auto gload = [&](int kc, StateRegs& r) {
         // the kc-th chunk of the walk (clamped at the end); it goes to LDS during iteration kc - 2
         const int c = first + step * min(kc, cnt - 1), clam = first + step * min(max(kc - 2, 0), cnt - 1);
@@ -337,7 +338,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     StateRegs r0, r1, r2;
     if (cnt <= 0) {  // an empty sequence of a packed input: the state passes through
         if (edge_out) {
-            float* e = edge_out + size_t(walk.edge) * D * erow + D * vh;
+            float* e = edge_out + size_t(walk.edge) * D * erow + vcol;
             _Pragma("unroll") for (int x = 0; x < 16; ++x) {
                 const int mm = 32 * mb + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * nb + n;
                 if (MODE == 0) e[mm * erow + nn] = acc[x];
@@ -402,7 +403,7 @@ __device__ __forceinline__ void state_scan_body(const Dims& d, const StateArgs& 
     if (k + 1 < cnt) iteration(k + 1, r1, r0);
     __syncthreads();
     if (edge_out) {
-        float* e = edge_out + size_t(walk.edge) * D * erow + D * vh;
+        float* e = edge_out + size_t(walk.edge) * D * erow + vcol;
         _Pragma("unroll") for (int x = 0; x < 16; ++x) {
             const int mm = 32 * mb + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * nb + n;
             if (MODE == 0) e[mm * erow + nn] = acc[x];
@@ -488,7 +489,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     float* bs = reinterpret_cast<float*>(V + C * LD);
     uint16_t* stage = K;
 
-    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const ChunkPos cp = chunk_pos(d, c, bh);
     const int L = cp.L;
     if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
@@ -684,6 +685,7 @@ struct WalkWs {
     float *wdec, *winc, *lam;    // backward: decay tables of the reverse scan
     float* dgc;                  // per-head kind: per-chunk sums of dg
     size_t bytes;
+    uint16_t* part[4];  // d_v = 256: the first value-slice pass's dq and dk (head, remainder), [BH*T][128] each
 };
 // The forward part comes first, at the same offsets in both carvings: with saved states the backward
 // call finds the entry states where the forward call left them.
@@ -707,6 +709,9 @@ WalkWs carve_walk(const Dims& d, void* ws, bool bwd) {
         if (rev_plan(d, sp).nseg > 1) {
             w.bound_r = take(nb);
             w.gseg_r = take(ng);
+        }
+        if (d.dv > D) {  // two value-slice passes: the first pass's dq and dk, head and remainder
+            for (auto& pl : w.part) pl = reinterpret_cast<uint16_t*>(take(size_t(d.BH()) * d.T * D * 2));
         }
     }
     w.bytes = off;
@@ -743,8 +748,9 @@ hipError_t allow_lds(K kernel, int bytes) {
 }  // namespace
 
 bool mfma_supported(const Dims& d) {
-    if (!(d.bf16 && d.C == C && d.dk == D)) return false;
-    return d.kind == 3 ? d.dv % D == 0 : d.dv == D;
+    // d_v: any multiple of 128.  The vector kind scans each 128-wide value slice as a sequence of its own; the scalar
+    // kinds run their walkers once per slice (the value columns of the state evolve independently).
+    return d.bf16 && d.C == C && d.dk == D && d.dv % D == 0 && (d.kind == 3 || d.dv <= 2 * D);
 }
 bool mfma_bwd_supported(const Dims& d) { return mfma_supported(d); }
 
@@ -854,7 +860,8 @@ hipError_t walk_bounds(const Dims& d, hipStream_t st, const SegPlan& sp, const u
     return hipSuccess;
 }
 
-hipError_t walk_fwd(const Dims& d, const FwdArgs& a) {
+// One 128-wide slice of the value dimension (d.vm slices, this one d.vs; a single pass when d_v = 128).
+hipError_t walk_fwd_slice(const Dims& d, const FwdArgs& a) {
     const WalkWs w = carve_walk(d, a.ws, false);
     const SegPlan sp = seg_plan(d);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
@@ -875,6 +882,15 @@ hipError_t walk_fwd(const Dims& d, const FwdArgs& a) {
     }
     return hipGetLastError();
 }
+hipError_t walk_fwd(const Dims& d0, const FwdArgs& a) {
+    Dims d = d0;
+    d.vm = d0.dv / D;
+    for (d.vs = 0; d.vs < d.vm; ++d.vs) {  // the passes share the workspace: same stream, one after the other
+        const hipError_t e = walk_fwd_slice(d, a);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
 
 hipError_t launch_walk_grad(const Dims& d, const SegPlan& sp, const GradArgs& ga, hipStream_t st) {
     const dim3 grid(sp.nseg, d.seqs()), block(kGrad8Threads);
@@ -891,27 +907,30 @@ hipError_t launch_walk_grad(const Dims& d, const SegPlan& sp, const GradArgs& ga
         }
         return hipSuccess;
     }
-    if (d.kind == 0) {
-        if ((e = allow_lds(mk_walk_grad<false, false>, kWalkGradLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_walk_grad<false, false>), grid, block, kWalkGradLds, st, d, ga);
-    } else if (!ga.dg_tok) {
-        if ((e = allow_lds(mk_walk_grad<true, false>, kWalkGradLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_walk_grad<true, false>), grid, block, kWalkGradLds, st, d, ga);
-    } else {
-        if ((e = allow_lds(mk_walk_grad<true, true>, kWalkGradLds)) != hipSuccess) return e;
-        hipLaunchKernelGGL((mk_walk_grad<true, true>), grid, block, kWalkGradLds, st, d, ga);
-    }
-    return hipSuccess;
+    // d_v = 256: pass 0 leaves dq and dk in the partial planes (WIDE 1), pass 1 adds them to its own (WIDE 2)
+    const int wide = d.vm == 1 ? 0 : (d.vs == 0 ? 1 : 2);
+    auto launch = [&](auto kernel) -> hipError_t {
+        const hipError_t le = allow_lds(kernel, kWalkGradLds);
+        if (le != hipSuccess) return le;
+        hipLaunchKernelGGL(kernel, grid, block, kWalkGradLds, st, d, ga);
+        return hipSuccess;
+    };
+    auto pick = [&](auto w0, auto w1, auto w2) { return wide == 0 ? launch(w0) : wide == 1 ? launch(w1) : launch(w2); };
+    if (d.kind == 0)
+        return pick(mk_walk_grad<false, false, false, 0>, mk_walk_grad<false, false, false, 1>, mk_walk_grad<false, false, false, 2>);
+    if (!ga.dg_tok)
+        return pick(mk_walk_grad<true, false, false, 0>, mk_walk_grad<true, false, false, 1>, mk_walk_grad<true, false, false, 2>);
+    return pick(mk_walk_grad<true, true, false, 0>, mk_walk_grad<true, true, false, 1>, mk_walk_grad<true, true, false, 2>);
 }
 
-hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
+hipError_t walk_bwd_slice(const Dims& d, const BwdArgs& a) {
     const WalkWs w = carve_walk(d, a.ws, true);
     const SegPlan sp = seg_plan(d);
     auto q = static_cast<const uint16_t*>(a.q), k = static_cast<const uint16_t*>(a.k), v = static_cast<const uint16_t*>(a.v);
     auto d_o = static_cast<const uint16_t*>(a.d_o);
     hipError_t e;
     // state gradients: the reverse scan leaves one per chunk (and d_init_state)
-    if (d.kind != 0) {
+    if (d.kind != 0 && d.vs == 0) {  // the decay tables are the same for every value slice
         ProfScope ps(KID_MFMA_PREP, a.stream);
         hipLaunchKernelGGL(mk_decay_prep, dim3(d.N, d.BH()), dim3(64), 0, a.stream, d, a.g, w.wdec, w.winc, w.lam);
     }
@@ -932,6 +951,7 @@ hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
     if (!d.save && (e = walk_bounds<false>(d, a.stream, sp, k, v, a.g, a.m0, w.bound_f, w.gseg_f)) != hipSuccess) return e;
     GradArgs ga{q, k, v, d_o, a.g, w.dstates, static_cast<uint16_t*>(a.dq), static_cast<uint16_t*>(a.dk), static_cast<uint16_t*>(a.dv),
                 a.dg ? (d.kind == 1 ? w.dgc : a.dg) : nullptr, a.m0, w.bound_f, sp.m, sp.nseg};
+    for (int i = 0; i < 4; ++i) ga.part[i] = w.part[i];
     const dim3 block(kThreads);
     // the gradient walker holds one workgroup per compute unit, the forward walker two: where the plan gives every unit
     // two workgroups, the gradient walker takes segments of twice the length (half as many state loads and prologues)
@@ -941,11 +961,20 @@ hipError_t walk_bwd(const Dims& d, const BwdArgs& a) {
         ga.m = gp.m; ga.nseg = gp.nseg; ga.bound_per = 2; ga.bound_n = sp.nseg;
     }
     if ((e = launch_walk_grad(d, gp, ga, a.stream)) != hipSuccess) return e;
-    if (a.dg && d.kind == 1) {
+    if (a.dg && d.kind == 1 && d.vs == d.vm - 1) {  // after the last slice has added its share
         ProfScope ps(KID_HEAD_REDUCE, a.stream);
         hipLaunchKernelGGL(mk_head_reduce, dim3(d.H), block, 0, a.stream, d, w.dgc, a.dg);
     }
     return hipGetLastError();
+}
+hipError_t walk_bwd(const Dims& d0, const BwdArgs& a) {
+    Dims d = d0;
+    d.vm = d0.dv / D;
+    for (d.vs = 0; d.vs < d.vm; ++d.vs) {  // dq, dk and the decay gradient sum over the slices: later passes add to them
+        const hipError_t e = walk_bwd_slice(d, a);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 }  // namespace
 
@@ -1001,7 +1030,7 @@ hipError_t vec_bwd(const Dims& d, const BwdArgs& a) {
 }  // namespace
 
 hipError_t mfma_intra_bench(const Dims& d0, const FwdArgs& a, int reps) {
-    if (d0.kind == 3 || !mfma_supported(d0)) return hipErrorInvalidValue;
+    if (d0.kind == 3 || d0.dv != D || !mfma_supported(d0)) return hipErrorInvalidValue;
     Dims d = d0;
     d.save = false;
     Ws w = carve(d, a.ws, false);

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kThreads, 2) void mk_delta_prep(Dims d, DeltaPrepAr
     float* be = lg + C;
     float* bb = be + C;
 
-    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), n = lane & 31, half = lane >> 5;
     const ChunkPos cp = chunk_pos(d, c, bh);
     const int L = cp.L;
     if (L <= 0) return;
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_combine(Dims d, const fl
     uint16_t* Al = Ah + D * LD;
     uint16_t* Eh = Al + D * LD;
     uint16_t* El = Eh + D * LD;
-    const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), n = lane & 31, half = lane >> 5;
     const SeqWalk walk = seq_walk(d, seq);
     const int nsq = max(1, (walk.n + m - 1) / m);
     const float* e0 = edge_in ? edge_in + size_t(seq) * D * D : nullptr;
@@ -552,7 +552,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_rwalk(Dims d, DeltaRevAr
     float* wo = bs + C + 4;
     float* gm = wo + C + 4;
 
-    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int seg = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), n = lane & 31, half = lane >> 5;
     const SeqWalk walk = seq_walk(d, seq);
     const int nsq = max(1, (walk.n + a.m - 1) / a.m);
     const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = max(kend - kbeg, 0);
@@ -772,7 +772,7 @@ __global__ __launch_bounds__(kThreads, 1) void mk_delta_grad(Dims d, DeltaGradAr
     uint16_t* stk = stv + C * LD;    // stage of dk
     static_assert(4 * C * LDP + 2 * C * LD <= 5 * C * LD, "second phase fits behind K");
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), n = lane & 31, half = lane >> 5;
     const int jobs = d.N * d.BH();
     // One workgroup per compute unit walks over chunks; the rows of the next chunk are requested into registers while
     // this one is worked on (the kernel needs most of the unit's LDS, so no second workgroup hides the loads).

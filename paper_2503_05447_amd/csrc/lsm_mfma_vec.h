@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kThreads, 2) void mk_vec_prep(Dims d, const uint16_
     float* red = reinterpret_cast<float*>(smem);                      // [8][32][kPrepRedLd], after the levels
     float* diag = reinterpret_cast<float*>(smem + kPrepLdsMain);      // [64]
 
-    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const ChunkPos pos = chunk_pos(d, c, bh);
     const int L = pos.L;
     if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(kThreads, 2) void mk_output_vec(Dims d, const uint1
     uint16_t* Pl = Ph + C * LDP;
 
     const int c = blockIdx.x, bh = blockIdx.y, vh = blockIdx.z, nvh = gridDim.z;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const ChunkPos pos = chunk_pos(d, c, bh);
     const int L = pos.L;
     if (L <= 0) return;  // packed input: the grid is sized for an upper bound of the chunk count

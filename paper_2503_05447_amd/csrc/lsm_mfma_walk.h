@@ -285,20 +285,23 @@ __device__ __forceinline__ float walk_decay_tables(float gval, int L, float extr
     return bC;
 }
 // state block layout <-> the [i][v] fp32 arrays (transposed: the walker's state is the transpose of the array)
-__device__ __forceinline__ void walk_state_load(f32x16 (&S)[4], const float* e, bool transposed, int w4, int n, int half) {
+// (erow: row stride of the array; the caller's states have d_v columns, the library's own 128)
+__device__ __forceinline__ void walk_state_load(f32x16 (&S)[4], const float* e, bool transposed, int w4, int n, int half, int erow = D) {
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
         _Pragma("unroll") for (int x = 0; x < 16; ++x) {
             const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * w4 + n;
-            S[ib][x] = transposed ? e[nn * D + mm] : e[mm * D + nn];
+            S[ib][x] = transposed ? e[nn * erow + mm] : e[mm * erow + nn];
         }
 }
-__device__ __forceinline__ void walk_state_store(const f32x16 (&S)[4], float* e, bool transposed, int w4, int n, int half) {
+__device__ __forceinline__ void walk_state_store(const f32x16 (&S)[4], float* e, bool transposed, int w4, int n, int half, int erow = D) {
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib)
         _Pragma("unroll") for (int x = 0; x < 16; ++x) {
             const int mm = 32 * ib + 8 * (x >> 2) + 4 * half + (x & 3), nn = 32 * w4 + n;
-            e[transposed ? nn * D + mm : mm * D + nn] = S[ib][x];
+            e[transposed ? nn * erow + mm : mm * erow + nn] = S[ib][x];
         }
 }
+// the caller's state of recurrence `seq` ([d_k][d_v] fp32), at the value slice of this pass
+__device__ __forceinline__ size_t edge_off(const Dims& d, int seq) { return (size_t(seq) * D * d.vm + d.vs) * D; }
 // REV: walk backward in time.  DEC: a decay is present.  SUMMARY: the state update alone, from a zero
 // state, result to a.bound / a.gseg.
 template <bool REV, bool DEC, bool SUMMARY, bool VSPLIT = false>
@@ -315,7 +318,7 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
     uint16_t* V2 = reinterpret_cast<uint16_t*>(smem + walk_lds(SUMMARY));  // VSPLIT only
     static_assert(!VSPLIT || SUMMARY, "two value planes: summary pass only");
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), n = lane & 31, half = lane >> 5;
     const SeqWalk walk = seq_walk(d, seq);
     const int nsq = (walk.n + a.m - 1) / a.m;  // segments of this sequence
     const int kbeg = seg * a.m, kend = min(walk.n, kbeg + a.m), cnt = kend - kbeg;
@@ -331,9 +334,8 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
     f32x16 S[4];
     _Pragma("unroll") for (int ib = 0; ib < 4; ++ib) S[ib] = f32x16{0};
     if (!SUMMARY) {
-        const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * a.nseg + seg) * D * D
-                                      : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-        if (ein) walk_state_load(S, ein, false, wave, n, half);
+        if (a.nseg > 1) walk_state_load(S, a.bound + (size_t(seq) * a.nseg + seg) * D * D, false, wave, n, half);
+        else if (a.edge_in) walk_state_load(S, a.edge_in + edge_off(d, seq), false, wave, n, half, D * d.vm);
     }
 
     TileRegs rq, rk, rv, rv2;
@@ -350,8 +352,8 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         }
         if (!SUMMARY) walk_gload<REV, kThreads>(rq, a.xq, p.tok0, p.ts, p.L, tid);
         walk_gload<REV, kThreads>(rk, a.xk, p.tok0, p.ts, p.L, tid);
-        walk_gload<REV, kThreads>(rv, a.xv, p.tok0, p.ts, p.L, tid);
-        if (VSPLIT) walk_gload<REV, kThreads>(rv2, a.xv_lo, p.tok0, p.ts, p.L, tid);
+        walk_gload<REV, kThreads>(rv, a.xv, p.vtok0, p.vts, p.L, tid);
+        if (VSPLIT) walk_gload<REV, kThreads>(rv2, a.xv_lo, p.vtok0, p.vts, p.L, tid);
     };
     if (cnt > 0) gload(0);
 
@@ -382,7 +384,7 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         else walk_update<DEC, !SUMMARY>(S, K, V, wo, bC, wave, lane, half);
         __syncthreads();  // (D) the output stage is complete and every read of this chunk's tiles is done
         // every thread reads back exactly the stage pieces that its own next walk_commit overwrites: no barrier
-        if (!SUMMARY) walk_store<REV>(a.out, stage, cp.tok0, cp.ts, L, tid);
+        if (!SUMMARY) walk_store<REV>(a.out, stage, cp.vtok0, cp.vts, L, tid);
     }
 
     // ---- the state this walk ends with
@@ -391,7 +393,7 @@ __device__ __forceinline__ void walk_body(const Dims& d, const WalkArgs& a, int 
         if (tid == 0) a.gseg[size_t(seq) * a.nseg + seg] = gtot;
         return;
     }
-    if (last && a.edge_out) walk_state_store(S, a.edge_out + size_t(seq) * D * D, false, wave, n, half);
+    if (last && a.edge_out) walk_state_store(S, a.edge_out + edge_off(d, seq), false, wave, n, half, D * d.vm);
 }
 
 // forward walker, or the summary pass of either direction (grid: segments x sequences)
@@ -437,6 +439,10 @@ struct GradArgs {
     // the entry states may be kept at a finer grain than this walk's segments: bound holds bound_n slots per sequence,
     // one per m / bound_per chunks, and segment s enters with slot s * bound_per (0: same grain, nseg slots)
     int bound_per, bound_n;
+    // d_v = 256 (two passes, one per 128-wide value slice; dq and dk sum over them): the first pass leaves its dq and dk as
+    // bf16 head + remainder in these four planes ([BH*T][128], library order: dq head, dq remainder, dk head, dk remainder),
+    // the second adds them to its own before the one rounding
+    uint16_t* part[4];
 };
 // VSPLIT (the delta-rule backward, whose values are the pseudo-values U = head + remainder): the values enter
 // every product with both planes; the value gradient is not formed (it is the caller's dU once more) and its
@@ -487,8 +493,10 @@ __device__ __forceinline__ void walk_inter_split(f32x16 (&O)[2], const f32x16 (&
 // that the accumulators of dW and dq never coexist.
 constexpr int kGrad8Threads = 512;
 
-template <bool DEC, bool WANT_DG, bool VSPLIT = false>
+// WIDE: 0 the only pass; 1 the first of two value-slice passes (dq, dk to the partial planes); 2 the second
+template <bool DEC, bool WANT_DG, bool VSPLIT = false, int WIDE = 0>
 __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArgs a) {
+    static_assert(!(VSPLIT && WIDE), "the two-plane case has 128 value columns");
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = Q + C * LD;
@@ -507,6 +515,9 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
     uint16_t* dUh = dSt;             // VSPLIT: 64 x LD each, over the dS rows
     uint16_t* dUl = dSt + C * LD;
     uint16_t* Wl = Ah;               // VSPLIT (no As): stage of the remainder plane of dW, 64 x LD
+    uint16_t* Lq = Gh;               // WIDE == 1: stages of the remainder planes of dq and dk (G and As are spent after (3))
+    uint16_t* Lk = Ah;
+    static_assert(2 * C * LDP >= C * LD, "a 64 x LD stage fits the area of G");
     static_assert(2 * C * LDP >= C * LD, "the dW stage fits the area of As");
     constexpr int NT = VSPLIT ? 256 : kGrad8Threads;  // threads that share the tile traffic
 
@@ -541,12 +552,12 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
         if (!VSPLIT || !first_group) {
             walk_gload<false, NT>(tq, a.q, p.tok0, p.ts, p.L, tt);
             walk_gload<false, NT>(tk, a.k, p.tok0, p.ts, p.L, tt);
-            walk_gload<false, NT>(tv, a.v, p.tok0, p.ts, p.L, tt);
+            walk_gload<false, NT>(tv, a.v, p.vtok0, p.vts, p.L, tt);
         }
-        if (!VSPLIT || first_group == kCarrierMovesDo) walk_gload<false, NT>(to, a.d_o, p.tok0, p.ts, p.L, tt);
+        if (!VSPLIT || first_group == kCarrierMovesDo) walk_gload<false, NT>(to, a.d_o, p.vtok0, p.vts, p.L, tt);
         if (VSPLIT && first_group) walk_gload<false, NT>(tdh, a.du_h, p.wtok0, 1, p.L, tt);
         if (VSPLIT && !first_group) {
-            walk_gload<false, NT>(tv2, a.v_lo, p.tok0, p.ts, p.L, tt);
+            walk_gload<false, NT>(tv2, a.v_lo, p.vtok0, p.vts, p.L, tt);
             walk_gload<false, NT>(tdl, a.du_l, p.wtok0, 1, p.L, tt);
         }
     };
@@ -568,12 +579,36 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
         // the next chunk's commit.  (VSPLIT: the head of dW is staged over the plane of dU that the carrier group commits,
         // so that group stores it; the stage of the remainder is next written after barrier (1).)
         if (!VSPLIT || !first_group) {
-            walk_store<false, NT>(a.dq, Q, cp.tok0, cp.ts, cp.L, tt);
-            walk_store<false, NT>(a.dk, K, cp.tok0, cp.ts, cp.L, tt);
-            walk_store<false, NT>(a.dv, V, cp.tok0, cp.ts, cp.L, tt);
+            if (WIDE == 1) {  // head and remainder of this pass's dq and dk, for the second pass
+                walk_store<false, NT>(a.part[0], Q, cp.wtok0, 1, cp.L, tt);
+                walk_store<false, NT>(a.part[1], Lq, cp.wtok0, 1, cp.L, tt);
+                walk_store<false, NT>(a.part[2], K, cp.wtok0, 1, cp.L, tt);
+                walk_store<false, NT>(a.part[3], Lk, cp.wtok0, 1, cp.L, tt);
+            } else {
+                walk_store<false, NT>(a.dq, Q, cp.tok0, cp.ts, cp.L, tt);
+                walk_store<false, NT>(a.dk, K, cp.tok0, cp.ts, cp.L, tt);
+            }
+            walk_store<false, NT>(a.dv, V, cp.vtok0, cp.vts, cp.L, tt);
         }
         if (VSPLIT && first_group) walk_store<false, NT>(a.dw_h, dUh, cp.wtok0, 1, cp.L, tt);
         if (VSPLIT && !first_group) walk_store<false, NT>(a.dw_l, Wl, cp.wtok0, 1, cp.L, tt);
+    };
+    // WIDE == 2: the first pass's share of a gradient block (lane = token 32 nb + n, registers = this wave's 32 features)
+    struct Part { u32x2 h[4], l[4]; };
+    auto part_load = [&](Part& pt, const uint16_t* ph, const uint16_t* pl, const ChunkPos& cp, int nb) {
+        const size_t row = (cp.wtok0 + size_t(min(32 * nb + n, max(cp.L, 1) - 1))) * D + 32 * wave + 4 * half;
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            pt.h[g] = *reinterpret_cast<const u32x2*>(ph + row + 8 * g);
+            pt.l[g] = *reinterpret_cast<const u32x2*>(pl + row + 8 * g);
+        }
+    };
+    auto part_add = [](f32x16& x, const Part& pt) {
+        _Pragma("unroll") for (int g = 0; g < 4; ++g) {
+            x[4 * g + 0] += bf16_lo(pt.h[g].x) + bf16_lo(pt.l[g].x);
+            x[4 * g + 1] += bf16_hi(pt.h[g].x) + bf16_hi(pt.l[g].x);
+            x[4 * g + 2] += bf16_lo(pt.h[g].y) + bf16_lo(pt.l[g].y);
+            x[4 * g + 3] += bf16_hi(pt.h[g].y) + bf16_hi(pt.l[g].y);
+        }
     };
     // head of a block; the block keeps its remainder
     auto split_block = [](f32x16& x) {
@@ -592,9 +627,10 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
         f32x16 S[4];
         _Pragma("unroll") for (int vb = 0; vb < 4; ++vb) S[vb] = f32x16{0};
         {
-            const float* ein = a.nseg > 1 ? a.bound + (size_t(seq) * (a.bound_per ? a.bound_n : a.nseg) + seg * (a.bound_per ? a.bound_per : 1)) * D * D
-                                          : (a.edge_in ? a.edge_in + size_t(seq) * D * D : nullptr);
-            if (ein) walk_state_load(S, ein, true, wave, n, half);
+            if (a.nseg > 1)
+                walk_state_load(S, a.bound + (size_t(seq) * (a.bound_per ? a.bound_n : a.nseg) + seg * (a.bound_per ? a.bound_per : 1)) * D * D,
+                                true, wave, n, half);
+            else if (a.edge_in) walk_state_load(S, a.edge_in + edge_off(d, seq), true, wave, n, half, D * d.vm);
         }
         float gval = 0.f;
         auto gload = [&](int kk) {
@@ -603,7 +639,12 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
             gload_tiles(p, true);
         };
         // dq^T[i][j] += sum_{r<=j} K^T[i][r] G[j][r] (keys r >= 32 never reach queries j < 32), its share of the decay gradient
-        auto dq_intra = [&](f32x16 (&aq)[2], PackedBlock (&resq)[2]) {
+        auto dq_intra = [&](f32x16 (&aq)[2], PackedBlock (&resq)[2], PackedBlock (&resql)[2], const ChunkPos& cp) {
+            Part pt[2];
+            if (WIDE == 2) {
+                part_load(pt[0], a.part[0], a.part[1], cp, 0);
+                part_load(pt[1], a.part[0], a.part[1], cp, 1);
+            }
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 const int tok = 32 * nb + n;
                 _Pragma("unroll") for (int ks = 0; ks < 2 * (nb + 1); ++ks) {
@@ -616,7 +657,13 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
                     pq += __shfl_xor(pq, 32, 64);
                     if (half == 0) red[(wave * 2 + 0) * 64 + tok] = pq;
                 }
-                resq[nb] = pack_block(aq[nb]);
+                if (WIDE == 2) part_add(aq[nb], pt[nb]);  // after the decay gradient took this pass's own share
+                if (WIDE == 1) {
+                    resq[nb] = split_block(aq[nb]);
+                    resql[nb] = pack_block(aq[nb]);
+                } else {
+                    resq[nb] = pack_block(aq[nb]);
+                }
             }
         };
         // <S, dS> with the state at the END of the chunk, over this wave's rows i: together with the running sums of
@@ -645,7 +692,7 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
             fresh();
             const float bC = DEC ? bs[C] : 0.f;
             f32x16 aq[2];
-            PackedBlock resw[2], resq[2];
+            PackedBlock resw[2], resq[2], resql[2];
             if (VSPLIT) {
                 // dW^T[i][t] = -sum_v S[i][v] dU[t][v]; the remainder plane is staged at once (nobody else uses its area)
                 f32x16 dw[2];
@@ -671,7 +718,7 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
                 // the planes of dU are dead: the head of dW is staged over the first
                 _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) store_packed(dUh, LD, 32 * nb + n, 32 * wave, half, resw[nb]);
                 walk_inter<DEC>(aq, S, dO, bs, n, half);
-                dq_intra(aq, resq);
+                dq_intra(aq, resq, resql, cp);
                 fresh();
                 if (WANT_DG) {
                     const uint16_t* dS = a.dstates + cp.slot * D * D;
@@ -683,12 +730,13 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
                 if (WANT_DG) state_dot(dsz);
                 if (kk + 1 < cnt) gload(kk + 1);
             } else {
-                dq_intra(aq, resq);
+                dq_intra(aq, resq, resql, cp);
             }
             __syncthreads();  // (3) every wave is done with the tiles
             fresh();
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 store_packed(Q, LD, 32 * nb + n, 32 * wave, half, resq[nb]);
+                if (WIDE == 1) store_packed(Lq, LD, 32 * nb + n, 32 * wave, half, resql[nb]);
             }
             __syncthreads();  // (4)
             fresh();
@@ -704,12 +752,14 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
                     if (tid + off < 64) sfx += y;
                 }
                 float dgv = tid < L ? sfx + z : 0.f;
+                constexpr bool add = WIDE == 2;  // the decay gradient sums over the value slices too
                 if (d.kind == 1) {
                     // one decay per head: only the sum over tokens is wanted; this chunk's share, in a fixed order
                     for (int off = 32; off > 0; off >>= 1) dgv += __shfl_xor(dgv, off, 64);
-                    if (tid == 0) a.dg_tok[cp.slot] = dgv;
+                    if (tid == 0) a.dg_tok[cp.slot] = add ? a.dg_tok[cp.slot] + dgv : dgv;
                 } else if (tid < L) {
-                    a.dg_tok[cp.tok0 + size_t(tid) * cp.ts] = dgv;
+                    float* pg = a.dg_tok + cp.tok0 + size_t(tid) * cp.ts;
+                    *pg = add ? *pg + dgv : dgv;
                 }
             }
         }
@@ -782,7 +832,12 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
             }
             __syncthreads();  // (2) G and As are in LDS
             fresh();
-            PackedBlock resk[2], resv[2];
+            PackedBlock resk[2], resv[2], reskl[2];
+            Part pt[2];
+            if (WIDE == 2) {
+                part_load(pt[0], a.part[2], a.part[3], cp, 0);
+                part_load(pt[1], a.part[2], a.part[3], cp, 1);
+            }
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 const int tok = 32 * nb + n;
                 // dk^T[i][r] += sum_{j>=r} Q^T[i][j] G[j][r]: queries j < 32 never see keys r >= 32
@@ -800,7 +855,13 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
                     resk[nb] = split_block(ak[nb]);
                     resv[nb] = pack_block(ak[nb]);
                 } else {
-                    resk[nb] = pack_block(ak[nb]);
+                    if (WIDE == 2) part_add(ak[nb], pt[nb]);
+                    if (WIDE == 1) {
+                        resk[nb] = split_block(ak[nb]);
+                        reskl[nb] = pack_block(ak[nb]);
+                    } else {
+                        resk[nb] = pack_block(ak[nb]);
+                    }
                     // dv^T[v][r] += sum_{j>=r} dO^T[v][j] As[j][r]
                     _Pragma("unroll") for (int ks = 2 * nb; ks < 4; ++ks) {
                         const bf16x8 dot = frag_tr(dO, LD, 16 * ks, 32 * wave, lane);
@@ -815,6 +876,7 @@ __global__ __launch_bounds__(kGrad8Threads, 1) void mk_walk_grad(Dims d, GradArg
             _Pragma("unroll") for (int nb = 0; nb < 2; ++nb) {
                 store_packed(K, LD, 32 * nb + n, 32 * wave, half, resk[nb]);
                 store_packed(V, LD, 32 * nb + n, 32 * wave, half, resv[nb]);
+                if (WIDE == 1) store_packed(Lk, LD, 32 * nb + n, 32 * wave, half, reskl[nb]);
             }
             __syncthreads();  // (4)
             fresh();
@@ -834,7 +896,7 @@ __global__ __launch_bounds__(kThreads) void mk_bound_scan(Dims d, const float* _
     const int nsq = max(1, (walk.n + m - 1) / m);
     float* b = bound + size_t(seq) * nseg * D * D + e;
     const float* gs = gseg + size_t(seq) * nseg;
-    float E = edge_in ? edge_in[size_t(seq) * D * D + e] : 0.f;
+    float E = edge_in ? edge_in[edge_off(d, seq) + size_t(e / D) * D * d.vm + e % D] : 0.f;
     // The contributions are read eight segments at a time before any of them is replaced: the reads of a batch do not
     // depend on each other, only the recurrence does (read - update - write in turn pays one memory latency per segment).
     constexpr int G = 8;

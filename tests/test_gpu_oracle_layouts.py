@@ -170,3 +170,77 @@ def test_segment_plans_of_the_chunk_walkers(kind, shape, saved):
         r = pkg.lsm_chunk_bwd(t["q"], t["k"], t["v"], t["g"], kind, t["d_o"], 64, t["m0"], t["d_mT"])
     torch.cuda.synchronize()
     check_all(x, o, mT, r, oracle_all(x))
+
+
+# ---- scalar decay kinds with d_v = 256: the matrix-core walkers take one 128-wide value slice per pass; the query,
+# key and decay gradients sum over the slices
+
+WIDE_SHAPES = [(2, 3, 333), (1, 2, 1300), (8, 8, 200)]   # a few segments; many chunks; one segment per sequence
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("kind", [wl.KIND_NONE, wl.KIND_HEAD, wl.KIND_SCALAR])
+@pytest.mark.parametrize("shape", WIDE_SHAPES)
+def test_scalar_kinds_with_wide_values_run_on_the_matrix_cores(shape, kind, layout):
+    import torch
+    import paper_2503_05447_amd as pkg
+    B, H, T = shape
+    x = wl.make_inputs(B, H, T, 128, 256, kind, dtype="bf16", seed=2500 + T + kind, decay="weak", init_state=True, d_final=True)
+    p = pkg.make_params(B, H, T, 128, 256, 64, kind, 1, layout=layout)
+    assert pkg.kernel_path(p) == 1, "bf16, chunk 64, d_k = 128, d_v = 256 must run on the MFMA kernels"
+    assert pkg.keeps_states(pkg.make_params(B, H, T, 128, 256, 64, kind, 1, layout=layout, flags=pkg.FLAG_SAVE_STATES)) == 0
+    if layout == 1:
+        o, mT, r = compare_token_major(x)
+    else:
+        t = to_device(x)
+        # the flag is accepted and changes nothing here: the backward call recomputes
+        ws = pkg.lsm_chunk_workspace(t["q"], t["k"], t["v"], t["g"], kind, 64, save_states=True)
+        o, mT = pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"], t["g"], kind, 64, t["m0"], workspace=ws, save_states=True)
+        r = pkg.lsm_chunk_bwd(t["q"], t["k"], t["v"], t["g"], kind, t["d_o"], 64, t["m0"], t["d_mT"], workspace=ws,
+                              states_saved=True)
+        torch.cuda.synchronize()
+    check_all(x, o, mT, r, oracle_all(x))
+
+
+def test_wide_values_equal_two_narrow_calls_in_the_forward():
+    """Each 128-wide slice of the values is a recurrence of its own: o and the final state of a d_v = 256 call equal,
+    bit for bit, those of two d_v = 128 calls on the halves of v."""
+    import torch
+    import paper_2503_05447_amd as pkg
+    x = wl.make_inputs(2, 2, 700, 128, 256, wl.KIND_SCALAR, dtype="bf16", seed=2601, decay="default", init_state=True)
+    t = to_device(x)
+    o, mT = pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"], t["g"], wl.KIND_SCALAR, 64, t["m0"])
+    for s in range(2):
+        sl = slice(128 * s, 128 * s + 128)
+        o_s, mT_s = pkg.lsm_chunk_fwd(t["q"], t["k"], t["v"][..., sl].contiguous(), t["g"], wl.KIND_SCALAR, 64,
+                                      t["m0"][..., sl].contiguous())
+        torch.cuda.synchronize()
+        assert torch.equal(o[..., sl], o_s) and torch.equal(mT[..., sl], mT_s), s
+
+
+def test_packed_wide_values_against_oracle():
+    import torch
+    from oracle import lsm_oracle_bwd, lsm_oracle_fwd
+    kind, dk, dv, dtype = wl.KIND_SCALAR, 128, 256, "bf16"
+    lens = [70, 1, 700, 64, 5]
+    T, H, n = sum(lens), 2, len(lens)
+    x = wl.make_inputs(1, H, T, dk, dv, kind, dtype=dtype, seed=2700, decay="weak")
+    rng = np.random.default_rng(2701)
+    x["m0"] = (rng.standard_normal((n, H, dk, dv)) * 0.1).astype(np.float32)
+    x["d_mT"] = (rng.standard_normal((n, H, dk, dv)) * 0.1).astype(np.float32)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    o, mT, r = compare_token_major(x, cu=torch.from_numpy(cu).to("cuda:0"))
+    ref = {m: [] for m in ("o", "mT", "dq", "dk", "dv", "dg", "d_m0")}
+    for s, (lo, hi) in enumerate(zip(cu[:-1], cu[1:])):
+        cut = lambda a: np.ascontiguousarray(a[:, :, lo:hi])
+        o_s, mT_s = lsm_oracle_fwd(cut(x["q"]), cut(x["k"]), cut(x["v"]), cut(x["g"]), kind, x["m0"][s:s + 1])
+        r_s = lsm_oracle_bwd(cut(x["q"]), cut(x["k"]), cut(x["v"]), cut(x["g"]), kind, cut(x["d_o"]), x["m0"][s:s + 1], x["d_mT"][s:s + 1])
+        ref["o"].append(o_s); ref["mT"].append(mT_s); ref["d_m0"].append(r_s["d_m0"])
+        for m in ("dq", "dk", "dv", "dg"):
+            ref[m].append(r_s[m])
+    cat_t = lambda m: np.concatenate(ref[m], axis=2)
+    check("o", host(o), cat_t("o"), dtype)
+    check("final_state", host(mT), np.concatenate(ref["mT"], axis=0), dtype)
+    for m in ("dq", "dk", "dv", "dg"):
+        check(m, host(r[m]), cat_t(m), dtype)
+    check("d_init_state", host(r["d_init_state"]), np.concatenate(ref["d_m0"], axis=0), dtype)
