@@ -137,7 +137,8 @@ def test_packed_sequences_against_oracle(kind):
     check("d_init_state", host(r["d_init_state"]), np.concatenate(ref["d_m0"], axis=0), "bf16")
 
 
-@pytest.mark.parametrize("case", [("bf16", wl.KIND_SCALAR, 128, 128), ("bf16", wl.KIND_VECTOR, 128, 256), ("f32", wl.KIND_SCALAR, 64, 64)])
+@pytest.mark.parametrize("case", [("bf16", wl.KIND_SCALAR, 128, 128), ("bf16", wl.KIND_SCALAR, 128, 256), ("bf16", wl.KIND_VECTOR, 128, 256),
+                                  ("f32", wl.KIND_SCALAR, 64, 64)])
 def test_packed_input_with_an_empty_sequence(case):
     """A sequence of length zero passes its initial state (and the gradient of its final state) through."""
     import torch
