@@ -473,7 +473,11 @@ __device__ __forceinline__ float row_dot(const uint16_t* X, int tok, int wave, i
 // REPEAT (benchmark aid): the compute phase runs `reps` times on the tiles resident in LDS, so that
 // the rate of the intra-chunk arithmetic can be measured without the HBM traffic that bounds the
 // streamed kernel; the stored result is that of the last pass, identical to reps = 1.
-constexpr int kOutLds = 3 * C * LD * 2 + C * 4;
+// The V tile is only ever read through the transpose read, whose 16-lane groups fetch 4 rows x 32 bytes: with the row
+// stride of the other tiles (68 words, == 4 mod 64: conflict-free for 16-byte row reads) consecutive rows overlap in
+// half of their banks; 80 words (== 16 mod 64) lets the 4 rows x 2 groups of a half-wave tile the 64 banks exactly.
+constexpr int LDV = D + 32;
+constexpr int kOutLds = 2 * C * LD * 2 + C * LDV * 2 + C * 4;
 constexpr int kOutLdsRepeat = kOutLds + 2 * C * LDP * 2;
 
 template <bool REPEAT>
@@ -486,7 +490,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
     uint16_t* Q = reinterpret_cast<uint16_t*>(smem);
     uint16_t* K = Q + C * LD;
     uint16_t* V = K + C * LD;
-    float* bs = reinterpret_cast<float*>(V + C * LD);
+    float* bs = reinterpret_cast<float*>(V + C * LDV);
     uint16_t* stage = K;
 
     const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -512,7 +516,11 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
 
     tile_commit(Q, tq, L, tid);
     tile_commit(K, tk, L, tid);
-    tile_commit(V, tv, L, tid);
+    _Pragma("unroll") for (int it = 0; it < 4; ++it) {  // tile_commit with the V tile's own row stride
+        const int p = tid + kThreads * it, row = p >> 4, cpp = p & 15;
+        const uint32_t keep = row < L ? 0xffffffffu : 0u;
+        *reinterpret_cast<u32x4*>(V + row * LDV + cpp * 8) = u32x4{tv.v[it].x & keep, tv.v[it].y & keep, tv.v[it].z & keep, tv.v[it].w & keep};
+    }
     cumulative_decay(gval, L, bs, tid);
     __syncthreads();
 
@@ -544,7 +552,7 @@ __global__ __launch_bounds__(kThreads, 3) void mk_output(Dims d, const uint16_t*
         _Pragma("unroll") for (int jb = 0; jb < 2; ++jb) {
             const int j = 32 * jb + n;
             _Pragma("unroll") for (int ks = 0; ks < 2 * (jb + 1); ++ks) {  // keys r >= 32 never reach queries j < 32
-                const bf16x8 vt = frag_tr(V, LD, 16 * ks, 32 * wave, lane);
+                const bf16x8 vt = frag_tr(V, LDV, 16 * ks, 32 * wave, lane);
                 acc[jb] = mfma(vt, frag(Ph, LDP, j, 16 * ks + 8 * half), acc[jb]);
                 acc[jb] = mfma(vt, frag(Pl, LDP, j, 16 * ks + 8 * half), acc[jb]);
             }
